@@ -1,0 +1,289 @@
+"""Float64 CPU oracle for the SwitchHead attention layer (arXiv 2312.07987).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, __graft_entry__.smoke() and bench.py's
+cpu_baseline leg; never by the product path.  It shares no code with the HIP kernels.
+
+What it computes, in the paper's notation (Sec. 2.1 and 2.2):
+
+  s_S^h = sigmoid(x W_S^h),  E_S^h = argtopk(s_S^h, k)          source-side router
+  s_D^h = sigmoid(x W_D^h),  E_D^h = argtopk(s_D^h, k)          destination-side router
+  Q^h = x W_Q^h,  K^h = x W_K^h                                  dense, one copy per head
+  V^h = sum_{e in E_S^h} s_S^h[e] x W_V^{h,e}                    value experts
+  A^h = softmax(Q^h K^h^T / sqrt(d_head))                        Sec. 2.1, first equation
+  y   = sum_h sum_{e in E_D^h} s_D^h[e] A^h V^h W_O^{h,e}        output experts
+
+Everything is plain numpy float64, written as the definitions read: no blocking, no
+fusion, no reordering.  The paper gives no backward pass; `backward` is the chain rule
+applied to the six forward steps (the top-k selection is piecewise constant, so only the
+selected gates carry gradient).
+
+Readings where the paper is silent (all listed in the design notes of the repository):
+  * selection is made on the pre-sigmoid logit (sigmoid is strictly increasing, so the
+    chosen set is the same in exact arithmetic); equal logits -> the lower index wins;
+    the k slots are ordered by descending logit;
+  * the router logit is the float64 sum over i = 0..d_model-1 taken IN THAT ORDER with a
+    single accumulator, bias (if any) added last;
+  * gates are not renormalised (non-competitive selection, Sec. 2.2);
+  * causal mask: key u is visible to query t iff u <= t; masked logits are -inf;
+  * no positional encoding, dropout, bias or normalisation inside the layer.
+
+Pinned by tests/test_oracle_pins.py against: a dense-masked brute force in pure Python
+loops, the k=E dense mixture, the single-expert case against a textbook concat-form MHA,
+closed forms (all gates 0.5), invariants (causality, T=1, batch equivariance, permutation
+properties), exact ties, central finite differences and torch.autograd of an independent
+dense-masked formulation for the backward pass.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = ["router_logits", "select_topk", "routing_tables", "forward", "backward"]
+
+
+def _f64(a):
+    return None if a is None else np.asarray(a, dtype=np.float64)
+
+
+def router_logits(x2, W, b=None):
+    """z[n, c] = sum_i x2[n, i] * W[i, c] (+ b[c]); Sec. 2.2, argument of the sigmoid.
+
+    The sum runs over i ascending with one accumulator per output, so that the value is
+    a fixed function of the inputs (a BLAS call would block the sum in an unspecified way).
+    """
+    x2 = _f64(x2)
+    W = _f64(W)
+    z = np.zeros((x2.shape[0], W.shape[1]), dtype=np.float64)
+    for i in range(x2.shape[1]):
+        z += x2[:, i:i + 1] * W[i:i + 1, :]
+    if b is not None:
+        z += _f64(b)[None, :]
+    return z
+
+
+def select_topk(z, nheads, k):
+    """argtopk of Sec. 2.2 per (token, head): indices of the k largest logits, in
+    descending order of logit, equal logits -> lower index first; gates = sigmoid(logit).
+
+    z: [N, nheads*E] -> idx int32 [nheads, N, k], gate float64 [nheads, N, k],
+    margin float64 [nheads, N] (gap between the k-th and (k+1)-th logit; inf if k == E).
+    """
+    N = z.shape[0]
+    E = z.shape[1] // nheads
+    zh = z.reshape(N, nheads, E).transpose(1, 0, 2)          # [H, N, E]
+    order = np.argsort(-zh, axis=-1, kind="stable")          # stable: ties keep index order
+    idx = order[..., :k].astype(np.int32)
+    zsel = np.take_along_axis(zh, idx.astype(np.int64), axis=-1)
+    gate = 1.0 / (1.0 + np.exp(-zsel))
+    if k < E:
+        znext = np.take_along_axis(zh, order[..., k:k + 1], axis=-1)[..., 0]
+        margin = zsel[..., k - 1] - znext
+    else:
+        margin = np.full((nheads, N), np.inf)
+    return idx, gate, margin
+
+
+def routing_tables(idx, E):
+    """Expert-sorted permutation of the N*k assignments of one (side, head).
+
+    idx: int [N, k].  Assignment id a = n*k + j.  Returns
+      perm    int32 [N*k]  assignment ids sorted by expert, stable (ascending a inside an expert)
+      offsets int32 [E+1]  exclusive scan of the per-expert counts
+      inv     int32 [N*k]  inverse permutation: inv[perm[p]] = p
+    (the "sorting and top-k steps" mentioned in Sec. 3.5).
+    """
+    flat = np.asarray(idx).reshape(-1)
+    perm = np.argsort(flat, kind="stable").astype(np.int32)
+    counts = np.bincount(flat, minlength=E)
+    offsets = np.zeros(E + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(perm.size, dtype=np.int32)
+    return perm, offsets, inv
+
+
+def _attention_matrix(Qbh, Kbh, causal):
+    """A = softmax(Q K^T / sqrt(d_head)) for one (sequence, head); Sec. 2.1."""
+    T, dh = Qbh.shape
+    S = (Qbh @ Kbh.T) / np.sqrt(float(dh))
+    if causal:
+        t = np.arange(T)
+        S = np.where(t[None, :] <= t[:, None], S, -np.inf)
+    S = S - S.max(axis=-1, keepdims=True)
+    P = np.exp(S)
+    return P / P.sum(axis=-1, keepdims=True)
+
+
+def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, causal=True):
+    """One SwitchHead layer call.
+
+    x [B,T,dm]; W_Q, W_K [H,dm,dh]; W_V [H,E,dm,dh]; W_O [H,E,dh,dm];
+    W_S, W_D [dm, H*E] (column h*E+e); b_S, b_D [H*E] or None.
+    W_D None  -> shared selection: the destination side reuses the source side's choice
+                 (Sec. 3.5).
+    W_S None  -> dense multi-head attention (requires E == 1; every gate is exactly 1;
+                 Sec. 2.1, per-head-sum form of the output).
+    Returns a dict with y and every intermediate the backward pass and the tests need.
+    """
+    x, W_Q, W_K, W_V, W_O = map(_f64, (x, W_Q, W_K, W_V, W_O))
+    B, T, dm = x.shape
+    H, E = W_V.shape[0], W_V.shape[1]
+    dh = W_Q.shape[2]
+    N = B * T
+    x2 = x.reshape(N, dm)
+
+    # step 1: routers (Sec. 2.2)
+    if W_S is None:
+        assert E == 1 and k == 1
+        zS = zD = None
+        idx_S = idx_D = np.zeros((H, N, 1), dtype=np.int32)
+        g_S = g_D = np.ones((H, N, 1))
+        mar_S = mar_D = np.full((H, N), np.inf)
+    else:
+        zS = router_logits(x2, W_S, b_S)
+        idx_S, g_S, mar_S = select_topk(zS, H, k)
+        if W_D is None:
+            zD, idx_D, g_D, mar_D = zS, idx_S, g_S, mar_S
+        else:
+            zD = router_logits(x2, W_D, b_D)
+            idx_D, g_D, mar_D = select_topk(zD, H, k)
+
+    # step 2: dense per-head queries and keys
+    Q = np.stack([x2 @ W_Q[h] for h in range(H)], axis=1)       # [N,H,dh]
+    K = np.stack([x2 @ W_K[h] for h in range(H)], axis=1)
+
+    # step 3: V^h = sum_{e in E_S} s_S[e] x W_V^{h,e}
+    V = np.zeros((N, H, dh))
+    for h in range(H):
+        for j in range(k):
+            for e in range(E):
+                rows = np.nonzero(idx_S[h, :, j] == e)[0]
+                if rows.size:
+                    V[rows, h, :] += g_S[h, rows, j][:, None] * (x2[rows] @ W_V[h, e])
+
+    # step 4: one attention matrix per (sequence, head)
+    ctx = np.zeros((N, H, dh))
+    for b in range(B):
+        sl = slice(b * T, (b + 1) * T)
+        for h in range(H):
+            A = _attention_matrix(Q[sl, h], K[sl, h], causal)
+            ctx[sl, h, :] = A @ V[sl, h]
+
+    # step 5: y = sum_h sum_{e in E_D} s_D[e] (A V) W_O^{h,e}
+    y = np.zeros((N, dm))
+    for h in range(H):
+        for j in range(k):
+            for e in range(E):
+                rows = np.nonzero(idx_D[h, :, j] == e)[0]
+                if rows.size:
+                    y[rows] += g_D[h, rows, j][:, None] * (ctx[rows, h, :] @ W_O[h, e])
+
+    # step 6: routing artefacts per (side, head)
+    tabs = {}
+    for name, idx in (("S", idx_S), ("D", idx_D)):
+        pr, of, iv = zip(*(routing_tables(idx[h], E) for h in range(H)))
+        tabs["perm_" + name] = np.stack(pr)
+        tabs["offsets_" + name] = np.stack(of)
+        tabs["inv_" + name] = np.stack(iv)
+
+    out = dict(y=y.reshape(B, T, dm), Q=Q, K=K, V=V, ctx=ctx, zS=zS, zD=zD,
+               idx_S=idx_S, idx_D=idx_D, gate_S=g_S, gate_D=g_D,
+               margin_S=mar_S, margin_D=mar_D, k=k, causal=causal,
+               shared=(W_S is not None and W_D is None), dense=(W_S is None))
+    out.update(tabs)
+    return out
+
+
+def backward(x, W_Q, W_K, W_V, W_O, W_S, W_D, fwd, dy):
+    """Gradients of sum(y * dy) w.r.t. every input of `forward` (chain rule; the paper
+    prints no backward equations, it trains with automatic differentiation, App. A.2).
+
+    `fwd` is the dict returned by `forward` on the same inputs.  Returns dx [B,T,dm],
+    dW_Q, dW_K, dW_V, dW_O, dW_S, dW_D, db_S, db_D (router entries None in dense mode;
+    dW_D/db_D None with shared selection, whose dW_S collects both sides).
+    """
+    x, W_Q, W_K, W_V, W_O, dy = map(_f64, (x, W_Q, W_K, W_V, W_O, dy))
+    W_S, W_D = _f64(W_S), _f64(W_D)
+    B, T, dm = x.shape
+    H, E = W_V.shape[0], W_V.shape[1]
+    dh = W_Q.shape[2]
+    N = B * T
+    k, causal = fwd["k"], fwd["causal"]
+    x2, dy2 = x.reshape(N, dm), dy.reshape(N, dm)
+    Q, K, V, ctx = fwd["Q"], fwd["K"], fwd["V"], fwd["ctx"]
+    idx_S, idx_D, g_S, g_D = fwd["idx_S"], fwd["idx_D"], fwd["gate_S"], fwd["gate_D"]
+
+    dx = np.zeros((N, dm))
+    dW_Q, dW_K = np.zeros_like(W_Q), np.zeros_like(W_K)
+    dW_V, dW_O = np.zeros_like(W_V), np.zeros_like(W_O)
+
+    # output experts: y[n] = sum_h sum_j gD * ctx[n,h] W_O[h,e_j]
+    dgD = np.zeros((H, N, k))
+    dctx = np.zeros((N, H, dh))
+    for h in range(H):
+        for j in range(k):
+            for e in range(E):
+                rows = np.nonzero(idx_D[h, :, j] == e)[0]
+                if not rows.size:
+                    continue
+                g = g_D[h, rows, j][:, None]
+                P6 = ctx[rows, h, :] @ W_O[h, e]                       # [r, dm]
+                dgD[h, rows, j] = np.sum(P6 * dy2[rows], axis=1)
+                dctx[rows, h, :] += g * (dy2[rows] @ W_O[h, e].T)
+                dW_O[h, e] += (g * ctx[rows, h, :]).T @ dy2[rows]
+
+    # attention: ctx = A V, A = softmax(S), S = Q K^T / sqrt(dh)
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    scale = 1.0 / np.sqrt(float(dh))
+    for b in range(B):
+        sl = slice(b * T, (b + 1) * T)
+        for h in range(H):
+            A = _attention_matrix(Q[sl, h], K[sl, h], causal)
+            dV[sl, h] = A.T @ dctx[sl, h]
+            dA = dctx[sl, h] @ V[sl, h].T
+            dS = A * (dA - np.sum(dA * A, axis=-1, keepdims=True))
+            dQ[sl, h] = (dS @ K[sl, h]) * scale
+            dK[sl, h] = (dS.T @ Q[sl, h]) * scale
+
+    # value experts: V[n,h] = sum_j gS * x[n] W_V[h,e_j]
+    dgS = np.zeros((H, N, k))
+    for h in range(H):
+        for j in range(k):
+            for e in range(E):
+                rows = np.nonzero(idx_S[h, :, j] == e)[0]
+                if not rows.size:
+                    continue
+                g = g_S[h, rows, j][:, None]
+                P3 = x2[rows] @ W_V[h, e]                              # [r, dh]
+                dgS[h, rows, j] = np.sum(P3 * dV[rows, h, :], axis=1)
+                dW_V[h, e] += (g * x2[rows]).T @ dV[rows, h, :]
+                dx[rows] += g * (dV[rows, h, :] @ W_V[h, e].T)
+
+    # dense queries and keys
+    for h in range(H):
+        dW_Q[h] = x2.T @ dQ[:, h, :]
+        dW_K[h] = x2.T @ dK[:, h, :]
+        dx += dQ[:, h, :] @ W_Q[h].T + dK[:, h, :] @ W_K[h].T
+
+    # routers: g = sigmoid(z) at the selected entries, nothing elsewhere
+    dW_S = dW_D = db_S = db_D = None
+    if not fwd["dense"]:
+        def dz_of(idx, g, dg):
+            dz = np.zeros((N, H * E))
+            for h in range(H):
+                for j in range(k):
+                    dz[np.arange(N), h * E + idx[h, :, j]] += dg[h, :, j] * g[h, :, j] * (1.0 - g[h, :, j])
+            return dz
+        dzS = dz_of(idx_S, g_S, dgS)
+        dzD = dz_of(idx_D, g_D, dgD)
+        if fwd["shared"]:
+            dzS = dzS + dzD
+            dW_S, db_S = x2.T @ dzS, dzS.sum(axis=0)
+            dx += dzS @ W_S.T
+        else:
+            dW_S, db_S = x2.T @ dzS, dzS.sum(axis=0)
+            dW_D, db_D = x2.T @ dzD, dzD.sum(axis=0)
+            dx += dzS @ W_S.T + dzD @ W_D.T
+
+    return dict(dx=dx.reshape(B, T, dm), dW_Q=dW_Q, dW_K=dW_K, dW_V=dW_V, dW_O=dW_O,
+                dW_S=dW_S, dW_D=dW_D, db_S=db_S, db_D=db_D,
+                dQ=dQ, dK=dK, dV=dV, dctx=dctx, dgate_S=dgS, dgate_D=dgD)

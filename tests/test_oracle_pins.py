@@ -1,0 +1,462 @@
+"""Pins for the float64 oracle: everything here compares oracle/ with something that is
+not the oracle - pure-Python brute force, closed forms, textbook multi-head attention
+written in the concatenated form of Sec. 2.1, invariants the equations imply, central
+finite differences and torch.autograd over an independently written dense-masked layer.
+The paper prints no worked numeric example of the layer, so no stored output values exist.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import switchhead_oracle as orc
+from paper_2312_07987_amd.inputs import make_inputs, round_to_bf16
+
+TINY = dict(name="tiny", dtype="f32", B=2, T=5, d_model=6, nheads=2, d_head=4, E=3, k=2, causal=1, bias0=0.0)
+
+
+def _inputs(cfg, seed=7):
+    return make_inputs(cfg, seed=seed)
+
+
+def _fwd(t, k, causal=True, **over):
+    a = dict(t)
+    a.update(over)
+    return orc.forward(a["x"], a["W_Q"], a["W_K"], a["W_V"], a["W_O"], a["W_S"], a["W_D"],
+                       a["b_S"], a["b_D"], k=k, causal=causal)
+
+
+def _bwd(t, fwd, **over):
+    a = dict(t)
+    a.update(over)
+    return orc.backward(a["x"], a["W_Q"], a["W_K"], a["W_V"], a["W_O"], a["W_S"], a["W_D"], fwd, a["dy"])
+
+
+# --------------------------------------------------------------------------------------
+# independent formulations
+# --------------------------------------------------------------------------------------
+def brute_force_layer(t, k, causal):
+    """Every expert computed densely for every token, unselected ones multiplied by 0;
+    pure Python floats and loops (tiny inputs only).  Selection re-derived here with a
+    plain scan: repeatedly take the largest remaining logit, lowest index on ties."""
+    x, WQ, WK, WV, WO, WS, WD = (np.asarray(t[n], dtype=np.float64).tolist() for n in
+                                 ("x", "W_Q", "W_K", "W_V", "W_O", "W_S", "W_D"))
+    B, T, dm = len(x), len(x[0]), len(x[0][0])
+    H, E, dh = len(WV), len(WV[0]), len(WV[0][0][0])
+
+    def gates(xv, W, h):
+        z = []
+        for e in range(E):
+            acc = 0.0
+            for i in range(dm):
+                acc += xv[i] * W[i][h * E + e]
+            z.append(acc)
+        left = list(range(E))
+        m = [0.0] * E
+        for _ in range(k):
+            best = left[0]
+            for e in left:
+                if z[e] > z[best]:
+                    best = e
+            left.remove(best)
+            m[best] = 1.0 / (1.0 + math.exp(-z[best]))
+        return m
+
+    y = [[[0.0] * dm for _ in range(T)] for _ in range(B)]
+    for b in range(B):
+        for h in range(H):
+            Q = [[sum(x[b][t_][i] * WQ[h][i][d] for i in range(dm)) for d in range(dh)] for t_ in range(T)]
+            K = [[sum(x[b][t_][i] * WK[h][i][d] for i in range(dm)) for d in range(dh)] for t_ in range(T)]
+            V = []
+            for t_ in range(T):
+                m = gates(x[b][t_], WS, h)
+                V.append([sum(m[e] * sum(x[b][t_][i] * WV[h][e][i][d] for i in range(dm)) for e in range(E))
+                          for d in range(dh)])
+            for t_ in range(T):
+                last = t_ if causal else T - 1
+                logit = [sum(Q[t_][d] * K[u][d] for d in range(dh)) / math.sqrt(dh) for u in range(last + 1)]
+                mx = max(logit)
+                w = [math.exp(l - mx) for l in logit]
+                s = sum(w)
+                c = [sum(w[u] / s * V[u][d] for u in range(last + 1)) for d in range(dh)]
+                m = gates(x[b][t_], WD, h)
+                for e in range(E):
+                    if m[e] != 0.0:
+                        for cc in range(dm):
+                            y[b][t_][cc] += m[e] * sum(c[d] * WO[h][e][d][cc] for d in range(dh))
+    return np.array(y)
+
+
+def textbook_mha(x, W_Q, W_K, W_V, W_O, causal):
+    """Sec. 2.1, concatenated form: y = (A^1 V^1 | ... | A^H V^H) W_O with W_O the per-head
+    blocks stacked along the first dimension.  W_V [H,dm,dh], W_O [H,dh,dm]."""
+    x = np.asarray(x, dtype=np.float64)
+    B, T, dm = x.shape
+    H, _, dh = W_Q.shape
+    W_O_stacked = np.concatenate([np.asarray(W_O[h], dtype=np.float64) for h in range(H)], axis=0)
+    y = np.zeros((B, T, dm))
+    for b in range(B):
+        heads = []
+        for h in range(H):
+            Q, K, V = x[b] @ W_Q[h].astype(np.float64), x[b] @ W_K[h].astype(np.float64), x[b] @ W_V[h].astype(np.float64)
+            L = Q @ K.T / math.sqrt(dh)
+            if causal:
+                L = L + np.triu(np.full((T, T), -np.inf), 1)
+            P = np.exp(L - L.max(-1, keepdims=True))
+            heads.append((P / P.sum(-1, keepdims=True)) @ V)
+        y[b] = np.concatenate(heads, axis=-1) @ W_O_stacked
+    return y
+
+
+def torch_dense_masked(t, idx_S, idx_D, causal, shared=False):
+    """Dense-masked SwitchHead in torch float64 with autograd: all experts for all tokens,
+    times (selection mask) * sigmoid(logit).  The 0/1 masks are constants."""
+    T64 = {n: (None if t[n] is None else torch.tensor(np.asarray(t[n], dtype=np.float64), requires_grad=True))
+           for n in ("x", "W_Q", "W_K", "W_V", "W_O", "W_S", "W_D", "b_S", "b_D")}
+    x = T64["x"]
+    B, T, dm = x.shape
+    H, E, _, dh = T64["W_V"].shape
+
+    def mask_of(idx):
+        m = np.zeros((B * T, H, E))
+        for h in range(H):
+            for j in range(idx.shape[2]):
+                m[np.arange(B * T), h, idx[h, :, j]] = 1.0
+        return torch.tensor(m).reshape(B, T, H, E)
+
+    zS = x @ T64["W_S"] + (0 if T64["b_S"] is None else T64["b_S"])
+    if shared:
+        zD = zS
+    else:
+        zD = x @ T64["W_D"] + (0 if T64["b_D"] is None else T64["b_D"])
+    gS = torch.sigmoid(zS).reshape(B, T, H, E) * mask_of(idx_S)
+    gD = torch.sigmoid(zD).reshape(B, T, H, E) * mask_of(idx_D)
+    Q = torch.einsum("bti,hid->bhtd", x, T64["W_Q"])
+    K = torch.einsum("bti,hid->bhtd", x, T64["W_K"])
+    V = torch.einsum("bti,heid,bthe->bhtd", x, T64["W_V"], gS)
+    L = Q @ K.transpose(-1, -2) / math.sqrt(dh)
+    if causal:
+        L = L + torch.triu(torch.full((T, T), float("-inf"), dtype=torch.float64), 1)
+    ctx = torch.softmax(L, dim=-1) @ V
+    y = torch.einsum("bhtd,hedc,bthe->btc", ctx, T64["W_O"], gD)
+    return y, T64
+
+
+# --------------------------------------------------------------------------------------
+# forward pins
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("E,k", [(3, 2), (3, 1), (4, 4)])
+def test_brute_force_dense_masked(E, k, causal):
+    cfg = dict(TINY, E=E, k=k)
+    t = _inputs(cfg, seed=11 + E + k)
+    got = _fwd(t, k, causal)["y"]
+    ref = brute_force_layer(t, k, causal)
+    assert np.max(np.abs(got - ref)) < 1e-12 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_k_equals_E_is_dense_sigmoid_mixture():
+    cfg = dict(TINY, B=2, T=9, d_model=10, E=4, k=4)
+    t = _inputs(cfg)
+    f = _fwd(t, 4)
+    x = t["x"].astype(np.float64)
+    B, T, dm = x.shape
+    sS = 1 / (1 + np.exp(-(x @ t["W_S"].astype(np.float64)))).reshape(B * T, 2, 4)
+    V = np.einsum("ni,heid,nhe->nhd", x.reshape(B * T, dm), t["W_V"].astype(np.float64), sS)
+    assert np.allclose(f["V"], V, rtol=0, atol=1e-12)
+    sD = 1 / (1 + np.exp(-(x @ t["W_D"].astype(np.float64)))).reshape(B * T, 2, 4)
+    y = np.einsum("nhd,hedc,nhe->nc", f["ctx"], t["W_O"].astype(np.float64), sD)
+    assert np.allclose(f["y"].reshape(B * T, dm), y, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_single_expert_is_textbook_mha(causal):
+    cfg = dict(TINY, B=2, T=12, d_model=16, nheads=3, d_head=8, E=1, k=1)
+    t = _inputs(cfg)
+    ref = textbook_mha(t["x"], t["W_Q"], t["W_K"], t["W_V"][:, 0], t["W_O"][:, 0], causal)
+    # dense mode: no router at all
+    f = _fwd(t, 1, causal, W_S=None, W_D=None)
+    assert np.allclose(f["y"], ref, rtol=0, atol=1e-12)
+    # router present but saturated: sigmoid(40) rounds to exactly 1.0 in float64
+    Z = np.zeros_like(t["W_S"])
+    b = np.full(3, 40.0, dtype=np.float32)
+    f = _fwd(t, 1, causal, W_S=Z, W_D=Z, b_S=b, b_D=b)
+    assert np.all(f["gate_S"] == 1.0) and np.all(f["gate_D"] == 1.0)
+    assert np.allclose(f["y"], ref, rtol=0, atol=1e-12)
+    # all logits zero: every gate is exactly 0.5, so y = 0.25 * MHA(x)
+    f = _fwd(t, 1, causal, W_S=Z, W_D=Z)
+    assert np.all(f["gate_S"] == 0.5)
+    assert np.allclose(f["y"], 0.25 * ref, rtol=0, atol=1e-12)
+
+
+def test_identical_experts_collapse_to_gate_sum():
+    cfg = dict(TINY, B=1, T=7, d_model=8, E=4, k=2)
+    t = _inputs(cfg)
+    t["W_V"] = np.repeat(t["W_V"][:, :1], 4, axis=1)
+    t["W_O"] = np.repeat(t["W_O"][:, :1], 4, axis=1)
+    f = _fwd(t, 2)
+    x2 = t["x"].reshape(7, 8).astype(np.float64)
+    for h in range(2):
+        V = f["gate_S"][h].sum(-1)[:, None] * (x2 @ t["W_V"][h, 0].astype(np.float64))
+        assert np.allclose(f["V"][:, h], V, rtol=0, atol=1e-12)
+    y = sum(f["gate_D"][h].sum(-1)[:, None] * (f["ctx"][:, h] @ t["W_O"][h, 0].astype(np.float64)) for h in range(2))
+    assert np.allclose(f["y"].reshape(7, 8), y, rtol=0, atol=1e-12)
+
+
+def test_causality_first_token_and_batch_equivariance():
+    cfg = dict(TINY, B=3, T=8)
+    t = _inputs(cfg)
+    f = _fwd(t, 2)
+    # perturbing the future leaves the past unchanged
+    t2 = dict(t)
+    x2 = t["x"].copy()
+    x2[:, 5:] += 1.0
+    t2["x"] = x2
+    f2 = _fwd(t2, 2)
+    assert np.array_equal(f["y"][:, :5], f2["y"][:, :5])
+    assert not np.allclose(f["y"][:, 5:], f2["y"][:, 5:])
+    # non-causal: the past does change
+    g, g2 = _fwd(t, 2, causal=False), _fwd(t2, 2, causal=False)
+    assert not np.allclose(g["y"][:, :5], g2["y"][:, :5])
+    # the first query sees only itself
+    V = f["V"].reshape(3, 8, 2, 4)
+    assert np.allclose(f["ctx"].reshape(3, 8, 2, 4)[:, 0], V[:, 0], rtol=0, atol=1e-15)
+    # permuting the batch permutes the output
+    p = np.array([2, 0, 1])
+    t3 = dict(t)
+    t3["x"] = t["x"][p]
+    assert np.array_equal(_fwd(t3, 2)["y"], f["y"][p])
+
+
+def test_T1_closed_form():
+    cfg = dict(TINY, B=4, T=1, d_model=6, E=3, k=2)
+    t = _inputs(cfg)
+    f = _fwd(t, 2)
+    for n in range(4):
+        x = t["x"][n, 0].astype(np.float64)
+        y = np.zeros(6)
+        for h in range(2):
+            Wv = sum(f["gate_S"][h, n, j] * t["W_V"][h, f["idx_S"][h, n, j]].astype(np.float64) for j in range(2))
+            Wo = sum(f["gate_D"][h, n, j] * t["W_O"][h, f["idx_D"][h, n, j]].astype(np.float64) for j in range(2))
+            y += (x @ Wv) @ Wo
+        assert np.allclose(f["y"][n, 0], y, rtol=0, atol=1e-13)
+
+
+def test_attention_rows_sum_to_one_and_uniform_case():
+    # Q = 0 -> uniform attention over the visible keys -> ctx is the running mean of V
+    cfg = dict(TINY, B=1, T=6)
+    t = _inputs(cfg)
+    t["W_Q"] = np.zeros_like(t["W_Q"])
+    f = _fwd(t, 2)
+    V = f["V"]
+    run = np.cumsum(V, axis=0) / np.arange(1, 7)[:, None, None]
+    assert np.allclose(f["ctx"], run, rtol=0, atol=1e-14)
+    g = _fwd(t, 2, causal=False)
+    assert np.allclose(g["ctx"], np.broadcast_to(V.mean(0), V.shape), rtol=0, atol=1e-14)
+
+
+def test_softmax_scale_is_inverse_sqrt_dhead():
+    # two keys, one query, hand-computed: logits q.k/sqrt(dh)
+    dh = 4
+    Q = np.array([[0.0, 0, 0, 0], [2.0, 0, 0, 0]])
+    K = np.array([[1.0, 0, 0, 0], [3.0, 0, 0, 0]])
+    A = orc._attention_matrix(Q, K, causal=True)
+    assert A[0, 0] == 1.0 and A[0, 1] == 0.0
+    l0, l1 = 2.0 * 1.0 / 2.0, 2.0 * 3.0 / 2.0
+    assert np.isclose(A[1, 1] / A[1, 0], math.exp(l1 - l0), rtol=1e-14)
+
+
+# --------------------------------------------------------------------------------------
+# routing pins
+# --------------------------------------------------------------------------------------
+def test_router_logit_is_sequential_sum():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((4, 50)).astype(np.float32)
+    W = rng.standard_normal((50, 6)).astype(np.float32)
+    b = rng.standard_normal(6).astype(np.float32)
+    z = orc.router_logits(x, W, b)
+    for n in range(4):
+        for c in range(6):
+            acc = 0.0
+            for i in range(50):
+                acc += float(x[n, i]) * float(W[i, c])      # Python floats are IEEE doubles
+            acc += float(b[c])
+            assert z[n, c] == acc
+
+
+def test_topk_order_ties_and_gates():
+    z = np.array([[0.5, 2.0, 2.0, -1.0, 0.5],      # tie between 1 and 2, and between 0 and 4
+                  [-3.0, -3.0, -3.0, -3.0, -3.0],  # all equal
+                  [1.0, 4.0, 3.0, 2.0, 5.0]])
+    idx, gate, margin = orc.select_topk(z, nheads=1, k=3)
+    assert idx[0].tolist() == [[1, 2, 0], [0, 1, 2], [4, 1, 2]]
+    assert np.allclose(gate[0, 2], 1 / (1 + np.exp(-np.array([5.0, 4.0, 3.0]))), rtol=1e-15)
+    assert margin[0].tolist() == [0.0, 0.0, 1.0]
+    # two heads: columns h*E+e
+    z2 = np.array([[1.0, 2.0, 3.0, 9.0, 8.0, 7.0]])
+    idx2, _, _ = orc.select_topk(z2, nheads=2, k=1)
+    assert idx2[:, 0, 0].tolist() == [2, 0]
+
+
+def test_duplicate_router_column_lower_index_wins():
+    cfg = dict(TINY, B=2, T=16, E=4, k=2)
+    t = _inputs(cfg)
+    for W in ("W_S", "W_D"):
+        w = t[W].copy()
+        w[:, 2] = w[:, 0]          # head 0: experts 0 and 2 have bitwise-equal logits
+        w[:, 4 + 3] = w[:, 4 + 1]  # head 1: experts 1 and 3
+        t[W] = w
+    f = _fwd(t, 2)
+    for side in ("S", "D"):
+        idx = f["idx_" + side]
+        for (h, lo, hi) in ((0, 0, 2), (1, 1, 3)):
+            sel_hi = (idx[h] == hi).any(-1)
+            sel_lo = (idx[h] == lo).any(-1)
+            assert np.all(sel_lo[sel_hi])                 # hi never chosen without lo
+            both = sel_lo & sel_hi
+            pos_lo = np.argmax(idx[h] == lo, axis=-1)
+            pos_hi = np.argmax(idx[h] == hi, axis=-1)
+            assert np.all(pos_lo[both] < pos_hi[both])    # and lo comes first
+            assert (sel_lo & ~sel_hi).any()               # the tie was actually decisive somewhere
+
+
+def test_routing_tables_are_a_stable_counting_sort():
+    rng = np.random.default_rng(5)
+    N, k, E = 37, 3, 6
+    idx = np.stack([rng.permutation(E)[:k] for _ in range(N)]).astype(np.int32)
+    perm, offsets, inv = orc.routing_tables(idx, E)
+    flat = idx.reshape(-1)
+    assert sorted(perm.tolist()) == list(range(N * k))
+    assert offsets[0] == 0 and offsets[-1] == N * k
+    assert np.array_equal(np.diff(offsets), np.bincount(flat, minlength=E))
+    keys = flat[perm]
+    assert np.all(np.diff(keys) >= 0)
+    for e in range(E):
+        seg = perm[offsets[e]:offsets[e + 1]]
+        assert np.all(flat[seg] == e) and np.all(np.diff(seg) > 0)
+    assert np.array_equal(inv[perm], np.arange(N * k))
+    # brute-force reference: scan experts in order, tokens in order
+    ref = [a for e in range(E) for a in range(N * k) if flat[a] == e]
+    assert perm.tolist() == ref
+    # an expert nobody chose has an empty segment
+    idx2 = np.zeros((5, 1), dtype=np.int32)
+    _, off2, _ = orc.routing_tables(idx2, 3)
+    assert off2.tolist() == [0, 5, 5, 5]
+
+
+def test_shared_selection_reuses_source_side():
+    cfg = dict(TINY, B=2, T=6)
+    t = _inputs(cfg)
+    f = _fwd(t, 2, W_D=None)
+    assert np.array_equal(f["idx_S"], f["idx_D"]) and np.array_equal(f["gate_S"], f["gate_D"])
+    g = _fwd(t, 2, W_D=t["W_S"])
+    assert np.array_equal(f["y"], g["y"])
+
+
+def test_bias_enters_the_logit():
+    cfg = dict(TINY, B=2, T=6, E=3, k=1, bias0=30.0)
+    t = _inputs(cfg)
+    f = _fwd(t, 1)
+    assert np.all(f["idx_S"] == 0) and np.all(f["idx_D"] == 0)
+    assert f["offsets_S"].tolist() == [[0, 12, 12, 12]] * 2
+
+
+# --------------------------------------------------------------------------------------
+# backward pins
+# --------------------------------------------------------------------------------------
+GRADS = ("dx", "dW_Q", "dW_K", "dW_V", "dW_O", "dW_S", "dW_D", "db_S", "db_D")
+NAMES = ("x", "W_Q", "W_K", "W_V", "W_O", "W_S", "W_D", "b_S", "b_D")
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("shared", [False, True])
+def test_backward_matches_autograd_of_dense_masked_layer(causal, shared):
+    cfg = dict(TINY, B=2, T=7, d_model=6, nheads=2, d_head=4, E=4, k=2, bias0=0.25)
+    t = make_inputs(cfg, seed=21, shared_router=shared)
+    f = _fwd(t, 2, causal)
+    g = _bwd(t, f)
+    y, leaves = torch_dense_masked(t, f["idx_S"], f["idx_D"], causal, shared)
+    assert np.allclose(y.detach().numpy(), f["y"], rtol=0, atol=1e-12)
+    (y * torch.tensor(t["dy"].astype(np.float64))).sum().backward()
+    for gn, n in zip(GRADS, NAMES):
+        if leaves[n] is None:
+            assert g[gn] is None
+            continue
+        ref = leaves[n].grad.numpy()
+        assert np.max(np.abs(g[gn] - ref)) <= 1e-11 * max(1.0, np.max(np.abs(ref))), gn
+
+
+def test_backward_matches_central_differences():
+    cfg = dict(TINY, B=1, T=5, d_model=5, nheads=2, d_head=3, E=3, k=2)
+    t = {n: (None if a is None else a.astype(np.float64)) for n, a in _inputs(cfg, seed=4).items()}
+    t["b_S"], t["b_D"] = np.zeros(6), np.zeros(6)
+    f = _fwd(t, 2)
+    assert min(f["margin_S"].min(), f["margin_D"].min()) > 1e-3   # no selection flips under the probe
+    g = _bwd(t, f)
+    eps = 1e-6
+    rng = np.random.default_rng(0)
+    for gn, n in zip(GRADS, NAMES):
+        a = t[n]
+        for _ in range(6):
+            pos = tuple(rng.integers(0, s) for s in a.shape)
+            vals = []
+            for sgn in (+1, -1):
+                a2 = a.copy()
+                a2[pos] += sgn * eps
+                vals.append(float(np.sum(_fwd(t, 2, **{n: a2})["y"] * t["dy"])))
+            fd = (vals[0] - vals[1]) / (2 * eps)
+            assert abs(fd - g[gn][pos]) < 1e-6 * max(1.0, abs(fd)), (gn, pos, fd, g[gn][pos])
+
+
+def test_unselected_expert_gets_zero_gradient():
+    cfg = dict(TINY, B=2, T=6, E=4, k=2)
+    t = _inputs(cfg)
+    b = np.zeros(8, dtype=np.float32)
+    b[3::4] = -50.0                       # expert 3 of every head is never picked
+    t["b_S"], t["b_D"] = b, b.copy()
+    f = _fwd(t, 2)
+    assert not (f["idx_S"] == 3).any() and not (f["idx_D"] == 3).any()
+    g = _bwd(t, f)
+    assert np.all(g["dW_V"][:, 3] == 0) and np.all(g["dW_O"][:, 3] == 0)
+    assert np.all(g["dW_S"][:, 3::4] == 0) and np.all(g["db_D"][3::4] == 0)
+    assert np.any(g["dW_V"][:, 0] != 0)
+
+
+def test_dense_mode_gradients_match_textbook_autograd():
+    cfg = dict(TINY, B=2, T=6, d_model=8, nheads=2, d_head=4, E=1, k=1)
+    t = _inputs(cfg)
+    f = _fwd(t, 1, W_S=None, W_D=None)
+    g = _bwd(t, f, W_S=None, W_D=None)
+    X = {n: torch.tensor(t[n].astype(np.float64), requires_grad=True) for n in ("x", "W_Q", "W_K", "W_V", "W_O")}
+    heads = []
+    for h in range(2):
+        Q, K, V = X["x"] @ X["W_Q"][h], X["x"] @ X["W_K"][h], X["x"] @ X["W_V"][h, 0]
+        L = Q @ K.transpose(-1, -2) / 2.0 + torch.triu(torch.full((6, 6), float("-inf"), dtype=torch.float64), 1)
+        heads.append(torch.softmax(L, -1) @ V)
+    y = torch.cat(heads, -1) @ torch.cat([X["W_O"][0, 0], X["W_O"][1, 0]], 0)
+    assert np.allclose(y.detach().numpy(), f["y"], rtol=0, atol=1e-13)
+    (y * torch.tensor(t["dy"].astype(np.float64))).sum().backward()
+    for gn, n in (("dx", "x"), ("dW_Q", "W_Q"), ("dW_K", "W_K"), ("dW_V", "W_V"), ("dW_O", "W_O")):
+        assert np.allclose(g[gn], X[n].grad.numpy(), rtol=0, atol=1e-12), gn
+    assert g["dW_S"] is None and g["db_D"] is None
+
+
+# --------------------------------------------------------------------------------------
+# the input generator (no method arithmetic, but both sides depend on it)
+# --------------------------------------------------------------------------------------
+def test_bf16_rounding_is_nearest_even():
+    a = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -7, 1.0 + 3 * 2 ** -8, -0.3, 3.0e38], dtype=np.float32)
+    r = round_to_bf16(a)
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.0 + 2 ** -7 and r[3] == 1.0 + 2 ** -6
+    assert r.tolist() == torch.tensor(a).to(torch.bfloat16).to(torch.float32).numpy().tolist()
+
+
+def test_inputs_are_seeded_and_scaled():
+    from paper_2312_07987_amd.inputs import config
+    c = config("c1")
+    c.update(B=2, T=32)
+    a, b = make_inputs(c), make_inputs(c)
+    assert all((a[n] is None and b[n] is None) or np.array_equal(a[n], b[n]) for n in a)
+    assert np.array_equal(a["W_V"], round_to_bf16(a["W_V"]))
+    assert abs(a["W_V"].std() * math.sqrt(412) - 1) < 0.02 and abs(a["W_O"].std() * math.sqrt(76) - 1) < 0.02
