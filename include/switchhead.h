@@ -1,0 +1,168 @@
+/*
+ * switchhead.h - C ABI of the SwitchHead attention layer for AMD MI355X (gfx950).
+ *
+ * The layer is the one defined in arXiv 2312.07987, Sec. 2.2 ("From Dense to SwitchHead
+ * Attention Layer"): per head h a source-side and a destination-side sigmoid router pick
+ * k of E experts per token; queries and keys are dense per head; the value projection and
+ * the output projection are gate-weighted sums over the selected experts; one softmax
+ * attention matrix is computed per head (Sec. 2.1, first equation).
+ *
+ * Conventions shared by every entry point
+ *   - every tensor pointer is a DEVICE pointer to row-major, contiguous memory owned by
+ *     the caller; the library allocates no device memory and frees none;
+ *   - `workspace` is caller-owned device memory of at least
+ *     switchhead_workspace_bytes(shape) bytes, 256-byte aligned; forward fills it,
+ *     backward and get_routing read what forward left there (same shape, untouched);
+ *   - calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without synchronising;
+ *   - arguments are checked on the host before anything is launched; a failed check
+ *     returns an error code, launches nothing and leaves every buffer untouched;
+ *     switchhead_last_error() then gives a description (thread-local, static storage);
+ *   - storage type of x, weights, y, dy, dx is shape->dtype (fp32 or bf16); arithmetic
+ *     accumulates in fp32; router logits are evaluated in fp64 (see below); weight and
+ *     bias gradients are always fp32;
+ *   - two calls that share a workspace must not overlap in time.
+ */
+#ifndef SWITCHHEAD_H
+#define SWITCHHEAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SH_OK = 0,
+  SH_ERR_INVALID_ARG = 1,         /* null required pointer, dimension < 1, k > E, ...      */
+  SH_ERR_UNSUPPORTED = 2,         /* a limit of the kernels: E > 64, k > 8, d_head > 256   */
+  SH_ERR_WORKSPACE_TOO_SMALL = 3,
+  SH_ERR_HIP = 4                  /* a HIP runtime call (launch, copy) reported an error   */
+} sh_status;
+
+typedef enum { SH_F32 = 0, SH_BF16 = 1 } sh_dtype;
+
+/* Problem shape, in the paper's notation (Sec. 2.1-2.2): T sequence length, d_model,
+ * nheads = number of attention matrices, d_head, E experts per head, k active experts. */
+typedef struct {
+  int32_t B;        /* sequences per call                                                 */
+  int32_t T;        /* tokens per sequence                                                */
+  int32_t d_model;
+  int32_t nheads;
+  int32_t d_head;
+  int32_t E;
+  int32_t k;
+  int32_t causal;   /* 1: key u visible to query t iff u <= t; 0: full attention (the
+                       paper's ListOps analysis, Sec. 4, uses the unmasked form)          */
+  int32_t dtype;    /* sh_dtype                                                           */
+} sh_shape;
+
+/* Bytes of workspace a forward (+ backward) call of this shape needs; 0 if the shape is
+ * invalid or unsupported (switchhead_last_error() says why).  Host-only, no GPU needed.  */
+size_t switchhead_workspace_bytes(const sh_shape* shape);
+
+/*
+ * Forward pass: Sec. 2.2, the equations for s_S, E_S, s_D, E_D, V^h and y.
+ *
+ *   x    [B, T, d_model]                     input
+ *   W_Q  [nheads, d_model, d_head]           dense query projection per head
+ *   W_K  [nheads, d_model, d_head]           dense key projection per head
+ *   W_V  [nheads, E, d_model, d_head]        value experts
+ *   W_O  [nheads, E, d_head, d_model]        output experts
+ *   W_S  [d_model, nheads*E]                 source-side router, column h*E+e.
+ *                                            NULL = dense multi-head attention (needs
+ *                                            E == 1, k == 1; every gate is 1; Sec. 2.1)
+ *   W_D  [d_model, nheads*E]                 destination-side router; NULL = shared
+ *                                            selection, the destination side reuses the
+ *                                            source side's choice and gates (Sec. 3.5)
+ *   b_S, b_D  fp32 [nheads*E] or NULL        logit bias added after the sum (not in the
+ *                                            paper; used to skew the routing on purpose)
+ *   y    [B, T, d_model]                     output, overwritten
+ *
+ * Selection: logits z = x W (+ b) are evaluated in fp64 with the sum taken over
+ * i = 0..d_model-1 in that order; the k largest logits win, equal logits -> lower expert
+ * index; slots are ordered by descending logit; gate = sigmoid(z) stored as fp32; gates
+ * are not renormalised.  Per (side, head) the N*k assignments a = n*k + j (n = b*T + t)
+ * are stably sorted by expert into `perm`, with `offsets[e]` = first position of expert e.
+ */
+sh_status switchhead_forward(const sh_shape* shape,
+                             const void* x, const void* W_Q, const void* W_K,
+                             const void* W_V, const void* W_O,
+                             const void* W_S, const void* W_D,
+                             const float* b_S, const float* b_D,
+                             void* y,
+                             void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+/*
+ * Backward pass: the chain rule through the six steps of the forward pass (the paper
+ * trains with automatic differentiation and prints no backward equations; App. A.2 only
+ * notes that all intermediate results are stored).  The top-k choice is piecewise
+ * constant: only the selected gates carry gradient, through sigmoid' = g (1 - g).
+ *
+ *   inputs   the same x, W_* (and shape) that were given to forward; dy [B, T, d_model];
+ *            `workspace` exactly as forward left it
+ *   outputs  dx [B, T, d_model] in shape->dtype; dW_Q, dW_K, dW_V, dW_O, dW_S, dW_D fp32
+ *            with the shapes of the corresponding weights; db_S, db_D fp32 [nheads*E].
+ *            All are overwritten; an expert no token chose gets zeros.
+ *            dW_S, dW_D, db_S, db_D may be NULL when not wanted; dW_D/db_D are ignored
+ *            with shared selection (dW_S then holds the sum of both sides) and all four
+ *            are ignored in dense mode.
+ * Weight gradients are accumulated with fp32 atomic adds over token chunks: their last
+ * bits may differ from run to run.
+ */
+sh_status switchhead_backward(const sh_shape* shape,
+                              const void* x, const void* W_Q, const void* W_K,
+                              const void* W_V, const void* W_O,
+                              const void* W_S, const void* W_D,
+                              const void* dy,
+                              void* workspace, size_t workspace_bytes,
+                              void* dx,
+                              float* dW_Q, float* dW_K, float* dW_V, float* dW_O,
+                              float* dW_S, float* dW_D, float* db_S, float* db_D,
+                              void* hip_stream);
+
+/*
+ * Copies the routing artefacts of the last forward call out of `workspace`
+ * (device-to-device, asynchronous on `hip_stream`); any destination may be NULL.
+ *   topk_idx        int32 [2, nheads, N, k]      side 0 = source, 1 = destination
+ *   gate            fp32  [2, nheads, N, k]      sigmoid of the selected logits
+ *   perm            int32 [2, nheads, N*k]       assignment ids sorted by expert (stable)
+ *   expert_offsets  int32 [2, nheads, E+1]       exclusive scan of per-expert counts
+ * With shared selection (or dense mode) side 1 repeats side 0.  (Sec. 2.2 defines the
+ * sets E_S, E_D and scores; Sec. 3.5 names the sorting step that `perm` is the result of.)
+ */
+sh_status switchhead_get_routing(const sh_shape* shape,
+                                 const void* workspace, size_t workspace_bytes,
+                                 int32_t* topk_idx, float* gate,
+                                 int32_t* perm, int32_t* expert_offsets,
+                                 void* hip_stream);
+
+/*
+ * Copies intermediates of the last forward call out of `workspace`, converted to fp32
+ * (device-to-device, asynchronous); any destination may be NULL.  For tests and debugging.
+ *   Q, K, V, ctx  fp32 [N, nheads, d_head]   queries, keys, mixed values V^h (Sec. 2.2),
+ *                                            attention read-out A^h V^h
+ *   lse           fp32 [B, nheads, T]        natural-log sum of exp of the scaled logits
+ */
+sh_status switchhead_get_intermediates(const sh_shape* shape,
+                                       const void* workspace, size_t workspace_bytes,
+                                       float* Q, float* K, float* V, float* ctx, float* lse,
+                                       void* hip_stream);
+
+/* Description of the last error on this thread ("" if none). Never NULL. */
+const char* switchhead_last_error(void);
+
+/* Selects the kernel family for later calls on any thread: 0 = automatic (MFMA kernels
+ * for bf16 shapes they support, plain fp32 kernels otherwise), 1 = always the plain fp32
+ * kernels.  Returns the previous value.  Used by tests to cross-check both families.     */
+int32_t switchhead_set_kernel_family(int32_t family);
+
+/* Library version, "major.minor". */
+const char* switchhead_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWITCHHEAD_H */

@@ -1,0 +1,191 @@
+// Internal declarations shared by the HIP translation units of libswitchhead.
+// Nothing here is part of the C ABI (that is include/switchhead.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sh {
+
+// ----------------------------------------------------------------------------------------
+// storage types
+// ----------------------------------------------------------------------------------------
+struct bf16_t {
+  unsigned short v;
+};
+
+__device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ unsigned short f32_to_bf16(float f) {
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+
+__device__ __forceinline__ float ld(const float* p, long i) { return p[i]; }
+__device__ __forceinline__ float ld(const bf16_t* p, long i) { return bf16_to_f32(p[i].v); }
+__device__ __forceinline__ void st(float* p, long i, float v) { p[i] = v; }
+__device__ __forceinline__ void st(bf16_t* p, long i, float v) { p[i].v = f32_to_bf16(v); }
+
+// ----------------------------------------------------------------------------------------
+// Grouped row GEMM:   C[crow, n] (op)= scale * sum_k A[arow, k] * B_g[k, n]
+//
+// Rows come either from an expert-sorted permutation (perm != NULL: head h owns positions
+// [h*M, (h+1)*M) of perm; expert e of head h owns positions offsets[h*(E+1)+e] ..
+// offsets[h*(E+1)+e+1]; a position holds an assignment id a = token*k + slot) or from the
+// identity (perm == NULL: every head covers rows a = 0..M-1, E must be 1).
+//   arow = a / a_div,  crow = a / c_div,  scale = gate ? gate[h*gate_hstride + a] : 1
+//   A[arow*lda + h*a_hoff + k],  B[h*b_hstride + e*b_estride + k*sbk + n*sbn],
+//   C[crow*ldc + h*c_hoff + n]
+// ----------------------------------------------------------------------------------------
+enum { STORE_T = 0, STORE_F32 = 1, ATOMIC_F32 = 2 };
+
+struct RowGemmArgs {
+  const int* perm;
+  const int* offsets;
+  int heads, E, M;
+  int a_div, c_div;
+  const void* A;
+  long lda, a_hoff;
+  const void* B;
+  long b_hstride, b_estride;
+  int sbk, sbn;
+  void* C;
+  long ldc, c_hoff;
+  const float* gate;
+  long gate_hstride;
+  int K, Nc;
+  int mode;
+};
+
+// ----------------------------------------------------------------------------------------
+// Grouped weight-gradient GEMM (reduction over the rows of a group):
+//   dW_g[i, j] += sum_{rows a of group g} scale * A[arow, i] * Bm[brow, j]
+//   A[arow*lda + h*a_hoff + i] (i < Ka),  Bm[brow*ldb + h*b_hoff + j] (j < Kb),
+//   dW[h*w_hstride + e*w_estride + i*swa + j]   fp32, atomic add (zeroed by the caller).
+// ----------------------------------------------------------------------------------------
+struct WgradArgs {
+  const int* perm;
+  const int* offsets;
+  int heads, E, M;
+  int a_div, b_div;
+  const void* A;
+  long lda, a_hoff;
+  int Ka;
+  const void* Bm;
+  long ldb, b_hoff;
+  int Kb;
+  float* dW;
+  long w_hstride, w_estride;
+  int swa;
+  const float* gate;
+  long gate_hstride;
+  int chunk;  // rows reduced by one block
+};
+
+// Finds the tile `tile` (of `bm` rows) among the E groups of one head.  Returns false when
+// `tile` lies beyond the last tile.  off points at the head's E+1 offsets.
+__device__ __forceinline__ bool find_tile(const int* off, int E, int bm, int tile, int& e, int& row0, int& rows) {
+  for (e = 0; e < E; ++e) {
+    int beg = off[e], end = off[e + 1];
+    int nt = (end - beg + bm - 1) / bm;
+    if (tile < nt) {
+      row0 = beg + tile * bm;
+      rows = end - row0 < bm ? end - row0 : bm;
+      return true;
+    }
+    tile -= nt;
+  }
+  return false;
+}
+
+// ----------------------------------------------------------------------------------------
+// Attention
+//   Q, K, V, O: [N, H, dh] with N = B*T (row stride H*dh); lse: [B, H, T] fp32.
+// ----------------------------------------------------------------------------------------
+struct AttnArgs {
+  const void *Q, *K, *V;
+  void* O;
+  float* lse;
+  int B, T, H, dh, causal;
+  float scale;  // 1/sqrt(dh)
+};
+
+struct AttnBwdArgs {
+  const void *Q, *K, *V, *dO;
+  const float *lse, *delta;  // delta[N, H] = <dO, O>
+  void *dQ, *dK, *dV;
+  int B, T, H, dh, causal;
+  float scale;
+};
+
+// ----------------------------------------------------------------------------------------
+// launchers (defined in routing.hip, simt.hip, mfma_*.hip); all enqueue on `s`
+// ----------------------------------------------------------------------------------------
+struct RouterArgs {
+  const void* x;          // [N, dm]
+  const void* W[2];       // per side [dm, HE]; W[1] == NULL -> one side only
+  const float* b[2];      // per side [HE] or NULL
+  double* Z;              // [sides, N, HE] fp64 logits (scratch)
+  int* idx;               // [sides, H, N, k]
+  float* gate;            // [sides, H, N, k]
+  int* perm;              // [sides, H, N*k]
+  int* offsets;           // [sides, H, E+1]
+  int* blockcnt;          // [sides*H, nblk, E] scratch
+  int N, dm, H, E, k, sides;
+  int bf16;
+};
+void launch_router(const RouterArgs& a, hipStream_t s);
+void launch_dense_routing(int* idx, float* gate, int* perm, int* offsets, int N, int H, hipStream_t s);
+int router_blocks(int N);  // token blocks used by the histogram/scatter kernels
+
+void launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
+void launch_cast_from_f32(const float* src, void* dst, size_t n, int bf16, hipStream_t s);
+void launch_cast_to_f32(const void* src, float* dst, size_t n, int bf16, hipStream_t s);
+
+// out[n,h,:] = sum_j gate[h][n*k+j] * slots[h][n*k+j][:]   (slots fp32 [H, N*k, dh])
+// dots[h][n*k+j] = <other[n,h,:], slots[h][n*k+j][:]>        (if dots != NULL)
+// delta[n,h]     = <out[n,h,:], other[n,h,:]>                (if delta != NULL)
+// out may be NULL (dots only).  out/other have storage type T, layout [N, H, dh].
+struct SlotArgs {
+  const float* slots;
+  const float* gate;
+  const void* other;
+  void* out;
+  float* dots;
+  float* delta;
+  int N, H, k, dh;
+};
+void launch_slot_combine(const SlotArgs& a, int bf16, hipStream_t s);
+
+// dz[n, side*HE + h*E + e] = dg*g*(1-g) at selected entries, 0 elsewhere.  With `shared`
+// there is one side and dg = dgate[0] + dgate[1].  dz has storage type T, [N, sides*HE];
+// the bias gradients are summed from the unrounded fp32 values.
+struct RouterBwdArgs {
+  const int* idx;       // [2 or 1, H, N, k]
+  const float* gate;    // same
+  const float* dgate;   // [2, H, N, k]
+  void* dz;
+  float* db[2];         // per side [HE] or NULL, atomic add (zeroed by caller)
+  int N, H, E, k, sides, shared;
+};
+void launch_router_bwd(const RouterBwdArgs& a, int bf16, hipStream_t s);
+
+void launch_simt_row_gemm(const RowGemmArgs& a, int bf16, hipStream_t s);
+void launch_simt_wgrad(const WgradArgs& a, int bf16, hipStream_t s);
+void launch_simt_attn_fwd(const AttnArgs& a, int bf16, hipStream_t s);
+void launch_simt_attn_bwd(const AttnBwdArgs& a, int bf16, hipStream_t s);
+
+// MFMA family (bf16 storage only).  *_supported() say whether a launch can be served.
+bool mfma_row_gemm_supported(const RowGemmArgs& a);
+void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s);
+bool mfma_wgrad_supported(const WgradArgs& a);
+void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s);
+bool mfma_attn_supported(int T, int dh);
+void launch_mfma_attn_fwd(const AttnArgs& a, hipStream_t s);
+void launch_mfma_attn_bwd(const AttnBwdArgs& a, hipStream_t s);
+
+}  // namespace sh

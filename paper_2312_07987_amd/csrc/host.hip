@@ -1,0 +1,632 @@
+// C ABI of libswitchhead (declared in include/switchhead.h): argument checks, workspace
+// carving and the launch sequence of the forward and backward passes of the SwitchHead
+// layer (arXiv 2312.07987, Sec. 2.2).  Nothing here allocates or synchronises.
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/switchhead.h"
+#include "common.h"
+
+using namespace sh;
+
+namespace {
+
+thread_local char g_err[512] = "";
+std::atomic<int> g_family{0};
+
+sh_status fail(sh_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Layout {
+  size_t total = 0;
+  size_t idx, gate, perm, offsets, Q, K, V, ctx, lse, pV;          // saved by forward
+  size_t Z, blockcnt, acc32;                                       // forward scratch
+  size_t u, dctx, dQ, dK, dV, delta, dgate, dz;                    // backward scratch
+};
+
+sh_status check_shape(const sh_shape* s) {
+  if (!s) return fail(SH_ERR_INVALID_ARG, "shape is NULL");
+  if (s->B < 1 || s->T < 1 || s->d_model < 1 || s->nheads < 1 || s->d_head < 1 || s->E < 1 || s->k < 1)
+    return fail(SH_ERR_INVALID_ARG, "every dimension must be >= 1 (B=%d T=%d d_model=%d nheads=%d d_head=%d E=%d k=%d)",
+                s->B, s->T, s->d_model, s->nheads, s->d_head, s->E, s->k);
+  if (s->k > s->E) return fail(SH_ERR_INVALID_ARG, "k=%d exceeds E=%d", s->k, s->E);
+  if (s->dtype != SH_F32 && s->dtype != SH_BF16) return fail(SH_ERR_INVALID_ARG, "unknown dtype %d", s->dtype);
+  if (s->causal != 0 && s->causal != 1) return fail(SH_ERR_INVALID_ARG, "causal must be 0 or 1");
+  if (s->E > 64) return fail(SH_ERR_UNSUPPORTED, "E=%d exceeds the limit of 64", s->E);
+  if (s->k > 8) return fail(SH_ERR_UNSUPPORTED, "k=%d exceeds the limit of 8", s->k);
+  if (s->d_head > 256) return fail(SH_ERR_UNSUPPORTED, "d_head=%d exceeds the limit of 256", s->d_head);
+  if (s->B > 65535 || s->nheads > 4096) return fail(SH_ERR_UNSUPPORTED, "B > 65535 or nheads > 4096");
+  const long long N = (long long)s->B * s->T;
+  if (N * s->k >= (1ll << 31) || N * s->d_model >= (1ll << 40) || N * s->nheads * s->d_head >= (1ll << 40))
+    return fail(SH_ERR_UNSUPPORTED, "problem too large (B*T*k must stay below 2^31)");
+  return SH_OK;
+}
+
+Layout make_layout(const sh_shape* s) {
+  Layout L;
+  const size_t N = (size_t)s->B * s->T, H = s->nheads, E = s->E, k = s->k, dh = s->d_head, dm = s->d_model;
+  const size_t esz = s->dtype == SH_BF16 ? 2 : 4;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += align_up(bytes);
+    return o;
+  };
+  L.idx = take(2 * H * N * k * 4);
+  L.gate = take(2 * H * N * k * 4);
+  L.perm = take(2 * H * N * k * 4);
+  L.offsets = take(2 * H * (E + 1) * 4);
+  L.Q = take(N * H * dh * esz);
+  L.K = take(N * H * dh * esz);
+  L.V = take(N * H * dh * esz);
+  L.ctx = take(N * H * dh * esz);
+  L.lse = take(N * H * 4);
+  L.pV = take(H * N * k * dh * 4);
+  L.Z = take(2 * N * H * E * 8);
+  L.blockcnt = take(2 * H * (size_t)router_blocks((int)N) * E * 4);
+  L.acc32 = take(N * dm * 4);
+  L.u = take(H * N * k * dh * 4);
+  L.dctx = take(N * H * dh * esz);
+  L.dQ = take(N * H * dh * esz);
+  L.dK = take(N * H * dh * esz);
+  L.dV = take(N * H * dh * esz);
+  L.delta = take(N * H * 4);
+  L.dgate = take(2 * H * N * k * 4);
+  L.dz = take(N * 2 * H * E * esz);
+  L.total = off;
+  return L;
+}
+
+struct Ctx {
+  const sh_shape* s;
+  Layout L;
+  char* ws;
+  hipStream_t st;
+  int N, H, E, k, dh, dm, bf16;
+  bool dense, shared;
+  template <typename T>
+  T* p(size_t off) const {
+    return (T*)(ws + off);
+  }
+  // per-side routing tables (side 0 = source, 1 = destination)
+  int* idx(int side) const { return p<int>(L.idx) + (size_t)side * H * N * k; }
+  float* gate(int side) const { return p<float>(L.gate) + (size_t)side * H * N * k; }
+  int* perm(int side) const { return p<int>(L.perm) + (size_t)side * H * N * k; }
+  int* offsets(int side) const { return p<int>(L.offsets) + (size_t)side * H * (E + 1); }
+};
+
+sh_status make_ctx(Ctx& c, const sh_shape* s, const void* W_S, const void* W_D, const void* ws, size_t ws_bytes,
+                   void* stream) {
+  sh_status r = check_shape(s);
+  if (r != SH_OK) return r;
+  c.s = s;
+  c.L = make_layout(s);
+  if (!ws) return fail(SH_ERR_INVALID_ARG, "workspace is NULL");
+  if (((uintptr_t)ws & 255) != 0) return fail(SH_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  if (ws_bytes < c.L.total)
+    return fail(SH_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", ws_bytes, c.L.total);
+  c.ws = (char*)ws;
+  c.st = (hipStream_t)stream;
+  c.N = s->B * s->T;
+  c.H = s->nheads;
+  c.E = s->E;
+  c.k = s->k;
+  c.dh = s->d_head;
+  c.dm = s->d_model;
+  c.bf16 = s->dtype == SH_BF16;
+  c.dense = W_S == nullptr;
+  c.shared = W_S != nullptr && W_D == nullptr;
+  if (c.dense && (s->E != 1 || s->k != 1))
+    return fail(SH_ERR_INVALID_ARG, "W_S is NULL (dense attention) but E=%d, k=%d; both must be 1", s->E, s->k);
+  return SH_OK;
+}
+
+sh_status check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(SH_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return SH_OK;
+}
+
+bool use_mfma(const Ctx& c) { return c.bf16 && g_family.load() == 0; }
+
+void row_gemm(const Ctx& c, const RowGemmArgs& a) {
+  if (use_mfma(c) && mfma_row_gemm_supported(a))
+    launch_mfma_row_gemm(a, c.st);
+  else
+    launch_simt_row_gemm(a, c.bf16, c.st);
+}
+
+void wgrad(const Ctx& c, const WgradArgs& a) {
+  if (use_mfma(c) && mfma_wgrad_supported(a))
+    launch_mfma_wgrad(a, c.st);
+  else
+    launch_simt_wgrad(a, c.bf16, c.st);
+}
+
+// rows taken through the expert-sorted permutation of one side
+RowGemmArgs perm_rows(const Ctx& c, int side) {
+  RowGemmArgs a{};
+  a.perm = c.perm(side);
+  a.offsets = c.offsets(side);
+  a.heads = c.H;
+  a.E = c.E;
+  a.M = c.N * c.k;
+  a.a_div = c.k;
+  a.c_div = 1;
+  return a;
+}
+
+RowGemmArgs identity_rows(const Ctx& c, int heads) {
+  RowGemmArgs a{};
+  a.heads = heads;
+  a.E = 1;
+  a.M = c.N;
+  a.a_div = 1;
+  a.c_div = 1;
+  return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* switchhead_last_error(void) { return g_err; }
+const char* switchhead_version(void) { return "0.1"; }
+
+int32_t switchhead_set_kernel_family(int32_t family) { return g_family.exchange(family ? 1 : 0); }
+
+size_t switchhead_workspace_bytes(const sh_shape* shape) {
+  if (check_shape(shape) != SH_OK) return 0;
+  return make_layout(shape).total;
+}
+
+sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W_Q, const void* W_K, const void* W_V,
+                             const void* W_O, const void* W_S, const void* W_D, const float* b_S, const float* b_D,
+                             void* y, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Ctx c;
+  sh_status r = make_ctx(c, shape, W_S, W_D, workspace, workspace_bytes, hip_stream);
+  if (r != SH_OK) return r;
+  if (!x || !W_Q || !W_K || !W_V || !W_O || !y) return fail(SH_ERR_INVALID_ARG, "x, W_Q, W_K, W_V, W_O, y must not be NULL");
+  if (c.dense && W_D) return fail(SH_ERR_INVALID_ARG, "W_D given without W_S");
+  const int N = c.N, H = c.H, E = c.E, k = c.k, dh = c.dh, dm = c.dm;
+  const long hd = (long)H * dh;
+
+  // step 1: routers, top-k, expert-sorted permutation
+  if (c.dense) {
+    launch_dense_routing(c.idx(0), c.gate(0), c.perm(0), c.offsets(0), N, H, c.st);
+  } else {
+    RouterArgs ra{};
+    ra.x = x;
+    ra.W[0] = W_S;
+    ra.W[1] = W_D;
+    ra.b[0] = b_S;
+    ra.b[1] = b_D;
+    ra.Z = c.p<double>(c.L.Z);
+    ra.idx = c.idx(0);
+    ra.gate = c.gate(0);
+    ra.perm = c.perm(0);
+    ra.offsets = c.offsets(0);
+    ra.blockcnt = c.p<int>(c.L.blockcnt);
+    ra.N = N;
+    ra.dm = dm;
+    ra.H = H;
+    ra.E = E;
+    ra.k = k;
+    ra.sides = c.shared ? 1 : 2;
+    ra.bf16 = c.bf16;
+    launch_router(ra, c.st);
+  }
+  if (c.dense || c.shared) {
+    // one selection serves both sides: the destination tables repeat the source tables
+    const size_t n1 = (size_t)H * N * k * 4;
+    hipMemcpyAsync(c.idx(1), c.idx(0), n1, hipMemcpyDeviceToDevice, c.st);
+    hipMemcpyAsync(c.gate(1), c.gate(0), n1, hipMemcpyDeviceToDevice, c.st);
+    hipMemcpyAsync(c.perm(1), c.perm(0), n1, hipMemcpyDeviceToDevice, c.st);
+    hipMemcpyAsync(c.offsets(1), c.offsets(0), (size_t)H * (E + 1) * 4, hipMemcpyDeviceToDevice, c.st);
+  }
+
+  // step 2: dense queries and keys
+  for (int which = 0; which < 2; ++which) {
+    RowGemmArgs a = identity_rows(c, H);
+    a.A = x;
+    a.lda = dm;
+    a.a_hoff = 0;
+    a.B = which ? W_K : W_Q;
+    a.b_hstride = (long)dm * dh;
+    a.sbk = dh;
+    a.sbn = 1;
+    a.C = c.p<void>(which ? c.L.K : c.L.Q);
+    a.ldc = hd;
+    a.c_hoff = dh;
+    a.K = dm;
+    a.Nc = dh;
+    a.mode = STORE_T;
+    row_gemm(c, a);
+  }
+
+  // step 3: value experts, unscaled per-slot results, then the gate-weighted sum over slots
+  {
+    RowGemmArgs a = perm_rows(c, 0);
+    a.A = x;
+    a.lda = dm;
+    a.B = W_V;
+    a.b_hstride = (long)E * dm * dh;
+    a.b_estride = (long)dm * dh;
+    a.sbk = dh;
+    a.sbn = 1;
+    a.C = c.p<void>(c.L.pV);
+    a.ldc = dh;
+    a.c_hoff = (long)N * k * dh;
+    a.K = dm;
+    a.Nc = dh;
+    a.mode = STORE_F32;
+    row_gemm(c, a);
+    SlotArgs sa{};
+    sa.slots = c.p<float>(c.L.pV);
+    sa.gate = c.gate(0);
+    sa.out = c.p<void>(c.L.V);
+    sa.N = N;
+    sa.H = H;
+    sa.k = k;
+    sa.dh = dh;
+    launch_slot_combine(sa, c.bf16, c.st);
+  }
+
+  // step 4: one attention matrix per head
+  {
+    AttnArgs a{};
+    a.Q = c.p<void>(c.L.Q);
+    a.K = c.p<void>(c.L.K);
+    a.V = c.p<void>(c.L.V);
+    a.O = c.p<void>(c.L.ctx);
+    a.lse = c.p<float>(c.L.lse);
+    a.B = shape->B;
+    a.T = shape->T;
+    a.H = H;
+    a.dh = dh;
+    a.causal = shape->causal;
+    a.scale = 1.0f / sqrtf((float)dh);
+    if (use_mfma(c) && mfma_attn_supported(shape->T, dh))
+      launch_mfma_attn_fwd(a, c.st);
+    else
+      launch_simt_attn_fwd(a, c.bf16, c.st);
+  }
+
+  // step 5: output experts, gate-scaled, summed over heads and slots in fp32
+  {
+    float* acc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)y;
+    launch_fill_f32(acc, (size_t)N * dm, 0.f, c.st);
+    RowGemmArgs a = perm_rows(c, 1);
+    a.c_div = k;
+    a.A = c.p<void>(c.L.ctx);
+    a.lda = hd;
+    a.a_hoff = dh;
+    a.B = W_O;
+    a.b_hstride = (long)E * dh * dm;
+    a.b_estride = (long)dh * dm;
+    a.sbk = dm;
+    a.sbn = 1;
+    a.C = acc;
+    a.ldc = dm;
+    a.c_hoff = 0;
+    a.gate = c.gate(1);
+    a.gate_hstride = (long)N * k;
+    a.K = dh;
+    a.Nc = dm;
+    a.mode = ATOMIC_F32;
+    row_gemm(c, a);
+    if (c.bf16) launch_cast_from_f32(acc, y, (size_t)N * dm, 1, c.st);
+  }
+  return check_launch("switchhead_forward");
+}
+
+sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* W_Q, const void* W_K, const void* W_V,
+                              const void* W_O, const void* W_S, const void* W_D, const void* dy, void* workspace,
+                              size_t workspace_bytes, void* dx, float* dW_Q, float* dW_K, float* dW_V, float* dW_O,
+                              float* dW_S, float* dW_D, float* db_S, float* db_D, void* hip_stream) {
+  Ctx c;
+  sh_status r = make_ctx(c, shape, W_S, W_D, workspace, workspace_bytes, hip_stream);
+  if (r != SH_OK) return r;
+  if (!x || !W_Q || !W_K || !W_V || !W_O || !dy || !dx || !dW_Q || !dW_K || !dW_V || !dW_O)
+    return fail(SH_ERR_INVALID_ARG, "x, W_Q, W_K, W_V, W_O, dy, dx, dW_Q, dW_K, dW_V, dW_O must not be NULL");
+  const int N = c.N, H = c.H, E = c.E, k = c.k, dh = c.dh, dm = c.dm;
+  const long hd = (long)H * dh;
+  const int chunk = 1024;
+
+  launch_fill_f32(dW_Q, (size_t)H * dm * dh, 0.f, c.st);
+  launch_fill_f32(dW_K, (size_t)H * dm * dh, 0.f, c.st);
+  launch_fill_f32(dW_V, (size_t)H * E * dm * dh, 0.f, c.st);
+  launch_fill_f32(dW_O, (size_t)H * E * dh * dm, 0.f, c.st);
+
+  // output experts: u[h][a][:] = dy[n] W_O[h,e]^T (unscaled), then dctx, d(gate_D), delta
+  {
+    RowGemmArgs a = perm_rows(c, 1);
+    a.A = dy;
+    a.lda = dm;
+    a.B = W_O;
+    a.b_hstride = (long)E * dh * dm;
+    a.b_estride = (long)dh * dm;
+    a.sbk = 1;
+    a.sbn = dm;
+    a.C = c.p<void>(c.L.u);
+    a.ldc = dh;
+    a.c_hoff = (long)N * k * dh;
+    a.K = dm;
+    a.Nc = dh;
+    a.mode = STORE_F32;
+    row_gemm(c, a);
+    SlotArgs sa{};
+    sa.slots = c.p<float>(c.L.u);
+    sa.gate = c.gate(1);
+    sa.other = c.p<void>(c.L.ctx);
+    sa.out = c.p<void>(c.L.dctx);
+    sa.dots = c.p<float>(c.L.dgate) + (size_t)H * N * k;
+    sa.delta = c.p<float>(c.L.delta);
+    sa.N = N;
+    sa.H = H;
+    sa.k = k;
+    sa.dh = dh;
+    launch_slot_combine(sa, c.bf16, c.st);
+    WgradArgs w{};
+    w.perm = c.perm(1);
+    w.offsets = c.offsets(1);
+    w.heads = H;
+    w.E = E;
+    w.M = N * k;
+    w.a_div = k;
+    w.b_div = k;
+    w.A = c.p<void>(c.L.ctx);
+    w.lda = hd;
+    w.a_hoff = dh;
+    w.Ka = dh;
+    w.Bm = dy;
+    w.ldb = dm;
+    w.b_hoff = 0;
+    w.Kb = dm;
+    w.dW = dW_O;
+    w.w_hstride = (long)E * dh * dm;
+    w.w_estride = (long)dh * dm;
+    w.swa = dm;
+    w.gate = c.gate(1);
+    w.gate_hstride = (long)N * k;
+    w.chunk = chunk;
+    wgrad(c, w);
+  }
+
+  // attention
+  {
+    AttnBwdArgs a{};
+    a.Q = c.p<void>(c.L.Q);
+    a.K = c.p<void>(c.L.K);
+    a.V = c.p<void>(c.L.V);
+    a.dO = c.p<void>(c.L.dctx);
+    a.lse = c.p<float>(c.L.lse);
+    a.delta = c.p<float>(c.L.delta);
+    a.dQ = c.p<void>(c.L.dQ);
+    a.dK = c.p<void>(c.L.dK);
+    a.dV = c.p<void>(c.L.dV);
+    a.B = shape->B;
+    a.T = shape->T;
+    a.H = H;
+    a.dh = dh;
+    a.causal = shape->causal;
+    a.scale = 1.0f / sqrtf((float)dh);
+    if (use_mfma(c) && mfma_attn_supported(shape->T, dh))
+      launch_mfma_attn_bwd(a, c.st);
+    else
+      launch_simt_attn_bwd(a, c.bf16, c.st);
+  }
+
+  // value experts: d(gate_S), dW_V, dx
+  float* dxacc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)dx;
+  launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
+  {
+    SlotArgs sa{};
+    sa.slots = c.p<float>(c.L.pV);
+    sa.gate = c.gate(0);
+    sa.other = c.p<void>(c.L.dV);
+    sa.dots = c.p<float>(c.L.dgate);
+    sa.N = N;
+    sa.H = H;
+    sa.k = k;
+    sa.dh = dh;
+    launch_slot_combine(sa, c.bf16, c.st);
+    WgradArgs w{};
+    w.perm = c.perm(0);
+    w.offsets = c.offsets(0);
+    w.heads = H;
+    w.E = E;
+    w.M = N * k;
+    w.a_div = k;
+    w.b_div = k;
+    w.A = x;
+    w.lda = dm;
+    w.a_hoff = 0;
+    w.Ka = dm;
+    w.Bm = c.p<void>(c.L.dV);
+    w.ldb = hd;
+    w.b_hoff = dh;
+    w.Kb = dh;
+    w.dW = dW_V;
+    w.w_hstride = (long)E * dm * dh;
+    w.w_estride = (long)dm * dh;
+    w.swa = dh;
+    w.gate = c.gate(0);
+    w.gate_hstride = (long)N * k;
+    w.chunk = chunk;
+    wgrad(c, w);
+    RowGemmArgs a = perm_rows(c, 0);
+    a.c_div = k;
+    a.A = c.p<void>(c.L.dV);
+    a.lda = hd;
+    a.a_hoff = dh;
+    a.B = W_V;
+    a.b_hstride = (long)E * dm * dh;
+    a.b_estride = (long)dm * dh;
+    a.sbk = 1;
+    a.sbn = dh;
+    a.C = dxacc;
+    a.ldc = dm;
+    a.gate = c.gate(0);
+    a.gate_hstride = (long)N * k;
+    a.K = dh;
+    a.Nc = dm;
+    a.mode = ATOMIC_F32;
+    row_gemm(c, a);
+  }
+
+  // dense queries and keys
+  for (int which = 0; which < 2; ++which) {
+    const void* g = c.p<void>(which ? c.L.dK : c.L.dQ);
+    WgradArgs w{};
+    w.heads = H;
+    w.E = 1;
+    w.M = N;
+    w.a_div = 1;
+    w.b_div = 1;
+    w.A = x;
+    w.lda = dm;
+    w.a_hoff = 0;
+    w.Ka = dm;
+    w.Bm = g;
+    w.ldb = hd;
+    w.b_hoff = dh;
+    w.Kb = dh;
+    w.dW = which ? dW_K : dW_Q;
+    w.w_hstride = (long)dm * dh;
+    w.swa = dh;
+    w.chunk = chunk;
+    wgrad(c, w);
+    RowGemmArgs a = identity_rows(c, H);
+    a.A = g;
+    a.lda = hd;
+    a.a_hoff = dh;
+    a.B = which ? W_K : W_Q;
+    a.b_hstride = (long)dm * dh;
+    a.sbk = 1;
+    a.sbn = dh;
+    a.C = dxacc;
+    a.ldc = dm;
+    a.K = dh;
+    a.Nc = dm;
+    a.mode = ATOMIC_F32;
+    row_gemm(c, a);
+  }
+
+  // routers
+  if (!c.dense) {
+    const int sides = c.shared ? 1 : 2;
+    const int HE = H * E;
+    float* dWs[2] = {dW_S, c.shared ? nullptr : dW_D};
+    float* dbs[2] = {db_S, c.shared ? nullptr : db_D};
+    for (int sd = 0; sd < sides; ++sd) {
+      if (dWs[sd]) launch_fill_f32(dWs[sd], (size_t)dm * HE, 0.f, c.st);
+      if (dbs[sd]) launch_fill_f32(dbs[sd], (size_t)HE, 0.f, c.st);
+    }
+    RouterBwdArgs rb{};
+    rb.idx = c.idx(0);
+    rb.gate = c.gate(0);
+    rb.dgate = c.p<float>(c.L.dgate);
+    rb.dz = c.p<void>(c.L.dz);
+    rb.db[0] = dbs[0];
+    rb.db[1] = dbs[1];
+    rb.N = N;
+    rb.H = H;
+    rb.E = E;
+    rb.k = k;
+    rb.sides = sides;
+    rb.shared = c.shared;
+    launch_router_bwd(rb, c.bf16, c.st);
+    for (int sd = 0; sd < sides; ++sd) {
+      const void* dz = c.p<char>(c.L.dz) + (size_t)sd * HE * (c.bf16 ? 2 : 4);
+      if (dWs[sd]) {
+        WgradArgs w{};
+        w.heads = 1;
+        w.E = 1;
+        w.M = N;
+        w.a_div = 1;
+        w.b_div = 1;
+        w.A = x;
+        w.lda = dm;
+        w.Ka = dm;
+        w.Bm = dz;
+        w.ldb = (long)sides * HE;
+        w.Kb = HE;
+        w.dW = dWs[sd];
+        w.swa = HE;
+        w.chunk = chunk;
+        wgrad(c, w);
+      }
+      RowGemmArgs a = identity_rows(c, 1);
+      a.A = dz;
+      a.lda = (long)sides * HE;
+      a.B = sd ? W_D : W_S;
+      a.sbk = 1;
+      a.sbn = HE;
+      a.C = dxacc;
+      a.ldc = dm;
+      a.K = HE;
+      a.Nc = dm;
+      a.mode = ATOMIC_F32;
+      row_gemm(c, a);
+    }
+  }
+  if (c.bf16) launch_cast_from_f32(dxacc, dx, (size_t)N * dm, 1, c.st);
+  return check_launch("switchhead_backward");
+}
+
+sh_status switchhead_get_routing(const sh_shape* shape, const void* workspace, size_t workspace_bytes,
+                                 int32_t* topk_idx, float* gate, int32_t* perm, int32_t* expert_offsets,
+                                 void* hip_stream) {
+  sh_status r = check_shape(shape);
+  if (r != SH_OK) return r;
+  Layout L = make_layout(shape);
+  if (!workspace) return fail(SH_ERR_INVALID_ARG, "workspace is NULL");
+  if (workspace_bytes < L.total) return fail(SH_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+  const char* ws = (const char*)workspace;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t n1 = (size_t)2 * shape->nheads * shape->B * shape->T * shape->k;
+  hipError_t e = hipSuccess;
+  if (topk_idx) e = hipMemcpyAsync(topk_idx, ws + L.idx, n1 * 4, hipMemcpyDeviceToDevice, st);
+  if (e == hipSuccess && gate) e = hipMemcpyAsync(gate, ws + L.gate, n1 * 4, hipMemcpyDeviceToDevice, st);
+  if (e == hipSuccess && perm) e = hipMemcpyAsync(perm, ws + L.perm, n1 * 4, hipMemcpyDeviceToDevice, st);
+  if (e == hipSuccess && expert_offsets)
+    e = hipMemcpyAsync(expert_offsets, ws + L.offsets, (size_t)2 * shape->nheads * (shape->E + 1) * 4,
+                       hipMemcpyDeviceToDevice, st);
+  if (e != hipSuccess) return fail(SH_ERR_HIP, "switchhead_get_routing: %s", hipGetErrorString(e));
+  return SH_OK;
+}
+
+sh_status switchhead_get_intermediates(const sh_shape* shape, const void* workspace, size_t workspace_bytes, float* Q,
+                                       float* K, float* V, float* ctx, float* lse, void* hip_stream) {
+  sh_status r = check_shape(shape);
+  if (r != SH_OK) return r;
+  Layout L = make_layout(shape);
+  if (!workspace) return fail(SH_ERR_INVALID_ARG, "workspace is NULL");
+  if (workspace_bytes < L.total) return fail(SH_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+  const char* ws = (const char*)workspace;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t n = (size_t)shape->B * shape->T * shape->nheads * shape->d_head;
+  const int bf = shape->dtype == SH_BF16;
+  if (Q) launch_cast_to_f32(ws + L.Q, Q, n, bf, st);
+  if (K) launch_cast_to_f32(ws + L.K, K, n, bf, st);
+  if (V) launch_cast_to_f32(ws + L.V, V, n, bf, st);
+  if (ctx) launch_cast_to_f32(ws + L.ctx, ctx, n, bf, st);
+  if (lse) {
+    hipError_t e = hipMemcpyAsync(lse, ws + L.lse, (size_t)shape->B * shape->T * shape->nheads * 4,
+                                  hipMemcpyDeviceToDevice, st);
+    if (e != hipSuccess) return fail(SH_ERR_HIP, "switchhead_get_intermediates: %s", hipGetErrorString(e));
+  }
+  return check_launch("switchhead_get_intermediates");
+}
+
+}  // extern "C"

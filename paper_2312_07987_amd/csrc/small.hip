@@ -1,0 +1,160 @@
+// Small memory-bound kernels around the GEMMs: fills, casts, the gate-weighted sum over a
+// token's k expert slots (the weighted average of Sec. 2.2's V^h equation and its mirror
+// image in the backward pass) and the router's backward step.
+#include "common.h"
+
+namespace sh {
+
+__global__ void fill_f32_kernel(float* p, size_t n, float v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+
+template <typename T>
+__global__ void cast_from_f32_kernel(const float* __restrict__ src, T* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) st(dst, (long)i, src[i]);
+}
+
+template <typename T>
+__global__ void cast_to_f32_kernel(const T* __restrict__ src, float* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = ld(src, (long)i);
+}
+
+static unsigned grid_for(size_t n, int block) {
+  size_t g = (n + block - 1) / block;
+  return (unsigned)(g < 1 ? 1 : (g > 65536 ? 65536 : g));
+}
+
+void launch_fill_f32(float* p, size_t n, float v, hipStream_t s) {
+  if (n) fill_f32_kernel<<<grid_for(n, 256), 256, 0, s>>>(p, n, v);
+}
+
+void launch_cast_from_f32(const float* src, void* dst, size_t n, int bf16, hipStream_t s) {
+  if (!n) return;
+  if (bf16)
+    cast_from_f32_kernel<bf16_t><<<grid_for(n, 256), 256, 0, s>>>(src, (bf16_t*)dst, n);
+  else
+    cast_from_f32_kernel<float><<<grid_for(n, 256), 256, 0, s>>>(src, (float*)dst, n);
+}
+
+void launch_cast_to_f32(const void* src, float* dst, size_t n, int bf16, hipStream_t s) {
+  if (!n) return;
+  if (bf16)
+    cast_to_f32_kernel<bf16_t><<<grid_for(n, 256), 256, 0, s>>>((const bf16_t*)src, dst, n);
+  else
+    cast_to_f32_kernel<float><<<grid_for(n, 256), 256, 0, s>>>((const float*)src, dst, n);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// One wave per (token, head); lane handles elements lane, lane+64, ... of the d_head row.
+template <typename T>
+__global__ __launch_bounds__(256) void slot_combine_kernel(SlotArgs a) {
+  const int lane = threadIdx.x & 63;
+  const long pair = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (pair >= (long)a.N * a.H) return;
+  const int n = (int)(pair / a.H), h = (int)(pair % a.H);
+  const int dh = a.dh, k = a.k;
+  const T* other = (const T*)a.other;
+  T* out = (T*)a.out;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f}, oth[4] = {0.f, 0.f, 0.f, 0.f};
+  const long row = ((long)n * a.H + h) * dh;
+  if (other) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int d = lane + 64 * i;
+      if (d < dh) oth[i] = ld(other, row + d);
+    }
+  }
+  for (int j = 0; j < k; ++j) {
+    const long aid = (long)h * a.N * k + (long)n * k + j;
+    const float* sl = a.slots + aid * dh;
+    const float g = a.gate[aid];
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int d = lane + 64 * i;
+      if (d < dh) {
+        float v = sl[d];
+        acc[i] += g * v;
+        dot += oth[i] * v;
+      }
+    }
+    if (a.dots) {
+      dot = wave_sum(dot);
+      if (lane == 0) a.dots[aid] = dot;
+    }
+  }
+  if (out) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int d = lane + 64 * i;
+      if (d < dh) st(out, row + d, acc[i]);
+    }
+  }
+  if (a.delta) {
+    float dd = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dd += acc[i] * oth[i];
+    dd = wave_sum(dd);
+    if (lane == 0) a.delta[pair] = dd;
+  }
+}
+
+void launch_slot_combine(const SlotArgs& a, int bf16, hipStream_t s) {
+  long pairs = (long)a.N * a.H;
+  unsigned g = (unsigned)((pairs + 3) / 4);
+  if (bf16)
+    slot_combine_kernel<bf16_t><<<g, 256, 0, s>>>(a);
+  else
+    slot_combine_kernel<float><<<g, 256, 0, s>>>(a);
+}
+
+// One thread per (token, side, head): writes the E logit-gradient entries it owns.
+template <typename T>
+__global__ __launch_bounds__(256) void router_bwd_kernel(RouterBwdArgs a) {
+  __shared__ float bsum[64];
+  const int sh_ = blockIdx.y;  // side*H + h over the sides that own a router
+  const int side = sh_ / a.H, h = sh_ % a.H;
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  const int E = a.E, k = a.k, HE = a.H * a.E;
+  if (threadIdx.x < 64) bsum[threadIdx.x] = 0.f;
+  __syncthreads();
+  if (n < a.N) {
+    const long cols = (long)a.sides * HE;
+    T* dz = (T*)a.dz;
+    const long base = (long)n * cols + (long)side * HE + (long)h * E;
+    for (int e = 0; e < E; ++e) st(dz, base + e, 0.f);
+    const long o = ((long)sh_ * a.N + n) * k;  // side-major layout [side][H][N][k]
+    for (int j = 0; j < k; ++j) {
+      int e = a.idx[o + j];
+      float g = a.gate[o + j];
+      float dg = a.dgate[o + j];
+      if (a.shared) dg += a.dgate[(long)a.H * a.N * k + o + j];
+      float v = dg * g * (1.f - g);
+      st(dz, base + e, v);
+      atomicAdd(&bsum[e], v);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < E && a.db[side]) atomicAdd(&a.db[side][h * E + threadIdx.x], bsum[threadIdx.x]);
+}
+
+void launch_router_bwd(const RouterBwdArgs& a, int bf16, hipStream_t s) {
+  dim3 g((a.N + 255) / 256, a.sides * a.H);
+  if (bf16)
+    router_bwd_kernel<bf16_t><<<g, 256, 0, s>>>(a);
+  else
+    router_bwd_kernel<float><<<g, 256, 0, s>>>(a);
+}
+
+}  // namespace sh
