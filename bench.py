@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the SwitchHead attention layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2]
+
+One step = one forward + backward pass of the whole layer (router, top-k, permutation, Q/K
+projections, value experts, attention, output experts and every gradient) over one batch
+of synthetic input that is already resident in HBM.  Prints ONE JSON line:
+value = tokens/s of forward+backward; `extra` carries the forward-only figure and the
+per-step times; `roofline` describes the step that takes the most time, measured with HIP
+events recorded by the library on the launch stream; `cpu_baseline` is the float64 oracle
+timed on the host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP64_VEC_TFLOPS = 78.6   # MI355X fp64 vector ALU (256 CUs x 4 SIMD x 16 lanes x 2 x 2.4 GHz)
+PEAK_HBM_GBS = 8000.0
+
+
+def step_work(cfg):
+    """Algorithmic flops (MFMA-bound steps) and bytes (HBM-bound steps) per launch of each step."""
+    B, T, dm, H, dh, E, k = (cfg[s] for s in ("B", "T", "d_model", "nheads", "d_head", "E", "k"))
+    N = B * T
+    es = 2 if cfg["dtype"] == "bf16" else 4
+    pairs = T * (T + 1) // 2 if cfg["causal"] else T * T
+    proj = 2 * N * dm * H * dh
+    expert = 2 * N * k * dm * H * dh
+    attn = 4 * B * H * dh * pairs
+    router = 2 * N * dm * 2 * H * E
+    slots = N * H * k * dh * 4
+    flops = {
+        "fwd.q_proj": proj, "fwd.k_proj": proj, "fwd.v_experts": expert, "fwd.o_experts": expert,
+        "fwd.attention": attn, "bwd.attention": 5 * attn // 2,
+        "bwd.o_dgrad": expert, "bwd.o_wgrad": expert, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
+        "bwd.q_wgrad": proj, "bwd.k_wgrad": proj, "bwd.q_dgrad": proj, "bwd.k_dgrad": proj,
+        "bwd.router_wgrad": router // 2, "bwd.router_dgrad": router // 2,
+    }
+    alu = {"fwd.router": router}
+    nbytes = {
+        "fwd.v_combine": slots + N * H * dh * es + N * H * k * 4,
+        "bwd.dctx_combine": slots + 2 * N * H * dh * es + 2 * N * H * k * 4,
+        "bwd.dgate_s": slots + N * H * dh * es + N * H * k * 4,
+        "fwd.y_zero": N * dm * 4, "bwd.dx_zero": N * dm * 4,
+        "fwd.y_cast": N * dm * (4 + es), "bwd.dx_cast": N * dm * (4 + es),
+        "bwd.zero_dw": 4 * (2 * H * dm * dh + 2 * H * E * dm * dh),
+        "bwd.router": 4 * H * N * k * 4 + N * 2 * H * E * es,
+    }
+    return flops, alu, nbytes
+
+
+def time_loop(fn, steps):
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def cpu_baseline(cfg, budget_tokens):
+    """The float64 oracle, forward + backward, on the first sequences of the same workload."""
+    import numpy as np
+    from oracle import switchhead_oracle as orc
+    from paper_2312_07987_amd.inputs import make_inputs
+    sub = dict(cfg)
+    sub["B"] = max(1, min(cfg["B"], budget_tokens // cfg["T"]))
+    t = make_inputs(sub)
+    t0 = time.perf_counter()
+    f = orc.forward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], t["b_S"], t["b_D"],
+                    k=sub["k"], causal=bool(sub["causal"]))
+    t1 = time.perf_counter()
+    orc.backward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], f, t["dy"])
+    t2 = time.perf_counter()
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    ntok = sub["B"] * sub["T"]
+    return {"value": ntok / (t2 - t0), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "float64 numpy oracle, forward+backward, first %d of %d sequences of %s (%d tokens, %.1f s; "
+                      "forward alone %.0f tokens/s)" % (sub["B"], cfg["B"], cfg["name"], ntok, t2 - t0, ntok / (t1 - t0))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c2", help="c1..c4 (c2 = the 262M-model-scale layer)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=2048)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the layer shards over the batch; see DESIGN.md); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2312_07987_amd import binding
+    from paper_2312_07987_amd.flops import layer_flops
+    from paper_2312_07987_amd.inputs import config, make_inputs
+    from paper_2312_07987_amd.runner import DeviceLayer
+
+    cfg = config(args.config)
+    host = make_inputs(cfg)
+    layer = DeviceLayer(cfg, host)
+    N = cfg["B"] * cfg["T"]
+
+    def step():
+        layer.forward()
+        layer.backward()
+
+    for _ in range(args.warmup):
+        step()
+    ms_step = time_loop(step, args.steps)
+    ms_fwd = time_loop(layer.forward, args.steps)
+
+    # per-step times from HIP events on the launch stream (separate pass, same work)
+    binding.switchhead_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = binding.switchhead_profile_read()
+    binding.switchhead_profile_enable(False)
+    per_step = {n: ms / c for n, (ms, c) in prof.items() if c}
+    flops, alu, nbytes = step_work(cfg)
+    dom = max(per_step, key=per_step.get)
+    if dom in flops:
+        ach = flops[dom] / (per_step[dom] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+    elif dom in alu:
+        ach = alu[dom] / (per_step[dom] * 1e-3) / 1e12
+        roof = {"bound": "alu", "achieved": ach, "peak": PEAK_FP64_VEC_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_FP64_VEC_TFLOPS, "traffic": None}
+    else:
+        ach = nbytes.get(dom, 0) / (per_step[dom] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": None}
+    roof["step"] = dom
+    roof["avg_ms"] = per_step[dom]
+
+    lf = layer_flops(cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
+                     bool(cfg["causal"]))
+    counts = layer.routing()["offsets"]
+    out = {
+        "metric": "switchhead_layer_fwd_bwd_tokens_per_s",
+        "value": N / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s: B=%d T=%d d_model=%d nheads=%d d_head=%d E=%d k=%d causal=%d bias0=%g" % (
+            cfg["name"], cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
+            cfg["causal"], cfg["bias0"]), "tokens_per_step": N},
+        "roofline": roof,
+        "extra": {
+            "fwd_ms": ms_fwd, "fwd_tokens_per_s": N / (ms_fwd * 1e-3),
+            "fwd_tflops": lf["fwd"] / (ms_fwd * 1e-3) / 1e12,
+            "fwd_bwd_tflops": lf["fwd_bwd"] / (ms_step * 1e-3) / 1e12,
+            "fwd_frac_of_bf16_peak": lf["fwd"] / (ms_fwd * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "fwd_bwd_frac_of_bf16_peak": lf["fwd_bwd"] / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "step_ms": {n: round(v, 4) for n, v in sorted(per_step.items())},
+            "step_tflops": {n: round(flops[n] / (per_step[n] * 1e-3) / 1e12, 1) for n in sorted(per_step) if n in flops},
+            "expert_counts_side0_head0": [int(v) for v in (counts[0, 0, 1:] - counts[0, 0, :-1])],
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -159,6 +159,19 @@ const char* switchhead_last_error(void);
  * kernels.  Returns the previous value.  Used by tests to cross-check both families.     */
 int32_t switchhead_set_kernel_family(int32_t family);
 
+/*
+ * Per-step timing for benchmarks (not part of the method).  While enabled, forward and
+ * backward record one HIP event on the launch stream before each step of the layer
+ * ("fwd.v_experts", "bwd.attention", ...).  switchhead_profile_read waits for the recorded
+ * events, adds up the elapsed time and the number of occurrences per step label over all
+ * calls since the last read (or enable), writes up to max_entries of them (labels as one
+ * '\n'-separated string) and returns how many it wrote.  Host-side events only: no device
+ * memory is allocated.  Enabling or reading resets the record.
+ */
+sh_status switchhead_profile_enable(int32_t on);
+int32_t switchhead_profile_read(char* labels, size_t labels_bytes, float* total_ms,
+                                int32_t* launches, int32_t max_entries);
+
 /* Library version, "major.minor". */
 const char* switchhead_version(void);
 

@@ -17,7 +17,8 @@ SH_F32, SH_BF16 = 0, 1
 
 EXPORTS = ("switchhead_workspace_bytes", "switchhead_forward", "switchhead_backward",
            "switchhead_get_routing", "switchhead_get_intermediates", "switchhead_last_error",
-           "switchhead_set_kernel_family", "switchhead_version")
+           "switchhead_set_kernel_family", "switchhead_version",
+           "switchhead_profile_enable", "switchhead_profile_read")
 
 
 class sh_shape(ctypes.Structure):
@@ -63,6 +64,11 @@ def lib():
     L.switchhead_set_kernel_family.argtypes = [i32]
     L.switchhead_version.restype = ctypes.c_char_p
     L.switchhead_version.argtypes = []
+    L.switchhead_profile_enable.restype = i32
+    L.switchhead_profile_enable.argtypes = [i32]
+    L.switchhead_profile_read.restype = i32
+    L.switchhead_profile_read.argtypes = [ctypes.c_char_p, sz, ctypes.POINTER(ctypes.c_float),
+                                          ctypes.POINTER(i32), i32]
     _lib = L
     return L
 
@@ -131,3 +137,17 @@ def switchhead_get_intermediates(shape, workspace, Q, K, V, ctx, lse, stream=Non
     _check(lib().switchhead_get_intermediates(ctypes.byref(shape), _ptr(workspace),
                                               workspace.numel() * workspace.element_size(),
                                               _ptr(Q), _ptr(K), _ptr(V), _ptr(ctx), _ptr(lse), _stream(stream)))
+
+
+def switchhead_profile_enable(on):
+    _check(lib().switchhead_profile_enable(int(bool(on))))
+
+
+def switchhead_profile_read(max_entries=64):
+    """Returns {step label: (total milliseconds, occurrences)} since the last read."""
+    buf = ctypes.create_string_buffer(64 * max_entries)
+    ms = (ctypes.c_float * max_entries)()
+    cnt = (ctypes.c_int32 * max_entries)()
+    n = lib().switchhead_profile_read(buf, len(buf), ms, cnt, max_entries)
+    names = buf.value.decode().split("\n")[:n]
+    return {names[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}

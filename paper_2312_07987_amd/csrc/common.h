@@ -43,6 +43,15 @@ __device__ __forceinline__ void st(bf16_t* p, long i, float v) { p[i].v = f32_to
 // ----------------------------------------------------------------------------------------
 enum { STORE_T = 0, STORE_F32 = 1, ATOMIC_F32 = 2 };
 
+// Which step of the layer a launch serves.  The MFMA kernels are instantiated once per tag so
+// that a profiler shows one kernel name per step; the arithmetic is the same for every tag.
+enum {
+  TAG_GENERIC = 0,
+  TAG_QK_PROJ, TAG_V_EXPERTS, TAG_O_EXPERTS,   // forward row GEMMs
+  TAG_O_DGRAD, TAG_V_DGRAD, TAG_QK_DGRAD,      // backward row GEMMs
+  TAG_O_WGRAD, TAG_V_WGRAD, TAG_QK_WGRAD       // weight gradients
+};
+
 struct RowGemmArgs {
   const int* perm;
   const int* offsets;
@@ -59,6 +68,7 @@ struct RowGemmArgs {
   long gate_hstride;
   int K, Nc;
   int mode;
+  int tag;
 };
 
 // ----------------------------------------------------------------------------------------
@@ -84,6 +94,7 @@ struct WgradArgs {
   const float* gate;
   long gate_hstride;
   int chunk;  // rows reduced by one block
+  int tag;
 };
 
 // Finds the tile `tile` (of `bm` rows) among the E groups of one head.  Returns false when

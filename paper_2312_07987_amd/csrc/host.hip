@@ -5,6 +5,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
 
 #include "../../include/switchhead.h"
 #include "common.h"
@@ -22,6 +25,33 @@ sh_status fail(sh_status code, const char* fmt, ...) {
   vsnprintf(g_err, sizeof g_err, fmt, ap);
   va_end(ap);
   return code;
+}
+
+// ---- per-step timing for benchmarks: one HIP event per mark on the launch stream ----------
+struct ProfMark {
+  const char* label;  // NULL closes the previous step
+  hipEvent_t ev;
+};
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfMark> g_marks;
+std::vector<hipEvent_t> g_event_pool;
+
+void prof_mark(hipStream_t st, const char* label) {
+  if (!g_prof_on) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  hipEvent_t ev;
+  if (!g_event_pool.empty()) {
+    ev = g_event_pool.back();
+    g_event_pool.pop_back();
+  } else if (hipEventCreate(&ev) != hipSuccess) {
+    return;
+  }
+  if (hipEventRecord(ev, st) != hipSuccess) {
+    g_event_pool.push_back(ev);
+    return;
+  }
+  g_marks.push_back({label, ev});
 }
 
 inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -184,6 +214,56 @@ const char* switchhead_version(void) { return "0.1"; }
 
 int32_t switchhead_set_kernel_family(int32_t family) { return g_family.exchange(family ? 1 : 0); }
 
+sh_status switchhead_profile_enable(int32_t on) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_on = on != 0;
+  for (auto& m : g_marks) g_event_pool.push_back(m.ev);
+  g_marks.clear();
+  return SH_OK;
+}
+
+int32_t switchhead_profile_read(char* labels, size_t labels_bytes, float* total_ms, int32_t* launches,
+                                int32_t max_entries) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  std::vector<std::string> names;
+  std::vector<float> ms;
+  std::vector<int> cnt;
+  for (size_t i = 0; i + 1 < g_marks.size(); ++i) {
+    if (!g_marks[i].label) continue;
+    if (hipEventSynchronize(g_marks[i + 1].ev) != hipSuccess) break;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, g_marks[i].ev, g_marks[i + 1].ev) != hipSuccess) continue;
+    size_t j = 0;
+    for (; j < names.size(); ++j)
+      if (names[j] == g_marks[i].label) break;
+    if (j == names.size()) {
+      names.push_back(g_marks[i].label);
+      ms.push_back(0.f);
+      cnt.push_back(0);
+    }
+    ms[j] += t;
+    cnt[j] += 1;
+  }
+  for (auto& m : g_marks) g_event_pool.push_back(m.ev);
+  g_marks.clear();
+  int32_t n = 0;
+  size_t used = 0;
+  if (labels && labels_bytes) labels[0] = 0;
+  for (size_t j = 0; j < names.size() && n < max_entries; ++j) {
+    if (labels) {
+      if (used + names[j].size() + 2 > labels_bytes) break;
+      memcpy(labels + used, names[j].c_str(), names[j].size());
+      used += names[j].size();
+      labels[used++] = '\n';
+      labels[used] = 0;
+    }
+    if (total_ms) total_ms[n] = ms[j];
+    if (launches) launches[n] = cnt[j];
+    ++n;
+  }
+  return n;
+}
+
 size_t switchhead_workspace_bytes(const sh_shape* shape) {
   if (check_shape(shape) != SH_OK) return 0;
   return make_layout(shape).total;
@@ -201,6 +281,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
   const long hd = (long)H * dh;
 
   // step 1: routers, top-k, expert-sorted permutation
+  prof_mark(c.st, "fwd.router");
   if (c.dense) {
     launch_dense_routing(c.idx(0), c.gate(0), c.perm(0), c.offsets(0), N, H, c.st);
   } else {
@@ -228,15 +309,17 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
   if (c.dense || c.shared) {
     // one selection serves both sides: the destination tables repeat the source tables
     const size_t n1 = (size_t)H * N * k * 4;
-    hipMemcpyAsync(c.idx(1), c.idx(0), n1, hipMemcpyDeviceToDevice, c.st);
-    hipMemcpyAsync(c.gate(1), c.gate(0), n1, hipMemcpyDeviceToDevice, c.st);
-    hipMemcpyAsync(c.perm(1), c.perm(0), n1, hipMemcpyDeviceToDevice, c.st);
-    hipMemcpyAsync(c.offsets(1), c.offsets(0), (size_t)H * (E + 1) * 4, hipMemcpyDeviceToDevice, c.st);
+    (void)hipMemcpyAsync(c.idx(1), c.idx(0), n1, hipMemcpyDeviceToDevice, c.st);
+    (void)hipMemcpyAsync(c.gate(1), c.gate(0), n1, hipMemcpyDeviceToDevice, c.st);
+    (void)hipMemcpyAsync(c.perm(1), c.perm(0), n1, hipMemcpyDeviceToDevice, c.st);
+    (void)hipMemcpyAsync(c.offsets(1), c.offsets(0), (size_t)H * (E + 1) * 4, hipMemcpyDeviceToDevice, c.st);
   }
 
   // step 2: dense queries and keys
   for (int which = 0; which < 2; ++which) {
+    prof_mark(c.st, which ? "fwd.k_proj" : "fwd.q_proj");
     RowGemmArgs a = identity_rows(c, H);
+    a.tag = TAG_QK_PROJ;
     a.A = x;
     a.lda = dm;
     a.a_hoff = 0;
@@ -255,7 +338,9 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
 
   // step 3: value experts, unscaled per-slot results, then the gate-weighted sum over slots
   {
+    prof_mark(c.st, "fwd.v_experts");
     RowGemmArgs a = perm_rows(c, 0);
+    a.tag = TAG_V_EXPERTS;
     a.A = x;
     a.lda = dm;
     a.B = W_V;
@@ -270,6 +355,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     a.Nc = dh;
     a.mode = STORE_F32;
     row_gemm(c, a);
+    prof_mark(c.st, "fwd.v_combine");
     SlotArgs sa{};
     sa.slots = c.p<float>(c.L.pV);
     sa.gate = c.gate(0);
@@ -283,6 +369,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
 
   // step 4: one attention matrix per head
   {
+    prof_mark(c.st, "fwd.attention");
     AttnArgs a{};
     a.Q = c.p<void>(c.L.Q);
     a.K = c.p<void>(c.L.K);
@@ -303,9 +390,12 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
 
   // step 5: output experts, gate-scaled, summed over heads and slots in fp32
   {
+    prof_mark(c.st, "fwd.y_zero");
     float* acc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)y;
     launch_fill_f32(acc, (size_t)N * dm, 0.f, c.st);
+    prof_mark(c.st, "fwd.o_experts");
     RowGemmArgs a = perm_rows(c, 1);
+    a.tag = TAG_O_EXPERTS;
     a.c_div = k;
     a.A = c.p<void>(c.L.ctx);
     a.lda = hd;
@@ -324,8 +414,10 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     a.Nc = dm;
     a.mode = ATOMIC_F32;
     row_gemm(c, a);
+    prof_mark(c.st, "fwd.y_cast");
     if (c.bf16) launch_cast_from_f32(acc, y, (size_t)N * dm, 1, c.st);
   }
+  prof_mark(c.st, nullptr);
   return check_launch("switchhead_forward");
 }
 
@@ -342,6 +434,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   const long hd = (long)H * dh;
   const int chunk = 1024;
 
+  prof_mark(c.st, "bwd.zero_dw");
   launch_fill_f32(dW_Q, (size_t)H * dm * dh, 0.f, c.st);
   launch_fill_f32(dW_K, (size_t)H * dm * dh, 0.f, c.st);
   launch_fill_f32(dW_V, (size_t)H * E * dm * dh, 0.f, c.st);
@@ -349,7 +442,9 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
 
   // output experts: u[h][a][:] = dy[n] W_O[h,e]^T (unscaled), then dctx, d(gate_D), delta
   {
+    prof_mark(c.st, "bwd.o_dgrad");
     RowGemmArgs a = perm_rows(c, 1);
+    a.tag = TAG_O_DGRAD;
     a.A = dy;
     a.lda = dm;
     a.B = W_O;
@@ -364,6 +459,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.Nc = dh;
     a.mode = STORE_F32;
     row_gemm(c, a);
+    prof_mark(c.st, "bwd.dctx_combine");
     SlotArgs sa{};
     sa.slots = c.p<float>(c.L.u);
     sa.gate = c.gate(1);
@@ -376,7 +472,9 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     sa.k = k;
     sa.dh = dh;
     launch_slot_combine(sa, c.bf16, c.st);
+    prof_mark(c.st, "bwd.o_wgrad");
     WgradArgs w{};
+    w.tag = TAG_O_WGRAD;
     w.perm = c.perm(1);
     w.offsets = c.offsets(1);
     w.heads = H;
@@ -404,6 +502,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
 
   // attention
   {
+    prof_mark(c.st, "bwd.attention");
     AttnBwdArgs a{};
     a.Q = c.p<void>(c.L.Q);
     a.K = c.p<void>(c.L.K);
@@ -427,9 +526,11 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   }
 
   // value experts: d(gate_S), dW_V, dx
+  prof_mark(c.st, "bwd.dx_zero");
   float* dxacc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)dx;
   launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
   {
+    prof_mark(c.st, "bwd.dgate_s");
     SlotArgs sa{};
     sa.slots = c.p<float>(c.L.pV);
     sa.gate = c.gate(0);
@@ -440,7 +541,9 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     sa.k = k;
     sa.dh = dh;
     launch_slot_combine(sa, c.bf16, c.st);
+    prof_mark(c.st, "bwd.v_wgrad");
     WgradArgs w{};
+    w.tag = TAG_V_WGRAD;
     w.perm = c.perm(0);
     w.offsets = c.offsets(0);
     w.heads = H;
@@ -464,7 +567,9 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.gate_hstride = (long)N * k;
     w.chunk = chunk;
     wgrad(c, w);
+    prof_mark(c.st, "bwd.v_dgrad");
     RowGemmArgs a = perm_rows(c, 0);
+    a.tag = TAG_V_DGRAD;
     a.c_div = k;
     a.A = c.p<void>(c.L.dV);
     a.lda = hd;
@@ -487,7 +592,9 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   // dense queries and keys
   for (int which = 0; which < 2; ++which) {
     const void* g = c.p<void>(which ? c.L.dK : c.L.dQ);
+    prof_mark(c.st, which ? "bwd.k_wgrad" : "bwd.q_wgrad");
     WgradArgs w{};
+    w.tag = TAG_QK_WGRAD;
     w.heads = H;
     w.E = 1;
     w.M = N;
@@ -506,7 +613,9 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.swa = dh;
     w.chunk = chunk;
     wgrad(c, w);
+    prof_mark(c.st, which ? "bwd.k_dgrad" : "bwd.q_dgrad");
     RowGemmArgs a = identity_rows(c, H);
+    a.tag = TAG_QK_DGRAD;
     a.A = g;
     a.lda = hd;
     a.a_hoff = dh;
@@ -524,6 +633,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
 
   // routers
   if (!c.dense) {
+    prof_mark(c.st, "bwd.router");
     const int sides = c.shared ? 1 : 2;
     const int HE = H * E;
     float* dWs[2] = {dW_S, c.shared ? nullptr : dW_D};
@@ -549,6 +659,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     for (int sd = 0; sd < sides; ++sd) {
       const void* dz = c.p<char>(c.L.dz) + (size_t)sd * HE * (c.bf16 ? 2 : 4);
       if (dWs[sd]) {
+        prof_mark(c.st, "bwd.router_wgrad");
         WgradArgs w{};
         w.heads = 1;
         w.E = 1;
@@ -566,6 +677,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
         w.chunk = chunk;
         wgrad(c, w);
       }
+      prof_mark(c.st, "bwd.router_dgrad");
       RowGemmArgs a = identity_rows(c, 1);
       a.A = dz;
       a.lda = (long)sides * HE;
@@ -580,7 +692,9 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       row_gemm(c, a);
     }
   }
+  prof_mark(c.st, "bwd.dx_cast");
   if (c.bf16) launch_cast_from_f32(dxacc, dx, (size_t)N * dm, 1, c.st);
+  prof_mark(c.st, nullptr);
   return check_launch("switchhead_backward");
 }
 

@@ -1,7 +1,446 @@
+// bf16 matrix-core (MFMA) kernels for the projections of the SwitchHead layer (arXiv
+// 2312.07987, Sec. 2.2): the grouped conditional expert GEMMs of the V^h and y equations,
+// the dense per-head Q/K projections of Sec. 2.1, their data gradients and their weight
+// gradients.  gfx950 only: v_mfma_f32_32x32x16_bf16, 64-wide waves, LDS-staged tiles,
+// ds_read_b64_tr_b16 for operands whose reduction index is the slow one in memory.
+//
+// Fragment layouts of v_mfma_f32_32x32x16_bf16 (lane = 32*g + r, g in {0,1}):
+//   A operand: A[row r][k = 8g .. 8g+7]      B operand: B[k = 8g .. 8g+7][col r]
+//   D: register q (0..15) holds D[8*(q/4) + 4g + q%4][col r]
 #include "common.h"
+
 namespace sh {
-bool mfma_row_gemm_supported(const RowGemmArgs&) { return false; }
-void launch_mfma_row_gemm(const RowGemmArgs&, hipStream_t) {}
-bool mfma_wgrad_supported(const WgradArgs&) { return false; }
-void launch_mfma_wgrad(const WgradArgs&, hipStream_t) {}
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+// 8 consecutive bf16 of one LDS row -> operand fragment
+__device__ __forceinline__ bf16x8 frag_rowmajor(const unsigned short* p) { return *(const bf16x8*)p; }
+
+// Operand fragment from a tile stored [k][n] (n contiguous): the lane needs k = kb..kb+7 of
+// column n.  Two transposing reads; inside each group of 16 lanes, lane s addresses row
+// kb + s/4, columns 4*(s%4).. and receives rows kb..kb+3 of column s.
+__device__ __forceinline__ bf16x8 frag_transposed(const unsigned short* tile, int ld, int kb, int nb, int lane) {
+  const int s = lane & 15;
+  const unsigned short* p = tile + (kb + (s >> 2)) * ld + nb + ((lane >> 4) & 1) * 16 + (s & 3) * 4;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p + 4 * ld));
+  union {
+    struct {
+      s16x4 a, b;
+    } s2;
+    bf16x8 v;
+  } u;
+  u.s2.a = lo;
+  u.s2.b = hi;
+  return u.v;
 }
+
+template <int VEC>
+struct Chunk;
+template <>
+struct Chunk<8> {
+  typedef uint4 type;
+};
+template <>
+struct Chunk<4> {
+  typedef uint2 type;
+};
+
+template <int VEC>
+__device__ __forceinline__ typename Chunk<VEC>::type zero_chunk() {
+  typename Chunk<VEC>::type z;
+  if constexpr (VEC == 8)
+    z = make_uint4(0, 0, 0, 0);
+  else
+    z = make_uint2(0, 0);
+  return z;
+}
+
+__device__ __forceinline__ unsigned scale_pair(unsigned w, float g) {
+  float lo = __uint_as_float(w << 16) * g, hi = __uint_as_float(w & 0xffff0000u) * g;
+  return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+}
+__device__ __forceinline__ uint4 scale_chunk(uint4 c, float g) {
+  return make_uint4(scale_pair(c.x, g), scale_pair(c.y, g), scale_pair(c.z, g), scale_pair(c.w, g));
+}
+__device__ __forceinline__ uint2 scale_chunk(uint2 c, float g) { return make_uint2(scale_pair(c.x, g), scale_pair(c.y, g)); }
+
+// ----------------------------------------------------------------------------------------
+// Row GEMM.  Block tile 128 x 128, K step 32, 4 waves as 2 x 2, each 64 x 64 = 2 x 2 MFMA
+// blocks.  Global -> registers -> LDS software pipeline with two LDS buffers.
+// ----------------------------------------------------------------------------------------
+namespace rg {
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int LDA = BK + 8;        // A tile [BM][LDA], k contiguous
+constexpr int LDB_NT = BK + 8;     // B tile [BN][LDB_NT] when k is contiguous in memory
+constexpr int LDB_NN = BN + 32;    // B tile [BK][LDB_NN] when n is contiguous in memory
+constexpr int B_ELEMS = (BN * LDB_NT > BK * LDB_NN) ? BN * LDB_NT : BK * LDB_NN;
+}  // namespace rg
+
+template <int VEC, bool BNT, int TAG>
+__global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
+  using namespace rg;
+  typedef typename Chunk<VEC>::type chunk_t;
+  __shared__ __attribute__((aligned(16))) unsigned short As[2][BM * LDA];
+  __shared__ __attribute__((aligned(16))) unsigned short Bs[2][B_ELEMS];
+  __shared__ int ids[BM];
+  __shared__ float gsc[BM];
+
+  const int h = blockIdx.z;
+  int e = 0, row0, rows;
+  if (a.perm) {
+    if (!find_tile(a.offsets + (long)h * (a.E + 1), a.E, BM, blockIdx.x, e, row0, rows)) return;
+  } else {
+    row0 = blockIdx.x * BM;
+    if (row0 >= a.M) return;
+    rows = a.M - row0 < BM ? a.M - row0 : BM;
+  }
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < BM) {
+    int id = -1;
+    float g = 0.f;
+    if (tid < rows) {
+      id = a.perm ? a.perm[(long)h * a.M + row0 + tid] : row0 + tid;
+      g = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
+    }
+    ids[tid] = id;
+    gsc[tid] = g;
+  }
+  __syncthreads();
+
+  const unsigned short* A = (const unsigned short*)a.A;
+  const unsigned short* B = (const unsigned short*)a.B + (long)h * a.b_hstride + (long)e * a.b_estride;
+  const int n0 = blockIdx.y * BN;
+  const int K = a.K, Nc = a.Nc;
+
+  // ---- per-thread load plan -----------------------------------------------------------
+  constexpr int A_CPR = BK / VEC;                 // chunks per A row
+  constexpr int A_N = BM * A_CPR / 256;           // chunks per thread
+  constexpr int B_N = (BK * BN / VEC) / 256;
+  long a_off[A_N];
+  int a_kc[A_N], a_lds[A_N];
+#pragma unroll
+  for (int i = 0; i < A_N; ++i) {
+    int c = tid + i * 256;
+    int r = c / A_CPR, kc = (c % A_CPR) * VEC;
+    int id = ids[r];
+    a_off[i] = id >= 0 ? (long)(id / a.a_div) * a.lda + (long)h * a.a_hoff + kc : -1;
+    a_kc[i] = kc;
+    a_lds[i] = r * LDA + kc;
+  }
+  long b_off[B_N];
+  int b_kc[B_N], b_lds[B_N];
+  bool b_ok[B_N];
+#pragma unroll
+  for (int i = 0; i < B_N; ++i) {
+    int c = tid + i * 256;
+    if constexpr (BNT) {
+      constexpr int CPR = BK / VEC;
+      int n = c / CPR, kc = (c % CPR) * VEC;
+      b_ok[i] = n0 + n < Nc;
+      b_off[i] = (long)(n0 + n) * a.sbn + kc;
+      b_kc[i] = kc;
+      b_lds[i] = n * LDB_NT + kc;
+    } else {
+      constexpr int CPR = BN / VEC;
+      int kr = c / CPR, nc = (c % CPR) * VEC;
+      b_ok[i] = n0 + nc < Nc;
+      b_off[i] = (long)kr * a.sbk + n0 + nc;
+      b_kc[i] = kr;
+      b_lds[i] = kr * LDB_NN + nc;
+    }
+  }
+
+  chunk_t ra[A_N], rb[B_N];
+  auto load_global = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < A_N; ++i) {
+      ra[i] = zero_chunk<VEC>();
+      if (a_off[i] >= 0 && k0 + a_kc[i] < K) ra[i] = *(const chunk_t*)(A + a_off[i] + k0);
+    }
+#pragma unroll
+    for (int i = 0; i < B_N; ++i) {
+      rb[i] = zero_chunk<VEC>();
+      if (b_ok[i] && k0 + b_kc[i] < K) {
+        if constexpr (BNT)
+          rb[i] = *(const chunk_t*)(B + b_off[i] + k0);
+        else
+          rb[i] = *(const chunk_t*)(B + b_off[i] + (long)k0 * a.sbk);
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_N; ++i) *(chunk_t*)(&As[buf][a_lds[i]]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_N; ++i) *(chunk_t*)(&Bs[buf][b_lds[i]]) = rb[i];
+  };
+
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int r = lane & 31, g = lane >> 5;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+  const int nk = (K + BK - 1) / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) load_global((kt + 1) * BK);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fa[i] = frag_rowmajor(&As[buf][(wm + i * 32 + r) * LDA + kk + 8 * g]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        if constexpr (BNT)
+          fb[j] = frag_rowmajor(&Bs[buf][(wn + j * 32 + r) * LDB_NT + kk + 8 * g]);
+        else
+          fb[j] = frag_transposed(&Bs[buf][0], LDB_NN, kk + 8 * g, wn + j * 32, lane);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue -------------------------------------------------------------------------
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
+      const int id = ids[row];
+      if (id < 0) continue;
+      const float sc = gsc[row];
+      const long crow = (long)(id / a.c_div) * a.ldc + (long)h * a.c_hoff;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = n0 + wn + j * 32 + r;
+        if (n >= Nc) continue;
+        const float v = acc[i][j][q] * sc;
+        if (a.mode == STORE_T)
+          ((unsigned short*)a.C)[crow + n] = f32_to_bf16(v);
+        else if (a.mode == STORE_F32)
+          ((float*)a.C)[crow + n] = v;
+        else
+          atomicAdd((float*)a.C + crow + n, v);
+      }
+    }
+  }
+}
+
+static bool aligned_to(const void* p, size_t b) { return ((uintptr_t)p % b) == 0; }
+
+// vector width (bf16 elements) all loads of a row GEMM can use, 0 if none
+static int row_gemm_vec(const RowGemmArgs& a) {
+  const bool nt = a.sbk == 1;
+  if (!nt && a.sbn != 1) return 0;
+  for (int vec = 8; vec >= 4; vec -= 4) {
+    const size_t bytes = vec * 2;
+    bool ok = aligned_to(a.A, bytes) && aligned_to(a.B, bytes) && a.lda % vec == 0 && a.a_hoff % vec == 0 &&
+              a.K % vec == 0 && a.b_hstride % vec == 0 && a.b_estride % vec == 0;
+    if (nt)
+      ok = ok && a.sbn % vec == 0;
+    else
+      ok = ok && a.sbk % vec == 0 && a.Nc % vec == 0;
+    if (ok) return vec;
+  }
+  return 0;
+}
+
+bool mfma_row_gemm_supported(const RowGemmArgs& a) { return row_gemm_vec(a) != 0; }
+
+void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s) {
+  if (a.M <= 0 || a.Nc <= 0) return;
+  const int vec = row_gemm_vec(a);
+  const bool nt = a.sbk == 1;
+  dim3 g((a.M + rg::BM - 1) / rg::BM + (a.perm ? a.E : 0), (a.Nc + rg::BN - 1) / rg::BN, a.heads);
+  if (vec == 8 && nt) {
+    switch (a.tag) {
+      case TAG_O_DGRAD: mfma_row_gemm_kernel<8, true, TAG_O_DGRAD><<<g, 256, 0, s>>>(a); break;
+      case TAG_V_DGRAD: mfma_row_gemm_kernel<8, true, TAG_V_DGRAD><<<g, 256, 0, s>>>(a); break;
+      case TAG_QK_DGRAD: mfma_row_gemm_kernel<8, true, TAG_QK_DGRAD><<<g, 256, 0, s>>>(a); break;
+      default: mfma_row_gemm_kernel<8, true, TAG_GENERIC><<<g, 256, 0, s>>>(a); break;
+    }
+  } else if (vec == 8) {
+    switch (a.tag) {
+      case TAG_QK_PROJ: mfma_row_gemm_kernel<8, false, TAG_QK_PROJ><<<g, 256, 0, s>>>(a); break;
+      case TAG_V_EXPERTS: mfma_row_gemm_kernel<8, false, TAG_V_EXPERTS><<<g, 256, 0, s>>>(a); break;
+      case TAG_O_EXPERTS: mfma_row_gemm_kernel<8, false, TAG_O_EXPERTS><<<g, 256, 0, s>>>(a); break;
+      default: mfma_row_gemm_kernel<8, false, TAG_GENERIC><<<g, 256, 0, s>>>(a); break;
+    }
+  } else if (nt) {
+    mfma_row_gemm_kernel<4, true, TAG_GENERIC><<<g, 256, 0, s>>>(a);
+  } else {
+    mfma_row_gemm_kernel<4, false, TAG_GENERIC><<<g, 256, 0, s>>>(a);
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// Weight-gradient GEMM: dW[i, j] += sum_rows g * A[row, i] * Bm[row, j].  The reduction runs
+// over gathered rows, so both tiles are stored [row][feature] and read with transposing
+// loads.  Block tile 128 (i) x 128 (j), 32 rows per step, `chunk` rows per block, fp32
+// atomic add of the block's partial sum.
+// ----------------------------------------------------------------------------------------
+namespace wg {
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int LD = 128 + 32;
+constexpr int MAX_CHUNK = 2048;
+}  // namespace wg
+
+template <int VEC, int TAG>
+__global__ __launch_bounds__(256) void mfma_wgrad_kernel(WgradArgs a) {
+  using namespace wg;
+  typedef typename Chunk<VEC>::type chunk_t;
+  __shared__ __attribute__((aligned(16))) unsigned short As[2][BK * LD];
+  __shared__ __attribute__((aligned(16))) unsigned short Bs[2][BK * LD];
+  __shared__ int ids[MAX_CHUNK];
+  __shared__ float gsc[MAX_CHUNK];
+
+  const int h = blockIdx.z;
+  int e = 0, row0, rows;
+  if (a.perm) {
+    if (!find_tile(a.offsets + (long)h * (a.E + 1), a.E, a.chunk, blockIdx.y, e, row0, rows)) return;
+  } else {
+    row0 = blockIdx.y * a.chunk;
+    if (row0 >= a.M) return;
+    rows = a.M - row0 < a.chunk ? a.M - row0 : a.chunk;
+  }
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int t = tid; t < rows; t += 256) {
+    int id = a.perm ? a.perm[(long)h * a.M + row0 + t] : row0 + t;
+    ids[t] = id;
+    gsc[t] = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
+  }
+  __syncthreads();
+
+  const int tj = (a.Kb + BN - 1) / BN;
+  const int i0 = (blockIdx.x / tj) * BM, j0 = (blockIdx.x % tj) * BN;
+  const unsigned short* A = (const unsigned short*)a.A;
+  const unsigned short* Bm = (const unsigned short*)a.Bm;
+  const bool scaled = a.gate != nullptr;
+
+  constexpr int CPR = BM / VEC;                // chunks per tile row (same for both tiles)
+  constexpr int NCH = BK * CPR / 256;          // chunks per thread per tile
+  chunk_t ra[NCH], rb[NCH];
+  auto load_global = [&](int r0) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      int c = tid + i * 256;
+      int rr = c / CPR, fc = (c % CPR) * VEC;
+      ra[i] = zero_chunk<VEC>();
+      rb[i] = zero_chunk<VEC>();
+      if (r0 + rr < rows) {
+        int id = ids[r0 + rr];
+        if (i0 + fc < a.Ka) {
+          ra[i] = *(const chunk_t*)(A + (long)(id / a.a_div) * a.lda + (long)h * a.a_hoff + i0 + fc);
+          if (scaled) ra[i] = scale_chunk(ra[i], gsc[r0 + rr]);
+        }
+        if (j0 + fc < a.Kb) rb[i] = *(const chunk_t*)(Bm + (long)(id / a.b_div) * a.ldb + (long)h * a.b_hoff + j0 + fc);
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      int c = tid + i * 256;
+      int rr = c / CPR, fc = (c % CPR) * VEC;
+      *(chunk_t*)(&As[buf][rr * LD + fc]) = ra[i];
+      *(chunk_t*)(&Bs[buf][rr * LD + fc]) = rb[i];
+    }
+  };
+
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int r = lane & 31, g = lane >> 5;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+  const int nk = (rows + BK - 1) / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) load_global((kt + 1) * BK);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fa[i] = frag_transposed(&As[buf][0], LD, kk + 8 * g, wm + i * 32, lane);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fb[j] = frag_transposed(&Bs[buf][0], LD, kk + 8 * g, wn + j * 32, lane);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  float* dW = a.dW + (long)h * a.w_hstride + (long)e * a.w_estride;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int ii = i0 + wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
+      if (ii >= a.Ka) continue;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int jj = j0 + wn + j * 32 + r;
+        if (jj < a.Kb) atomicAdd(dW + (long)ii * a.swa + jj, acc[i][j][q]);
+      }
+    }
+}
+
+static int wgrad_vec(const WgradArgs& a) {
+  if (a.chunk > wg::MAX_CHUNK || a.chunk % wg::BK != 0) return 0;
+  for (int vec = 8; vec >= 4; vec -= 4) {
+    const size_t bytes = vec * 2;
+    if (aligned_to(a.A, bytes) && aligned_to(a.Bm, bytes) && a.lda % vec == 0 && a.a_hoff % vec == 0 &&
+        a.ldb % vec == 0 && a.b_hoff % vec == 0 && a.Ka % vec == 0 && a.Kb % vec == 0)
+      return vec;
+  }
+  return 0;
+}
+
+bool mfma_wgrad_supported(const WgradArgs& a) { return wgrad_vec(a) != 0; }
+
+void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s) {
+  if (a.M <= 0) return;
+  const int vec = wgrad_vec(a);
+  int ti = (a.Ka + wg::BM - 1) / wg::BM, tj = (a.Kb + wg::BN - 1) / wg::BN;
+  dim3 g(ti * tj, (a.M + a.chunk - 1) / a.chunk + (a.perm ? a.E : 0), a.heads);
+  if (vec == 8) {
+    switch (a.tag) {
+      case TAG_O_WGRAD: mfma_wgrad_kernel<8, TAG_O_WGRAD><<<g, 256, 0, s>>>(a); break;
+      case TAG_V_WGRAD: mfma_wgrad_kernel<8, TAG_V_WGRAD><<<g, 256, 0, s>>>(a); break;
+      case TAG_QK_WGRAD: mfma_wgrad_kernel<8, TAG_QK_WGRAD><<<g, 256, 0, s>>>(a); break;
+      default: mfma_wgrad_kernel<8, TAG_GENERIC><<<g, 256, 0, s>>>(a); break;
+    }
+  } else {
+    mfma_wgrad_kernel<4, TAG_GENERIC><<<g, 256, 0, s>>>(a);
+  }
+}
+
+}  // namespace sh

@@ -147,4 +147,4 @@ def test_rerun_is_stable():
     layer.forward()
     y2, r2 = layer.outputs(), layer.routing()
     assert all(np.array_equal(r1[n], r2[n]) for n in r1)
-    assert nerr(y2, y1) < 1e-2 * TOL["bf16"]
+    assert nerr(y2, y1) <= 2.0 ** -7   # at most one bf16 rounding step of the largest value
