@@ -216,40 +216,275 @@ __global__ __launch_bounds__(256) void mfma_attn_fwd_kernel(AttnArgs a) {
   }
 }
 
-static int attn_vec(int H, int dh) {
-  if (dh % 8 == 0) return 8;
-  if (dh % 4 == 0) return 4;
-  (void)H;
-  return 0;
+// copies rows into two LDS tiles at once (one read with row fragments, one with transposing
+// loads; they need different row strides to stay free of bank conflicts).  t1 may equal t0.
+template <int DH, int VEC>
+__device__ __forceinline__ void stage_rows2(unsigned short* t0, int ld0, unsigned short* t1, int ld1,
+                                            const unsigned short* src, long row_stride, int nrows, int valid_rows,
+                                            int dh, int tid) {
+  constexpr int CPR = DH / VEC;
+  for (int c = tid; c < nrows * CPR; c += 256) {
+    const int r = c / CPR, d = (c % CPR) * VEC;
+    if constexpr (VEC == 8) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (r < valid_rows && d < dh) v = *(const uint4*)(src + (long)r * row_stride + d);
+      *(uint4*)(t0 + r * ld0 + d) = v;
+      if (t1 != t0) *(uint4*)(t1 + r * ld1 + d) = v;
+    } else {
+      uint2 v = make_uint2(0, 0);
+      if (r < valid_rows && d < dh) v = *(const uint2*)(src + (long)r * row_stride + d);
+      *(uint2*)(t0 + r * ld0 + d) = v;
+      if (t1 != t0) *(uint2*)(t1 + r * ld1 + d) = v;
+    }
+  }
 }
 
-bool mfma_attn_supported(int T, int dh) { return T >= 1 && dh >= 4 && dh <= 256 && attn_vec(1, dh) != 0; }
+template <int NDB>
+__device__ __forceinline__ void store_rows_T(unsigned short* dst, const f32x16* acc, float mul, int g, int dh) {
+  // acc[d] holds X^T[32*d + 8*(i/4) + 4g + i%4][this lane's row]; dst points at that row
+#pragma unroll
+  for (int d = 0; d < NDB; ++d)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const int dd = d * 32 + 8 * i4 + 4 * g;
+      if (dd < dh) {
+        uint2 w;
+        w.x = (unsigned)f32_to_bf16(acc[d][4 * i4] * mul) | ((unsigned)f32_to_bf16(acc[d][4 * i4 + 1] * mul) << 16);
+        w.y = (unsigned)f32_to_bf16(acc[d][4 * i4 + 2] * mul) | ((unsigned)f32_to_bf16(acc[d][4 * i4 + 3] * mul) << 16);
+        *(uint2*)(dst + dd) = w;
+      }
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// backward, dK and dV: block = 4 waves x 32 keys (K, V rows of a wave live in registers as
+// B operands); query tiles of 32 rows of Q and dO are staged in LDS.
+//   S[q][key] = Q K^T,  P = exp(S - lse),  dP[q][key] = dO V^T,  dS = P (dP - delta)
+//   dV^T[d][key] += dO^T[d][q] P[q][key],   dK^T[d][key] += Q^T[d][q] dS[q][key]
+// ----------------------------------------------------------------------------------------
+template <int DH, int VEC>
+__global__ __launch_bounds__(256) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
+  constexpr int QT = 32;
+  constexpr bool SEP = DH <= 128;                       // separate tiles for the two read patterns
+  constexpr int LDR = SEP ? DH + 8 : ld_tr(DH), LDT = ld_tr(DH);
+  constexpr int NKD = DH / 16, NDB = DH / 32;
+  __shared__ __attribute__((aligned(16))) unsigned short Qr[QT * LDR];
+  __shared__ __attribute__((aligned(16))) unsigned short Gr[QT * LDR];
+  __shared__ __attribute__((aligned(16))) unsigned short Qt_[SEP ? QT * LDT : 8];
+  __shared__ __attribute__((aligned(16))) unsigned short Gt_[SEP ? QT * LDT : 8];
+  __shared__ __attribute__((aligned(16))) float lse_s[QT];
+  __shared__ __attribute__((aligned(16))) float del_s[QT];
+  unsigned short* Qt = SEP ? Qt_ : Qr;
+  unsigned short* Gt = SEP ? Gt_ : Gr;
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int k0 = blockIdx.x * 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int T = a.T, dh = a.dh;
+  const long rs = (long)a.H * dh;
+  const long base = ((long)b * T) * rs + (long)h * dh;
+  const unsigned short* Q = (const unsigned short*)a.Q + base;
+  const unsigned short* K = (const unsigned short*)a.K + base;
+  const unsigned short* V = (const unsigned short*)a.V + base;
+  const unsigned short* dO = (const unsigned short*)a.dO + base;
+  const float* lse = a.lse + ((long)b * a.H + h) * T;
+  const float* delta = a.delta + (long)b * T * a.H + h;
+
+  const int key = k0 + wave * 32 + r;
+  const int wk_first = k0 + wave * 32;
+  bf16x8 kf[NKD], vf[NKD];
+#pragma unroll
+  for (int kk = 0; kk < NKD; ++kk) {
+    kf[kk] = global_frag<VEC>(K + (long)key * rs, kk * 16 + 8 * g, dh, key < T);
+    vf[kk] = global_frag<VEC>(V + (long)key * rs, kk * 16 + 8 * g, dh, key < T);
+  }
+  f32x16 accK[NDB], accV[NDB];
+#pragma unroll
+  for (int d = 0; d < NDB; ++d)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) accK[d][i] = accV[d][i] = 0.f;
+  const float sc = a.scale * 1.44269504088896340736f;
+
+  const int qbeg = a.causal ? (k0 / QT) * QT : 0;
+  for (int q0 = qbeg; q0 < T; q0 += QT) {
+    __syncthreads();
+    stage_rows2<DH, VEC>(Qr, LDR, Qt, LDT, Q + (long)q0 * rs, rs, QT, T - q0, dh, tid);
+    stage_rows2<DH, VEC>(Gr, LDR, Gt, LDT, dO + (long)q0 * rs, rs, QT, T - q0, dh, tid);
+    if (tid < QT) {
+      const bool ok = q0 + tid < T;
+      lse_s[tid] = ok ? lse[q0 + tid] * 1.44269504088896340736f : 0.f;
+      del_s[tid] = ok ? delta[(long)(q0 + tid) * a.H] : 0.f;
+    }
+    __syncthreads();
+    if (a.causal && q0 + QT - 1 < wk_first) continue;   // every query of the tile precedes this wave's keys
+
+    f32x16 S, dP;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) S[i] = dP[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < NKD; ++kk) {
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Qr[r * LDR + kk * 16 + 8 * g]), kf[kk], S, 0, 0, 0);
+      dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Gr[r * LDR + kk * 16 + 8 * g]), vf[kk], dP, 0, 0, 0);
+    }
+    float p[16], ds[16];
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const float4 L = *(const float4*)&lse_s[8 * i4 + 4 * g];
+      const float4 D = *(const float4*)&del_s[8 * i4 + 4 * g];
+      const float Lv[4] = {L.x, L.y, L.z, L.w}, Dv[4] = {D.x, D.y, D.z, D.w};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int i = 4 * i4 + t;
+        const int qq = q0 + 8 * i4 + 4 * g + t;
+        const bool vis = qq < T && key < T && (!a.causal || key <= qq);
+        const float pv = vis ? exp2f(S[i] * sc - Lv[t]) : 0.f;
+        p[i] = pv;
+        ds[i] = pv * (dP[i] - Dv[t]);
+      }
+    }
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+      const bf16x8 pb = pack8(&p[8 * st]), db = pack8(&ds[8 * st]);
+      const int kb0 = 16 * st + 4 * g;
+#pragma unroll
+      for (int d = 0; d < NDB; ++d) {
+        accV[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Gt, LDT, kb0, kb0 + 8, d * 32, lane), pb, accV[d], 0, 0, 0);
+        accK[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Qt, LDT, kb0, kb0 + 8, d * 32, lane), db, accK[d], 0, 0, 0);
+      }
+    }
+  }
+  if (key < T) {
+    store_rows_T<NDB>((unsigned short*)a.dK + base + (long)key * rs, accK, a.scale, g, dh);
+    store_rows_T<NDB>((unsigned short*)a.dV + base + (long)key * rs, accV, 1.f, g, dh);
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// backward, dQ: block = 4 waves x 32 queries (Q and dO rows of a wave live in registers);
+// key tiles of K (both read patterns) and V are staged in LDS.
+//   S^T[key][q] = K Q^T, dP^T[key][q] = V dO^T, dS^T = P^T (dP^T - delta),
+//   dQ^T[d][q] += K^T[d][key] dS^T[key][q]
+// ----------------------------------------------------------------------------------------
+template <int DH, int VEC>
+__global__ __launch_bounds__(256) void mfma_attn_dq_kernel(AttnBwdArgs a) {
+  constexpr int KT = DH > 128 ? 32 : 64;
+  constexpr bool SEP = DH <= 128;
+  constexpr int LDR = SEP ? DH + 8 : ld_tr(DH), LDT = ld_tr(DH);
+  constexpr int NKD = DH / 16, NDB = DH / 32;
+  __shared__ __attribute__((aligned(16))) unsigned short Kr[KT * LDR];
+  __shared__ __attribute__((aligned(16))) unsigned short Vr[KT * LDR];
+  __shared__ __attribute__((aligned(16))) unsigned short Kt_[SEP ? KT * LDT : 8];
+  unsigned short* Kt = SEP ? Kt_ : Kr;
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int qt = a.causal ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;
+  const int q0 = qt * 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int T = a.T, dh = a.dh;
+  const long rs = (long)a.H * dh;
+  const long base = ((long)b * T) * rs + (long)h * dh;
+  const unsigned short* Q = (const unsigned short*)a.Q + base;
+  const unsigned short* K = (const unsigned short*)a.K + base;
+  const unsigned short* V = (const unsigned short*)a.V + base;
+  const unsigned short* dO = (const unsigned short*)a.dO + base;
+
+  const int q = q0 + wave * 32 + r;
+  const int wq_last = q0 + wave * 32 + 31;
+  bf16x8 qf[NKD], gf[NKD];
+#pragma unroll
+  for (int kk = 0; kk < NKD; ++kk) {
+    qf[kk] = global_frag<VEC>(Q + (long)q * rs, kk * 16 + 8 * g, dh, q < T);
+    gf[kk] = global_frag<VEC>(dO + (long)q * rs, kk * 16 + 8 * g, dh, q < T);
+  }
+  const float lse2 = q < T ? a.lse[((long)b * a.H + h) * T + q] * 1.44269504088896340736f : 0.f;
+  const float del = q < T ? a.delta[((long)b * T + q) * a.H + h] : 0.f;
+  f32x16 acc[NDB];
+#pragma unroll
+  for (int d = 0; d < NDB; ++d)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[d][i] = 0.f;
+  const float sc = a.scale * 1.44269504088896340736f;
+
+  const int kend = a.causal ? min(T, q0 + 128) : T;
+  for (int k0 = 0; k0 < kend; k0 += KT) {
+    __syncthreads();
+    stage_rows2<DH, VEC>(Kr, LDR, Kt, LDT, K + (long)k0 * rs, rs, KT, T - k0, dh, tid);
+    stage_rows2<DH, VEC>(Vr, LDR, Vr, LDR, V + (long)k0 * rs, rs, KT, T - k0, dh, tid);
+    __syncthreads();
+    if (a.causal && k0 > wq_last) continue;
+#pragma unroll
+    for (int kb = 0; kb < KT / 32; ++kb) {
+      f32x16 S, dP;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[i] = dP[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NKD; ++kk) {
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Kr[(kb * 32 + r) * LDR + kk * 16 + 8 * g]), qf[kk], S, 0, 0, 0);
+        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Vr[(kb * 32 + r) * LDR + kk * 16 + 8 * g]), gf[kk], dP, 0, 0, 0);
+      }
+      float ds[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = k0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+        const bool vis = key < T && (!a.causal || key <= q);
+        const float pv = vis ? exp2f(S[i] * sc - lse2) : 0.f;
+        ds[i] = pv * (dP[i] - del);
+      }
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        const bf16x8 db = pack8(&ds[8 * st]);
+        const int kb0 = kb * 32 + 16 * st + 4 * g;
+#pragma unroll
+        for (int d = 0; d < NDB; ++d)
+          acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Kt, LDT, kb0, kb0 + 8, d * 32, lane), db, acc[d], 0, 0, 0);
+      }
+    }
+  }
+  if (q < T) store_rows_T<NDB>((unsigned short*)a.dQ + base + (long)q * rs, acc, a.scale, g, dh);
+}
+
+static int attn_vec(int dh) { return dh % 8 == 0 ? 8 : (dh % 4 == 0 ? 4 : 0); }
+
+bool mfma_attn_supported(int T, int dh) { return T >= 1 && dh >= 4 && dh <= 256 && attn_vec(dh) != 0; }
 
 template <int DH>
-static void launch_fwd_dh(const AttnArgs& a, hipStream_t s) {
-  dim3 g((a.T + 127) / 128, a.H, a.B);
-  if (attn_vec(a.H, a.dh) == 8)
-    mfma_attn_fwd_kernel<DH, 8><<<g, 256, 0, s>>>(a);
-  else
-    mfma_attn_fwd_kernel<DH, 4><<<g, 256, 0, s>>>(a);
+static void launch_dh(const AttnArgs* f, const AttnBwdArgs* bw, hipStream_t s) {
+  if (f) {
+    dim3 g((f->T + 127) / 128, f->H, f->B);
+    if (attn_vec(f->dh) == 8)
+      mfma_attn_fwd_kernel<DH, 8><<<g, 256, 0, s>>>(*f);
+    else
+      mfma_attn_fwd_kernel<DH, 4><<<g, 256, 0, s>>>(*f);
+  } else {
+    dim3 g((bw->T + 127) / 128, bw->H, bw->B);
+    if (attn_vec(bw->dh) == 8) {
+      mfma_attn_dkv_kernel<DH, 8><<<g, 256, 0, s>>>(*bw);
+      mfma_attn_dq_kernel<DH, 8><<<g, 256, 0, s>>>(*bw);
+    } else {
+      mfma_attn_dkv_kernel<DH, 4><<<g, 256, 0, s>>>(*bw);
+      mfma_attn_dq_kernel<DH, 4><<<g, 256, 0, s>>>(*bw);
+    }
+  }
 }
 
-void launch_mfma_attn_fwd(const AttnArgs& a, hipStream_t s) {
-  const int dh = a.dh;
+static void dispatch_dh(int dh, const AttnArgs* f, const AttnBwdArgs* bw, hipStream_t s) {
   if (dh <= 32)
-    launch_fwd_dh<32>(a, s);
+    launch_dh<32>(f, bw, s);
   else if (dh <= 64)
-    launch_fwd_dh<64>(a, s);
+    launch_dh<64>(f, bw, s);
   else if (dh <= 96)
-    launch_fwd_dh<96>(a, s);
+    launch_dh<96>(f, bw, s);
   else if (dh <= 128)
-    launch_fwd_dh<128>(a, s);
+    launch_dh<128>(f, bw, s);
   else if (dh <= 192)
-    launch_fwd_dh<192>(a, s);
+    launch_dh<192>(f, bw, s);
   else
-    launch_fwd_dh<256>(a, s);
+    launch_dh<256>(f, bw, s);
 }
 
-void launch_mfma_attn_bwd(const AttnBwdArgs& a, hipStream_t s) { launch_simt_attn_bwd(a, 1, s); }
+void launch_mfma_attn_fwd(const AttnArgs& a, hipStream_t s) { dispatch_dh(a.dh, &a, nullptr, s); }
+void launch_mfma_attn_bwd(const AttnBwdArgs& a, hipStream_t s) { dispatch_dh(a.dh, nullptr, &a, s); }
 
 }  // namespace sh
