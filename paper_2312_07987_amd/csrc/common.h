@@ -69,6 +69,12 @@ struct RowGemmArgs {
   int K, Nc;
   int mode;
   int tag;
+  // expert-set mode (nseg > 0): perm holds token ids sorted by expert set, offsets the
+  // nsets+1 set boundaries per head (E = nsets); a tile's rows share nseg = k experts, the
+  // reduction runs over nseg segments of length K: segment p reads the same A row scaled by
+  // segate[h*gate_hstride + token*nseg + p] against B of expert p of the set.
+  int nseg, experts;
+  const float* segate;
 };
 
 // ----------------------------------------------------------------------------------------
@@ -153,9 +159,24 @@ void launch_router(const RouterArgs& a, hipStream_t s);
 void launch_dense_routing(int* idx, float* gate, int* perm, int* offsets, int N, int H, hipStream_t s);
 int router_blocks(int N);  // token blocks used by the histogram/scatter kernels
 
+// Sorting of tokens by expert set (see routing.hip).  nsets = C(E,k) <= 128.
+struct SetSortArgs {
+  const int* idx;      // [sides, H, N, k]
+  const float* gate;   // [sides, H, N, k]
+  int* setid;          // [sides, H, N] scratch
+  float* gset;         // [sides, H, N, k] gates in ascending-expert order
+  int* setperm;        // [sides, H, N] token ids sorted by set id (stable)
+  int* setoff;         // [sides, H, nsets+1]
+  int* blockcnt;       // [sides*H, nblk, nsets] scratch
+  int N, H, k, nsets, sides;
+};
+void launch_set_sort(const SetSortArgs& a, hipStream_t s);
+
 void launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 void launch_cast_from_f32(const float* src, void* dst, size_t n, int bf16, hipStream_t s);
 void launch_cast_to_f32(const void* src, float* dst, size_t n, int bf16, hipStream_t s);
+// out[i] = sum_h part[h*hstride + i] (+ add32[i]) for bf16 part/out; n must be a multiple of 8
+void launch_sum_heads(const void* part, const float* add32, void* out, size_t n, size_t hstride, int H, hipStream_t s);
 
 // out[n,h,:] = sum_j gate[h][n*k+j] * slots[h][n*k+j][:]   (slots fp32 [H, N*k, dh])
 // dots[h][n*k+j] = <other[n,h,:], slots[h][n*k+j][:]>        (if dots != NULL)

@@ -60,8 +60,20 @@ struct Layout {
   size_t total = 0;
   size_t idx, gate, perm, offsets, Q, K, V, ctx, lse, pV;          // saved by forward
   size_t Z, blockcnt, acc32;                                       // forward scratch
+  size_t setid, gset, setperm, setoff, setcnt, yh;                 // expert-set path (bf16 only)
   size_t u, dctx, dQ, dK, dV, delta, dgate, dz;                    // backward scratch
 };
+
+// number of k-subsets of E experts, saturating at MAX_SETS + 1
+constexpr int MAX_SETS = 128;
+int count_sets(int E, int k) {
+  long v = 1;
+  for (int i = 1; i <= k; ++i) {
+    v = v * (E - k + i) / i;
+    if (v > MAX_SETS) return MAX_SETS + 1;
+  }
+  return (int)v;
+}
 
 sh_status check_shape(const sh_shape* s) {
   if (!s) return fail(SH_ERR_INVALID_ARG, "shape is NULL");
@@ -112,6 +124,17 @@ Layout make_layout(const sh_shape* s) {
   L.delta = take(N * H * 4);
   L.dgate = take(2 * H * N * k * 4);
   L.dz = take(N * 2 * H * E * esz);
+  if (s->dtype == SH_BF16 && count_sets(s->E, s->k) <= MAX_SETS) {
+    const size_t ns = count_sets(s->E, s->k);
+    L.setid = take(2 * H * N * 4);
+    L.gset = take(2 * H * N * k * 4);
+    L.setperm = take(2 * H * N * 4);
+    L.setoff = take(2 * H * (ns + 1) * 4);
+    L.setcnt = take(2 * H * (size_t)router_blocks((int)N) * ns * 4);
+    L.yh = take(H * N * dm * esz);
+  } else {
+    L.setid = L.gset = L.setperm = L.setoff = L.setcnt = L.yh = 0;
+  }
   L.total = off;
   return L;
 }
@@ -193,6 +216,28 @@ RowGemmArgs perm_rows(const Ctx& c, int side) {
   a.a_div = c.k;
   a.c_div = 1;
   return a;
+}
+
+// rows taken through the expert-set permutation of one side (one row per token and head)
+RowGemmArgs set_rows(const Ctx& c, int side) {
+  RowGemmArgs a{};
+  const int ns = count_sets(c.E, c.k);
+  a.perm = c.p<int>(c.L.setperm) + (size_t)side * c.H * c.N;
+  a.offsets = c.p<int>(c.L.setoff) + (size_t)side * c.H * (ns + 1);
+  a.heads = c.H;
+  a.E = ns;
+  a.M = c.N;
+  a.a_div = 1;
+  a.c_div = 1;
+  a.nseg = c.k;
+  a.experts = c.E;
+  a.segate = c.p<float>(c.L.gset) + (size_t)side * c.H * c.N * c.k;
+  a.gate_hstride = (long)c.N * c.k;
+  return a;
+}
+
+bool sets_usable(const Ctx& c) {
+  return use_mfma(c) && count_sets(c.E, c.k) <= MAX_SETS && c.dm % 8 == 0 && c.dh % 8 == 0;
 }
 
 RowGemmArgs identity_rows(const Ctx& c, int heads) {
@@ -315,6 +360,25 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     (void)hipMemcpyAsync(c.offsets(1), c.offsets(0), (size_t)H * (E + 1) * 4, hipMemcpyDeviceToDevice, c.st);
   }
 
+  const bool sets = sets_usable(c);
+  if (sets) {
+    prof_mark(c.st, "fwd.set_sort");
+    SetSortArgs sa{};
+    sa.idx = c.idx(0);
+    sa.gate = c.gate(0);
+    sa.setid = c.p<int>(c.L.setid);
+    sa.gset = c.p<float>(c.L.gset);
+    sa.setperm = c.p<int>(c.L.setperm);
+    sa.setoff = c.p<int>(c.L.setoff);
+    sa.blockcnt = c.p<int>(c.L.setcnt);
+    sa.N = N;
+    sa.H = H;
+    sa.k = k;
+    sa.nsets = count_sets(E, k);
+    sa.sides = 2;
+    launch_set_sort(sa, c.st);
+  }
+
   // step 2: dense queries and keys
   for (int which = 0; which < 2; ++which) {
     prof_mark(c.st, which ? "fwd.k_proj" : "fwd.q_proj");
@@ -388,7 +452,33 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
       launch_simt_attn_fwd(a, c.bf16, c.st);
   }
 
-  // step 5: output experts, gate-scaled, summed over heads and slots in fp32
+  // step 5: output experts.  Expert-set path: per head one GEMM whose reduction runs over the
+  // k gate-scaled copies of the token's read-out row, then the sum over heads.
+  if (sets) {
+    prof_mark(c.st, "fwd.o_experts");
+    RowGemmArgs a = set_rows(c, 1);
+    a.tag = TAG_O_EXPERTS;
+    a.A = c.p<void>(c.L.ctx);
+    a.lda = hd;
+    a.a_hoff = dh;
+    a.B = W_O;
+    a.b_hstride = (long)E * dh * dm;
+    a.b_estride = (long)dh * dm;
+    a.sbk = dm;
+    a.sbn = 1;
+    a.C = H == 1 ? y : c.p<void>(c.L.yh);
+    a.ldc = dm;
+    a.c_hoff = (long)N * dm;
+    a.K = dh;
+    a.Nc = dm;
+    a.mode = STORE_T;
+    launch_mfma_row_gemm(a, c.st);
+    if (H > 1) {
+      prof_mark(c.st, "fwd.y_sum");
+      launch_sum_heads(c.p<void>(c.L.yh), nullptr, y, (size_t)N * dm, (size_t)N * dm, H, c.st);
+    }
+  } else
+  // fallback: expert-sorted rows, gate-scaled, summed over heads and slots with fp32 atomics
   {
     prof_mark(c.st, "fwd.y_zero");
     float* acc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)y;
@@ -433,6 +523,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   const int N = c.N, H = c.H, E = c.E, k = c.k, dh = c.dh, dm = c.dm;
   const long hd = (long)H * dh;
   const int chunk = 1024;
+  const bool sets = sets_usable(c);
 
   prof_mark(c.st, "bwd.zero_dw");
   launch_fill_f32(dW_Q, (size_t)H * dm * dh, 0.f, c.st);
@@ -568,9 +659,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.chunk = chunk;
     wgrad(c, w);
     prof_mark(c.st, "bwd.v_dgrad");
-    RowGemmArgs a = perm_rows(c, 0);
+    RowGemmArgs a = sets ? set_rows(c, 0) : perm_rows(c, 0);
     a.tag = TAG_V_DGRAD;
-    a.c_div = k;
     a.A = c.p<void>(c.L.dV);
     a.lda = hd;
     a.a_hoff = dh;
@@ -579,14 +669,24 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.b_estride = (long)dm * dh;
     a.sbk = 1;
     a.sbn = dh;
-    a.C = dxacc;
-    a.ldc = dm;
-    a.gate = c.gate(0);
-    a.gate_hstride = (long)N * k;
     a.K = dh;
     a.Nc = dm;
-    a.mode = ATOMIC_F32;
-    row_gemm(c, a);
+    if (sets) {
+      // per-head partial sums of dx in bf16; they are added to the rest of dx at the end
+      a.C = c.p<void>(c.L.yh);
+      a.ldc = dm;
+      a.c_hoff = (long)N * dm;
+      a.mode = STORE_T;
+      launch_mfma_row_gemm(a, c.st);
+    } else {
+      a.c_div = k;
+      a.C = dxacc;
+      a.ldc = dm;
+      a.gate = c.gate(0);
+      a.gate_hstride = (long)N * k;
+      a.mode = ATOMIC_F32;
+      row_gemm(c, a);
+    }
   }
 
   // dense queries and keys
@@ -693,7 +793,10 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     }
   }
   prof_mark(c.st, "bwd.dx_cast");
-  if (c.bf16) launch_cast_from_f32(dxacc, dx, (size_t)N * dm, 1, c.st);
+  if (sets)
+    launch_sum_heads(c.p<void>(c.L.yh), dxacc, dx, (size_t)N * dm, (size_t)N * dm, H, c.st);
+  else if (c.bf16)
+    launch_cast_from_f32(dxacc, dx, (size_t)N * dm, 1, c.st);
   prof_mark(c.st, nullptr);
   return check_launch("switchhead_backward");
 }

@@ -81,14 +81,15 @@ constexpr int LDB_NN = BN + 32;    // B tile [BK][LDB_NN] when n is contiguous i
 constexpr int B_ELEMS = (BN * LDB_NT > BK * LDB_NN) ? BN * LDB_NT : BK * LDB_NN;
 }  // namespace rg
 
-template <int VEC, bool BNT, int TAG>
+template <int VEC, bool BNT, int TAG, bool SETS = false>
 __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
   using namespace rg;
   typedef typename Chunk<VEC>::type chunk_t;
   __shared__ __attribute__((aligned(16))) unsigned short As[2][BM * LDA];
   __shared__ __attribute__((aligned(16))) unsigned short Bs[2][B_ELEMS];
   __shared__ int ids[BM];
-  __shared__ float gsc[BM];
+  __shared__ float gsc[SETS ? BM * 8 : BM];   // SETS: [row][segment]
+  __shared__ long bseg[8];                    // SETS: B offset of each segment's expert
 
   const int h = blockIdx.z;
   int e = 0, row0, rows;
@@ -100,20 +101,47 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
     rows = a.M - row0 < BM ? a.M - row0 : BM;
   }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nseg = SETS ? a.nseg : 1;
   if (tid < BM) {
     int id = -1;
     float g = 0.f;
     if (tid < rows) {
       id = a.perm ? a.perm[(long)h * a.M + row0 + tid] : row0 + tid;
-      g = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
+      if constexpr (!SETS) g = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
     }
     ids[tid] = id;
-    gsc[tid] = g;
+    if constexpr (!SETS) gsc[tid] = g;
+  }
+  if constexpr (SETS) {
+    for (int t = tid; t < BM * nseg; t += 256) {
+      int rr = t / nseg, p = t % nseg;
+      float g = 0.f;
+      if (rr < rows) g = a.segate[(long)h * a.gate_hstride + (long)a.perm[(long)h * a.M + row0 + rr] * nseg + p];
+      gsc[rr * 8 + p] = g;
+    }
+    if (tid == 0) {
+      // unrank the combination: set id e -> ascending experts
+      int rank = e;
+      for (int p = nseg - 1; p >= 0; --p) {
+        int x = p;   // smallest candidate: C(p, p+1) = 0
+        while (x + 1 < a.experts) {
+          long v = 1;
+          for (int i = 1; i <= p + 1; ++i) v = v * (x + 1 - (p + 1) + i) / i;   // C(x+1, p+1)
+          if (v > rank) break;
+          ++x;
+        }
+        long v = 1;
+        for (int i = 1; i <= p + 1; ++i) v = v * (x - (p + 1) + i) / i;          // C(x, p+1)
+        if (x < p + 1) v = 0;
+        rank -= (int)v;
+        bseg[p] = (long)h * a.b_hstride + (long)x * a.b_estride;
+      }
+    }
   }
   __syncthreads();
 
   const unsigned short* A = (const unsigned short*)a.A;
-  const unsigned short* B = (const unsigned short*)a.B + (long)h * a.b_hstride + (long)e * a.b_estride;
+  const unsigned short* B = (const unsigned short*)a.B + (SETS ? 0 : (long)h * a.b_hstride + (long)e * a.b_estride);
   const int n0 = blockIdx.y * BN;
   const int K = a.K, Nc = a.Nc;
 
@@ -156,20 +184,27 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
   }
 
   chunk_t ra[A_N], rb[B_N];
-  auto load_global = [&](int k0) {
+  const int nks = (K + BK - 1) / BK;   // K steps per segment
+  auto load_global = [&](int it) {
+    const int seg = SETS ? it / nks : 0;
+    const int k0 = (SETS ? it % nks : it) * BK;
+    const unsigned short* Bs_ = SETS ? B + bseg[seg] : B;
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
       ra[i] = zero_chunk<VEC>();
-      if (a_off[i] >= 0 && k0 + a_kc[i] < K) ra[i] = *(const chunk_t*)(A + a_off[i] + k0);
+      if (a_off[i] >= 0 && k0 + a_kc[i] < K) {
+        ra[i] = *(const chunk_t*)(A + a_off[i] + k0);
+        if constexpr (SETS) ra[i] = scale_chunk(ra[i], gsc[(a_lds[i] / LDA) * 8 + seg]);
+      }
     }
 #pragma unroll
     for (int i = 0; i < B_N; ++i) {
       rb[i] = zero_chunk<VEC>();
       if (b_ok[i] && k0 + b_kc[i] < K) {
         if constexpr (BNT)
-          rb[i] = *(const chunk_t*)(B + b_off[i] + k0);
+          rb[i] = *(const chunk_t*)(Bs_ + b_off[i] + k0);
         else
-          rb[i] = *(const chunk_t*)(B + b_off[i] + (long)k0 * a.sbk);
+          rb[i] = *(const chunk_t*)(Bs_ + b_off[i] + (long)k0 * a.sbk);
       }
     }
   };
@@ -190,13 +225,13 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-  const int nk = (K + BK - 1) / BK;
+  const int nk = nks * nseg;
   load_global(0);
   store_lds(0);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) load_global((kt + 1) * BK);
+    if (kt + 1 < nk) load_global(kt + 1);
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 fa[2], fb[2];
@@ -226,7 +261,7 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
       const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
       const int id = ids[row];
       if (id < 0) continue;
-      const float sc = gsc[row];
+      const float sc = SETS ? 1.f : gsc[row];
       const long crow = (long)(id / a.c_div) * a.ldc + (long)h * a.c_hoff;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
@@ -270,6 +305,17 @@ void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s) {
   const int vec = row_gemm_vec(a);
   const bool nt = a.sbk == 1;
   dim3 g((a.M + rg::BM - 1) / rg::BM + (a.perm ? a.E : 0), (a.Nc + rg::BN - 1) / rg::BN, a.heads);
+  if (a.nseg > 0) {
+    if (vec == 8 && nt)
+      mfma_row_gemm_kernel<8, true, TAG_V_DGRAD, true><<<g, 256, 0, s>>>(a);
+    else if (vec == 8)
+      mfma_row_gemm_kernel<8, false, TAG_O_EXPERTS, true><<<g, 256, 0, s>>>(a);
+    else if (nt)
+      mfma_row_gemm_kernel<4, true, TAG_GENERIC, true><<<g, 256, 0, s>>>(a);
+    else
+      mfma_row_gemm_kernel<4, false, TAG_GENERIC, true><<<g, 256, 0, s>>>(a);
+    return;
+  }
   if (vec == 8 && nt) {
     switch (a.tag) {
       case TAG_O_DGRAD: mfma_row_gemm_kernel<8, true, TAG_O_DGRAD><<<g, 256, 0, s>>>(a); break;

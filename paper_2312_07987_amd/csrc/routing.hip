@@ -119,9 +119,9 @@ __global__ __launch_bounds__(RB) void topk_hist_kernel(const double* __restrict_
 
 // One block per (side, head).  blockcnt[sh][blk][e] (counts) -> in place: first position of
 // expert e for token block blk; offsets[sh][0..E].
-__global__ __launch_bounds__(64) void scan_kernel(int* __restrict__ blockcnt, int* __restrict__ offsets, int E,
+__global__ __launch_bounds__(128) void scan_kernel(int* __restrict__ blockcnt, int* __restrict__ offsets, int E,
                                                   int nblk) {
-  __shared__ int tot[65];
+  __shared__ int tot[129];
   const int sh_ = blockIdx.x;
   const int e = threadIdx.x;
   int* c = blockcnt + (long)sh_ * nblk * E;
@@ -219,8 +219,100 @@ void launch_router(const RouterArgs& a, hipStream_t s) {
   const int nblk = router_blocks(a.N);
   dim3 g2(nblk, a.sides * a.H);
   topk_hist_kernel<<<g2, RB, 0, s>>>(a.Z, a.idx, a.gate, a.blockcnt, a.N, a.H, a.E, a.k, nblk);
-  scan_kernel<<<a.sides * a.H, 64, 0, s>>>(a.blockcnt, a.offsets, a.E, nblk);
+  scan_kernel<<<a.sides * a.H, 128, 0, s>>>(a.blockcnt, a.offsets, a.E, nblk);
   scatter_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.perm, a.N, a.E, a.k, nblk);
+}
+
+// ----------------------------------------------------------------------------------------
+// Expert-SET sorting.  A token's k experts of one head form one of C(E,k) sets; tokens that
+// share a set share all k weight matrices, so the k gate-weighted products of Sec. 2.2's
+// output equation can be summed inside one matrix-core accumulator.  Set id = rank of the
+// ascending combination (combinatorial number system), tokens are counting-sorted by it.
+// ----------------------------------------------------------------------------------------
+__device__ __forceinline__ int binom(int n, int r) {
+  if (r < 0 || r > n) return 0;
+  long v = 1;
+  for (int i = 1; i <= r; ++i) v = v * (n - r + i) / i;
+  return (int)v;
+}
+
+__global__ __launch_bounds__(RB) void set_hist_kernel(const int* __restrict__ idx, const float* __restrict__ gate,
+                                                      int* __restrict__ setid, float* __restrict__ gset,
+                                                      int* __restrict__ blockcnt, int N, int k, int nsets, int nblk) {
+  __shared__ int cnt[128];
+  const int sh_ = blockIdx.y;
+  const int n = blockIdx.x * RB + threadIdx.x;
+  const bool valid = n < N;
+  if (threadIdx.x < 128) cnt[threadIdx.x] = 0;
+  __syncthreads();
+  int sid = -1;
+  if (valid) {
+    int e[8];
+    float g[8];
+    const long o = ((long)sh_ * N + n) * k;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      e[j] = j < k ? idx[o + j] : 0x7fffffff;
+      g[j] = j < k ? gate[o + j] : 0.f;
+    }
+    // ascending experts (k <= 8: odd-even transposition sort with static indexing)
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass)
+#pragma unroll
+      for (int j = pass & 1; j + 1 < 8; j += 2)
+        if (e[j] > e[j + 1]) {
+          int te = e[j];
+          e[j] = e[j + 1];
+          e[j + 1] = te;
+          float tg = g[j];
+          g[j] = g[j + 1];
+          g[j + 1] = tg;
+        }
+    sid = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < k) {
+        sid += binom(e[j], j + 1);
+        gset[o + j] = g[j];
+      }
+    setid[(long)sh_ * N + n] = sid;
+  }
+  const int lane = threadIdx.x & 63;
+  for (int s = 0; s < nsets; ++s) {
+    unsigned long long bal = __ballot(sid == s);
+    if (lane == 0 && bal) atomicAdd(&cnt[s], __popcll(bal));
+  }
+  __syncthreads();
+  if (threadIdx.x < nsets) blockcnt[((long)sh_ * nblk + blockIdx.x) * nsets + threadIdx.x] = cnt[threadIdx.x];
+}
+
+__global__ __launch_bounds__(RB) void set_scatter_kernel(const int* __restrict__ setid, const int* __restrict__ base,
+                                                         int* __restrict__ setperm, int N, int nsets, int nblk) {
+  __shared__ int wcnt[RB / 64][128];
+  const int sh_ = blockIdx.y;
+  const int n = blockIdx.x * RB + threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sid = n < N ? setid[(long)sh_ * N + n] : -1;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  int rk = 0;
+  for (int s = 0; s < nsets; ++s) {
+    unsigned long long bal = __ballot(sid == s);
+    if (sid == s) rk = __popcll(bal & lt);
+    if (lane == 0) wcnt[wave][s] = __popcll(bal);
+  }
+  __syncthreads();
+  if (sid < 0) return;
+  int pos = base[((long)sh_ * nblk + blockIdx.x) * nsets + sid] + rk;
+  for (int w = 0; w < wave; ++w) pos += wcnt[w][sid];
+  setperm[(long)sh_ * N + pos] = n;
+}
+
+void launch_set_sort(const SetSortArgs& a, hipStream_t s) {
+  const int nblk = router_blocks(a.N);
+  dim3 g(nblk, a.sides * a.H);
+  set_hist_kernel<<<g, RB, 0, s>>>(a.idx, a.gate, a.setid, a.gset, a.blockcnt, a.N, a.k, a.nsets, nblk);
+  scan_kernel<<<a.sides * a.H, 128, 0, s>>>(a.blockcnt, a.setoff, a.nsets, nblk);
+  set_scatter_kernel<<<g, RB, 0, s>>>(a.setid, a.blockcnt, a.setperm, a.N, a.nsets, nblk);
 }
 
 void launch_dense_routing(int* idx, float* gate, int* perm, int* offsets, int N, int H, hipStream_t s) {

@@ -50,6 +50,42 @@ void launch_cast_to_f32(const void* src, float* dst, size_t n, int bf16, hipStre
     cast_to_f32_kernel<float><<<grid_for(n, 256), 256, 0, s>>>((const float*)src, dst, n);
 }
 
+// out[i] = sum_h part[h][i] (+ add32[i]); part and out are bf16, 8 elements per thread.
+__global__ __launch_bounds__(256) void sum_heads_kernel(const unsigned short* __restrict__ part, const float* __restrict__ add32,
+                                                        unsigned short* __restrict__ out, size_t n8, size_t hstride, int H) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n8) return;
+  float acc[8];
+  if (add32) {
+    const float4 a0 = *(const float4*)(add32 + i * 8), a1 = *(const float4*)(add32 + i * 8 + 4);
+    acc[0] = a0.x; acc[1] = a0.y; acc[2] = a0.z; acc[3] = a0.w;
+    acc[4] = a1.x; acc[5] = a1.y; acc[6] = a1.z; acc[7] = a1.w;
+  } else {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = 0.f;
+  }
+  for (int h = 0; h < H; ++h) {
+    const uint4 v = *(const uint4*)(part + (size_t)h * hstride + i * 8);
+    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      acc[2 * t] += __uint_as_float(w[t] << 16);
+      acc[2 * t + 1] += __uint_as_float(w[t] & 0xffff0000u);
+    }
+  }
+  uint4 o;
+  o.x = (unsigned)f32_to_bf16(acc[0]) | ((unsigned)f32_to_bf16(acc[1]) << 16);
+  o.y = (unsigned)f32_to_bf16(acc[2]) | ((unsigned)f32_to_bf16(acc[3]) << 16);
+  o.z = (unsigned)f32_to_bf16(acc[4]) | ((unsigned)f32_to_bf16(acc[5]) << 16);
+  o.w = (unsigned)f32_to_bf16(acc[6]) | ((unsigned)f32_to_bf16(acc[7]) << 16);
+  *(uint4*)(out + i * 8) = o;
+}
+
+void launch_sum_heads(const void* part, const float* add32, void* out, size_t n, size_t hstride, int H, hipStream_t s) {
+  const size_t n8 = n / 8;
+  if (n8) sum_heads_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, s>>>((const unsigned short*)part, add32, (unsigned short*)out, n8, hstride, H);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
