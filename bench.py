@@ -38,7 +38,8 @@ def step_work(cfg):
     router = 2 * N * dm * 2 * H * E
     slots = N * H * k * dh * 4
     flops = {
-        "fwd.q_proj": proj, "fwd.k_proj": proj, "fwd.v_experts": expert, "fwd.o_experts": expert,
+        "fwd.q_proj": proj, "fwd.k_proj": proj, "fwd.qk_proj": 2 * proj, "bwd.qk_dgrad": 2 * proj,
+        "fwd.v_experts": expert, "fwd.o_experts": expert,
         "fwd.attention": attn, "bwd.attention": 5 * attn // 2,
         "bwd.o_dgrad": expert, "bwd.o_wgrad": expert, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
         "bwd.q_wgrad": proj, "bwd.k_wgrad": proj, "bwd.q_dgrad": proj, "bwd.k_dgrad": proj,
@@ -50,6 +51,7 @@ def step_work(cfg):
         "bwd.dctx_combine": slots + 2 * N * H * dh * es + 2 * N * H * k * 4,
         "bwd.dgate_s": slots + N * H * dh * es + N * H * k * 4,
         "fwd.y_zero": N * dm * 4, "bwd.dx_zero": N * dm * 4,
+        "fwd.y_sum": N * dm * es * (H + 1), "fwd.set_sort": 2 * H * N * (k * 8 + 12),
         "fwd.y_cast": N * dm * (4 + es), "bwd.dx_cast": N * dm * (4 + es),
         "bwd.zero_dw": 4 * (2 * H * dm * dh + 2 * H * E * dm * dh),
         "bwd.router": 4 * H * N * k * 4 + N * 2 * H * E * es,

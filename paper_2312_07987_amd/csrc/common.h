@@ -69,12 +69,23 @@ struct RowGemmArgs {
   int K, Nc;
   int mode;
   int tag;
-  // expert-set mode (nseg > 0): perm holds token ids sorted by expert set, offsets the
-  // nsets+1 set boundaries per head (E = nsets); a tile's rows share nseg = k experts, the
-  // reduction runs over nseg segments of length K: segment p reads the same A row scaled by
-  // segate[h*gate_hstride + token*nseg + p] against B of expert p of the set.
-  int nseg, experts;
+  int max_group_rows;   // upper bound of the rows of one group (tokens per call)
+  // Second operand set: heads h >= hsplit (hsplit > 0) use B2 / C2 with head index h - hsplit
+  // (queries and keys projected by one launch).
+  const void* B2;
+  void* C2;
+  int hsplit;
+  // Segmented reduction, seg_mode:
+  //  1  expert sets: perm holds token ids sorted by expert set, offsets the nsets+1 set
+  //     boundaries per head (E = nsets); the reduction runs over nseg = k segments of length
+  //     K: segment p reads the same A row scaled by segate[h*gate_hstride + token*nseg + p]
+  //     against B of the p-th (ascending) expert of the set.
+  //  2  concatenation: segment p reads A columns (p/seg_split)*a_wstride + (p%seg_split)*a_sstride
+  //     against (p/seg_split ? B2 : B) + (p%seg_split)*b_sstride.
+  int seg_mode, nseg, experts;
   const float* segate;
+  int seg_split;
+  long a_sstride, a_wstride, b_sstride;
 };
 
 // ----------------------------------------------------------------------------------------

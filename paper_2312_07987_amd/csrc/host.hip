@@ -213,6 +213,7 @@ RowGemmArgs perm_rows(const Ctx& c, int side) {
   a.heads = c.H;
   a.E = c.E;
   a.M = c.N * c.k;
+  a.max_group_rows = c.N;
   a.a_div = c.k;
   a.c_div = 1;
   return a;
@@ -229,6 +230,8 @@ RowGemmArgs set_rows(const Ctx& c, int side) {
   a.M = c.N;
   a.a_div = 1;
   a.c_div = 1;
+  a.max_group_rows = c.N;
+  a.seg_mode = 1;
   a.nseg = c.k;
   a.experts = c.E;
   a.segate = c.p<float>(c.L.gset) + (size_t)side * c.H * c.N * c.k;
@@ -379,25 +382,39 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     launch_set_sort(sa, c.st);
   }
 
-  // step 2: dense queries and keys
-  for (int which = 0; which < 2; ++which) {
-    prof_mark(c.st, which ? "fwd.k_proj" : "fwd.q_proj");
-    RowGemmArgs a = identity_rows(c, H);
+  // step 2: dense queries and keys (one launch for both when the MFMA kernel takes it)
+  {
+    RowGemmArgs a = identity_rows(c, 2 * H);
     a.tag = TAG_QK_PROJ;
     a.A = x;
     a.lda = dm;
     a.a_hoff = 0;
-    a.B = which ? W_K : W_Q;
+    a.B = W_Q;
+    a.B2 = W_K;
+    a.hsplit = H;
     a.b_hstride = (long)dm * dh;
     a.sbk = dh;
     a.sbn = 1;
-    a.C = c.p<void>(which ? c.L.K : c.L.Q);
+    a.C = c.p<void>(c.L.Q);
+    a.C2 = c.p<void>(c.L.K);
     a.ldc = hd;
     a.c_hoff = dh;
     a.K = dm;
     a.Nc = dh;
     a.mode = STORE_T;
-    row_gemm(c, a);
+    if (use_mfma(c) && mfma_row_gemm_supported(a)) {
+      prof_mark(c.st, "fwd.qk_proj");
+      launch_mfma_row_gemm(a, c.st);
+    } else {
+      a.heads = H;
+      a.hsplit = 0;
+      for (int which = 0; which < 2; ++which) {
+        prof_mark(c.st, which ? "fwd.k_proj" : "fwd.q_proj");
+        a.B = which ? W_K : W_Q;
+        a.C = c.p<void>(which ? c.L.K : c.L.Q);
+        row_gemm(c, a);
+      }
+    }
   }
 
   // step 3: value experts, unscaled per-slot results, then the gate-weighted sum over slots
@@ -616,10 +633,83 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       launch_simt_attn_bwd(a, c.bf16, c.st);
   }
 
-  // value experts: d(gate_S), dW_V, dx
-  prof_mark(c.st, "bwd.dx_zero");
+  // dense queries and keys: weight gradients, then dx = dQ W_Q^T + dK W_K^T.  With the MFMA
+  // kernel this is one GEMM whose reduction runs over the 2*nheads (projection, head) segments
+  // and that overwrites the fp32 dx accumulator; otherwise the accumulator is zeroed and every
+  // head adds its part atomically.
   float* dxacc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)dx;
-  launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
+  for (int which = 0; which < 2; ++which) {
+    const void* g = c.p<void>(which ? c.L.dK : c.L.dQ);
+    prof_mark(c.st, which ? "bwd.k_wgrad" : "bwd.q_wgrad");
+    WgradArgs w{};
+    w.tag = TAG_QK_WGRAD;
+    w.heads = H;
+    w.E = 1;
+    w.M = N;
+    w.a_div = 1;
+    w.b_div = 1;
+    w.A = x;
+    w.lda = dm;
+    w.a_hoff = 0;
+    w.Ka = dm;
+    w.Bm = g;
+    w.ldb = hd;
+    w.b_hoff = dh;
+    w.Kb = dh;
+    w.dW = which ? dW_K : dW_Q;
+    w.w_hstride = (long)dm * dh;
+    w.swa = dh;
+    w.chunk = chunk;
+    wgrad(c, w);
+  }
+  {
+    RowGemmArgs a = identity_rows(c, 1);
+    a.tag = TAG_QK_DGRAD;
+    a.A = c.p<void>(c.L.dQ);
+    a.lda = hd;
+    a.seg_mode = 2;
+    a.nseg = 2 * H;
+    a.seg_split = H;
+    a.a_sstride = dh;
+    a.a_wstride = (long)((c.L.dK - c.L.dQ) / (c.bf16 ? 2 : 4));
+    a.B = W_Q;
+    a.B2 = W_K;
+    a.b_sstride = (long)dm * dh;
+    a.sbk = 1;
+    a.sbn = dh;
+    a.C = dxacc;
+    a.ldc = dm;
+    a.K = dh;
+    a.Nc = dm;
+    a.mode = STORE_F32;
+    if (use_mfma(c) && mfma_row_gemm_supported(a)) {
+      prof_mark(c.st, "bwd.qk_dgrad");
+      launch_mfma_row_gemm(a, c.st);
+    } else {
+      prof_mark(c.st, "bwd.dx_zero");
+      launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
+      for (int which = 0; which < 2; ++which) {
+        prof_mark(c.st, which ? "bwd.k_dgrad" : "bwd.q_dgrad");
+        RowGemmArgs b = identity_rows(c, H);
+        b.tag = TAG_QK_DGRAD;
+        b.A = c.p<void>(which ? c.L.dK : c.L.dQ);
+        b.lda = hd;
+        b.a_hoff = dh;
+        b.B = which ? W_K : W_Q;
+        b.b_hstride = (long)dm * dh;
+        b.sbk = 1;
+        b.sbn = dh;
+        b.C = dxacc;
+        b.ldc = dm;
+        b.K = dh;
+        b.Nc = dm;
+        b.mode = ATOMIC_F32;
+        row_gemm(c, b);
+      }
+    }
+  }
+
+  // value experts: d(gate_S), dW_V, dx
   {
     prof_mark(c.st, "bwd.dgate_s");
     SlotArgs sa{};
@@ -687,48 +777,6 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       a.mode = ATOMIC_F32;
       row_gemm(c, a);
     }
-  }
-
-  // dense queries and keys
-  for (int which = 0; which < 2; ++which) {
-    const void* g = c.p<void>(which ? c.L.dK : c.L.dQ);
-    prof_mark(c.st, which ? "bwd.k_wgrad" : "bwd.q_wgrad");
-    WgradArgs w{};
-    w.tag = TAG_QK_WGRAD;
-    w.heads = H;
-    w.E = 1;
-    w.M = N;
-    w.a_div = 1;
-    w.b_div = 1;
-    w.A = x;
-    w.lda = dm;
-    w.a_hoff = 0;
-    w.Ka = dm;
-    w.Bm = g;
-    w.ldb = hd;
-    w.b_hoff = dh;
-    w.Kb = dh;
-    w.dW = which ? dW_K : dW_Q;
-    w.w_hstride = (long)dm * dh;
-    w.swa = dh;
-    w.chunk = chunk;
-    wgrad(c, w);
-    prof_mark(c.st, which ? "bwd.k_dgrad" : "bwd.q_dgrad");
-    RowGemmArgs a = identity_rows(c, H);
-    a.tag = TAG_QK_DGRAD;
-    a.A = g;
-    a.lda = hd;
-    a.a_hoff = dh;
-    a.B = which ? W_K : W_Q;
-    a.b_hstride = (long)dm * dh;
-    a.sbk = 1;
-    a.sbn = dh;
-    a.C = dxacc;
-    a.ldc = dm;
-    a.K = dh;
-    a.Nc = dm;
-    a.mode = ATOMIC_F32;
-    row_gemm(c, a);
   }
 
   // routers

@@ -70,49 +70,90 @@ __device__ __forceinline__ uint4 scale_chunk(uint4 c, float g) {
 __device__ __forceinline__ uint2 scale_chunk(uint2 c, float g) { return make_uint2(scale_pair(c.x, g), scale_pair(c.y, g)); }
 
 // ----------------------------------------------------------------------------------------
-// Row GEMM.  Block tile 128 x 128, K step 32, 4 waves as 2 x 2, each 64 x 64 = 2 x 2 MFMA
-// blocks.  Global -> registers -> LDS software pipeline with two LDS buffers.
+// Work-group placement.  Consecutive work-group ids are dealt round-robin to the 8 XCDs,
+// each with its own L2.  decode_block turns a linear id into (window, slot) such that all
+// `per_window` slots of window w run on XCD w % 8 back to back: work-groups that read the
+// same rows (the column tiles of a row tile; the same token window of every expert) then
+// meet in one L2 instead of fetching the rows from HBM once per XCD.
+// ----------------------------------------------------------------------------------------
+__device__ __forceinline__ void decode_block(int L, int per_window, int& w, int& slot) {
+  const int S = 8 * per_window;
+  const int w8 = L / S, rr = L % S;
+  w = w8 * 8 + (rr & 7);
+  slot = rr >> 3;
+}
+static inline unsigned grid_windows(int nwin, int per_window) { return (unsigned)(((nwin + 7) / 8) * 8) * per_window; }
+
+// ----------------------------------------------------------------------------------------
+// Row GEMM.  Block tile 128 x 128, K step 64 (a full 128-byte line of every gathered row per
+// step), 4 waves as 2 x 2, each 64 x 64 = 2 x 2 MFMA blocks.  One LDS stage; the next K step
+// is fetched into registers while the current one is multiplied.
 // ----------------------------------------------------------------------------------------
 namespace rg {
-constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int LDA = BK + 8;        // A tile [BM][LDA], k contiguous
 constexpr int LDB_NT = BK + 8;     // B tile [BN][LDB_NT] when k is contiguous in memory
 constexpr int LDB_NN = BN + 32;    // B tile [BK][LDB_NN] when n is contiguous in memory
 constexpr int B_ELEMS = (BN * LDB_NT > BK * LDB_NN) ? BN * LDB_NT : BK * LDB_NN;
+constexpr int LDC = BN + 8;        // staged output tile
+static_assert(BM * LDC <= BM * LDA + B_ELEMS, "output staging must fit in the operand tiles");
 }  // namespace rg
 
-template <int VEC, bool BNT, int TAG, bool SETS = false>
+template <int VEC, bool BNT, int TAG, int SEG>
 __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
   using namespace rg;
   typedef typename Chunk<VEC>::type chunk_t;
-  __shared__ __attribute__((aligned(16))) unsigned short As[2][BM * LDA];
-  __shared__ __attribute__((aligned(16))) unsigned short Bs[2][B_ELEMS];
+  __shared__ __attribute__((aligned(16))) unsigned short smem[BM * LDA + B_ELEMS];
   __shared__ int ids[BM];
-  __shared__ float gsc[SETS ? BM * 8 : BM];   // SETS: [row][segment]
-  __shared__ long bseg[8];                    // SETS: B offset of each segment's expert
+  __shared__ float gsc[SEG == 1 ? BM * 8 : BM];   // SEG 1: [row][segment]
+  __shared__ long bseg[8];                        // SEG 1: B offset of each segment's expert
+  unsigned short* As = smem;
+  unsigned short* Bs = smem + BM * LDA;
 
-  const int h = blockIdx.z;
-  int e = 0, row0, rows;
-  if (a.perm) {
-    if (!find_tile(a.offsets + (long)h * (a.E + 1), a.E, BM, blockIdx.x, e, row0, rows)) return;
+  // ---- which tile ------------------------------------------------------------------------
+  const int ncol = (a.Nc + BN - 1) / BN;
+  int h, e = 0, row0, rows, ct, w, slot;
+  if constexpr (SEG == 1) {
+    decode_block(blockIdx.x, ncol, w, slot);
+    ct = slot;
+    const int tph = (a.M + BM - 1) / BM + a.E;   // upper bound of the row tiles of one head
+    h = w / tph;
+    if (h >= a.heads) return;
+    if (!find_tile(a.offsets + (long)h * (a.E + 1), a.E, BM, w % tph, e, row0, rows)) return;
   } else {
-    row0 = blockIdx.x * BM;
-    if (row0 >= a.M) return;
-    rows = a.M - row0 < BM ? a.M - row0 : BM;
+    decode_block(blockIdx.x, a.heads * a.E * ncol, w, slot);
+    const int grp = slot / ncol;
+    ct = slot % ncol;
+    h = grp / a.E;
+    e = grp % a.E;
+    if (a.perm) {
+      const int* off = a.offsets + (long)h * (a.E + 1);
+      row0 = off[e] + w * BM;
+      const int end = off[e + 1];
+      if (row0 >= end) return;
+      rows = end - row0 < BM ? end - row0 : BM;
+    } else {
+      row0 = w * BM;
+      if (row0 >= a.M) return;
+      rows = a.M - row0 < BM ? a.M - row0 : BM;
+    }
   }
+  const bool second = a.hsplit > 0 && h >= a.hsplit;
+  const int hh = second ? h - a.hsplit : h;
+
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nseg = SETS ? a.nseg : 1;
+  const int nseg = SEG ? a.nseg : 1;
   if (tid < BM) {
     int id = -1;
     float g = 0.f;
     if (tid < rows) {
       id = a.perm ? a.perm[(long)h * a.M + row0 + tid] : row0 + tid;
-      if constexpr (!SETS) g = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
+      if constexpr (SEG != 1) g = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
     }
     ids[tid] = id;
-    if constexpr (!SETS) gsc[tid] = g;
+    if constexpr (SEG != 1) gsc[tid] = g;
   }
-  if constexpr (SETS) {
+  if constexpr (SEG == 1) {
     for (int t = tid; t < BM * nseg; t += 256) {
       int rr = t / nseg, p = t % nseg;
       float g = 0.f;
@@ -120,10 +161,10 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
       gsc[rr * 8 + p] = g;
     }
     if (tid == 0) {
-      // unrank the combination: set id e -> ascending experts
+      // unrank the combination: set id e -> ascending experts x_0 < x_1 < ...
       int rank = e;
       for (int p = nseg - 1; p >= 0; --p) {
-        int x = p;   // smallest candidate: C(p, p+1) = 0
+        int x = p;
         while (x + 1 < a.experts) {
           long v = 1;
           for (int i = 1; i <= p + 1; ++i) v = v * (x + 1 - (p + 1) + i) / i;   // C(x+1, p+1)
@@ -132,17 +173,17 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
         }
         long v = 1;
         for (int i = 1; i <= p + 1; ++i) v = v * (x - (p + 1) + i) / i;          // C(x, p+1)
-        if (x < p + 1) v = 0;
         rank -= (int)v;
-        bseg[p] = (long)h * a.b_hstride + (long)x * a.b_estride;
+        bseg[p] = (long)hh * a.b_hstride + (long)x * a.b_estride;
       }
     }
   }
   __syncthreads();
 
   const unsigned short* A = (const unsigned short*)a.A;
-  const unsigned short* B = (const unsigned short*)a.B + (SETS ? 0 : (long)h * a.b_hstride + (long)e * a.b_estride);
-  const int n0 = blockIdx.y * BN;
+  const unsigned short* Bbase = (const unsigned short*)(second ? a.B2 : a.B);
+  const unsigned short* B = Bbase + (SEG ? 0 : (long)hh * a.b_hstride + (long)e * a.b_estride);
+  const int n0 = ct * BN;
   const int K = a.K, Nc = a.Nc;
 
   // ---- per-thread load plan -----------------------------------------------------------
@@ -154,11 +195,11 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
 #pragma unroll
   for (int i = 0; i < A_N; ++i) {
     int c = tid + i * 256;
-    int r = c / A_CPR, kc = (c % A_CPR) * VEC;
-    int id = ids[r];
-    a_off[i] = id >= 0 ? (long)(id / a.a_div) * a.lda + (long)h * a.a_hoff + kc : -1;
+    int rr = c / A_CPR, kc = (c % A_CPR) * VEC;
+    int id = ids[rr];
+    a_off[i] = id >= 0 ? (long)(id / a.a_div) * a.lda + (long)hh * a.a_hoff + kc : -1;
     a_kc[i] = kc;
-    a_lds[i] = r * LDA + kc;
+    a_lds[i] = rr * LDA + kc;
   }
   long b_off[B_N];
   int b_kc[B_N], b_lds[B_N];
@@ -186,15 +227,22 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
   chunk_t ra[A_N], rb[B_N];
   const int nks = (K + BK - 1) / BK;   // K steps per segment
   auto load_global = [&](int it) {
-    const int seg = SETS ? it / nks : 0;
-    const int k0 = (SETS ? it % nks : it) * BK;
-    const unsigned short* Bs_ = SETS ? B + bseg[seg] : B;
+    const int seg = SEG ? it / nks : 0;
+    const int k0 = (SEG ? it % nks : it) * BK;
+    const unsigned short* Ap = A;
+    const unsigned short* Bp = B;
+    if constexpr (SEG == 1) Bp = B + bseg[seg];
+    if constexpr (SEG == 2) {
+      const int which = seg / a.seg_split, sh_ = seg % a.seg_split;
+      Ap = A + (long)which * a.a_wstride + (long)sh_ * a.a_sstride;
+      Bp = (const unsigned short*)(which ? a.B2 : a.B) + (long)sh_ * a.b_sstride;
+    }
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
       ra[i] = zero_chunk<VEC>();
       if (a_off[i] >= 0 && k0 + a_kc[i] < K) {
-        ra[i] = *(const chunk_t*)(A + a_off[i] + k0);
-        if constexpr (SETS) ra[i] = scale_chunk(ra[i], gsc[(a_lds[i] / LDA) * 8 + seg]);
+        ra[i] = *(const chunk_t*)(Ap + a_off[i] + k0);
+        if constexpr (SEG == 1) ra[i] = scale_chunk(ra[i], gsc[(a_lds[i] / LDA) * 8 + seg]);
       }
     }
 #pragma unroll
@@ -202,17 +250,17 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
       rb[i] = zero_chunk<VEC>();
       if (b_ok[i] && k0 + b_kc[i] < K) {
         if constexpr (BNT)
-          rb[i] = *(const chunk_t*)(Bs_ + b_off[i] + k0);
+          rb[i] = *(const chunk_t*)(Bp + b_off[i] + k0);
         else
-          rb[i] = *(const chunk_t*)(Bs_ + b_off[i] + (long)k0 * a.sbk);
+          rb[i] = *(const chunk_t*)(Bp + b_off[i] + (long)k0 * a.sbk);
       }
     }
   };
-  auto store_lds = [&](int buf) {
+  auto store_lds = [&]() {
 #pragma unroll
-    for (int i = 0; i < A_N; ++i) *(chunk_t*)(&As[buf][a_lds[i]]) = ra[i];
+    for (int i = 0; i < A_N; ++i) *(chunk_t*)(&As[a_lds[i]]) = ra[i];
 #pragma unroll
-    for (int i = 0; i < B_N; ++i) *(chunk_t*)(&Bs[buf][b_lds[i]]) = rb[i];
+    for (int i = 0; i < B_N; ++i) *(chunk_t*)(&Bs[b_lds[i]]) = rb[i];
   };
 
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -227,33 +275,60 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
 
   const int nk = nks * nseg;
   load_global(0);
-  store_lds(0);
+  store_lds();
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
     if (kt + 1 < nk) load_global(kt + 1);
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 fa[2], fb[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = frag_rowmajor(&As[buf][(wm + i * 32 + r) * LDA + kk + 8 * g]);
+      for (int i = 0; i < 2; ++i) fa[i] = frag_rowmajor(&As[(wm + i * 32 + r) * LDA + kk + 8 * g]);
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         if constexpr (BNT)
-          fb[j] = frag_rowmajor(&Bs[buf][(wn + j * 32 + r) * LDB_NT + kk + 8 * g]);
+          fb[j] = frag_rowmajor(&Bs[(wn + j * 32 + r) * LDB_NT + kk + 8 * g]);
         else
-          fb[j] = frag_transposed(&Bs[buf][0], LDB_NN, kk + 8 * g, wn + j * 32, lane);
+          fb[j] = frag_transposed(Bs, LDB_NN, kk + 8 * g, wn + j * 32, lane);
       }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_lds(buf ^ 1);
     __syncthreads();
+    if (kt + 1 < nk) {
+      store_lds();
+      __syncthreads();
+    }
   }
 
   // ---- epilogue -------------------------------------------------------------------------
+  char* Cb = (char*)(second ? a.C2 : a.C);
+  if (VEC == 8 && a.mode == STORE_T) {
+    // stage the bf16 tile in LDS (the operand tiles are dead), then 16-byte row-contiguous stores
+    unsigned short* Cs = smem;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
+        const float sc = SEG == 1 ? 1.f : gsc[row];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) Cs[row * LDC + wn + j * 32 + r] = f32_to_bf16(acc[i][j][q] * sc);
+      }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < BM * (BN / 8) / 256; ++i) {
+      const int c = tid + i * 256;
+      const int row = c / (BN / 8), cc = (c % (BN / 8)) * 8;
+      const int id = ids[row];
+      if (id < 0 || n0 + cc >= Nc) continue;
+      const long crow = (long)(id / a.c_div) * a.ldc + (long)hh * a.c_hoff;
+      *(uint4*)((unsigned short*)Cb + crow + n0 + cc) = *(const uint4*)(&Cs[row * LDC + cc]);
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -261,19 +336,19 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
       const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
       const int id = ids[row];
       if (id < 0) continue;
-      const float sc = SETS ? 1.f : gsc[row];
-      const long crow = (long)(id / a.c_div) * a.ldc + (long)h * a.c_hoff;
+      const float sc = SEG == 1 ? 1.f : gsc[row];
+      const long crow = (long)(id / a.c_div) * a.ldc + (long)hh * a.c_hoff;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int n = n0 + wn + j * 32 + r;
         if (n >= Nc) continue;
         const float v = acc[i][j][q] * sc;
         if (a.mode == STORE_T)
-          ((unsigned short*)a.C)[crow + n] = f32_to_bf16(v);
+          ((unsigned short*)Cb)[crow + n] = f32_to_bf16(v);
         else if (a.mode == STORE_F32)
-          ((float*)a.C)[crow + n] = v;
+          ((float*)Cb)[crow + n] = v;
         else
-          atomicAdd((float*)a.C + crow + n, v);
+          atomicAdd((float*)Cb + crow + n, v);
       }
     }
   }
@@ -289,6 +364,9 @@ static int row_gemm_vec(const RowGemmArgs& a) {
     const size_t bytes = vec * 2;
     bool ok = aligned_to(a.A, bytes) && aligned_to(a.B, bytes) && a.lda % vec == 0 && a.a_hoff % vec == 0 &&
               a.K % vec == 0 && a.b_hstride % vec == 0 && a.b_estride % vec == 0;
+    if (a.hsplit > 0 || a.seg_mode == 2) ok = ok && aligned_to(a.B2, bytes);
+    if (a.seg_mode == 2) ok = ok && a.a_sstride % vec == 0 && a.a_wstride % vec == 0 && a.b_sstride % vec == 0;
+    if (a.mode == STORE_T) ok = ok && aligned_to(a.C, bytes) && a.ldc % vec == 0 && a.c_hoff % vec == 0;
     if (nt)
       ok = ok && a.sbn % vec == 0;
     else
@@ -298,42 +376,63 @@ static int row_gemm_vec(const RowGemmArgs& a) {
   return 0;
 }
 
-bool mfma_row_gemm_supported(const RowGemmArgs& a) { return row_gemm_vec(a) != 0; }
+bool mfma_row_gemm_supported(const RowGemmArgs& a) {
+  if (a.seg_mode == 1 && (a.nseg < 1 || a.nseg > 8)) return false;
+  return row_gemm_vec(a) != 0;
+}
+
+// Only the (step tag, segment mode) pairs the layer uses get a kernel of their own name;
+// everything else runs under the generic tag.
+template <int VEC, bool BNT, int TAG>
+static void launch_rg(const RowGemmArgs& a, dim3 g, hipStream_t s) {
+  constexpr bool sets_ok = TAG == TAG_GENERIC || TAG == TAG_O_EXPERTS || TAG == TAG_V_DGRAD;
+  constexpr bool cat_ok = TAG == TAG_GENERIC || TAG == TAG_QK_DGRAD;
+  if (a.seg_mode == 1) {
+    if constexpr (sets_ok)
+      mfma_row_gemm_kernel<VEC, BNT, TAG, 1><<<g, 256, 0, s>>>(a);
+    else
+      mfma_row_gemm_kernel<VEC, BNT, TAG_GENERIC, 1><<<g, 256, 0, s>>>(a);
+  } else if (a.seg_mode == 2) {
+    if constexpr (cat_ok)
+      mfma_row_gemm_kernel<VEC, BNT, TAG, 2><<<g, 256, 0, s>>>(a);
+    else
+      mfma_row_gemm_kernel<VEC, BNT, TAG_GENERIC, 2><<<g, 256, 0, s>>>(a);
+  } else {
+    mfma_row_gemm_kernel<VEC, BNT, TAG, 0><<<g, 256, 0, s>>>(a);
+  }
+}
 
 void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.Nc <= 0) return;
   const int vec = row_gemm_vec(a);
   const bool nt = a.sbk == 1;
-  dim3 g((a.M + rg::BM - 1) / rg::BM + (a.perm ? a.E : 0), (a.Nc + rg::BN - 1) / rg::BN, a.heads);
-  if (a.nseg > 0) {
-    if (vec == 8 && nt)
-      mfma_row_gemm_kernel<8, true, TAG_V_DGRAD, true><<<g, 256, 0, s>>>(a);
-    else if (vec == 8)
-      mfma_row_gemm_kernel<8, false, TAG_O_EXPERTS, true><<<g, 256, 0, s>>>(a);
-    else if (nt)
-      mfma_row_gemm_kernel<4, true, TAG_GENERIC, true><<<g, 256, 0, s>>>(a);
-    else
-      mfma_row_gemm_kernel<4, false, TAG_GENERIC, true><<<g, 256, 0, s>>>(a);
-    return;
+  const int ncol = (a.Nc + rg::BN - 1) / rg::BN;
+  dim3 g;
+  if (a.seg_mode == 1) {
+    const int tph = (a.M + rg::BM - 1) / rg::BM + a.E;
+    g = dim3(grid_windows(a.heads * tph, ncol));
+  } else {
+    const int group_rows = a.perm ? a.max_group_rows : a.M;
+    g = dim3(grid_windows((group_rows + rg::BM - 1) / rg::BM, a.heads * a.E * ncol));
   }
   if (vec == 8 && nt) {
     switch (a.tag) {
-      case TAG_O_DGRAD: mfma_row_gemm_kernel<8, true, TAG_O_DGRAD><<<g, 256, 0, s>>>(a); break;
-      case TAG_V_DGRAD: mfma_row_gemm_kernel<8, true, TAG_V_DGRAD><<<g, 256, 0, s>>>(a); break;
-      case TAG_QK_DGRAD: mfma_row_gemm_kernel<8, true, TAG_QK_DGRAD><<<g, 256, 0, s>>>(a); break;
-      default: mfma_row_gemm_kernel<8, true, TAG_GENERIC><<<g, 256, 0, s>>>(a); break;
+      case TAG_O_DGRAD: launch_rg<8, true, TAG_O_DGRAD>(a, g, s); break;
+      case TAG_V_DGRAD: launch_rg<8, true, TAG_V_DGRAD>(a, g, s); break;
+      case TAG_QK_DGRAD: launch_rg<8, true, TAG_QK_DGRAD>(a, g, s); break;
+      default: launch_rg<8, true, TAG_GENERIC>(a, g, s); break;
     }
   } else if (vec == 8) {
     switch (a.tag) {
-      case TAG_QK_PROJ: mfma_row_gemm_kernel<8, false, TAG_QK_PROJ><<<g, 256, 0, s>>>(a); break;
-      case TAG_V_EXPERTS: mfma_row_gemm_kernel<8, false, TAG_V_EXPERTS><<<g, 256, 0, s>>>(a); break;
-      case TAG_O_EXPERTS: mfma_row_gemm_kernel<8, false, TAG_O_EXPERTS><<<g, 256, 0, s>>>(a); break;
-      default: mfma_row_gemm_kernel<8, false, TAG_GENERIC><<<g, 256, 0, s>>>(a); break;
+      case TAG_QK_PROJ: launch_rg<8, false, TAG_QK_PROJ>(a, g, s); break;
+      case TAG_V_EXPERTS: launch_rg<8, false, TAG_V_EXPERTS>(a, g, s); break;
+      case TAG_O_EXPERTS: launch_rg<8, false, TAG_O_EXPERTS>(a, g, s); break;
+      default: launch_rg<8, false, TAG_GENERIC>(a, g, s); break;
     }
   } else if (nt) {
-    mfma_row_gemm_kernel<4, true, TAG_GENERIC><<<g, 256, 0, s>>>(a);
+    launch_rg<4, true, TAG_GENERIC>(a, g, s);
   } else {
-    mfma_row_gemm_kernel<4, false, TAG_GENERIC><<<g, 256, 0, s>>>(a);
+    launch_rg<4, false, TAG_GENERIC>(a, g, s);
   }
 }
 
