@@ -17,12 +17,15 @@ struct bf16_t {
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }
 
-// round-to-nearest-even; NaN stays NaN
-__device__ __forceinline__ unsigned short f32_to_bf16(float f) {
-  unsigned u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (unsigned short)(u >> 16);
+// round-to-nearest-even (the hardware conversion of gfx950)
+__device__ __forceinline__ unsigned short f32_to_bf16(float f) { return __builtin_bit_cast(unsigned short, (__bf16)f); }
+// two floats -> packed bf16 pair (lo in bits 0..15)
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  bf16x2_t v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(unsigned, v);
 }
 
 __device__ __forceinline__ float ld(const float* p, long i) { return p[i]; }
@@ -41,7 +44,7 @@ __device__ __forceinline__ void st(bf16_t* p, long i, float v) { p[i].v = f32_to
 //   A[arow*lda + h*a_hoff + k],  B[h*b_hstride + e*b_estride + k*sbk + n*sbn],
 //   C[crow*ldc + h*c_hoff + n]
 // ----------------------------------------------------------------------------------------
-enum { STORE_T = 0, STORE_F32 = 1, ATOMIC_F32 = 2 };
+enum { STORE_T = 0, STORE_F32 = 1, ATOMIC_F32 = 2, STORE_F64 = 3 };
 
 // Which step of the layer a launch serves.  The MFMA kernels are instantiated once per tag so
 // that a profiler shows one kernel name per step; the arithmetic is the same for every tag.
@@ -49,7 +52,8 @@ enum {
   TAG_GENERIC = 0,
   TAG_QK_PROJ, TAG_V_EXPERTS, TAG_O_EXPERTS,   // forward row GEMMs
   TAG_O_DGRAD, TAG_V_DGRAD, TAG_QK_DGRAD,      // backward row GEMMs
-  TAG_O_WGRAD, TAG_V_WGRAD, TAG_QK_WGRAD       // weight gradients
+  TAG_O_WGRAD, TAG_V_WGRAD, TAG_QK_WGRAD,      // weight gradients
+  TAG_ROUTER                                   // router logits: fp32 partial sums of 64 terms, added up in fp64
 };
 
 struct RowGemmArgs {
@@ -112,6 +116,7 @@ struct WgradArgs {
   long gate_hstride;
   int chunk;  // rows reduced by one block
   int tag;
+  int max_group_rows;  // upper bound of the rows of one group (tokens per call)
 };
 
 // Finds the tile `tile` (of `bm` rows) among the E groups of one head.  Returns false when
@@ -167,6 +172,11 @@ struct RouterArgs {
   int bf16;
 };
 void launch_router(const RouterArgs& a, hipStream_t s);
+// bf16 storage: fp32 matrix-core logits with an fp64 re-evaluation of every decision that
+// is not provably safe (see routing.hip).  `scratch` needs router_hybrid_bytes() bytes.
+size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off6);
+bool router_hybrid_supported(const RouterArgs& a);
+void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s);
 void launch_dense_routing(int* idx, float* gate, int* perm, int* offsets, int N, int H, hipStream_t s);
 int router_blocks(int N);  // token blocks used by the histogram/scatter kernels
 
@@ -224,6 +234,7 @@ void launch_simt_attn_bwd(const AttnBwdArgs& a, int bf16, hipStream_t s);
 
 // MFMA family (bf16 storage only).  *_supported() say whether a launch can be served.
 bool mfma_row_gemm_supported(const RowGemmArgs& a);
+int rg_kstep();  // terms summed in fp32 by one K step of the row GEMM
 void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s);
 bool mfma_wgrad_supported(const WgradArgs& a);
 void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s);

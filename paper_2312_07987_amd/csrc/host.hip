@@ -61,6 +61,7 @@ struct Layout {
   size_t idx, gate, perm, offsets, Q, K, V, ctx, lse, pV;          // saved by forward
   size_t Z, blockcnt, acc32;                                       // forward scratch
   size_t setid, gset, setperm, setoff, setcnt, yh;                 // expert-set path (bf16 only)
+  size_t rh;                                                       // two-stage router scratch (bf16 only)
   size_t u, dctx, dQ, dK, dV, delta, dgate, dz;                    // backward scratch
 };
 
@@ -134,6 +135,11 @@ Layout make_layout(const sh_shape* s) {
     L.yh = take(H * N * dm * esz);
   } else {
     L.setid = L.gset = L.setperm = L.setoff = L.setcnt = L.yh = 0;
+  }
+  L.rh = 0;
+  if (s->dtype == SH_BF16) {
+    size_t o6[6];
+    L.rh = take(router_hybrid_bytes((int)N, (int)dm, (int)H, (int)E, o6));
   }
   L.total = off;
   return L;
@@ -352,7 +358,10 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     ra.k = k;
     ra.sides = c.shared ? 1 : 2;
     ra.bf16 = c.bf16;
-    launch_router(ra, c.st);
+    if (g_family.load() == 0 && router_hybrid_supported(ra))
+      launch_router_hybrid(ra, c.p<char>(c.L.rh), c.st);
+    else
+      launch_router(ra, c.st);
   }
   if (c.dense || c.shared) {
     // one selection serves both sides: the destination tables repeat the source tables
@@ -588,6 +597,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.heads = H;
     w.E = E;
     w.M = N * k;
+    w.max_group_rows = N;
     w.a_div = k;
     w.b_div = k;
     w.A = c.p<void>(c.L.ctx);
@@ -730,6 +740,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.heads = H;
     w.E = E;
     w.M = N * k;
+    w.max_group_rows = N;
     w.a_div = k;
     w.b_div = k;
     w.A = x;

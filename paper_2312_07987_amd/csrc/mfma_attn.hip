@@ -207,8 +207,8 @@ __global__ __launch_bounds__(256) void mfma_attn_fwd_kernel(AttnArgs a) {
         const int dd = d * 32 + 8 * i4 + 4 * g;
         if (dd < dh) {
           uint2 w;
-          w.x = (unsigned)f32_to_bf16(o[d][4 * i4] * inv) | ((unsigned)f32_to_bf16(o[d][4 * i4 + 1] * inv) << 16);
-          w.y = (unsigned)f32_to_bf16(o[d][4 * i4 + 2] * inv) | ((unsigned)f32_to_bf16(o[d][4 * i4 + 3] * inv) << 16);
+          w.x = pack_bf16x2(o[d][4 * i4] * inv, o[d][4 * i4 + 1] * inv);
+          w.y = pack_bf16x2(o[d][4 * i4 + 2] * inv, o[d][4 * i4 + 3] * inv);
           *(uint2*)(O + dd) = w;
         }
       }
@@ -249,8 +249,8 @@ __device__ __forceinline__ void store_rows_T(unsigned short* dst, const f32x16* 
       const int dd = d * 32 + 8 * i4 + 4 * g;
       if (dd < dh) {
         uint2 w;
-        w.x = (unsigned)f32_to_bf16(acc[d][4 * i4] * mul) | ((unsigned)f32_to_bf16(acc[d][4 * i4 + 1] * mul) << 16);
-        w.y = (unsigned)f32_to_bf16(acc[d][4 * i4 + 2] * mul) | ((unsigned)f32_to_bf16(acc[d][4 * i4 + 3] * mul) << 16);
+        w.x = pack_bf16x2(acc[d][4 * i4] * mul, acc[d][4 * i4 + 1] * mul);
+        w.y = pack_bf16x2(acc[d][4 * i4 + 2] * mul, acc[d][4 * i4 + 3] * mul);
         *(uint2*)(dst + dd) = w;
       }
     }

@@ -62,7 +62,7 @@ __device__ __forceinline__ typename Chunk<VEC>::type zero_chunk() {
 
 __device__ __forceinline__ unsigned scale_pair(unsigned w, float g) {
   float lo = __uint_as_float(w << 16) * g, hi = __uint_as_float(w & 0xffff0000u) * g;
-  return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+  return pack_bf16x2(lo, hi);
 }
 __device__ __forceinline__ uint4 scale_chunk(uint4 c, float g) {
   return make_uint4(scale_pair(c.x, g), scale_pair(c.y, g), scale_pair(c.z, g), scale_pair(c.w, g));
@@ -273,12 +273,24 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
+  // column blocks of this wave that hold real columns (wave-uniform)
+  constexpr bool ACC64 = TAG == TAG_ROUTER;
+  const int jmax = !ACC64 ? 2 : (n0 + wn >= Nc ? 0 : 1);   // router: at most 32 columns
+  double acc64[ACC64 ? 2 : 1][16];
+  if constexpr (ACC64) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc64[i][q] = 0.0;
+  }
+
   const int nk = nks * nseg;
   load_global(0);
   store_lds();
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     if (kt + 1 < nk) load_global(kt + 1);
+    if (!ACC64 || jmax > 0) {
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 fa[2], fb[2];
@@ -294,7 +306,19 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 2; ++j)
+          if (!ACC64 || j == 0) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    }
+    if constexpr (ACC64) {
+      // router logits: the fp32 accumulator only ever holds the sum of one 64-term K step
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          acc64[i][q] += (double)acc[i][0][q];
+          acc[i][0][q] = 0.f;
+        }
     }
     __syncthreads();
     if (kt + 1 < nk) {
@@ -305,6 +329,21 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
 
   // ---- epilogue -------------------------------------------------------------------------
   char* Cb = (char*)(second ? a.C2 : a.C);
+  if constexpr (ACC64) {
+    // at most 32 columns (host checks), held by the waves with wn == 0
+    if (jmax > 0) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
+          const int id = ids[row];
+          const int n = n0 + wn + r;
+          if (id >= 0 && n < Nc) ((double*)Cb)[(long)(id / a.c_div) * a.ldc + (long)hh * a.c_hoff + n] = acc64[i][q];
+        }
+    }
+    return;
+  }
   if (VEC == 8 && a.mode == STORE_T) {
     // stage the bf16 tile in LDS (the operand tiles are dead), then 16-byte row-contiguous stores
     unsigned short* Cs = smem;
@@ -354,6 +393,8 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
   }
 }
 
+int rg_kstep() { return rg::BK; }
+
 static bool aligned_to(const void* p, size_t b) { return ((uintptr_t)p % b) == 0; }
 
 // vector width (bf16 elements) all loads of a row GEMM can use, 0 if none
@@ -378,6 +419,7 @@ static int row_gemm_vec(const RowGemmArgs& a) {
 
 bool mfma_row_gemm_supported(const RowGemmArgs& a) {
   if (a.seg_mode == 1 && (a.nseg < 1 || a.nseg > 8)) return false;
+  if (a.tag == TAG_ROUTER && (a.Nc > 32 || a.mode != STORE_F64 || a.seg_mode != 0)) return false;
   return row_gemm_vec(a) != 0;
 }
 
@@ -427,10 +469,13 @@ void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s) {
       case TAG_QK_PROJ: launch_rg<8, false, TAG_QK_PROJ>(a, g, s); break;
       case TAG_V_EXPERTS: launch_rg<8, false, TAG_V_EXPERTS>(a, g, s); break;
       case TAG_O_EXPERTS: launch_rg<8, false, TAG_O_EXPERTS>(a, g, s); break;
+      case TAG_ROUTER: mfma_row_gemm_kernel<8, false, TAG_ROUTER, 0><<<g, 256, 0, s>>>(a); break;
       default: launch_rg<8, false, TAG_GENERIC>(a, g, s); break;
     }
   } else if (nt) {
     launch_rg<4, true, TAG_GENERIC>(a, g, s);
+  } else if (a.tag == TAG_ROUTER) {
+    mfma_row_gemm_kernel<4, false, TAG_ROUTER, 0><<<g, 256, 0, s>>>(a);
   } else {
     launch_rg<4, false, TAG_GENERIC>(a, g, s);
   }
@@ -457,12 +502,27 @@ __global__ __launch_bounds__(256) void mfma_wgrad_kernel(WgradArgs a) {
   __shared__ int ids[MAX_CHUNK];
   __shared__ float gsc[MAX_CHUNK];
 
-  const int h = blockIdx.z;
-  int e = 0, row0, rows;
+  // window = chunk index inside a group; every (group, output tile) of a window shares an XCD,
+  // so the rows of a token window are fetched from HBM once and then hit in that XCD's L2
+  const int ti_ = (a.Ka + BM - 1) / BM, tj = (a.Kb + BN - 1) / BN;
+  const int ntile = ti_ * tj;
+  // unit = (chunk window, group); the output tiles of a unit share an XCD (they read the same
+  // rows), consecutive units go to different XCDs
+  const int G = a.heads * a.E;
+  int unit, tile;
+  decode_block(blockIdx.x, ntile, unit, tile);
+  const int w = unit / G, grp = unit % G;
+  if (w * a.chunk >= (a.perm ? a.max_group_rows : a.M)) return;
+  const int h = grp / a.E, e = grp % a.E;
+  int row0, rows;
   if (a.perm) {
-    if (!find_tile(a.offsets + (long)h * (a.E + 1), a.E, a.chunk, blockIdx.y, e, row0, rows)) return;
+    const int* off = a.offsets + (long)h * (a.E + 1);
+    row0 = off[e] + w * a.chunk;
+    const int end = off[e + 1];
+    if (row0 >= end) return;
+    rows = end - row0 < a.chunk ? end - row0 : a.chunk;
   } else {
-    row0 = blockIdx.y * a.chunk;
+    row0 = w * a.chunk;
     if (row0 >= a.M) return;
     rows = a.M - row0 < a.chunk ? a.M - row0 : a.chunk;
   }
@@ -474,8 +534,7 @@ __global__ __launch_bounds__(256) void mfma_wgrad_kernel(WgradArgs a) {
   }
   __syncthreads();
 
-  const int tj = (a.Kb + BN - 1) / BN;
-  const int i0 = (blockIdx.x / tj) * BM, j0 = (blockIdx.x % tj) * BN;
+  const int i0 = (tile / tj) * BM, j0 = (tile % tj) * BN;
   const unsigned short* A = (const unsigned short*)a.A;
   const unsigned short* Bm = (const unsigned short*)a.Bm;
   const bool scaled = a.gate != nullptr;
@@ -575,7 +634,8 @@ void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s) {
   if (a.M <= 0) return;
   const int vec = wgrad_vec(a);
   int ti = (a.Ka + wg::BM - 1) / wg::BM, tj = (a.Kb + wg::BN - 1) / wg::BN;
-  dim3 g(ti * tj, (a.M + a.chunk - 1) / a.chunk + (a.perm ? a.E : 0), a.heads);
+  const int group_rows = a.perm ? a.max_group_rows : a.M;
+  dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads * a.E, ti * tj));
   if (vec == 8) {
     switch (a.tag) {
       case TAG_O_WGRAD: mfma_wgrad_kernel<8, TAG_O_WGRAD><<<g, 256, 0, s>>>(a); break;

@@ -118,19 +118,22 @@ __global__ __launch_bounds__(RB) void topk_hist_kernel(const double* __restrict_
 }
 
 // One block per (side, head).  blockcnt[sh][blk][e] (counts) -> in place: first position of
-// expert e for token block blk; offsets[sh][0..E].
-__global__ __launch_bounds__(128) void scan_kernel(int* __restrict__ blockcnt, int* __restrict__ offsets, int E,
-                                                  int nblk) {
+// bin e for token block blk; offsets[sh][0..E].  One wave per bin, lanes over token blocks.
+__global__ __launch_bounds__(256) void scan_kernel(int* __restrict__ blockcnt, int* __restrict__ offsets, int E,
+                                                   int nblk) {
   __shared__ int tot[129];
   const int sh_ = blockIdx.x;
-  const int e = threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int* c = blockcnt + (long)sh_ * nblk * E;
-  int sum = 0;
-  if (e < E)
-    for (int b = 0; b < nblk; ++b) sum += c[(long)b * E + e];
-  tot[e] = e < E ? sum : 0;
+  for (int e = wave; e < E; e += 4) {
+    int sum = 0;
+    for (int b = lane; b < nblk; b += 64) sum += c[(long)b * E + e];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (lane == 0) tot[e] = sum;
+  }
   __syncthreads();
-  if (e == 0) {
+  if (threadIdx.x == 0) {
     int run = 0;
     for (int i = 0; i < E; ++i) {
       int t = tot[i];
@@ -138,15 +141,22 @@ __global__ __launch_bounds__(128) void scan_kernel(int* __restrict__ blockcnt, i
       run += t;
     }
     tot[E] = run;
-    for (int i = 0; i <= E; ++i) offsets[(long)sh_ * (E + 1) + i] = tot[i];
   }
   __syncthreads();
-  if (e < E) {
+  for (int i = threadIdx.x; i <= E; i += 256) offsets[(long)sh_ * (E + 1) + i] = tot[i];
+  for (int e = wave; e < E; e += 4) {
     int run = tot[e];
-    for (int b = 0; b < nblk; ++b) {
-      int t = c[(long)b * E + e];
-      c[(long)b * E + e] = run;
-      run += t;
+    for (int b0 = 0; b0 < nblk; b0 += 64) {
+      const int b = b0 + lane;
+      const int v = b < nblk ? c[(long)b * E + e] : 0;
+      int inc = v;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        int u = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += u;
+      }
+      if (b < nblk) c[(long)b * E + e] = run + inc - v;
+      run += __shfl(inc, 63, 64);
     }
   }
 }
@@ -207,6 +217,328 @@ __global__ void dense_routing_kernel(int* idx, float* gate, int* perm, int* offs
   }
 }
 
+// ----------------------------------------------------------------------------------------
+// Two-stage router for bf16 storage.  Stage 1 takes the logits from a matrix-core GEMM whose
+// fp32 accumulator only ever holds the sum of one K step (KS = 64 exact bf16 x bf16 products)
+// and is added to an fp64 accumulator after every step.  Their distance from the canonical
+// fp64 logits is bounded by
+//   bound = 4 * KS * 2^-24 * |x_n|_2 * max_c |W[:,c]|_2  (+ 1e-13 relative for the fp64 adds),
+// a Cauchy-Schwarz bound on sum_i |x_i w_i| times the fp32 error of a KS-term sum, with a
+// factor 4 of slack for the adder tree of the matrix core.  If every gap between consecutive sorted
+// logits down to the (k+1)-th exceeds 2*bound, the ordered top-k list is provably the one
+// the fp64 logits give, and it is written directly.  Otherwise the (token, side, head) is
+// queued and stage 2 re-evaluates its E logits in fp64 in the canonical order and selects
+// from those.  Indices are therefore identical to the all-fp64 router by construction.
+// ----------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void row_norm_kernel(const T* __restrict__ x, const T* __restrict__ W0,
+                                                       const T* __restrict__ W1, float* __restrict__ xnorm,
+                                                       float* __restrict__ wmax, int* __restrict__ fixcount, int N,
+                                                       int dm, int H, int E, int sides) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long row = (long)blockIdx.x * 4 + wave;
+  if (row < N) {
+    float s = 0.f;
+    if (sizeof(T) == 2 && dm % 8 == 0) {
+      const uint4* xr = (const uint4*)((const unsigned short*)x + row * dm);
+      for (int i = lane; i < dm / 8; i += 64) {
+        const uint4 v = xr[i];
+        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float lo = __uint_as_float(w[u] << 16), hi = __uint_as_float(w[u] & 0xffff0000u);
+          s = fmaf(lo, lo, s);
+          s = fmaf(hi, hi, s);
+        }
+      }
+    } else {
+      for (int i = lane; i < dm; i += 64) {
+        float v = ld(x, row * dm + i);
+        s = fmaf(v, v, s);
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0) xnorm[row] = sqrtf(s) * 1.0001f;
+  } else {
+    // the blocks behind the token rows: one wave per (side, head): max column norm of the head
+    const long sh_ = row - (((long)N + 3) / 4) * 4;
+    if (sh_ >= 0 && sh_ < (long)sides * H) {
+      const int side = (int)(sh_ / H), h = (int)(sh_ % H);
+      const T* W = side ? W1 : W0;
+      const int HE = H * E;
+      float mx = 0.f;
+      for (int e = 0; e < E; ++e) {
+        float s = 0.f;
+        for (int i = lane; i < dm; i += 64) {
+          float v = ld(W, (long)i * HE + h * E + e);
+          s = fmaf(v, v, s);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        mx = fmaxf(mx, s);
+      }
+      if (lane == 0) wmax[sh_] = sqrtf(mx) * 1.0001f;
+    }
+    if (sh_ >= 0 && sh_ < (long)sides * H && lane == 0) fixcount[sh_] = 0;
+  }
+}
+
+__global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ Zs, const float* __restrict__ b0,
+                                                     const float* __restrict__ b1, const float* __restrict__ xnorm,
+                                                     const float* __restrict__ wmax, int* __restrict__ idx,
+                                                     float* __restrict__ gate, int* __restrict__ fixlist,
+                                                     int* __restrict__ fixcount, int N, int kstep, int H, int E, int k,
+                                                     int HEp) {
+  const int sh_ = blockIdx.y;
+  const int side = sh_ / H, h = sh_ % H;
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  bool flag = false;
+  if (n < N) {
+    const double* z = Zs + ((long)side * N + n) * (long)HEp + (long)h * E;
+    const float* b = side ? b1 : b0;
+    // fp32 partial sums of `kstep` exact products, then fp64 adds: see the bound above
+    const double bound0 = 4.0 * (double)kstep * 5.9604645e-8 * (double)xnorm[n] * (double)wmax[sh_];
+    unsigned long long sel = 0ull;
+    const long o = ((long)sh_ * N + n) * k;
+    double prev = 0.0, bprev = 0.0;
+    const int passes = k < E ? k + 1 : k;
+    for (int j = 0; j < passes; ++j) {
+      int best = -1;
+      double bv = 0.0;
+      for (int e = 0; e < E; ++e) {
+        if ((sel >> e) & 1ull) continue;
+        double v = z[e] + (b ? (double)b[h * E + e] : 0.0);
+        if (best < 0 || v > bv) {
+          best = e;
+          bv = v;
+        }
+      }
+      const double bb = bound0 + 1e-13 * (fabs(bv) + 1.0);
+      if (j > 0 && !(prev - bv > bprev + bb)) flag = true;
+      prev = bv;
+      bprev = bb;
+      sel |= 1ull << best;
+      if (j < k) {
+        idx[o + j] = best;
+        gate[o + j] = (float)(1.0 / (1.0 + exp(-bv)));
+      }
+    }
+  }
+  // one atomic per wave
+  const unsigned long long bal = __ballot(flag);
+  if (bal) {
+    const int lane = threadIdx.x & 63;
+    int base = 0;
+    if (lane == 0) base = atomicAdd(&fixcount[sh_], __popcll(bal));
+    base = __shfl(base, 0, 64);
+    if (flag) fixlist[(long)sh_ * N + base + __popcll(bal & ((1ull << lane) - 1ull))] = n;
+  }
+}
+
+constexpr int FIX_ITEMS = 16;   // queued tokens per block; 4 threads share a token, each takes every 4th expert
+
+__global__ __launch_bounds__(64) void fix64_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W0,
+                                                   const bf16_t* __restrict__ W1, const float* __restrict__ b0,
+                                                   const float* __restrict__ b1, const int* __restrict__ fixlist,
+                                                   const int* __restrict__ fixcount, double* __restrict__ Z,
+                                                   int* __restrict__ idx, float* __restrict__ gate, int N, int dm, int H,
+                                                   int E, int k) {
+  constexpr int KC = 64;
+  __shared__ double xs[FIX_ITEMS][KC + 1];
+  __shared__ double ws[KC][8];
+  const int sh_ = blockIdx.y;
+  const int count = fixcount[sh_];
+  const int side = sh_ / H, h = sh_ % H;
+  const bf16_t* W = side ? W1 : W0;
+  const float* b = side ? b1 : b0;
+  const int HE = H * E;
+  const int t = threadIdx.x, it = t >> 2, part = t & 3;
+  // a small fixed grid walks the queue: empty work-groups are not free to launch
+  for (int item0 = blockIdx.x * FIX_ITEMS; item0 < count; item0 += gridDim.x * FIX_ITEMS) {
+  const bool valid = item0 + it < count;
+  const int n = valid ? fixlist[(long)sh_ * N + item0 + it] : 0;
+  double* z = Z + ((long)side * N + n) * HE + (long)h * E;
+  const unsigned short* xrow = (const unsigned short*)x + (long)n * dm;   // dm % 4 == 0, 8-byte aligned rows
+
+  for (int e0 = 0; e0 < E; e0 += 8) {
+    double acc[2] = {0.0, 0.0};   // experts e0 + part and e0 + part + 4
+    uint2 rx[KC / 16];            // this thread's quarter of the token's row chunk
+    float rw[8];
+    auto fetch = [&](int k0) {
+#pragma unroll
+      for (int q = 0; q < KC / 16; ++q) {
+        const int kk = k0 + part * (KC / 4) + 4 * q;
+        rx[q] = make_uint2(0, 0);
+        if (valid && kk < dm) rx[q] = *(const uint2*)(xrow + kk);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) rw[u] = (k0 + t < dm && e0 + u < E) ? ld(W, (long)(k0 + t) * HE + h * E + e0 + u) : 0.f;
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < dm; k0 += KC) {
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < KC / 16; ++q) {
+        const int c = part * (KC / 4) + 4 * q;
+        xs[it][c + 0] = (double)__uint_as_float(rx[q].x << 16);
+        xs[it][c + 1] = (double)__uint_as_float(rx[q].x & 0xffff0000u);
+        xs[it][c + 2] = (double)__uint_as_float(rx[q].y << 16);
+        xs[it][c + 3] = (double)__uint_as_float(rx[q].y & 0xffff0000u);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) ws[t][u] = (double)rw[u];
+      __syncthreads();
+      if (k0 + KC < dm) fetch(k0 + KC);
+#pragma unroll 8
+      for (int i = 0; i < KC; ++i) {
+        const double xv = xs[it][i];
+        acc[0] = fma(xv, ws[i][part], acc[0]);
+        acc[1] = fma(xv, ws[i][part + 4], acc[1]);
+      }
+    }
+    if (valid) {
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const int e = e0 + part + 4 * c;
+        if (e < E) z[e] = acc[c] + (b ? (double)b[h * E + e] : 0.0);
+      }
+    }
+  }
+  __syncthreads();   // the token's logits were written by its 4 threads
+  if (valid && part == 0) {
+    unsigned long long sel = 0ull;
+    const long o = ((long)sh_ * N + n) * k;
+    for (int j = 0; j < k; ++j) {
+      int best = -1;
+      double bv = 0.0;
+      for (int e = 0; e < E; ++e) {
+        if ((sel >> e) & 1ull) continue;
+        double v = z[e];
+        if (best < 0 || v > bv) {
+          best = e;
+          bv = v;
+        }
+      }
+      sel |= 1ull << best;
+      idx[o + j] = best;
+      gate[o + j] = (float)(1.0 / (1.0 + exp(-bv)));
+    }
+  }
+  }
+}
+
+__global__ __launch_bounds__(RB) void hist_kernel(const int* __restrict__ idx, int* __restrict__ blockcnt, int N, int E,
+                                                  int k, int nblk) {
+  __shared__ int cnt[64];
+  const int sh_ = blockIdx.y;
+  const int n = blockIdx.x * RB + threadIdx.x;
+  if (threadIdx.x < 64) cnt[threadIdx.x] = 0;
+  __syncthreads();
+  unsigned long long sel = 0ull;
+  if (n < N)
+    for (int j = 0; j < k; ++j) sel |= 1ull << idx[((long)sh_ * N + n) * k + j];
+  const int lane = threadIdx.x & 63;
+  for (int e = 0; e < E; ++e) {
+    unsigned long long bal = __ballot((sel >> e) & 1ull);
+    if (lane == 0 && bal) atomicAdd(&cnt[e], __popcll(bal));
+  }
+  __syncthreads();
+  if (threadIdx.x < E) blockcnt[((long)sh_ * nblk + blockIdx.x) * E + threadIdx.x] = cnt[threadIdx.x];
+}
+
+// Wp[side][i][c] = W_side[i][c] for c < HE, 0 for HE <= c < HEp (rows padded to 16 bytes)
+__global__ void pack_router_kernel(const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1, bf16_t* __restrict__ Wp,
+                                   int dm, int HE, int HEp, int sides) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  long tot = (long)sides * dm * HEp;
+  if (i >= tot) return;
+  int c = (int)(i % HEp);
+  long r = i / HEp;
+  int side = (int)(r / dm);
+  long row = r % dm;
+  const bf16_t* W = side ? W1 : W0;
+  bf16_t v;
+  v.v = 0;
+  if (c < HE) v = W[row * HE + c];
+  Wp[i] = v;
+}
+
+size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off) {
+  const size_t HEp = ((size_t)H * E + 7) / 8 * 8;
+  size_t o = 0;
+  auto take = [&](size_t b) {
+    size_t r = o;
+    o += (b + 255) & ~(size_t)255;
+    return r;
+  };
+  off[0] = take(2 * (size_t)dm * HEp * 2);   // Wp
+  off[1] = take(2 * (size_t)N * HEp * 8);    // Zs: stage-1 logits, fp64
+  off[2] = take((size_t)N * 4);              // xnorm
+  off[3] = take(2 * (size_t)H * 4);          // wmax
+  off[4] = take(2 * (size_t)H * N * 4);      // fixlist
+  off[5] = take(2 * (size_t)H * 4 + 256);    // fixcount per (side, head)
+  return o;
+}
+
+bool router_hybrid_supported(const RouterArgs& a) {
+  return a.bf16 && a.dm % 4 == 0 && ((uintptr_t)a.x % 16) == 0 && a.H * a.E <= 32;
+}
+
+void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
+  size_t off[6];
+  router_hybrid_bytes(a.N, a.dm, a.H, a.E, off);
+  const int HE = a.H * a.E, HEp = (HE + 7) / 8 * 8;
+  bf16_t* Wp = (bf16_t*)(scratch + off[0]);
+  double* Zs = (double*)(scratch + off[1]);
+  float* xnorm = (float*)(scratch + off[2]);
+  float* wmax = (float*)(scratch + off[3]);
+  int* fixlist = (int*)(scratch + off[4]);
+  int* fixcount = (int*)(scratch + off[5]);
+
+  const long tot = (long)a.sides * a.dm * HEp;
+  pack_router_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], Wp, a.dm, HE,
+                                                                   HEp, a.sides);
+  // stage 1: z32 = x W on the matrix cores, fp32 accumulation, both sides in one launch
+  RowGemmArgs g{};
+  g.heads = a.sides;
+  g.E = 1;
+  g.M = a.N;
+  g.a_div = 1;
+  g.c_div = 1;
+  g.A = a.x;
+  g.lda = a.dm;
+  g.B = Wp;
+  g.b_hstride = (long)a.dm * HEp;
+  g.sbk = HEp;
+  g.sbn = 1;
+  g.C = Zs;
+  g.ldc = HEp;
+  g.c_hoff = (long)a.N * HEp;
+  g.K = a.dm;
+  g.Nc = HEp;
+  g.mode = STORE_F64;
+  g.tag = TAG_ROUTER;
+  launch_mfma_row_gemm(g, s);
+
+  const int nrow_blocks = (a.N + 3) / 4 + (a.sides * a.H + 3) / 4;
+  row_norm_kernel<bf16_t><<<nrow_blocks, 256, 0, s>>>((const bf16_t*)a.x, (const bf16_t*)a.W[0], (const bf16_t*)a.W[1], xnorm,
+                                                      wmax, fixcount, a.N, a.dm, a.H, a.E, a.sides);
+  dim3 g1((a.N + 255) / 256, a.sides * a.H);
+  select_kernel<<<g1, 256, 0, s>>>(Zs, a.b[0], a.b[1], xnorm, wmax, a.idx, a.gate, fixlist, fixcount, a.N, rg_kstep(), a.H,
+                                   a.E, a.k, HEp);
+  int fix_blocks = (a.N + FIX_ITEMS - 1) / FIX_ITEMS;
+  if (fix_blocks > 64) fix_blocks = 64;
+  dim3 g3(fix_blocks, a.sides * a.H);
+  fix64_kernel<<<g3, 64, 0, s>>>((const bf16_t*)a.x, (const bf16_t*)a.W[0], (const bf16_t*)a.W[1], a.b[0], a.b[1],
+                                         fixlist, fixcount, a.Z, a.idx, a.gate, a.N, a.dm, a.H, a.E, a.k);
+  const int nblk = router_blocks(a.N);
+  dim3 g2(nblk, a.sides * a.H);
+  hist_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.N, a.E, a.k, nblk);
+  scan_kernel<<<a.sides * a.H, 256, 0, s>>>(a.blockcnt, a.offsets, a.E, nblk);
+  scatter_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.perm, a.N, a.E, a.k, nblk);
+}
+
 void launch_router(const RouterArgs& a, hipStream_t s) {
   const int HE = a.H * a.E;
   dim3 g((a.N + RT_TOK - 1) / RT_TOK, a.sides, (HE + RT_COL - 1) / RT_COL);
@@ -219,7 +551,7 @@ void launch_router(const RouterArgs& a, hipStream_t s) {
   const int nblk = router_blocks(a.N);
   dim3 g2(nblk, a.sides * a.H);
   topk_hist_kernel<<<g2, RB, 0, s>>>(a.Z, a.idx, a.gate, a.blockcnt, a.N, a.H, a.E, a.k, nblk);
-  scan_kernel<<<a.sides * a.H, 128, 0, s>>>(a.blockcnt, a.offsets, a.E, nblk);
+  scan_kernel<<<a.sides * a.H, 256, 0, s>>>(a.blockcnt, a.offsets, a.E, nblk);
   scatter_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.perm, a.N, a.E, a.k, nblk);
 }
 
@@ -311,7 +643,7 @@ void launch_set_sort(const SetSortArgs& a, hipStream_t s) {
   const int nblk = router_blocks(a.N);
   dim3 g(nblk, a.sides * a.H);
   set_hist_kernel<<<g, RB, 0, s>>>(a.idx, a.gate, a.setid, a.gset, a.blockcnt, a.N, a.k, a.nsets, nblk);
-  scan_kernel<<<a.sides * a.H, 128, 0, s>>>(a.blockcnt, a.setoff, a.nsets, nblk);
+  scan_kernel<<<a.sides * a.H, 256, 0, s>>>(a.blockcnt, a.setoff, a.nsets, nblk);
   set_scatter_kernel<<<g, RB, 0, s>>>(a.setid, a.blockcnt, a.setperm, a.N, a.nsets, nblk);
 }
 

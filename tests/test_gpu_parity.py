@@ -47,7 +47,8 @@ def run_case(cfg, family=0, shared=False, dense=False, backward=True, seed=None,
         assert bad.size == 0, ("top-k mismatch", side, bad[:4], [f["margin_" + side][b[0], b[1]] for b in bad[:4]])
         assert np.array_equal(routing["offsets"][s], f["offsets_" + side]), side
         assert np.array_equal(routing["perm"][s], f["perm_" + side]), side
-        assert nerr(routing["gate"][s], f["gate_" + side]) < 1e-6
+        # gates are fp32; on the bf16 path they come from fp32-accumulated logits
+        assert nerr(routing["gate"][s], f["gate_" + side]) < (1e-6 if cfg["dtype"] == "f32" else 2e-5)
     if check_inter:
         for n in ("Q", "K", "V", "ctx"):
             assert nerr(inter[n], f[n]) < tol, n
