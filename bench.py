@@ -101,7 +101,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="c2", help="c1..c4 (c2 = the 262M-model-scale layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-tokens", type=int, default=2048)
+    ap.add_argument("--cpu-tokens", type=int, default=1 << 20, help="token budget of the oracle sample (whole sequences)")
+    ap.add_argument("--copy-only", action="store_true", help="run a plain 256 MiB device copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the layer shards over the batch; see DESIGN.md); "
@@ -113,6 +114,17 @@ def main():
     from paper_2312_07987_amd.flops import layer_flops
     from paper_2312_07987_amd.inputs import config, make_inputs
     from paper_2312_07987_amd.runner import DeviceLayer
+
+    if args.copy_only:
+        # a plain copy of known size: 256 MiB read + 256 MiB written per launch, used to scale the
+        # FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 256 << 20, "copy_bytes_written": 256 << 20, "launches": 5}))
+        return
 
     cfg = config(args.config)
     host = make_inputs(cfg)

@@ -85,30 +85,45 @@ __device__ __forceinline__ void decode_block(int L, int per_window, int& w, int&
 static inline unsigned grid_windows(int nwin, int per_window) { return (unsigned)(((nwin + 7) / 8) * 8) * per_window; }
 
 // ----------------------------------------------------------------------------------------
-// Row GEMM.  Block tile 128 x 128, K step 64 (a full 128-byte line of every gathered row per
-// step), 4 waves as 2 x 2, each 64 x 64 = 2 x 2 MFMA blocks.  One LDS stage; the next K step
-// is fetched into registers while the current one is multiplied.
+// Row GEMM.  4 waves per work-group arranged WM x WN, each wave owns MI x NJ MFMA blocks of
+// 32 x 32.  Two shapes of use:
+//   small   128 x 128 tile, wave 64 x 64, K step 64, one LDS stage (the next K step waits in
+//           registers); for small or ragged problems and the router logits
+//   big     wave 128 x 128 (16 accumulator blocks): 256 x 256 or 512 x 128 tile, K step 32, two
+//           LDS stages.  A 128 x 128 wave tile needs 16 bytes of LDS reads per lane and MFMA
+//           pair instead of 32, which is what keeps the matrix cores fed from LDS.
+// LDS is dynamic: [stages][A tile | B tile] bf16, then row ids, row scales, segment offsets.
 // ----------------------------------------------------------------------------------------
-namespace rg {
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int LDA = BK + 8;        // A tile [BM][LDA], k contiguous
-constexpr int LDB_NT = BK + 8;     // B tile [BN][LDB_NT] when k is contiguous in memory
-constexpr int LDB_NN = BN + 32;    // B tile [BK][LDB_NN] when n is contiguous in memory
-constexpr int B_ELEMS = (BN * LDB_NT > BK * LDB_NN) ? BN * LDB_NT : BK * LDB_NN;
-constexpr int LDC = BN + 8;        // staged output tile
-static_assert(BM * LDC <= BM * LDA + B_ELEMS, "output staging must fit in the operand tiles");
-}  // namespace rg
+template <int WM_, int WN_, int MI_, int NJ_, int BK_, int STAGES_, int MINB_ = 1>
+struct TileCfg {
+  static constexpr int WM = WM_, WN = WN_, MI = MI_, NJ = NJ_, BK = BK_, STAGES = STAGES_, MINB = MINB_;
+  static constexpr int BM = WM * MI * 32, BN = WN * NJ * 32;
+  static constexpr int LDA = BK + 8;        // A tile [BM][LDA], k contiguous
+  static constexpr int LDB_NT = BK + 8;     // B tile [BN][LDB_NT] when k is contiguous in memory
+  static constexpr int LDB_NN = BN + 32;    // B tile [BK][LDB_NN] when n is contiguous in memory
+  static constexpr int A_ELEMS = BM * LDA;
+  static constexpr int B_ELEMS = (BN * LDB_NT > BK * LDB_NN) ? BN * LDB_NT : BK * LDB_NN;
+  static constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
+  static constexpr int LDC = NJ * 32 + 8;   // staged output: 32 rows per wave at a time
+  static_assert(4 * 32 * LDC <= STAGES * STAGE_ELEMS, "output staging must fit in the operand tiles");
+  static constexpr size_t lds_bytes(bool sets) {
+    return (size_t)STAGES * STAGE_ELEMS * 2 + (size_t)BM * 4 + (size_t)BM * (sets ? 8 : 1) * 4 + 64;
+  }
+};
+typedef TileCfg<2, 2, 2, 2, 64, 1> CfgSmall;    // 128 x 128
+typedef TileCfg<2, 2, 4, 4, 32, 2> CfgSquare;   // 256 x 256
+typedef TileCfg<4, 1, 4, 4, 32, 2> CfgTall;     // 512 x 128
+typedef TileCfg<2, 2, 4, 2, 32, 2, 2> CfgMed;   // 256 x 128, two work-groups per CU
 
-template <int VEC, bool BNT, int TAG, int SEG>
-__global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
-  using namespace rg;
+template <class Cfg, int VEC, bool BNT, int TAG, int SEG>
+__global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmArgs a) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NJ = Cfg::NJ;
+  constexpr int LDA = Cfg::LDA, LDB_NT = Cfg::LDB_NT, LDB_NN = Cfg::LDB_NN;
   typedef typename Chunk<VEC>::type chunk_t;
-  __shared__ __attribute__((aligned(16))) unsigned short smem[BM * LDA + B_ELEMS];
-  __shared__ int ids[BM];
-  __shared__ float gsc[SEG == 1 ? BM * 8 : BM];   // SEG 1: [row][segment]
-  __shared__ long bseg[8];                        // SEG 1: B offset of each segment's expert
-  unsigned short* As = smem;
-  unsigned short* Bs = smem + BM * LDA;
+  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  int* ids = (int*)(smem + Cfg::STAGES * Cfg::STAGE_ELEMS);
+  float* gsc = (float*)(ids + BM);                         // SEG 1: [row][segment]
+  long* bseg = (long*)(gsc + BM * (SEG == 1 ? 8 : 1));     // SEG 1: B offset of each segment's expert
 
   // ---- which tile ------------------------------------------------------------------------
   const int ncol = (a.Nc + BN - 1) / BN;
@@ -143,15 +158,15 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nseg = SEG ? a.nseg : 1;
-  if (tid < BM) {
+  for (int t = tid; t < BM; t += 256) {
     int id = -1;
     float g = 0.f;
-    if (tid < rows) {
-      id = a.perm ? a.perm[(long)h * a.M + row0 + tid] : row0 + tid;
+    if (t < rows) {
+      id = a.perm ? a.perm[(long)h * a.M + row0 + t] : row0 + t;
       if constexpr (SEG != 1) g = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
     }
-    ids[tid] = id;
-    if constexpr (SEG != 1) gsc[tid] = g;
+    ids[t] = id;
+    if constexpr (SEG != 1) gsc[t] = g;
   }
   if constexpr (SEG == 1) {
     for (int t = tid; t < BM * nseg; t += 256) {
@@ -256,84 +271,107 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
       }
     }
   };
-  auto store_lds = [&]() {
+  auto store_lds = [&](int stage) {
+    unsigned short* As = smem + stage * Cfg::STAGE_ELEMS;
+    unsigned short* Bs = As + Cfg::A_ELEMS;
 #pragma unroll
     for (int i = 0; i < A_N; ++i) *(chunk_t*)(&As[a_lds[i]]) = ra[i];
 #pragma unroll
     for (int i = 0; i < B_N; ++i) *(chunk_t*)(&Bs[b_lds[i]]) = rb[i];
   };
 
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = (wave / Cfg::WN) * (MI * 32), wn = (wave % Cfg::WN) * (NJ * 32);
   const int r = lane & 31, g = lane >> 5;
-  f32x16 acc[2][2];
+  f32x16 acc[MI][NJ];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-  // column blocks of this wave that hold real columns (wave-uniform)
   constexpr bool ACC64 = TAG == TAG_ROUTER;
-  const int jmax = !ACC64 ? 2 : (n0 + wn >= Nc ? 0 : 1);   // router: at most 32 columns
-  double acc64[ACC64 ? 2 : 1][16];
+  const bool active = !ACC64 || n0 + wn < Nc;   // router: at most 32 columns, held by the waves with wn == 0
+  double acc64[ACC64 ? MI : 1][16];
   if constexpr (ACC64) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc64[i][q] = 0.0;
   }
 
-  const int nk = nks * nseg;
-  load_global(0);
-  store_lds();
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) load_global(kt + 1);
-    if (!ACC64 || jmax > 0) {
+  auto compute = [&](int stage) {
+    const unsigned short* As = smem + stage * Cfg::STAGE_ELEMS;
+    const unsigned short* Bs = As + Cfg::A_ELEMS;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 fa[2], fb[2];
+      bf16x8 fa[MI], fb[NJ];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = frag_rowmajor(&As[(wm + i * 32 + r) * LDA + kk + 8 * g]);
+      for (int i = 0; i < MI; ++i) fa[i] = frag_rowmajor(&As[(wm + i * 32 + r) * LDA + kk + 8 * g]);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < NJ; ++j) {
         if constexpr (BNT)
           fb[j] = frag_rowmajor(&Bs[(wn + j * 32 + r) * LDB_NT + kk + 8 * g]);
         else
           fb[j] = frag_transposed(Bs, LDB_NN, kk + 8 * g, wn + j * 32, lane);
       }
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NJ; ++j)
           if (!ACC64 || j == 0) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    }
     if constexpr (ACC64) {
-      // router logits: the fp32 accumulator only ever holds the sum of one 64-term K step
+      // router logits: the fp32 accumulator only ever holds the sum of one K step
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
           acc64[i][q] += (double)acc[i][0][q];
           acc[i][0][q] = 0.f;
         }
     }
+  };
+
+  const int nk = nks * nseg;
+  if constexpr (Cfg::STAGES == 1) {
+    load_global(0);
+    store_lds(0);
     __syncthreads();
-    if (kt + 1 < nk) {
-      store_lds();
+    for (int kt = 0; kt < nk; ++kt) {
+      if (kt + 1 < nk) load_global(kt + 1);
+      if (active) compute(0);
       __syncthreads();
+      if (kt + 1 < nk) {
+        store_lds(0);
+        __syncthreads();
+      }
     }
+  } else {
+    // two LDS stages: K step kt is multiplied from stage kt&1 while step kt+2 travels
+    // global -> registers; it is written into the stage just consumed
+    load_global(0);
+    store_lds(0);
+    if (nk > 1) {
+      load_global(1);
+      store_lds(1);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      if (kt + 2 < nk) load_global(kt + 2);
+      compute(kt & 1);
+      __syncthreads();
+      if (kt + 2 < nk) store_lds(kt & 1);
+    }
+    __syncthreads();
   }
 
   // ---- epilogue -------------------------------------------------------------------------
   char* Cb = (char*)(second ? a.C2 : a.C);
   if constexpr (ACC64) {
-    // at most 32 columns (host checks), held by the waves with wn == 0
-    if (jmax > 0) {
+    if (active) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
           const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
@@ -345,31 +383,35 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
     return;
   }
   if (VEC == 8 && a.mode == STORE_T) {
-    // stage the bf16 tile in LDS (the operand tiles are dead), then 16-byte row-contiguous stores
-    unsigned short* Cs = smem;
+    // bf16 output: each wave stages 32 rows of its tile in LDS (the operand tiles are dead),
+    // then stores them as 16-byte pieces along the rows
+    constexpr int LDC = Cfg::LDC;
+    unsigned short* Cs = smem + wave * 32 * LDC;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i) {
+      __syncthreads();
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
-        const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
-        const float sc = SEG == 1 ? 1.f : gsc[row];
+        const int lr = 8 * (q >> 2) + 4 * g + (q & 3);
+        const float sc = SEG == 1 ? 1.f : gsc[wm + i * 32 + lr];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) Cs[row * LDC + wn + j * 32 + r] = f32_to_bf16(acc[i][j][q] * sc);
+        for (int j = 0; j < NJ; ++j) Cs[lr * LDC + j * 32 + r] = f32_to_bf16(acc[i][j][q] * sc);
       }
-    __syncthreads();
+      __syncthreads();
 #pragma unroll
-    for (int i = 0; i < BM * (BN / 8) / 256; ++i) {
-      const int c = tid + i * 256;
-      const int row = c / (BN / 8), cc = (c % (BN / 8)) * 8;
-      const int id = ids[row];
-      if (id < 0 || n0 + cc >= Nc) continue;
-      const long crow = (long)(id / a.c_div) * a.ldc + (long)hh * a.c_hoff;
-      *(uint4*)((unsigned short*)Cb + crow + n0 + cc) = *(const uint4*)(&Cs[row * LDC + cc]);
+      for (int u = 0; u < 32 * NJ * 4 / 64; ++u) {
+        const int c = lane + u * 64;
+        const int lr = c / (NJ * 4), cc = (c % (NJ * 4)) * 8;
+        const int id = ids[wm + i * 32 + lr];
+        if (id < 0 || n0 + wn + cc >= Nc) continue;
+        const long crow = (long)(id / a.c_div) * a.ldc + (long)hh * a.c_hoff;
+        *(uint4*)((unsigned short*)Cb + crow + n0 + wn + cc) = *(const uint4*)(&Cs[lr * LDC + cc]);
+      }
     }
     return;
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < MI; ++i) {
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
       const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
@@ -378,7 +420,7 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
       const float sc = SEG == 1 ? 1.f : gsc[row];
       const long crow = (long)(id / a.c_div) * a.ldc + (long)hh * a.c_hoff;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < NJ; ++j) {
         const int n = n0 + wn + j * 32 + r;
         if (n >= Nc) continue;
         const float v = acc[i][j][q] * sc;
@@ -393,7 +435,7 @@ __global__ __launch_bounds__(256) void mfma_row_gemm_kernel(RowGemmArgs a) {
   }
 }
 
-int rg_kstep() { return rg::BK; }
+int rg_kstep() { return CfgSmall::BK; }
 
 static bool aligned_to(const void* p, size_t b) { return ((uintptr_t)p % b) == 0; }
 
@@ -423,62 +465,96 @@ bool mfma_row_gemm_supported(const RowGemmArgs& a) {
   return row_gemm_vec(a) != 0;
 }
 
-// Only the (step tag, segment mode) pairs the layer uses get a kernel of their own name;
-// everything else runs under the generic tag.
-template <int VEC, bool BNT, int TAG>
-static void launch_rg(const RowGemmArgs& a, dim3 g, hipStream_t s) {
-  constexpr bool sets_ok = TAG == TAG_GENERIC || TAG == TAG_O_EXPERTS || TAG == TAG_V_DGRAD;
-  constexpr bool cat_ok = TAG == TAG_GENERIC || TAG == TAG_QK_DGRAD;
-  if (a.seg_mode == 1) {
-    if constexpr (sets_ok)
-      mfma_row_gemm_kernel<VEC, BNT, TAG, 1><<<g, 256, 0, s>>>(a);
-    else
-      mfma_row_gemm_kernel<VEC, BNT, TAG_GENERIC, 1><<<g, 256, 0, s>>>(a);
-  } else if (a.seg_mode == 2) {
-    if constexpr (cat_ok)
-      mfma_row_gemm_kernel<VEC, BNT, TAG, 2><<<g, 256, 0, s>>>(a);
-    else
-      mfma_row_gemm_kernel<VEC, BNT, TAG_GENERIC, 2><<<g, 256, 0, s>>>(a);
+template <class Cfg, int VEC, bool BNT, int TAG, int SEG>
+static void launch_cfg(const RowGemmArgs& a, hipStream_t s) {
+  const int ncol = (a.Nc + Cfg::BN - 1) / Cfg::BN;
+  dim3 g;
+  if (SEG == 1) {
+    const int tph = (a.M + Cfg::BM - 1) / Cfg::BM + a.E;
+    g = dim3(grid_windows(a.heads * tph, ncol));
   } else {
-    mfma_row_gemm_kernel<VEC, BNT, TAG, 0><<<g, 256, 0, s>>>(a);
+    const int group_rows = a.perm ? a.max_group_rows : a.M;
+    g = dim3(grid_windows((group_rows + Cfg::BM - 1) / Cfg::BM, a.heads * a.E * ncol));
   }
+  const size_t lds = Cfg::lds_bytes(SEG == 1);
+  auto kern = mfma_row_gemm_kernel<Cfg, VEC, BNT, TAG, SEG>;
+  if (lds > 64 * 1024) {
+    static bool raised = false;   // per instantiation
+    if (!raised) {
+      (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      raised = true;
+    }
+  }
+  kern<<<g, 256, lds, s>>>(a);
+}
+
+// tile shape for a launch: the big tiles pay off when a group has enough rows to fill them
+enum { SHAPE_SMALL, SHAPE_SQUARE, SHAPE_TALL, SHAPE_MED };
+static int g_force_shape = -1;   // experiments only
+void rg_force_shape(int shape) { g_force_shape = shape; }
+static int pick_shape(const RowGemmArgs& a) {
+  if (g_force_shape >= 0 && a.tag != TAG_ROUTER && a.tag != TAG_GENERIC) return g_force_shape;
+  const int group_rows = a.perm ? a.max_group_rows : a.M;
+  if (a.tag == TAG_ROUTER || a.tag == TAG_GENERIC) return SHAPE_SMALL;
+  // measured on MI355X: the 256 x 128 tile with two work-groups per CU wins where the rows are
+  // dense (its operand traffic per flop is 25 % lower); expert-gathered rows do better with
+  // the small tile (more work-groups in flight per CU)
+  if (!a.perm && group_rows >= 4096 && a.Nc >= 128) return SHAPE_MED;
+  return SHAPE_SMALL;
+}
+
+// Only the (step tag, segment mode) pairs the layer uses get a kernel of their own name;
+// everything else runs under the generic tag with the small tile.
+template <bool BNT, int TAG, int SEG>
+static void launch_tagged(const RowGemmArgs& a, hipStream_t s) {
+  switch (pick_shape(a)) {
+    case SHAPE_SQUARE: launch_cfg<CfgSquare, 8, BNT, TAG, SEG>(a, s); break;
+    case SHAPE_TALL: launch_cfg<CfgTall, 8, BNT, TAG, SEG>(a, s); break;
+    case SHAPE_MED: launch_cfg<CfgMed, 8, BNT, TAG, SEG>(a, s); break;
+    default: launch_cfg<CfgSmall, 8, BNT, TAG, SEG>(a, s); break;
+  }
+}
+
+template <int VEC, bool BNT>
+static void launch_generic(const RowGemmArgs& a, hipStream_t s) {
+  if (a.seg_mode == 1)
+    launch_cfg<CfgSmall, VEC, BNT, TAG_GENERIC, 1>(a, s);
+  else if (a.seg_mode == 2)
+    launch_cfg<CfgSmall, VEC, BNT, TAG_GENERIC, 2>(a, s);
+  else
+    launch_cfg<CfgSmall, VEC, BNT, TAG_GENERIC, 0>(a, s);
 }
 
 void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.Nc <= 0) return;
   const int vec = row_gemm_vec(a);
   const bool nt = a.sbk == 1;
-  const int ncol = (a.Nc + rg::BN - 1) / rg::BN;
-  dim3 g;
-  if (a.seg_mode == 1) {
-    const int tph = (a.M + rg::BM - 1) / rg::BM + a.E;
-    g = dim3(grid_windows(a.heads * tph, ncol));
-  } else {
-    const int group_rows = a.perm ? a.max_group_rows : a.M;
-    g = dim3(grid_windows((group_rows + rg::BM - 1) / rg::BM, a.heads * a.E * ncol));
-  }
-  if (vec == 8 && nt) {
-    switch (a.tag) {
-      case TAG_O_DGRAD: launch_rg<8, true, TAG_O_DGRAD>(a, g, s); break;
-      case TAG_V_DGRAD: launch_rg<8, true, TAG_V_DGRAD>(a, g, s); break;
-      case TAG_QK_DGRAD: launch_rg<8, true, TAG_QK_DGRAD>(a, g, s); break;
-      default: launch_rg<8, true, TAG_GENERIC>(a, g, s); break;
+  if (vec == 8) {
+    const int key = a.tag * 4 + a.seg_mode;
+    if (nt) {
+      switch (key) {
+        case TAG_O_DGRAD * 4 + 0: return launch_tagged<true, TAG_O_DGRAD, 0>(a, s);
+        case TAG_V_DGRAD * 4 + 0: return launch_tagged<true, TAG_V_DGRAD, 0>(a, s);
+        case TAG_V_DGRAD * 4 + 1: return launch_tagged<true, TAG_V_DGRAD, 1>(a, s);
+        case TAG_QK_DGRAD * 4 + 0: return launch_tagged<true, TAG_QK_DGRAD, 0>(a, s);
+        case TAG_QK_DGRAD * 4 + 2: return launch_tagged<true, TAG_QK_DGRAD, 2>(a, s);
+        default: return launch_generic<8, true>(a, s);
+      }
+    } else {
+      switch (key) {
+        case TAG_QK_PROJ * 4 + 0: return launch_tagged<false, TAG_QK_PROJ, 0>(a, s);
+        case TAG_V_EXPERTS * 4 + 0: return launch_tagged<false, TAG_V_EXPERTS, 0>(a, s);
+        case TAG_O_EXPERTS * 4 + 0: return launch_tagged<false, TAG_O_EXPERTS, 0>(a, s);
+        case TAG_O_EXPERTS * 4 + 1: return launch_tagged<false, TAG_O_EXPERTS, 1>(a, s);
+        case TAG_ROUTER * 4 + 0: return launch_cfg<CfgSmall, 8, false, TAG_ROUTER, 0>(a, s);
+        default: return launch_generic<8, false>(a, s);
+      }
     }
-  } else if (vec == 8) {
-    switch (a.tag) {
-      case TAG_QK_PROJ: launch_rg<8, false, TAG_QK_PROJ>(a, g, s); break;
-      case TAG_V_EXPERTS: launch_rg<8, false, TAG_V_EXPERTS>(a, g, s); break;
-      case TAG_O_EXPERTS: launch_rg<8, false, TAG_O_EXPERTS>(a, g, s); break;
-      case TAG_ROUTER: mfma_row_gemm_kernel<8, false, TAG_ROUTER, 0><<<g, 256, 0, s>>>(a); break;
-      default: launch_rg<8, false, TAG_GENERIC>(a, g, s); break;
-    }
-  } else if (nt) {
-    launch_rg<4, true, TAG_GENERIC>(a, g, s);
-  } else if (a.tag == TAG_ROUTER) {
-    mfma_row_gemm_kernel<4, false, TAG_ROUTER, 0><<<g, 256, 0, s>>>(a);
-  } else {
-    launch_rg<4, false, TAG_GENERIC>(a, g, s);
   }
+  if (nt)
+    return launch_generic<4, true>(a, s);
+  if (a.tag == TAG_ROUTER) return launch_cfg<CfgSmall, 4, false, TAG_ROUTER, 0>(a, s);
+  return launch_generic<4, false>(a, s);
 }
 
 // ----------------------------------------------------------------------------------------
