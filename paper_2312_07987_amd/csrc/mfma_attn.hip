@@ -92,6 +92,48 @@ __device__ __forceinline__ bf16x8 global_frag(const unsigned short* row, int d, 
   return u.v;
 }
 
+// NROWS rows of `dh` bf16 (zero padded to DH columns and beyond `valid_rows`) on their way
+// from global memory to LDS: load() issues the global loads into registers, store() writes
+// them to one or two LDS tiles (the second with another row stride, for the transposing
+// reads).  Keeping the two apart lets the next tile travel while the current one is used.
+template <int DH, int VEC, int NROWS>
+struct RowTile {
+  static constexpr int CPR = DH / VEC, TOTAL = NROWS * CPR, NCH = (TOTAL + 255) / 256;
+  uint4 r[NCH];   // VEC == 4 uses .x/.y only
+  __device__ __forceinline__ void load(const unsigned short* src, long row_stride, int valid_rows, int dh, int tid) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + i * 256;
+      const int row = c / CPR, d = (c % CPR) * VEC;
+      r[i] = make_uint4(0, 0, 0, 0);
+      if (c < TOTAL && row < valid_rows && d < dh) {
+        if constexpr (VEC == 8) {
+          r[i] = *(const uint4*)(src + (long)row * row_stride + d);
+        } else {
+          const uint2 v = *(const uint2*)(src + (long)row * row_stride + d);
+          r[i].x = v.x;
+          r[i].y = v.y;
+        }
+      }
+    }
+  }
+  __device__ __forceinline__ void store(unsigned short* t0, int ld0, unsigned short* t1, int ld1, int tid) const {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + i * 256;
+      if (c >= TOTAL) continue;
+      const int row = c / CPR, d = (c % CPR) * VEC;
+      if constexpr (VEC == 8) {
+        *(uint4*)(t0 + row * ld0 + d) = r[i];
+        if (t1 != t0) *(uint4*)(t1 + row * ld1 + d) = r[i];
+      } else {
+        *(uint2*)(t0 + row * ld0 + d) = make_uint2(r[i].x, r[i].y);
+        if (t1 != t0) *(uint2*)(t1 + row * ld1 + d) = make_uint2(r[i].x, r[i].y);
+      }
+    }
+  }
+};
+
 // ----------------------------------------------------------------------------------------
 // forward: block = 4 waves x 32 queries, key tiles of KT keys
 // ----------------------------------------------------------------------------------------
@@ -131,11 +173,18 @@ __global__ __launch_bounds__(256) void mfma_attn_fwd_kernel(AttnArgs a) {
   const float sc = a.scale * 1.44269504088896340736f;   // logits in log2 units
 
   const int kend = a.causal ? min(T, q0 + 128) : T;
+  RowTile<DH, VEC, KT> tk, tv;
+  tk.load(K, rs, T, dh, tid);
+  tv.load(V, rs, T, dh, tid);
   for (int k0 = 0; k0 < kend; k0 += KT) {
     __syncthreads();
-    stage_rows<DH, VEC>(Ks, LDK, K + (long)k0 * rs, rs, KT, T - k0, dh, tid);
-    stage_rows<DH, VEC>(Vs, LDV, V + (long)k0 * rs, rs, KT, T - k0, dh, tid);
+    tk.store(Ks, LDK, Ks, LDK, tid);
+    tv.store(Vs, LDV, Vs, LDV, tid);
     __syncthreads();
+    if (k0 + KT < kend) {   // the next tile travels while this one is used
+      tk.load(K + (long)(k0 + KT) * rs, rs, T - k0 - KT, dh, tid);
+      tv.load(V + (long)(k0 + KT) * rs, rs, T - k0 - KT, dh, tid);
+    }
     if (a.causal && k0 > wq_last) continue;      // wave-uniform: nothing visible to this wave
 
     float s[KT / 32][16];
@@ -149,7 +198,7 @@ __global__ __launch_bounds__(256) void mfma_attn_fwd_kernel(AttnArgs a) {
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Ks[(kb * 32 + r) * LDK + kk * 16 + 8 * g]), qf[kk], acc, 0,
                                                       0, 0);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[kb][i] = acc[i] * sc;
+      for (int i = 0; i < 16; ++i) s[kb][i] = acc[i];
     }
     const bool need_mask = (a.causal && k0 + KT - 1 > q0 + wave * 32) || (k0 + KT > T);
     if (need_mask) {
@@ -166,23 +215,26 @@ __global__ __launch_bounds__(256) void mfma_attn_fwd_kernel(AttnArgs a) {
     for (int kb = 0; kb < KT / 32; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) mt = fmaxf(mt, s[kb][i]);
-    mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+    mt = fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc;  // sc > 0: the maximum of the scaled logits
     const float mn = fmaxf(m, mt);
-    const float alpha = exp2f(m - mn);           // m = -inf on the first tile -> 0
+    const bool moved = mn > m;                    // wave-uniform test below: most tiles move no maximum
+    const float alpha = moved ? __builtin_amdgcn_exp2f(m - mn) : 1.f;   // m = -inf on the first tile -> 0
     m = mn;
     float ps = 0.f;
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        s[kb][i] = exp2f(s[kb][i] - mn);
+        s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], sc, -mn));   // masked: -inf -> 0
         ps += s[kb][i];
       }
     l = l * alpha + ps;
+    if (__ballot(moved)) {
 #pragma unroll
-    for (int d = 0; d < NDB; ++d)
+      for (int d = 0; d < NDB; ++d)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
+        for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
+    }
 
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb)
@@ -307,16 +359,28 @@ __global__ __launch_bounds__(256) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
   const float sc = a.scale * 1.44269504088896340736f;
 
   const int qbeg = a.causal ? (k0 / QT) * QT : 0;
-  for (int q0 = qbeg; q0 < T; q0 += QT) {
-    __syncthreads();
-    stage_rows2<DH, VEC>(Qr, LDR, Qt, LDT, Q + (long)q0 * rs, rs, QT, T - q0, dh, tid);
-    stage_rows2<DH, VEC>(Gr, LDR, Gt, LDT, dO + (long)q0 * rs, rs, QT, T - q0, dh, tid);
+  RowTile<DH, VEC, QT> tq, tg;
+  float nlse = 0.f, ndel = 0.f;
+  auto prefetch = [&](int q0) {
+    tq.load(Q + (long)q0 * rs, rs, T - q0, dh, tid);
+    tg.load(dO + (long)q0 * rs, rs, T - q0, dh, tid);
     if (tid < QT) {
       const bool ok = q0 + tid < T;
-      lse_s[tid] = ok ? lse[q0 + tid] * 1.44269504088896340736f : 0.f;
-      del_s[tid] = ok ? delta[(long)(q0 + tid) * a.H] : 0.f;
+      nlse = ok ? lse[q0 + tid] * 1.44269504088896340736f : 0.f;
+      ndel = ok ? delta[(long)(q0 + tid) * a.H] : 0.f;
+    }
+  };
+  if (qbeg < T) prefetch(qbeg);
+  for (int q0 = qbeg; q0 < T; q0 += QT) {
+    __syncthreads();
+    tq.store(Qr, LDR, Qt, LDT, tid);
+    tg.store(Gr, LDR, Gt, LDT, tid);
+    if (tid < QT) {
+      lse_s[tid] = nlse;
+      del_s[tid] = ndel;
     }
     __syncthreads();
+    if (q0 + QT < T) prefetch(q0 + QT);
     if (a.causal && q0 + QT - 1 < wk_first) continue;   // every query of the tile precedes this wave's keys
 
     f32x16 S, dP;
@@ -338,7 +402,7 @@ __global__ __launch_bounds__(256) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
         const int i = 4 * i4 + t;
         const int qq = q0 + 8 * i4 + 4 * g + t;
         const bool vis = qq < T && key < T && (!a.causal || key <= qq);
-        const float pv = vis ? exp2f(S[i] * sc - Lv[t]) : 0.f;
+        const float pv = vis ? __builtin_amdgcn_exp2f(fmaf(S[i], sc, -Lv[t])) : 0.f;
         p[i] = pv;
         ds[i] = pv * (dP[i] - Dv[t]);
       }
@@ -408,11 +472,18 @@ __global__ __launch_bounds__(256) void mfma_attn_dq_kernel(AttnBwdArgs a) {
   const float sc = a.scale * 1.44269504088896340736f;
 
   const int kend = a.causal ? min(T, q0 + 128) : T;
+  RowTile<DH, VEC, KT> tk, tv;
+  tk.load(K, rs, T, dh, tid);
+  tv.load(V, rs, T, dh, tid);
   for (int k0 = 0; k0 < kend; k0 += KT) {
     __syncthreads();
-    stage_rows2<DH, VEC>(Kr, LDR, Kt, LDT, K + (long)k0 * rs, rs, KT, T - k0, dh, tid);
-    stage_rows2<DH, VEC>(Vr, LDR, Vr, LDR, V + (long)k0 * rs, rs, KT, T - k0, dh, tid);
+    tk.store(Kr, LDR, Kt, LDT, tid);
+    tv.store(Vr, LDR, Vr, LDR, tid);
     __syncthreads();
+    if (k0 + KT < kend) {
+      tk.load(K + (long)(k0 + KT) * rs, rs, T - k0 - KT, dh, tid);
+      tv.load(V + (long)(k0 + KT) * rs, rs, T - k0 - KT, dh, tid);
+    }
     if (a.causal && k0 > wq_last) continue;
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb) {
@@ -429,7 +500,7 @@ __global__ __launch_bounds__(256) void mfma_attn_dq_kernel(AttnBwdArgs a) {
       for (int i = 0; i < 16; ++i) {
         const int key = k0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
         const bool vis = key < T && (!a.causal || key <= q);
-        const float pv = vis ? exp2f(S[i] * sc - lse2) : 0.f;
+        const float pv = vis ? __builtin_amdgcn_exp2f(fmaf(S[i], sc, -lse2)) : 0.f;
         ds[i] = pv * (dP[i] - del);
       }
 #pragma unroll
