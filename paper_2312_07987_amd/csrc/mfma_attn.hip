@@ -134,6 +134,26 @@ struct RowTile {
   }
 };
 
+// Work-group -> (sequence, head, tile).  All work-groups of a launch are resident at once
+// (two per CU), so under a causal mask the order decides the balance: the first half of the
+// grid holds the heavy tiles in descending order, the second half the light tiles in
+// ascending order, and the CU that got the r-th heaviest tile also gets the r-th lightest.
+// Consecutive ids go to different XCDs; id % 8 = (b*H + h) % 8 keeps all tiles of one
+// (sequence, head) on one XCD, whose L2 then serves the K/V re-reads.
+__device__ __forceinline__ void attn_block_map(int L, int ntile, int P, int H, bool causal, bool heavy_is_high, int& b,
+                                               int& h, int& tile) {
+  const int rank = L / P, pair = L % P;
+  b = pair / H;
+  h = pair % H;
+  int t = rank;   // index counted from the heavy end
+  if (causal) {
+    const int nheavy = (ntile + 1) / 2;
+    t = rank < nheavy ? rank : ntile - 1 - (rank - nheavy);
+  }
+  tile = heavy_is_high ? ntile - 1 - t : t;
+  if (!causal) tile = rank;
+}
+
 // ----------------------------------------------------------------------------------------
 // forward: block = 4 waves x 32 queries, key tiles of KT keys
 // ----------------------------------------------------------------------------------------
@@ -146,8 +166,8 @@ __global__ __launch_bounds__(256) void mfma_attn_fwd_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned short Ks[KT * LDK];
   __shared__ __attribute__((aligned(16))) unsigned short Vs[KT * LDV];
 
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int qt = a.causal ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;   // heavy tiles first
+  int b, h, qt;
+  attn_block_map(blockIdx.x, (a.T + 127) / 128, a.B * a.H, a.H, a.causal, true, b, h, qt);
   const int q0 = qt * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
@@ -329,8 +349,9 @@ __global__ __launch_bounds__(256) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
   unsigned short* Qt = SEP ? Qt_ : Qr;
   unsigned short* Gt = SEP ? Gt_ : Gr;
 
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int k0 = blockIdx.x * 128;
+  int b, h, ktile;
+  attn_block_map(blockIdx.x, (a.T + 127) / 128, a.B * a.H, a.H, a.causal, false, b, h, ktile);
+  const int k0 = ktile * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
   const int T = a.T, dh = a.dh;
@@ -441,8 +462,8 @@ __global__ __launch_bounds__(256) void mfma_attn_dq_kernel(AttnBwdArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned short Kt_[SEP ? KT * LDT : 8];
   unsigned short* Kt = SEP ? Kt_ : Kr;
 
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int qt = a.causal ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;
+  int b, h, qt;
+  attn_block_map(blockIdx.x, (a.T + 127) / 128, a.B * a.H, a.H, a.causal, true, b, h, qt);
   const int q0 = qt * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
@@ -523,13 +544,13 @@ bool mfma_attn_supported(int T, int dh) { return T >= 1 && dh >= 4 && dh <= 256 
 template <int DH>
 static void launch_dh(const AttnArgs* f, const AttnBwdArgs* bw, hipStream_t s) {
   if (f) {
-    dim3 g((f->T + 127) / 128, f->H, f->B);
+    dim3 g(((f->T + 127) / 128) * f->H * f->B);
     if (attn_vec(f->dh) == 8)
       mfma_attn_fwd_kernel<DH, 8><<<g, 256, 0, s>>>(*f);
     else
       mfma_attn_fwd_kernel<DH, 4><<<g, 256, 0, s>>>(*f);
   } else {
-    dim3 g((bw->T + 127) / 128, bw->H, bw->B);
+    dim3 g(((bw->T + 127) / 128) * bw->H * bw->B);
     if (attn_vec(bw->dh) == 8) {
       mfma_attn_dkv_kernel<DH, 8><<<g, 256, 0, s>>>(*bw);
       mfma_attn_dq_kernel<DH, 8><<<g, 256, 0, s>>>(*bw);
