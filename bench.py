@@ -42,7 +42,7 @@ def step_work(cfg):
         "fwd.v_experts": expert, "fwd.o_experts": expert,
         "fwd.attention": attn, "bwd.attention": 5 * attn // 2,
         "bwd.o_dgrad": expert, "bwd.o_wgrad": expert, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
-        "bwd.q_wgrad": proj, "bwd.k_wgrad": proj, "bwd.q_dgrad": proj, "bwd.k_dgrad": proj,
+        "bwd.q_wgrad": proj, "bwd.k_wgrad": proj, "bwd.qk_wgrad": 2 * proj, "bwd.q_dgrad": proj, "bwd.k_dgrad": proj,
         "bwd.router_wgrad": router // 2, "bwd.router_dgrad": router // 2,
     }
     alu = {"fwd.router": router}

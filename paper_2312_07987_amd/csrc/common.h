@@ -117,7 +117,17 @@ struct WgradArgs {
   int chunk;  // rows reduced by one block
   int tag;
   int max_group_rows;  // upper bound of the rows of one group (tokens per call)
+  // Second operand set: heads h >= hsplit (hsplit > 0) use Bm2 / dW2 with head index h - hsplit.
+  const void* Bm2;
+  float* dW2;
+  int hsplit;
+  // Deterministic reduction (MFMA kernel): if partial != NULL every block stores the partial
+  // sum of its chunk to partial[((h*E + e)*max_chunks + chunk)*Ka*Kb + i*Kb + j] and
+  // launch_wgrad_reduce adds the chunks of each group into dW (plain stores, no zero fill).
+  float* partial;
+  int max_chunks;
 };
+void launch_wgrad_reduce(const WgradArgs& a, hipStream_t s);
 
 // Finds the tile `tile` (of `bm` rows) among the E groups of one head.  Returns false when
 // `tile` lies beyond the last tile.  off points at the head's E+1 offsets.

@@ -62,11 +62,13 @@ struct Layout {
   size_t Z, blockcnt, acc32;                                       // forward scratch
   size_t setid, gset, setperm, setoff, setcnt, yh;                 // expert-set path (bf16 only)
   size_t rh;                                                       // two-stage router scratch (bf16 only)
+  size_t wpart;                                                    // per-chunk weight-gradient partial sums (bf16 only)
   size_t u, dctx, dQ, dK, dV, delta, dgate, dz;                    // backward scratch
 };
 
 // number of k-subsets of E experts, saturating at MAX_SETS + 1
 constexpr int MAX_SETS = 128;
+constexpr size_t WGRAD_CHUNK = 1024;   // rows reduced by one weight-gradient block
 int count_sets(int E, int k) {
   long v = 1;
   for (int i = 1; i <= k; ++i) {
@@ -136,8 +138,11 @@ Layout make_layout(const sh_shape* s) {
   } else {
     L.setid = L.gset = L.setperm = L.setoff = L.setcnt = L.yh = 0;
   }
-  L.rh = 0;
+  L.rh = L.wpart = 0;
   if (s->dtype == SH_BF16) {
+    // groups x chunks-per-group x one expert matrix, fp32 (the dense Q/K pair counts as 2H groups)
+    const size_t groups = H * E > 2 * H ? H * E : 2 * H;
+    L.wpart = take(groups * ((N + WGRAD_CHUNK - 1) / WGRAD_CHUNK) * dm * dh * 4);
     size_t o6[6];
     L.rh = take(router_hybrid_bytes((int)N, (int)dm, (int)H, (int)E, o6));
   }
@@ -204,11 +209,42 @@ void row_gemm(const Ctx& c, const RowGemmArgs& a) {
     launch_simt_row_gemm(a, c.bf16, c.st);
 }
 
-void wgrad(const Ctx& c, const WgradArgs& a) {
-  if (use_mfma(c) && mfma_wgrad_supported(a))
+// Weight gradient of one step.  MFMA family: per-chunk partial sums + a reduction (deterministic,
+// the outputs need no zero fill); otherwise atomic adds into zeroed outputs.
+void wgrad(const Ctx& c, WgradArgs a, bool deterministic = true) {
+  if (use_mfma(c)) {
+    WgradArgs b = a;
+    if (deterministic) {
+      b.partial = c.p<float>(c.L.wpart);
+      b.max_chunks = (int)(((a.perm ? a.max_group_rows : a.M) + a.chunk - 1) / a.chunk);
+    }
+    if (b.partial && mfma_wgrad_supported(b)) {
+      launch_mfma_wgrad(b, c.st);
+      launch_wgrad_reduce(b, c.st);
+      return;
+    }
+  }
+  // atomic paths add into zeroed outputs
+  const int h1 = a.hsplit > 0 ? a.hsplit : a.heads;
+  launch_fill_f32(a.dW, (size_t)h1 * a.E * a.Ka * a.Kb, 0.f, c.st);
+  if (a.hsplit > 0) launch_fill_f32(a.dW2, (size_t)(a.heads - a.hsplit) * a.E * a.Ka * a.Kb, 0.f, c.st);
+  if (use_mfma(c) && mfma_wgrad_supported(a)) {
     launch_mfma_wgrad(a, c.st);
-  else
-    launch_simt_wgrad(a, c.bf16, c.st);
+    return;
+  }
+  if (a.hsplit > 0) {   // the plain kernels take one operand set at a time
+    WgradArgs a1 = a, a2 = a;
+    a1.heads = a.hsplit;
+    a1.hsplit = 0;
+    a2.heads = a.heads - a.hsplit;
+    a2.hsplit = 0;
+    a2.Bm = a.Bm2;
+    a2.dW = a.dW2;
+    launch_simt_wgrad(a1, c.bf16, c.st);
+    launch_simt_wgrad(a2, c.bf16, c.st);
+    return;
+  }
+  launch_simt_wgrad(a, c.bf16, c.st);
 }
 
 // rows taken through the expert-sorted permutation of one side
@@ -548,14 +584,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     return fail(SH_ERR_INVALID_ARG, "x, W_Q, W_K, W_V, W_O, dy, dx, dW_Q, dW_K, dW_V, dW_O must not be NULL");
   const int N = c.N, H = c.H, E = c.E, k = c.k, dh = c.dh, dm = c.dm;
   const long hd = (long)H * dh;
-  const int chunk = 1024;
+  const int chunk = (int)WGRAD_CHUNK;
   const bool sets = sets_usable(c);
-
-  prof_mark(c.st, "bwd.zero_dw");
-  launch_fill_f32(dW_Q, (size_t)H * dm * dh, 0.f, c.st);
-  launch_fill_f32(dW_K, (size_t)H * dm * dh, 0.f, c.st);
-  launch_fill_f32(dW_V, (size_t)H * E * dm * dh, 0.f, c.st);
-  launch_fill_f32(dW_O, (size_t)H * E * dh * dm, 0.f, c.st);
 
   // output experts: u[h][a][:] = dy[n] W_O[h,e]^T (unscaled), then dctx, d(gate_D), delta
   {
@@ -648,12 +678,12 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   // and that overwrites the fp32 dx accumulator; otherwise the accumulator is zeroed and every
   // head adds its part atomically.
   float* dxacc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)dx;
-  for (int which = 0; which < 2; ++which) {
-    const void* g = c.p<void>(which ? c.L.dK : c.L.dQ);
-    prof_mark(c.st, which ? "bwd.k_wgrad" : "bwd.q_wgrad");
+  {
+    prof_mark(c.st, "bwd.qk_wgrad");
     WgradArgs w{};
     w.tag = TAG_QK_WGRAD;
-    w.heads = H;
+    w.heads = 2 * H;
+    w.hsplit = H;
     w.E = 1;
     w.M = N;
     w.a_div = 1;
@@ -662,11 +692,13 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.lda = dm;
     w.a_hoff = 0;
     w.Ka = dm;
-    w.Bm = g;
+    w.Bm = c.p<void>(c.L.dQ);
+    w.Bm2 = c.p<void>(c.L.dK);
     w.ldb = hd;
     w.b_hoff = dh;
     w.Kb = dh;
-    w.dW = which ? dW_K : dW_Q;
+    w.dW = dW_Q;
+    w.dW2 = dW_K;
     w.w_hstride = (long)dm * dh;
     w.swa = dh;
     w.chunk = chunk;
@@ -798,7 +830,6 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     float* dWs[2] = {dW_S, c.shared ? nullptr : dW_D};
     float* dbs[2] = {db_S, c.shared ? nullptr : db_D};
     for (int sd = 0; sd < sides; ++sd) {
-      if (dWs[sd]) launch_fill_f32(dWs[sd], (size_t)dm * HE, 0.f, c.st);
       if (dbs[sd]) launch_fill_f32(dbs[sd], (size_t)HE, 0.f, c.st);
     }
     RouterBwdArgs rb{};
@@ -833,8 +864,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
         w.Kb = HE;
         w.dW = dWs[sd];
         w.swa = HE;
-        w.chunk = chunk;
-        wgrad(c, w);
+        w.chunk = 256;   // tiny output: many short chunks keep the GPU busy, atomics are few
+        wgrad(c, w, false);
       }
       prof_mark(c.st, "bwd.router_dgrad");
       RowGemmArgs a = identity_rows(c, 1);

@@ -563,27 +563,35 @@ void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s) {
 // loads.  Block tile 128 (i) x 128 (j), 32 rows per step, `chunk` rows per block, fp32
 // atomic add of the block's partial sum.
 // ----------------------------------------------------------------------------------------
-namespace wg {
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int LD = 128 + 32;
-constexpr int MAX_CHUNK = 2048;
-}  // namespace wg
+// Output tile BM (features of A) x BN (features of Bm), 4 waves as WM x WN with MI x NJ MFMA
+// blocks each, BK rows per step, two LDS stages (one barrier per step).  Dynamic LDS:
+// [2][A tile [BK][BM+32] | B tile [BK][BN+32]] bf16, then the chunk's row ids and gates.
+template <int WM_, int WN_, int MI_, int NJ_, int MINB_>
+struct WgCfg {
+  static constexpr int WM = WM_, WN = WN_, MI = MI_, NJ = NJ_, MINB = MINB_, BK = 32;
+  static constexpr int BM = WM * MI * 32, BN = WN * NJ * 32;
+  static constexpr int LDA = BM + 32, LDB = BN + 32;      // row strides 16 banks (mod 64) apart
+  static constexpr int STAGE_ELEMS = BK * (LDA + LDB);
+  static constexpr int MAX_CHUNK = 2048;
+  static constexpr size_t lds_bytes() { return (size_t)2 * STAGE_ELEMS * 2 + (size_t)MAX_CHUNK * 8; }
+};
+typedef WgCfg<2, 2, 2, 2, 1> WgSmall;   // 128 x 128
+typedef WgCfg<1, 4, 4, 2, 2> WgWide;    // 128 x 256, wave tile 128 x 64, two work-groups per CU
+typedef WgCfg<4, 1, 2, 4, 2> WgTall;    // 256 x 128, wave tile 64 x 128, two work-groups per CU
 
-template <int VEC, int TAG>
-__global__ __launch_bounds__(256) void mfma_wgrad_kernel(WgradArgs a) {
-  using namespace wg;
+template <class Cfg, int VEC, int TAG>
+__global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NJ = Cfg::NJ;
+  constexpr int LDA = Cfg::LDA, LDB = Cfg::LDB;
   typedef typename Chunk<VEC>::type chunk_t;
-  __shared__ __attribute__((aligned(16))) unsigned short As[2][BK * LD];
-  __shared__ __attribute__((aligned(16))) unsigned short Bs[2][BK * LD];
-  __shared__ int ids[MAX_CHUNK];
-  __shared__ float gsc[MAX_CHUNK];
+  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  int* ids = (int*)(smem + 2 * Cfg::STAGE_ELEMS);
+  float* gsc = (float*)(ids + Cfg::MAX_CHUNK);
 
-  // window = chunk index inside a group; every (group, output tile) of a window shares an XCD,
-  // so the rows of a token window are fetched from HBM once and then hit in that XCD's L2
-  const int ti_ = (a.Ka + BM - 1) / BM, tj = (a.Kb + BN - 1) / BN;
-  const int ntile = ti_ * tj;
   // unit = (chunk window, group); the output tiles of a unit share an XCD (they read the same
   // rows), consecutive units go to different XCDs
+  const int ti_ = (a.Ka + BM - 1) / BM, tj = (a.Kb + BN - 1) / BN;
+  const int ntile = ti_ * tj;
   const int G = a.heads * a.E;
   int unit, tile;
   decode_block(blockIdx.x, ntile, unit, tile);
@@ -611,47 +619,57 @@ __global__ __launch_bounds__(256) void mfma_wgrad_kernel(WgradArgs a) {
   __syncthreads();
 
   const int i0 = (tile / tj) * BM, j0 = (tile % tj) * BN;
+  const bool second = a.hsplit > 0 && h >= a.hsplit;
+  const int hh = second ? h - a.hsplit : h;
   const unsigned short* A = (const unsigned short*)a.A;
-  const unsigned short* Bm = (const unsigned short*)a.Bm;
+  const unsigned short* Bm = (const unsigned short*)(second ? a.Bm2 : a.Bm);
   const bool scaled = a.gate != nullptr;
 
-  constexpr int CPR = BM / VEC;                // chunks per tile row (same for both tiles)
-  constexpr int NCH = BK * CPR / 256;          // chunks per thread per tile
-  chunk_t ra[NCH], rb[NCH];
+  constexpr int A_CPR = BM / VEC, B_CPR = BN / VEC;     // chunks per tile row
+  constexpr int A_N = BK * A_CPR / 256, B_N = BK * B_CPR / 256;
+  chunk_t ra[A_N], rb[B_N];
   auto load_global = [&](int r0) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int c = tid + i * 256;
-      int rr = c / CPR, fc = (c % CPR) * VEC;
+    for (int i = 0; i < A_N; ++i) {
+      const int c = tid + i * 256;
+      const int rr = c / A_CPR, fc = (c % A_CPR) * VEC;
       ra[i] = zero_chunk<VEC>();
-      rb[i] = zero_chunk<VEC>();
-      if (r0 + rr < rows) {
-        int id = ids[r0 + rr];
-        if (i0 + fc < a.Ka) {
-          ra[i] = *(const chunk_t*)(A + (long)(id / a.a_div) * a.lda + (long)h * a.a_hoff + i0 + fc);
-          if (scaled) ra[i] = scale_chunk(ra[i], gsc[r0 + rr]);
-        }
-        if (j0 + fc < a.Kb) rb[i] = *(const chunk_t*)(Bm + (long)(id / a.b_div) * a.ldb + (long)h * a.b_hoff + j0 + fc);
+      if (r0 + rr < rows && i0 + fc < a.Ka) {
+        ra[i] = *(const chunk_t*)(A + (long)(ids[r0 + rr] / a.a_div) * a.lda + (long)hh * a.a_hoff + i0 + fc);
+        if (scaled) ra[i] = scale_chunk(ra[i], gsc[r0 + rr]);
       }
     }
-  };
-  auto store_lds = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int c = tid + i * 256;
-      int rr = c / CPR, fc = (c % CPR) * VEC;
-      *(chunk_t*)(&As[buf][rr * LD + fc]) = ra[i];
-      *(chunk_t*)(&Bs[buf][rr * LD + fc]) = rb[i];
+    for (int i = 0; i < B_N; ++i) {
+      const int c = tid + i * 256;
+      const int rr = c / B_CPR, fc = (c % B_CPR) * VEC;
+      rb[i] = zero_chunk<VEC>();
+      if (r0 + rr < rows && j0 + fc < a.Kb)
+        rb[i] = *(const chunk_t*)(Bm + (long)(ids[r0 + rr] / a.b_div) * a.ldb + (long)hh * a.b_hoff + j0 + fc);
+    }
+  };
+  auto store_lds = [&](int stage) {
+    unsigned short* As = smem + stage * Cfg::STAGE_ELEMS;
+    unsigned short* Bs = As + BK * LDA;
+#pragma unroll
+    for (int i = 0; i < A_N; ++i) {
+      const int c = tid + i * 256;
+      *(chunk_t*)(&As[(c / A_CPR) * LDA + (c % A_CPR) * VEC]) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < B_N; ++i) {
+      const int c = tid + i * 256;
+      *(chunk_t*)(&Bs[(c / B_CPR) * LDB + (c % B_CPR) * VEC]) = rb[i];
     }
   };
 
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = (wave / Cfg::WN) * (MI * 32), wn = (wave % Cfg::WN) * (NJ * 32);
   const int r = lane & 31, g = lane >> 5;
-  f32x16 acc[2][2];
+  f32x16 acc[MI][NJ];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
@@ -660,45 +678,100 @@ __global__ __launch_bounds__(256) void mfma_wgrad_kernel(WgradArgs a) {
   store_lds(0);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
+    const int stage = kt & 1;
     if (kt + 1 < nk) load_global((kt + 1) * BK);
+    const unsigned short* As = smem + stage * Cfg::STAGE_ELEMS;
+    const unsigned short* Bs = As + BK * LDA;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 fa[2], fb[2];
+      bf16x8 fa[MI], fb[NJ];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = frag_transposed(&As[buf][0], LD, kk + 8 * g, wm + i * 32, lane);
+      for (int i = 0; i < MI; ++i) fa[i] = frag_transposed(As, LDA, kk + 8 * g, wm + i * 32, lane);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) fb[j] = frag_transposed(&Bs[buf][0], LD, kk + 8 * g, wn + j * 32, lane);
+      for (int j = 0; j < NJ; ++j) fb[j] = frag_transposed(Bs, LDB, kk + 8 * g, wn + j * 32, lane);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_lds(buf ^ 1);
+    if (kt + 1 < nk) store_lds(stage ^ 1);
     __syncthreads();
   }
 
-  float* dW = a.dW + (long)h * a.w_hstride + (long)e * a.w_estride;
+  if (a.partial) {
+    // this chunk's partial sum, plain stores; launch_wgrad_reduce adds the chunks up
+    float* P = a.partial + ((long)grp * a.max_chunks + w) * ((long)a.Ka * a.Kb);
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int ii = i0 + wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
+        if (ii >= a.Ka) continue;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const int jj = j0 + wn + j * 32 + r;
+          if (jj < a.Kb) P[(long)ii * a.Kb + jj] = acc[i][j][q];
+        }
+      }
+    return;
+  }
+  float* dW = (second ? a.dW2 : a.dW) + (long)hh * a.w_hstride + (long)e * a.w_estride;
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
       const int ii = i0 + wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
       if (ii >= a.Ka) continue;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < NJ; ++j) {
         const int jj = j0 + wn + j * 32 + r;
         if (jj < a.Kb) atomicAdd(dW + (long)ii * a.swa + jj, acc[i][j][q]);
       }
     }
 }
 
+// dW_g = sum over the chunks of group g of its partial sums (4 consecutive j per thread)
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs a) {
+  const int grp = blockIdx.y;
+  const int h = grp / a.E, e = grp % a.E;
+  const long per = (long)a.Ka * a.Kb;
+  const long i4 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i4 >= per) return;
+  int rows = a.M;
+  if (a.perm) {
+    const int* off = a.offsets + (long)h * (a.E + 1);
+    rows = off[e + 1] - off[e];
+  }
+  const int nch = (rows + a.chunk - 1) / a.chunk;
+  const float* P = a.partial + (long)grp * a.max_chunks * per + i4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int c = 0; c < nch; ++c) {
+    const float4 v = *(const float4*)(P + (long)c * per);
+    s.x += v.x;
+    s.y += v.y;
+    s.z += v.z;
+    s.w += v.w;
+  }
+  const bool second = a.hsplit > 0 && h >= a.hsplit;
+  const int hh = second ? h - a.hsplit : h;
+  float* dW = (second ? a.dW2 : a.dW) + (long)hh * a.w_hstride + (long)e * a.w_estride;
+  const long ii = i4 / a.Kb, jj = i4 % a.Kb;   // Kb % 4 == 0: the 4 elements share a row
+  *(float4*)(dW + ii * a.swa + jj) = s;
+}
+
+void launch_wgrad_reduce(const WgradArgs& a, hipStream_t s) {
+  const long per = (long)a.Ka * a.Kb;
+  dim3 g((unsigned)((per / 4 + 255) / 256), a.heads * a.E);
+  wgrad_reduce_kernel<<<g, 256, 0, s>>>(a);
+}
+
 static int wgrad_vec(const WgradArgs& a) {
-  if (a.chunk > wg::MAX_CHUNK || a.chunk % wg::BK != 0) return 0;
+  if (a.chunk > WgSmall::MAX_CHUNK || a.chunk % 32 != 0) return 0;
   for (int vec = 8; vec >= 4; vec -= 4) {
     const size_t bytes = vec * 2;
     if (aligned_to(a.A, bytes) && aligned_to(a.Bm, bytes) && a.lda % vec == 0 && a.a_hoff % vec == 0 &&
-        a.ldb % vec == 0 && a.b_hoff % vec == 0 && a.Ka % vec == 0 && a.Kb % vec == 0)
+        a.ldb % vec == 0 && a.b_hoff % vec == 0 && a.Ka % vec == 0 && a.Kb % vec == 0 &&
+        (a.hsplit == 0 || aligned_to(a.Bm2, bytes)) && (!a.partial || (a.swa % 4 == 0 && aligned_to(a.dW, 16))))
       return vec;
   }
   return 0;
@@ -706,22 +779,51 @@ static int wgrad_vec(const WgradArgs& a) {
 
 bool mfma_wgrad_supported(const WgradArgs& a) { return wgrad_vec(a) != 0; }
 
+template <class Cfg, int VEC, int TAG>
+static void launch_wg(const WgradArgs& a, hipStream_t s) {
+  const int ti = (a.Ka + Cfg::BM - 1) / Cfg::BM, tj = (a.Kb + Cfg::BN - 1) / Cfg::BN;
+  const int group_rows = a.perm ? a.max_group_rows : a.M;
+  dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads * a.E, ti * tj));
+  const size_t lds = Cfg::lds_bytes();
+  auto kern = mfma_wgrad_kernel<Cfg, VEC, TAG>;
+  if (lds > 64 * 1024) {
+    static bool raised = false;
+    if (!raised) {
+      (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      raised = true;
+    }
+  }
+  kern<<<g, 256, lds, s>>>(a);
+}
+
+static int g_force_wshape = -1;   // experiments only
+void wg_force_shape(int shape) { g_force_wshape = shape; }
+
+template <int TAG>
+static void launch_wg_tagged(const WgradArgs& a, hipStream_t s) {
+  // wide outputs get the 128 x 256 tile, tall ones the 256 x 128 tile
+  int shape = a.Kb >= 256 && a.Ka <= 128 ? 1 : (a.Ka >= 256 && a.Kb >= 64 ? 2 : 0);
+  if (g_force_wshape >= 0) shape = g_force_wshape;
+  if (shape == 1)
+    launch_wg<WgWide, 8, TAG>(a, s);
+  else if (shape == 2)
+    launch_wg<WgTall, 8, TAG>(a, s);
+  else
+    launch_wg<WgSmall, 8, TAG>(a, s);
+}
+
 void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s) {
   if (a.M <= 0) return;
   const int vec = wgrad_vec(a);
-  int ti = (a.Ka + wg::BM - 1) / wg::BM, tj = (a.Kb + wg::BN - 1) / wg::BN;
-  const int group_rows = a.perm ? a.max_group_rows : a.M;
-  dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads * a.E, ti * tj));
   if (vec == 8) {
     switch (a.tag) {
-      case TAG_O_WGRAD: mfma_wgrad_kernel<8, TAG_O_WGRAD><<<g, 256, 0, s>>>(a); break;
-      case TAG_V_WGRAD: mfma_wgrad_kernel<8, TAG_V_WGRAD><<<g, 256, 0, s>>>(a); break;
-      case TAG_QK_WGRAD: mfma_wgrad_kernel<8, TAG_QK_WGRAD><<<g, 256, 0, s>>>(a); break;
-      default: mfma_wgrad_kernel<8, TAG_GENERIC><<<g, 256, 0, s>>>(a); break;
+      case TAG_O_WGRAD: return launch_wg_tagged<TAG_O_WGRAD>(a, s);
+      case TAG_V_WGRAD: return launch_wg_tagged<TAG_V_WGRAD>(a, s);
+      case TAG_QK_WGRAD: return launch_wg_tagged<TAG_QK_WGRAD>(a, s);
+      default: return launch_wg<WgSmall, 8, TAG_GENERIC>(a, s);
     }
-  } else {
-    mfma_wgrad_kernel<4, TAG_GENERIC><<<g, 256, 0, s>>>(a);
   }
+  launch_wg<WgSmall, 4, TAG_GENERIC>(a, s);
 }
 
 }  // namespace sh
