@@ -126,6 +126,7 @@ struct WgradArgs {
   // launch_wgrad_reduce adds the chunks of each group into dW (plain stores, no zero fill).
   float* partial;
   int max_chunks;
+  int scale_b;   // apply the gate to the rows of Bm instead of A (same product, fewer elements to scale)
 };
 void launch_wgrad_reduce(const WgradArgs& a, hipStream_t s);
 
@@ -209,12 +210,12 @@ void launch_cast_to_f32(const void* src, float* dst, size_t n, int bf16, hipStre
 // out[i] = sum_h part[h*hstride + i] (+ add32[i]) for bf16 part/out; n must be a multiple of 8
 void launch_sum_heads(const void* part, const float* add32, void* out, size_t n, size_t hstride, int H, hipStream_t s);
 
-// out[n,h,:] = sum_j gate[h][n*k+j] * slots[h][n*k+j][:]   (slots fp32 [H, N*k, dh])
+// out[n,h,:] = sum_j gate[h][n*k+j] * slots[h][n*k+j][:]   (slots [H, N*k, dh], storage type T)
 // dots[h][n*k+j] = <other[n,h,:], slots[h][n*k+j][:]>        (if dots != NULL)
 // delta[n,h]     = <out[n,h,:], other[n,h,:]>                (if delta != NULL)
 // out may be NULL (dots only).  out/other have storage type T, layout [N, H, dh].
 struct SlotArgs {
-  const float* slots;
+  const void* slots;
   const float* gate;
   const void* other;
   void* out;

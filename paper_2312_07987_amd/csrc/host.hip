@@ -115,11 +115,11 @@ Layout make_layout(const sh_shape* s) {
   L.V = take(N * H * dh * esz);
   L.ctx = take(N * H * dh * esz);
   L.lse = take(N * H * 4);
-  L.pV = take(H * N * k * dh * 4);
+  L.pV = take(H * N * k * dh * esz);
   L.Z = take(2 * N * H * E * 8);
   L.blockcnt = take(2 * H * (size_t)router_blocks((int)N) * E * 4);
   L.acc32 = take(N * dm * 4);
-  L.u = take(H * N * k * dh * 4);
+  L.u = take(H * N * k * dh * esz);
   L.dctx = take(N * H * dh * esz);
   L.dQ = take(N * H * dh * esz);
   L.dK = take(N * H * dh * esz);
@@ -479,11 +479,11 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     a.c_hoff = (long)N * k * dh;
     a.K = dm;
     a.Nc = dh;
-    a.mode = STORE_F32;
+    a.mode = STORE_T;
     row_gemm(c, a);
     prof_mark(c.st, "fwd.v_combine");
     SlotArgs sa{};
-    sa.slots = c.p<float>(c.L.pV);
+    sa.slots = c.p<void>(c.L.pV);
     sa.gate = c.gate(0);
     sa.out = c.p<void>(c.L.V);
     sa.N = N;
@@ -604,11 +604,11 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.c_hoff = (long)N * k * dh;
     a.K = dm;
     a.Nc = dh;
-    a.mode = STORE_F32;
+    a.mode = STORE_T;
     row_gemm(c, a);
     prof_mark(c.st, "bwd.dctx_combine");
     SlotArgs sa{};
-    sa.slots = c.p<float>(c.L.u);
+    sa.slots = c.p<void>(c.L.u);
     sa.gate = c.gate(1);
     sa.other = c.p<void>(c.L.ctx);
     sa.out = c.p<void>(c.L.dctx);
@@ -755,7 +755,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   {
     prof_mark(c.st, "bwd.dgate_s");
     SlotArgs sa{};
-    sa.slots = c.p<float>(c.L.pV);
+    sa.slots = c.p<void>(c.L.pV);
     sa.gate = c.gate(0);
     sa.other = c.p<void>(c.L.dV);
     sa.dots = c.p<float>(c.L.dgate);
@@ -767,6 +767,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     prof_mark(c.st, "bwd.v_wgrad");
     WgradArgs w{};
     w.tag = TAG_V_WGRAD;
+    w.scale_b = 1;   // gate on the d_head-wide dV rows instead of the d_model-wide x rows
     w.perm = c.perm(0);
     w.offsets = c.offsets(0);
     w.heads = H;

@@ -636,7 +636,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       ra[i] = zero_chunk<VEC>();
       if (r0 + rr < rows && i0 + fc < a.Ka) {
         ra[i] = *(const chunk_t*)(A + (long)(ids[r0 + rr] / a.a_div) * a.lda + (long)hh * a.a_hoff + i0 + fc);
-        if (scaled) ra[i] = scale_chunk(ra[i], gsc[r0 + rr]);
+        if (scaled && !a.scale_b) ra[i] = scale_chunk(ra[i], gsc[r0 + rr]);
       }
     }
 #pragma unroll
@@ -644,8 +644,10 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       const int c = tid + i * 256;
       const int rr = c / B_CPR, fc = (c % B_CPR) * VEC;
       rb[i] = zero_chunk<VEC>();
-      if (r0 + rr < rows && j0 + fc < a.Kb)
+      if (r0 + rr < rows && j0 + fc < a.Kb) {
         rb[i] = *(const chunk_t*)(Bm + (long)(ids[r0 + rr] / a.b_div) * a.ldb + (long)hh * a.b_hoff + j0 + fc);
+        if (scaled && a.scale_b) rb[i] = scale_chunk(rb[i], gsc[r0 + rr]);
+      }
     }
   };
   auto store_lds = [&](int stage) {

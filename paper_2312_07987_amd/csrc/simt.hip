@@ -161,8 +161,8 @@ __global__ __launch_bounds__(256) void simt_wgrad_kernel(WgradArgs a) {
       int id = ids[r];
       float va = 0.f, vb = 0.f;
       if (id >= 0) {
-        if (i0 + c < a.Ka) va = gs[r] * ld(A, (long)(id / a.a_div) * a.lda + (long)h * a.a_hoff + i0 + c);
-        if (j0 + c < a.Kb) vb = ld(Bm, (long)(id / a.b_div) * a.ldb + (long)h * a.b_hoff + j0 + c);
+        if (i0 + c < a.Ka) va = (a.scale_b ? 1.f : gs[r]) * ld(A, (long)(id / a.a_div) * a.lda + (long)h * a.a_hoff + i0 + c);
+        if (j0 + c < a.Kb) vb = (a.scale_b ? gs[r] : 1.f) * ld(Bm, (long)(id / a.b_div) * a.ldb + (long)h * a.b_hoff + j0 + c);
       }
       As[r][c] = va;
       Bs[r][c] = vb;

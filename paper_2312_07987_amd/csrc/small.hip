@@ -113,14 +113,14 @@ __global__ __launch_bounds__(256) void slot_combine_kernel(SlotArgs a) {
   }
   for (int j = 0; j < k; ++j) {
     const long aid = (long)h * a.N * k + (long)n * k + j;
-    const float* sl = a.slots + aid * dh;
+    const T* sl = (const T*)a.slots + aid * dh;
     const float g = a.gate[aid];
     float dot = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       int d = lane + 64 * i;
       if (d < dh) {
-        float v = sl[d];
+        float v = ld(sl, d);
         acc[i] += g * v;
         dot += oth[i] * v;
       }
