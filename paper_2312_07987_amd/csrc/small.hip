@@ -146,8 +146,84 @@ __global__ __launch_bounds__(256) void slot_combine_kernel(SlotArgs a) {
   }
 }
 
+// bf16 rows whose length is a multiple of 8: 16 bytes per thread, dh/8 threads per (token, head)
+// row (a power of two <= 32 so a row never straddles a wave), shuffles inside that lane group.
+template <int TPR>
+__global__ __launch_bounds__(256) void slot_combine_vec_kernel(SlotArgs a) {
+  const int lane_in = threadIdx.x % TPR;
+  const long pair = ((long)blockIdx.x * 256 + threadIdx.x) / TPR;
+  const bool valid = pair < (long)a.N * a.H;
+  const int n = valid ? (int)(pair / a.H) : 0, h = valid ? (int)(pair % a.H) : 0;
+  const int dh = a.dh, k = a.k, d0 = lane_in * 8;
+  const bool act = valid && d0 < dh;
+  const unsigned short* other = (const unsigned short*)a.other;
+  const long row = ((long)n * a.H + h) * dh + d0;
+  float oth[8], acc[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) oth[t] = acc[t] = 0.f;
+  if (other && act) {
+    const uint4 v = *(const uint4*)(other + row);
+    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      oth[2 * t] = __uint_as_float(w[t] << 16);
+      oth[2 * t + 1] = __uint_as_float(w[t] & 0xffff0000u);
+    }
+  }
+  for (int j = 0; j < k; ++j) {
+    const long aid = (long)h * a.N * k + (long)n * k + j;
+    float dot = 0.f;
+    if (act) {
+      const float g = a.gate[aid];
+      const uint4 v = *(const uint4*)((const unsigned short*)a.slots + aid * dh + d0);
+      const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const float lo = __uint_as_float(w[t] << 16), hi = __uint_as_float(w[t] & 0xffff0000u);
+        acc[2 * t] += g * lo;
+        acc[2 * t + 1] += g * hi;
+        dot += oth[2 * t] * lo + oth[2 * t + 1] * hi;
+      }
+    }
+    if (a.dots) {
+#pragma unroll
+      for (int o = TPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+      if (valid && lane_in == 0) a.dots[aid] = dot;
+    }
+  }
+  if (a.out && act) {
+    uint4 o;
+    o.x = pack_bf16x2(acc[0], acc[1]);
+    o.y = pack_bf16x2(acc[2], acc[3]);
+    o.z = pack_bf16x2(acc[4], acc[5]);
+    o.w = pack_bf16x2(acc[6], acc[7]);
+    *(uint4*)((unsigned short*)a.out + row) = o;
+  }
+  if (a.delta) {
+    float dd = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) dd += acc[t] * oth[t];
+#pragma unroll
+    for (int o = TPR / 2; o > 0; o >>= 1) dd += __shfl_xor(dd, o, 64);
+    if (valid && lane_in == 0) a.delta[pair] = dd;
+  }
+}
+
 void launch_slot_combine(const SlotArgs& a, int bf16, hipStream_t s) {
   long pairs = (long)a.N * a.H;
+  if (bf16 && a.dh % 8 == 0) {
+    int tpr = 1;
+    while (tpr * 8 < a.dh) tpr *= 2;   // threads per row, power of two
+    const unsigned g = (unsigned)((pairs * tpr + 255) / 256);
+    switch (tpr) {
+      case 1: slot_combine_vec_kernel<1><<<g, 256, 0, s>>>(a); return;
+      case 2: slot_combine_vec_kernel<2><<<g, 256, 0, s>>>(a); return;
+      case 4: slot_combine_vec_kernel<4><<<g, 256, 0, s>>>(a); return;
+      case 8: slot_combine_vec_kernel<8><<<g, 256, 0, s>>>(a); return;
+      case 16: slot_combine_vec_kernel<16><<<g, 256, 0, s>>>(a); return;
+      default: slot_combine_vec_kernel<32><<<g, 256, 0, s>>>(a); return;
+    }
+  }
   unsigned g = (unsigned)((pairs + 3) / 4);
   if (bf16)
     slot_combine_kernel<bf16_t><<<g, 256, 0, s>>>(a);
