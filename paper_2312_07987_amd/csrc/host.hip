@@ -68,7 +68,17 @@ struct Layout {
 
 // number of k-subsets of E experts, saturating at MAX_SETS + 1
 constexpr int MAX_SETS = 128;
-constexpr size_t WGRAD_CHUNK = 1024;   // rows reduced by one weight-gradient block
+// Rows reduced by one weight-gradient block.  Each block writes a partial sum of its output tile
+// that a second kernel adds up, so chunks should be long, but short enough that the launch still
+// fills the chip: about 480 blocks (256 CUs x 2 resident work-groups, a little slack for ragged
+// groups), output tiles of 256 x 128, chunks of 256 .. 2048 rows in multiples of 64.
+static int wgrad_chunk(size_t total_rows, size_t dm, size_t dh) {
+  const size_t tiles = ((dm + 255) / 256) * ((dh + 127) / 128);
+  const size_t units = 480 / tiles > 0 ? 480 / tiles : 1;
+  size_t chunk = (total_rows + units - 1) / units;
+  chunk = (chunk + 63) / 64 * 64;
+  return (int)(chunk < 256 ? 256 : chunk > 2048 ? 2048 : chunk);
+}
 int count_sets(int E, int k) {
   long v = 1;
   for (int i = 1; i <= k; ++i) {
@@ -142,7 +152,9 @@ Layout make_layout(const sh_shape* s) {
   if (s->dtype == SH_BF16) {
     // groups x chunks-per-group x one expert matrix, fp32 (the dense Q/K pair counts as 2H groups)
     const size_t groups = H * E > 2 * H ? H * E : 2 * H;
-    L.wpart = take(groups * ((N + WGRAD_CHUNK - 1) / WGRAD_CHUNK) * dm * dh * 4);
+    const size_t ce = wgrad_chunk(H * N * k, dm, dh), cd = wgrad_chunk(2 * H * N, dm, dh);
+    const size_t cmin = ce < cd ? ce : cd;
+    L.wpart = take(groups * ((N + cmin - 1) / cmin) * dm * dh * 4);
     size_t o6[6];
     L.rh = take(router_hybrid_bytes((int)N, (int)dm, (int)H, (int)E, o6));
   }
@@ -584,7 +596,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     return fail(SH_ERR_INVALID_ARG, "x, W_Q, W_K, W_V, W_O, dy, dx, dW_Q, dW_K, dW_V, dW_O must not be NULL");
   const int N = c.N, H = c.H, E = c.E, k = c.k, dh = c.dh, dm = c.dm;
   const long hd = (long)H * dh;
-  const int chunk = (int)WGRAD_CHUNK;
+  const int chunk = wgrad_chunk((size_t)H * N * k, dm, dh);         // expert-sorted operands
+  const int chunk_dense = wgrad_chunk((size_t)2 * H * N, dm, dh);   // fused dense Q/K
   const bool sets = sets_usable(c);
 
   // output experts: u[h][a][:] = dy[n] W_O[h,e]^T (unscaled), then dctx, d(gate_D), delta
@@ -701,7 +714,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.dW2 = dW_K;
     w.w_hstride = (long)dm * dh;
     w.swa = dh;
-    w.chunk = chunk;
+    w.chunk = chunk_dense;
     wgrad(c, w);
   }
   {

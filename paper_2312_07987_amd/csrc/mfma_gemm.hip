@@ -8,6 +8,7 @@
 //   A operand: A[row r][k = 8g .. 8g+7]      B operand: B[k = 8g .. 8g+7][col r]
 //   D: register q (0..15) holds D[8*(q/4) + 4g + q%4][col r]
 #include "common.h"
+#include <cstdlib>
 
 namespace sh {
 
@@ -588,16 +589,16 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   int* ids = (int*)(smem + 2 * Cfg::STAGE_ELEMS);
   float* gsc = (float*)(ids + Cfg::MAX_CHUNK);
 
-  // unit = (chunk window, group); the output tiles of a unit share an XCD (they read the same
-  // rows), consecutive units go to different XCDs
+  // unit = (chunk window, head): the output tiles of all its experts share an XCD, because the
+  // experts of a head gather overlapping rows of the token-major operand (every token is in k of the
+  // E groups) and the L2 then fetches each row once; consecutive units go to different XCDs
   const int ti_ = (a.Ka + BM - 1) / BM, tj = (a.Kb + BN - 1) / BN;
   const int ntile = ti_ * tj;
-  const int G = a.heads * a.E;
-  int unit, tile;
-  decode_block(blockIdx.x, ntile, unit, tile);
-  const int w = unit / G, grp = unit % G;
+  int unit, slot;
+  decode_block(blockIdx.x, a.E * ntile, unit, slot);
+  const int w = unit / a.heads, h = unit % a.heads;
   if (w * a.chunk >= (a.perm ? a.max_group_rows : a.M)) return;
-  const int h = grp / a.E, e = grp % a.E;
+  const int e = slot / ntile, tile = slot % ntile;
   int row0, rows;
   if (a.perm) {
     const int* off = a.offsets + (long)h * (a.E + 1);
@@ -702,7 +703,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
 
   if (a.partial) {
     // this chunk's partial sum, plain stores; launch_wgrad_reduce adds the chunks up
-    float* P = a.partial + ((long)grp * a.max_chunks + w) * ((long)a.Ka * a.Kb);
+    float* P = a.partial + ((long)(h * a.E + e) * a.max_chunks + w) * ((long)a.Ka * a.Kb);
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -785,7 +786,7 @@ template <class Cfg, int VEC, int TAG>
 static void launch_wg(const WgradArgs& a, hipStream_t s) {
   const int ti = (a.Ka + Cfg::BM - 1) / Cfg::BM, tj = (a.Kb + Cfg::BN - 1) / Cfg::BN;
   const int group_rows = a.perm ? a.max_group_rows : a.M;
-  dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads * a.E, ti * tj));
+  dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads, a.E * ti * tj));
   const size_t lds = Cfg::lds_bytes();
   auto kern = mfma_wgrad_kernel<Cfg, VEC, TAG>;
   if (lds > 64 * 1024) {
