@@ -59,6 +59,33 @@ def step_work(cfg):
     return flops, alu, nbytes
 
 
+# Which kernel a profiled step launches, as a pattern on the kernel name rocprofv3 reports
+# (row GEMM: "..., <B transposed>, <tag>, <segment mode>>"; weight gradient: "..., <vec>, <tag>>").
+STEP_KERNEL = {
+    "fwd.qk_proj": r"mfma_row_gemm_kernel<.*, 1, 0>", "fwd.v_experts": r"mfma_row_gemm_kernel<.*, 2, 0>",
+    "fwd.o_experts": r"mfma_row_gemm_kernel<.*, 3, 1>", "bwd.o_dgrad": r"mfma_row_gemm_kernel<.*, 4, 0>",
+    "bwd.v_dgrad": r"mfma_row_gemm_kernel<.*, 5, 1>", "bwd.qk_dgrad": r"mfma_row_gemm_kernel<.*, 6, 2>",
+    "bwd.o_wgrad": r"mfma_wgrad_kernel<.*, 8, 7>", "bwd.v_wgrad": r"mfma_wgrad_kernel<.*, 8, 8>",
+    "bwd.qk_wgrad": r"mfma_wgrad_kernel<.*, 8, 9>", "bwd.wgrad_reduce": r"wgrad_reduce_kernel",
+    "fwd.attention": r"mfma_attn_fwd_kernel", "fwd.y_sum": r"sum_heads_kernel", "bwd.dx_cast": r"sum_heads_kernel",
+    "fwd.v_combine": r"slot_combine", "bwd.dctx_combine": r"slot_combine", "bwd.dgate_s": r"slot_combine",
+}
+
+
+def measured_traffic(cfg_name, step):
+    """HBM bytes per launch of the step's kernel from the committed rocprofv3 counter summary, or None."""
+    import re
+    path = os.path.join(ROOT, "profiles", "traffic_%s.json" % cfg_name)
+    pat = STEP_KERNEL.get(step)
+    if pat is None or not os.path.exists(path):
+        return None
+    t = json.load(open(path))
+    for name, v in t["kernels"].items():
+        if re.search(pat, name):
+            return v["fetch_bytes"] + v["write_bytes"]
+    return None
+
+
 def time_loop(fn, steps):
     import torch
     torch.cuda.synchronize()
@@ -164,6 +191,7 @@ def main():
                 "frac": ach / PEAK_HBM_GBS, "traffic": None}
     roof["step"] = dom
     roof["avg_ms"] = per_step[dom]
+    roof["traffic"] = measured_traffic(cfg["name"], dom)
 
     lf = layer_flops(cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
                      bool(cfg["causal"]))

@@ -232,6 +232,7 @@ void wgrad(const Ctx& c, WgradArgs a, bool deterministic = true) {
     }
     if (b.partial && mfma_wgrad_supported(b)) {
       launch_mfma_wgrad(b, c.st);
+      prof_mark(c.st, "bwd.wgrad_reduce");
       launch_wgrad_reduce(b, c.st);
       return;
     }

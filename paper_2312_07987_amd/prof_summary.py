@@ -3,8 +3,13 @@
     python -m paper_2312_07987_amd.prof_summary stats  <kernel_stats.csv>            > profiles/x.txt
     python -m paper_2312_07987_amd.prof_summary pmc    <counter_collection.csv> NAME > profiles/y.txt
 
-`stats`: per-kernel calls / average / share from `rocprofv3 --kernel-trace --stats`.
-`pmc`:   per-kernel average of counter NAME per dispatch from `rocprofv3 --pmc NAME`.
+    python -m paper_2312_07987_amd.prof_summary traffic <fetch.csv> <write.csv> <copy_fetch.csv> <copy_write.csv> > profiles/t.json
+
+`stats`:   per-kernel calls / average / share from `rocprofv3 --kernel-trace --stats`.
+`pmc`:     per-kernel average of counter NAME per dispatch from `rocprofv3 --pmc NAME`.
+`traffic`: HBM bytes per dispatch of every kernel as JSON, from a `--pmc FETCH_SIZE` and a
+           `--pmc WRITE_SIZE` run of the benchmark (counters in KiB), each scaled by what the same
+           counter reads for `bench.py --copy-only` (a 256 MiB device copy, 5 launches).
 """
 import collections
 import csv
@@ -31,8 +36,36 @@ def pmc(path, name):
         print("%-110s %6d %14.1f" % (k[:110], cnt[k], tot[k] / cnt[k]))
 
 
+def _avg(path, name):
+    tot = collections.defaultdict(float)
+    cnt = collections.Counter()
+    for r in csv.DictReader(open(path)):
+        if r["Counter_Name"] == name:
+            tot[r["Kernel_Name"]] += float(r["Counter_Value"])
+            cnt[r["Kernel_Name"]] += 1
+    return {k: tot[k] / cnt[k] for k in tot}
+
+
+def traffic(fetch, write, copy_fetch, copy_write, copy_bytes=256 << 20):
+    import json
+    cf = _avg(copy_fetch, "FETCH_SIZE")
+    cw = _avg(copy_write, "WRITE_SIZE")
+    kf = [k for k in cf if "copyBuffer" in k or "copy" in k.lower()]
+    kw = [k for k in cw if "copyBuffer" in k or "copy" in k.lower()]
+    sf = copy_bytes / (cf[kf[0]] * 1024.0)   # true bytes per counted KiB-unit, reads
+    sw = copy_bytes / (cw[kw[0]] * 1024.0)
+    f = _avg(fetch, "FETCH_SIZE")
+    w = _avg(write, "WRITE_SIZE")
+    out = {"fetch_scale": sf, "write_scale": sw, "copy_kernel": kf[0], "kernels": {}}
+    for k in sorted(set(f) | set(w)):
+        out["kernels"][k] = {"fetch_bytes": f.get(k, 0.0) * 1024.0 * sf, "write_bytes": w.get(k, 0.0) * 1024.0 * sw}
+    print(json.dumps(out, indent=1))
+
+
 if __name__ == "__main__":
     if sys.argv[1] == "stats":
         stats(sys.argv[2])
+    elif sys.argv[1] == "traffic":
+        traffic(*sys.argv[2:6])
     else:
         pmc(sys.argv[2], sys.argv[3])
