@@ -232,11 +232,14 @@ struct RouterBwdArgs {
   const int* idx;       // [2 or 1, H, N, k]
   const float* gate;    // same
   const float* dgate;   // [2, H, N, k]
-  void* dz;
+  void* dz;             // [N][ld]: side s owns columns s*side_stride .. +HE, the rest of its stride is zeroed
   float* db[2];         // per side [HE] or NULL, atomic add (zeroed by caller)
   int N, H, E, k, sides, shared;
+  int ld, side_stride;
 };
 void launch_router_bwd(const RouterBwdArgs& a, int bf16, hipStream_t s);
+// both routers' weights as bf16 [side][d_model][HEp], columns HE..HEp-1 zero (W1 unused when sides == 1)
+void launch_pack_router(const void* W0, const void* W1, void* Wp, int dm, int HE, int HEp, int sides, hipStream_t s);
 
 void launch_simt_row_gemm(const RowGemmArgs& a, int bf16, hipStream_t s);
 void launch_simt_wgrad(const WgradArgs& a, int bf16, hipStream_t s);

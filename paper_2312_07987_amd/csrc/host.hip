@@ -136,7 +136,7 @@ Layout make_layout(const sh_shape* s) {
   L.dV = take(N * H * dh * esz);
   L.delta = take(N * H * 4);
   L.dgate = take(2 * H * N * k * 4);
-  L.dz = take(N * 2 * H * E * esz);
+  L.dz = take(N * 2 * ((H * E + 7) / 8 * 8) * esz);   // each side padded to a multiple of 8 columns
   if (s->dtype == SH_BF16 && count_sets(s->E, s->k) <= MAX_SETS) {
     const size_t ns = count_sets(s->E, s->k);
     L.setid = take(2 * H * N * 4);
@@ -144,7 +144,7 @@ Layout make_layout(const sh_shape* s) {
     L.setperm = take(2 * H * N * 4);
     L.setoff = take(2 * H * (ns + 1) * 4);
     L.setcnt = take(2 * H * (size_t)router_blocks((int)N) * ns * 4);
-    L.yh = take(H * N * dm * esz);
+    L.yh = take((H + 1) * N * dm * esz);   // one partial per head + the routers' share of dx
   } else {
     L.setid = L.gset = L.setperm = L.setoff = L.setcnt = L.yh = 0;
   }
@@ -838,6 +838,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   }
 
   // routers
+  bool router_partial = false;
   if (!c.dense) {
     prof_mark(c.st, "bwd.router");
     const int sides = c.shared ? 1 : 2;
@@ -860,46 +861,95 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     rb.k = k;
     rb.sides = sides;
     rb.shared = c.shared;
+    const int HEp = (HE + 7) / 8 * 8;
+    rb.ld = sides * HEp;
+    rb.side_stride = HEp;
     launch_router_bwd(rb, c.bf16, c.st);
-    for (int sd = 0; sd < sides; ++sd) {
-      const void* dz = c.p<char>(c.L.dz) + (size_t)sd * HE * (c.bf16 ? 2 : 4);
-      if (dWs[sd]) {
+    const size_t esz = c.bf16 ? 2 : 4;
+    const char* dz0 = c.p<char>(c.L.dz);
+    // dW_S / dW_D = x^T dz: one launch for both sides when both are wanted
+    {
+      WgradArgs w{};
+      w.E = 1;
+      w.M = N;
+      w.a_div = 1;
+      w.b_div = 1;
+      w.A = x;
+      w.lda = dm;
+      w.Ka = dm;
+      w.ldb = rb.ld;
+      w.Kb = HE;
+      w.swa = HE;
+      w.chunk = 256;   // tiny output: many short chunks keep the GPU busy, atomics are few
+      if (sides == 2 && dWs[0] && dWs[1]) {
         prof_mark(c.st, "bwd.router_wgrad");
-        WgradArgs w{};
-        w.heads = 1;
-        w.E = 1;
-        w.M = N;
-        w.a_div = 1;
-        w.b_div = 1;
-        w.A = x;
-        w.lda = dm;
-        w.Ka = dm;
-        w.Bm = dz;
-        w.ldb = (long)sides * HE;
-        w.Kb = HE;
-        w.dW = dWs[sd];
-        w.swa = HE;
-        w.chunk = 256;   // tiny output: many short chunks keep the GPU busy, atomics are few
+        w.heads = 2;
+        w.hsplit = 1;
+        w.Bm = dz0;
+        w.Bm2 = dz0 + (size_t)HEp * esz;
+        w.dW = dWs[0];
+        w.dW2 = dWs[1];
         wgrad(c, w, false);
+      } else {
+        for (int sd = 0; sd < sides; ++sd) {
+          if (!dWs[sd]) continue;
+          prof_mark(c.st, "bwd.router_wgrad");
+          w.heads = 1;
+          w.Bm = dz0 + (size_t)sd * HEp * esz;
+          w.dW = dWs[sd];
+          wgrad(c, w, false);
+        }
       }
-      prof_mark(c.st, "bwd.router_dgrad");
+    }
+    // dx += dz_S W_S^T + dz_D W_D^T
+    prof_mark(c.st, "bwd.router_dgrad");
+    if (sets && c.bf16 && use_mfma(c)) {
+      // both routers packed as [side][d_model][HEp]: one GEMM over the concatenated columns,
+      // stored as one more partial of dx
+      bf16_t* Wp = (bf16_t*)(c.p<char>(c.L.rh));
       RowGemmArgs a = identity_rows(c, 1);
-      a.A = dz;
-      a.lda = (long)sides * HE;
-      a.B = sd ? W_D : W_S;
+      a.tag = TAG_QK_DGRAD;
+      a.A = dz0;
+      a.lda = rb.ld;
+      a.seg_mode = 2;
+      a.nseg = sides;
+      a.seg_split = 1;
+      a.a_wstride = HEp;
+      a.B = Wp;
+      a.B2 = Wp + (size_t)dm * HEp;
       a.sbk = 1;
-      a.sbn = HE;
-      a.C = dxacc;
+      a.sbn = HEp;
+      a.C = c.p<char>(c.L.yh) + (size_t)H * N * dm * esz;
       a.ldc = dm;
-      a.K = HE;
+      a.K = HEp;
       a.Nc = dm;
-      a.mode = ATOMIC_F32;
-      row_gemm(c, a);
+      a.mode = STORE_T;
+      if (mfma_row_gemm_supported(a)) {
+        launch_pack_router(W_S, c.shared ? nullptr : W_D, Wp, dm, HE, HEp, sides, c.st);
+        launch_mfma_row_gemm(a, c.st);
+        router_partial = true;
+      }
+    }
+    if (!router_partial) {
+      for (int sd = 0; sd < sides; ++sd) {
+        RowGemmArgs a = identity_rows(c, 1);
+        a.A = dz0 + (size_t)sd * HEp * esz;
+        a.lda = rb.ld;
+        a.B = sd ? W_D : W_S;
+        a.sbk = 1;
+        a.sbn = HE;
+        a.C = dxacc;
+        a.ldc = dm;
+        a.K = HE;
+        a.Nc = dm;
+        a.mode = ATOMIC_F32;
+        row_gemm(c, a);
+      }
     }
   }
   prof_mark(c.st, "bwd.dx_cast");
   if (sets)
-    launch_sum_heads(c.p<void>(c.L.yh), dxacc, dx, (size_t)N * dm, (size_t)N * dm, H, c.st);
+    launch_sum_heads(c.p<void>(c.L.yh), dxacc, dx, (size_t)N * dm, (size_t)N * dm, router_partial ? H + 1 : H, c.st);
   else if (c.bf16)
     launch_cast_from_f32(dxacc, dx, (size_t)N * dm, 1, c.st);
   prof_mark(c.st, nullptr);

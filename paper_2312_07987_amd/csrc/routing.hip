@@ -464,6 +464,11 @@ __global__ void pack_router_kernel(const bf16_t* __restrict__ W0, const bf16_t* 
   Wp[i] = v;
 }
 
+void launch_pack_router(const void* W0, const void* W1, void* Wp, int dm, int HE, int HEp, int sides, hipStream_t s) {
+  const long tot = (long)sides * dm * HEp;
+  pack_router_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const bf16_t*)W0, (const bf16_t*)W1, (bf16_t*)Wp, dm, HE, HEp, sides);
+}
+
 size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off) {
   const size_t HEp = ((size_t)H * E + 7) / 8 * 8;
   size_t o = 0;

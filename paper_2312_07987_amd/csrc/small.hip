@@ -242,10 +242,11 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(RouterBwdArgs a) {
   if (threadIdx.x < 64) bsum[threadIdx.x] = 0.f;
   __syncthreads();
   if (n < a.N) {
-    const long cols = (long)a.sides * HE;
     T* dz = (T*)a.dz;
-    const long base = (long)n * cols + (long)side * HE + (long)h * E;
+    const long base = (long)n * a.ld + (long)side * a.side_stride + (long)h * E;
     for (int e = 0; e < E; ++e) st(dz, base + e, 0.f);
+    if (h == a.H - 1)   // padding columns of this side
+      for (int c = HE; c < a.side_stride; ++c) st(dz, (long)n * a.ld + (long)side * a.side_stride + c, 0.f);
     const long o = ((long)sh_ * a.N + n) * k;  // side-major layout [side][H][N][k]
     for (int j = 0; j < k; ++j) {
       int e = a.idx[o + j];
