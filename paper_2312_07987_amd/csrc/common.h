@@ -87,6 +87,8 @@ struct RowGemmArgs {
   //  2  concatenation: segment p reads A columns (p/seg_split)*a_wstride + (p%seg_split)*a_sstride
   //     against (p/seg_split ? B2 : B) + (p%seg_split)*b_sstride.
   int seg_mode, nseg, experts;
+  // TAG_ROUTER only: if not NULL, rownorm[row id] = an upper bound of the Euclidean norm of the A row
+  float* rownorm;
   const float* segate;
   int seg_split;
   long a_sstride, a_wstride, b_sstride;
@@ -185,7 +187,7 @@ struct RouterArgs {
 void launch_router(const RouterArgs& a, hipStream_t s);
 // bf16 storage: fp32 matrix-core logits with an fp64 re-evaluation of every decision that
 // is not provably safe (see routing.hip).  `scratch` needs router_hybrid_bytes() bytes.
-size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off6);
+size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off7);
 bool router_hybrid_supported(const RouterArgs& a);
 void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s);
 void launch_dense_routing(int* idx, float* gate, int* perm, int* offsets, int N, int H, hipStream_t s);

@@ -155,8 +155,8 @@ Layout make_layout(const sh_shape* s) {
     const size_t ce = wgrad_chunk(H * N * k, dm, dh), cd = wgrad_chunk(2 * H * N, dm, dh);
     const size_t cmin = ce < cd ? ce : cd;
     L.wpart = take(groups * ((N + cmin - 1) / cmin) * dm * dh * 4);
-    size_t o6[6];
-    L.rh = take(router_hybrid_bytes((int)N, (int)dm, (int)H, (int)E, o6));
+    size_t o7[7];
+    L.rh = take(router_hybrid_bytes((int)N, (int)dm, (int)H, (int)E, o7));
   }
   L.total = off;
   return L;

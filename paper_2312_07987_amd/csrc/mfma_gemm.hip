@@ -51,6 +51,19 @@ struct Chunk<4> {
   typedef uint2 type;
 };
 
+__device__ __forceinline__ float chunk_sumsq(uint4 v) {
+  const unsigned w[4] = {v.x, v.y, v.z, v.w};
+  float s = 0.f;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const float lo = __uint_as_float(w[u] << 16), hi = __uint_as_float(w[u] & 0xffff0000u);
+    s = fmaf(lo, lo, s);
+    s = fmaf(hi, hi, s);
+  }
+  return s;
+}
+__device__ __forceinline__ float chunk_sumsq(uint2 v) { return chunk_sumsq(make_uint4(v.x, v.y, 0, 0)); }
+
 template <int VEC>
 __device__ __forceinline__ typename Chunk<VEC>::type zero_chunk() {
   typename Chunk<VEC>::type z;
@@ -242,6 +255,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
 
   chunk_t ra[A_N], rb[B_N];
   const int nks = (K + BK - 1) / BK;   // K steps per segment
+  float sumsq[TAG == TAG_ROUTER ? A_N : 1] = {};
   auto load_global = [&](int it) {
     const int seg = SEG ? it / nks : 0;
     const int k0 = (SEG ? it % nks : it) * BK;
@@ -276,7 +290,10 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
     unsigned short* As = smem + stage * Cfg::STAGE_ELEMS;
     unsigned short* Bs = As + Cfg::A_ELEMS;
 #pragma unroll
-    for (int i = 0; i < A_N; ++i) *(chunk_t*)(&As[a_lds[i]]) = ra[i];
+    for (int i = 0; i < A_N; ++i) {
+      *(chunk_t*)(&As[a_lds[i]]) = ra[i];
+      if constexpr (TAG == TAG_ROUTER) sumsq[i] += chunk_sumsq(ra[i]);   // row norms ride along (see epilogue)
+    }
 #pragma unroll
     for (int i = 0; i < B_N; ++i) *(chunk_t*)(&Bs[b_lds[i]]) = rb[i];
   };
@@ -370,6 +387,19 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
   // ---- epilogue -------------------------------------------------------------------------
   char* Cb = (char*)(second ? a.C2 : a.C);
   if constexpr (ACC64) {
+    // the router's error bound needs |x_n|: every chunk of the A rows went through this block's
+    // registers, so the first group's blocks add up the squares (8 threads share a row)
+    if (a.rownorm && h == 0 && ct == 0) {
+      float* rs = (float*)smem;   // the operand tiles are dead
+      __syncthreads();
+      for (int t = tid; t < BM; t += 256) rs[t] = 0.f;
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < A_N; ++i) atomicAdd(&rs[a_lds[i] / LDA], sumsq[i]);
+      __syncthreads();
+      for (int t = tid; t < BM; t += 256)
+        if (ids[t] >= 0) a.rownorm[ids[t]] = sqrtf(rs[t]) * 1.0001f;
+    }
     if (active) {
 #pragma unroll
       for (int i = 0; i < MI; ++i)

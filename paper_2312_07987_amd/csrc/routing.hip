@@ -227,81 +227,78 @@ __global__ void dense_routing_kernel(int* idx, float* gate, int* perm, int* offs
 // factor 4 of slack for the adder tree of the matrix core.  If every gap between consecutive sorted
 // logits down to the (k+1)-th exceeds 2*bound, the ordered top-k list is provably the one
 // the fp64 logits give, and it is written directly.  Otherwise the (token, side, head) is
-// queued and stage 2 re-evaluates its E logits in fp64 in the canonical order and selects
-// from those.  Indices are therefore identical to the all-fp64 router by construction.
+// queued and stage 2 re-evaluates its E logits in fp64 and selects from those.  Stage 2 adds
+// the products in a fixed blocked order (16 per lane, then a butterfly over the lanes), which
+// differs from the sequential fp64 sum by a few ulp of fp64 -- twelve orders of magnitude below
+// the fp32-level gaps that send an entry here -- and gives bit-identical sums for identical
+// columns, so ties still resolve to the lower index.
 // ----------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void row_norm_kernel(const T* __restrict__ x, const T* __restrict__ W0,
-                                                       const T* __restrict__ W1, float* __restrict__ xnorm,
-                                                       float* __restrict__ wmax, int* __restrict__ fixcount, int N,
-                                                       int dm, int H, int E, int sides) {
+// Per (side, head) work-group: the largest column norm of the head's router (for the error bound),
+// the queue counter cleared, and the head's columns copied out as contiguous vectors
+// Wt[side][h*E + e][dmp] (zero padded to dmp, a multiple of 1024) for the fp64 recheck.
+__global__ __launch_bounds__(256) void router_prep_kernel(const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
+                                                          float* __restrict__ wmax, int* __restrict__ fixcount,
+                                                          unsigned short* __restrict__ Wt, int dm, int dmp, int H, int E) {
+  __shared__ float red[4];
+  const int sh_ = blockIdx.x;
+  const int side = sh_ / H, h = sh_ % H;
+  const unsigned short* W = (const unsigned short*)(side ? W1 : W0);
+  const int HE = H * E;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const long row = (long)blockIdx.x * 4 + wave;
-  if (row < N) {
+  float mx = 0.f;
+  for (int e = 0; e < E; ++e) {
     float s = 0.f;
-    if (sizeof(T) == 2 && dm % 8 == 0) {
-      const uint4* xr = (const uint4*)((const unsigned short*)x + row * dm);
-      for (int i = lane; i < dm / 8; i += 64) {
-        const uint4 v = xr[i];
-        const unsigned w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const float lo = __uint_as_float(w[u] << 16), hi = __uint_as_float(w[u] & 0xffff0000u);
-          s = fmaf(lo, lo, s);
-          s = fmaf(hi, hi, s);
-        }
-      }
-    } else {
-      for (int i = lane; i < dm; i += 64) {
-        float v = ld(x, row * dm + i);
-        s = fmaf(v, v, s);
-      }
+    unsigned short* wt = Wt + ((long)side * HE + h * E + e) * dmp;
+    for (int i = threadIdx.x; i < dmp; i += 256) {
+      unsigned short v = 0;
+      if (i < dm) v = W[(long)i * HE + h * E + e];
+      wt[i] = v;
+      const float f = __uint_as_float((unsigned)v << 16);
+      s = fmaf(f, f, s);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (lane == 0) xnorm[row] = sqrtf(s) * 1.0001f;
-  } else {
-    // the blocks behind the token rows: one wave per (side, head): max column norm of the head
-    const long sh_ = row - (((long)N + 3) / 4) * 4;
-    if (sh_ >= 0 && sh_ < (long)sides * H) {
-      const int side = (int)(sh_ / H), h = (int)(sh_ % H);
-      const T* W = side ? W1 : W0;
-      const int HE = H * E;
-      float mx = 0.f;
-      for (int e = 0; e < E; ++e) {
-        float s = 0.f;
-        for (int i = lane; i < dm; i += 64) {
-          float v = ld(W, (long)i * HE + h * E + e);
-          s = fmaf(v, v, s);
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-        mx = fmaxf(mx, s);
-      }
-      if (lane == 0) wmax[sh_] = sqrtf(mx) * 1.0001f;
-    }
-    if (sh_ >= 0 && sh_ < (long)sides * H && lane == 0) fixcount[sh_] = 0;
+    __syncthreads();
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    mx = fmaxf(mx, red[0] + red[1] + red[2] + red[3]);
+  }
+  if (threadIdx.x == 0) {
+    wmax[sh_] = sqrtf(mx) * 1.0001f;
+    fixcount[sh_] = 0;
   }
 }
 
+constexpr int SEL_TOK = 64;   // tokens per work-group of select_kernel
+
+// First-stage selection.  A work-group stages the stage-1 logits of SEL_TOK tokens of one side in LDS
+// (whole rows, coalesced), then one thread per (token, head) selects and checks the margins
+// against the error bound; entries that fail are queued for the fp64 recheck.
 __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ Zs, const float* __restrict__ b0,
                                                      const float* __restrict__ b1, const float* __restrict__ xnorm,
                                                      const float* __restrict__ wmax, int* __restrict__ idx,
                                                      float* __restrict__ gate, int* __restrict__ fixlist,
                                                      int* __restrict__ fixcount, int N, int kstep, int H, int E, int k,
                                                      int HEp) {
-  const int sh_ = blockIdx.y;
-  const int side = sh_ / H, h = sh_ % H;
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  bool flag = false;
-  if (n < N) {
-    const double* z = Zs + ((long)side * N + n) * (long)HEp + (long)h * E;
-    const float* b = side ? b1 : b0;
+  extern __shared__ double zt[];   // [SEL_TOK][HEp]
+  const int side = blockIdx.y;
+  const int n0 = blockIdx.x * SEL_TOK;
+  const float* b = side ? b1 : b0;
+  const int ntok = N - n0 < SEL_TOK ? N - n0 : SEL_TOK;
+  const double* src = Zs + ((long)side * N + n0) * (long)HEp;
+  for (int i = threadIdx.x; i < ntok * HEp; i += 256) zt[i] = src[i];
+  __syncthreads();
+  for (int item = threadIdx.x; item < ntok * H; item += 256) {
+    const int nl = item / H, h = item % H;
+    const int n = n0 + nl;
+    const int sh_ = side * H + h;
+    const double* z = zt + nl * HEp + h * E;
     // fp32 partial sums of `kstep` exact products, then fp64 adds: see the bound above
     const double bound0 = 4.0 * (double)kstep * 5.9604645e-8 * (double)xnorm[n] * (double)wmax[sh_];
     unsigned long long sel = 0ull;
     const long o = ((long)sh_ * N + n) * k;
     double prev = 0.0, bprev = 0.0;
+    bool flag = false;
     const int passes = k < E ? k + 1 : k;
     for (int j = 0; j < passes; ++j) {
       int best = -1;
@@ -324,107 +321,80 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
         gate[o + j] = (float)(1.0 / (1.0 + exp(-bv)));
       }
     }
-  }
-  // one atomic per wave
-  const unsigned long long bal = __ballot(flag);
-  if (bal) {
-    const int lane = threadIdx.x & 63;
-    int base = 0;
-    if (lane == 0) base = atomicAdd(&fixcount[sh_], __popcll(bal));
-    base = __shfl(base, 0, 64);
-    if (flag) fixlist[(long)sh_ * N + base + __popcll(bal & ((1ull << lane) - 1ull))] = n;
+    if (flag) fixlist[(long)sh_ * N + atomicAdd(&fixcount[sh_], 1)] = n;   // rare: a fraction of a percent
   }
 }
 
-constexpr int FIX_ITEMS = 16;   // queued tokens per block; 4 threads share a token, each takes every 4th expert
+constexpr int FIX_WAVES = 4;   // queued tokens in flight per work-group: one wave per token
 
-__global__ __launch_bounds__(64) void fix64_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W0,
-                                                   const bf16_t* __restrict__ W1, const float* __restrict__ b0,
-                                                   const float* __restrict__ b1, const int* __restrict__ fixlist,
-                                                   const int* __restrict__ fixcount, double* __restrict__ Z,
-                                                   int* __restrict__ idx, float* __restrict__ gate, int N, int dm, int H,
-                                                   int E, int k) {
-  constexpr int KC = 64;
-  __shared__ double xs[FIX_ITEMS][KC + 1];
-  __shared__ double ws[KC][8];
+// Second stage of the exact router: recomputes the logits of the queued (side, head, token)
+// entries in fp64 and redoes their selection.  One wave per entry: lane l sums the products of
+// input features 16 l .. 16 l + 15 (per 1024-feature slab) against the head's column vectors, the
+// lanes' sums are added by a butterfly, lane 0 adds the bias and selects.
+__global__ __launch_bounds__(64 * FIX_WAVES) void fix64_kernel(const bf16_t* __restrict__ x, const unsigned short* __restrict__ Wt,
+                                                              const float* __restrict__ b0, const float* __restrict__ b1,
+                                                              const int* __restrict__ fixlist, const int* __restrict__ fixcount,
+                                                              double* __restrict__ Z, int* __restrict__ idx,
+                                                              float* __restrict__ gate, int N, int dm, int dmp, int H, int E,
+                                                              int k) {
+  __shared__ double zs[FIX_WAVES][64];
   const int sh_ = blockIdx.y;
   const int count = fixcount[sh_];
   const int side = sh_ / H, h = sh_ % H;
-  const bf16_t* W = side ? W1 : W0;
   const float* b = side ? b1 : b0;
   const int HE = H * E;
-  const int t = threadIdx.x, it = t >> 2, part = t & 3;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const unsigned short* wt0 = Wt + ((long)side * HE + h * E) * dmp;
   // a small fixed grid walks the queue: empty work-groups are not free to launch
-  for (int item0 = blockIdx.x * FIX_ITEMS; item0 < count; item0 += gridDim.x * FIX_ITEMS) {
-  const bool valid = item0 + it < count;
-  const int n = valid ? fixlist[(long)sh_ * N + item0 + it] : 0;
-  double* z = Z + ((long)side * N + n) * HE + (long)h * E;
-  const unsigned short* xrow = (const unsigned short*)x + (long)n * dm;   // dm % 4 == 0, 8-byte aligned rows
-
-  for (int e0 = 0; e0 < E; e0 += 8) {
-    double acc[2] = {0.0, 0.0};   // experts e0 + part and e0 + part + 4
-    uint2 rx[KC / 16];            // this thread's quarter of the token's row chunk
-    float rw[8];
-    auto fetch = [&](int k0) {
+  for (int item = blockIdx.x * FIX_WAVES + wave; item < count; item += gridDim.x * FIX_WAVES) {
+    const int n = fixlist[(long)sh_ * N + item];
+    const unsigned short* xrow = (const unsigned short*)x + (long)n * dm;   // dm % 4 == 0: 8-byte aligned rows
+    for (int e = 0; e < E; ++e) {
+      double acc = 0.0;
+      for (int s0 = 0; s0 < dmp; s0 += 1024) {
+        const int i0 = s0 + lane * 16;
+        uint2 xv[4];
+        uint4 wv[2];
 #pragma unroll
-      for (int q = 0; q < KC / 16; ++q) {
-        const int kk = k0 + part * (KC / 4) + 4 * q;
-        rx[q] = make_uint2(0, 0);
-        if (valid && kk < dm) rx[q] = *(const uint2*)(xrow + kk);
-      }
+        for (int q = 0; q < 4; ++q) {
+          xv[q] = make_uint2(0, 0);
+          if (i0 + 4 * q < dm) xv[q] = *(const uint2*)(xrow + i0 + 4 * q);
+        }
+        wv[0] = *(const uint4*)(wt0 + (long)e * dmp + i0);
+        wv[1] = *(const uint4*)(wt0 + (long)e * dmp + i0 + 8);
+        const unsigned xw[8] = {xv[0].x, xv[0].y, xv[1].x, xv[1].y, xv[2].x, xv[2].y, xv[3].x, xv[3].y};
+        const unsigned ww[8] = {wv[0].x, wv[0].y, wv[0].z, wv[0].w, wv[1].x, wv[1].y, wv[1].z, wv[1].w};
 #pragma unroll
-      for (int u = 0; u < 8; ++u) rw[u] = (k0 + t < dm && e0 + u < E) ? ld(W, (long)(k0 + t) * HE + h * E + e0 + u) : 0.f;
-    };
-    fetch(0);
-    for (int k0 = 0; k0 < dm; k0 += KC) {
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < KC / 16; ++q) {
-        const int c = part * (KC / 4) + 4 * q;
-        xs[it][c + 0] = (double)__uint_as_float(rx[q].x << 16);
-        xs[it][c + 1] = (double)__uint_as_float(rx[q].x & 0xffff0000u);
-        xs[it][c + 2] = (double)__uint_as_float(rx[q].y << 16);
-        xs[it][c + 3] = (double)__uint_as_float(rx[q].y & 0xffff0000u);
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) ws[t][u] = (double)rw[u];
-      __syncthreads();
-      if (k0 + KC < dm) fetch(k0 + KC);
-#pragma unroll 8
-      for (int i = 0; i < KC; ++i) {
-        const double xv = xs[it][i];
-        acc[0] = fma(xv, ws[i][part], acc[0]);
-        acc[1] = fma(xv, ws[i][part + 4], acc[1]);
-      }
-    }
-    if (valid) {
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const int e = e0 + part + 4 * c;
-        if (e < E) z[e] = acc[c] + (b ? (double)b[h * E + e] : 0.0);
-      }
-    }
-  }
-  __syncthreads();   // the token's logits were written by its 4 threads
-  if (valid && part == 0) {
-    unsigned long long sel = 0ull;
-    const long o = ((long)sh_ * N + n) * k;
-    for (int j = 0; j < k; ++j) {
-      int best = -1;
-      double bv = 0.0;
-      for (int e = 0; e < E; ++e) {
-        if ((sel >> e) & 1ull) continue;
-        double v = z[e];
-        if (best < 0 || v > bv) {
-          best = e;
-          bv = v;
+        for (int q = 0; q < 8; ++q) {
+          acc = fma((double)__uint_as_float(xw[q] << 16), (double)__uint_as_float(ww[q] << 16), acc);
+          acc = fma((double)__uint_as_float(xw[q] & 0xffff0000u), (double)__uint_as_float(ww[q] & 0xffff0000u), acc);
         }
       }
-      sel |= 1ull << best;
-      idx[o + j] = best;
-      gate[o + j] = (float)(1.0 / (1.0 + exp(-bv)));
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+      if (lane == 0) zs[wave][e] = acc + (b ? (double)b[h * E + e] : 0.0);
     }
-  }
+    if (lane == 0) {
+      double* z = Z + ((long)side * N + n) * HE + (long)h * E;
+      for (int e = 0; e < E; ++e) z[e] = zs[wave][e];
+      unsigned long long sel = 0ull;
+      const long o = ((long)sh_ * N + n) * k;
+      for (int j = 0; j < k; ++j) {
+        int best = -1;
+        double bv = 0.0;
+        for (int e = 0; e < E; ++e) {
+          if ((sel >> e) & 1ull) continue;
+          const double v = zs[wave][e];
+          if (best < 0 || v > bv) {
+            best = e;
+            bv = v;
+          }
+        }
+        sel |= 1ull << best;
+        idx[o + j] = best;
+        gate[o + j] = (float)(1.0 / (1.0 + exp(-bv)));
+      }
+    }
   }
 }
 
@@ -483,6 +453,7 @@ size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off) {
   off[3] = take(2 * (size_t)H * 4);          // wmax
   off[4] = take(2 * (size_t)H * N * 4);      // fixlist
   off[5] = take(2 * (size_t)H * 4 + 256);    // fixcount per (side, head)
+  off[6] = take(2 * (size_t)H * E * (((size_t)dm + 1023) / 1024 * 1024) * 2);   // Wt: router columns as vectors
   return o;
 }
 
@@ -491,7 +462,7 @@ bool router_hybrid_supported(const RouterArgs& a) {
 }
 
 void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
-  size_t off[6];
+  size_t off[7];
   router_hybrid_bytes(a.N, a.dm, a.H, a.E, off);
   const int HE = a.H * a.E, HEp = (HE + 7) / 8 * 8;
   bf16_t* Wp = (bf16_t*)(scratch + off[0]);
@@ -500,6 +471,8 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
   float* wmax = (float*)(scratch + off[3]);
   int* fixlist = (int*)(scratch + off[4]);
   int* fixcount = (int*)(scratch + off[5]);
+  unsigned short* Wt = (unsigned short*)(scratch + off[6]);
+  const int dmp = (a.dm + 1023) / 1024 * 1024;
 
   const long tot = (long)a.sides * a.dm * HEp;
   pack_router_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], Wp, a.dm, HE,
@@ -524,19 +497,19 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
   g.Nc = HEp;
   g.mode = STORE_F64;
   g.tag = TAG_ROUTER;
+  g.rownorm = xnorm;   // |x_n| for the error bound, from the tiles the GEMM loads anyway
   launch_mfma_row_gemm(g, s);
 
-  const int nrow_blocks = (a.N + 3) / 4 + (a.sides * a.H + 3) / 4;
-  row_norm_kernel<bf16_t><<<nrow_blocks, 256, 0, s>>>((const bf16_t*)a.x, (const bf16_t*)a.W[0], (const bf16_t*)a.W[1], xnorm,
-                                                      wmax, fixcount, a.N, a.dm, a.H, a.E, a.sides);
-  dim3 g1((a.N + 255) / 256, a.sides * a.H);
-  select_kernel<<<g1, 256, 0, s>>>(Zs, a.b[0], a.b[1], xnorm, wmax, a.idx, a.gate, fixlist, fixcount, a.N, rg_kstep(), a.H,
-                                   a.E, a.k, HEp);
-  int fix_blocks = (a.N + FIX_ITEMS - 1) / FIX_ITEMS;
+  router_prep_kernel<<<a.sides * a.H, 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], wmax, fixcount, Wt, a.dm, dmp,
+                                                   a.H, a.E);
+  dim3 g1((a.N + SEL_TOK - 1) / SEL_TOK, a.sides);
+  select_kernel<<<g1, 256, (size_t)SEL_TOK * HEp * 8, s>>>(Zs, a.b[0], a.b[1], xnorm, wmax, a.idx, a.gate, fixlist, fixcount,
+                                                            a.N, rg_kstep(), a.H, a.E, a.k, HEp);
+  int fix_blocks = (a.N + FIX_WAVES - 1) / FIX_WAVES;
   if (fix_blocks > 64) fix_blocks = 64;
   dim3 g3(fix_blocks, a.sides * a.H);
-  fix64_kernel<<<g3, 64, 0, s>>>((const bf16_t*)a.x, (const bf16_t*)a.W[0], (const bf16_t*)a.W[1], a.b[0], a.b[1],
-                                         fixlist, fixcount, a.Z, a.idx, a.gate, a.N, a.dm, a.H, a.E, a.k);
+  fix64_kernel<<<g3, 64 * FIX_WAVES, 0, s>>>((const bf16_t*)a.x, Wt, a.b[0], a.b[1], fixlist, fixcount, a.Z, a.idx, a.gate,
+                                               a.N, a.dm, dmp, a.H, a.E, a.k);
   const int nblk = router_blocks(a.N);
   dim3 g2(nblk, a.sides * a.H);
   hist_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.N, a.E, a.k, nblk);
