@@ -256,9 +256,11 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
   chunk_t ra[A_N], rb[B_N];
   const int nks = (K + BK - 1) / BK;   // K steps per segment
   float sumsq[TAG == TAG_ROUTER ? A_N : 1] = {};
+  int staged_seg = 0;   // segment of the K step that sits in ra / rb
   auto load_global = [&](int it) {
     const int seg = SEG ? it / nks : 0;
     const int k0 = (SEG ? it % nks : it) * BK;
+    staged_seg = seg;
     const unsigned short* Ap = A;
     const unsigned short* Bp = B;
     if constexpr (SEG == 1) Bp = B + bseg[seg];
@@ -270,10 +272,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
       ra[i] = zero_chunk<VEC>();
-      if (a_off[i] >= 0 && k0 + a_kc[i] < K) {
-        ra[i] = *(const chunk_t*)(Ap + a_off[i] + k0);
-        if constexpr (SEG == 1) ra[i] = scale_chunk(ra[i], gsc[(a_lds[i] / LDA) * 8 + seg]);
-      }
+      if (a_off[i] >= 0 && k0 + a_kc[i] < K) ra[i] = *(const chunk_t*)(Ap + a_off[i] + k0);
     }
 #pragma unroll
     for (int i = 0; i < B_N; ++i) {
@@ -291,6 +290,9 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
     unsigned short* Bs = As + Cfg::A_ELEMS;
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
+      // expert-set mode: the gate is applied here, not at the load, so that the load stays in
+      // flight while the previous step is multiplied
+      if constexpr (SEG == 1) ra[i] = scale_chunk(ra[i], gsc[(a_lds[i] / LDA) * 8 + staged_seg]);
       *(chunk_t*)(&As[a_lds[i]]) = ra[i];
       if constexpr (TAG == TAG_ROUTER) sumsq[i] += chunk_sumsq(ra[i]);   // row norms ride along (see epilogue)
     }
@@ -647,6 +649,8 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     ids[t] = id;
     gsc[t] = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
   }
+  // rows of the last step past the chunk are staged as zeros; give them a zero gate too
+  for (int t = rows + tid; t < rows + BK && t < Cfg::MAX_CHUNK; t += 256) gsc[t] = 0.f;
   __syncthreads();
 
   const int i0 = (tile / tj) * BM, j0 = (tile % tj) * BN;
@@ -659,7 +663,9 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   constexpr int A_CPR = BM / VEC, B_CPR = BN / VEC;     // chunks per tile row
   constexpr int A_N = BK * A_CPR / 256, B_N = BK * B_CPR / 256;
   chunk_t ra[A_N], rb[B_N];
+  int staged_r0 = 0;   // first row of the step that sits in ra / rb
   auto load_global = [&](int r0) {
+    staged_r0 = r0;
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
       const int c = tid + i * 256;
@@ -667,7 +673,6 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       ra[i] = zero_chunk<VEC>();
       if (r0 + rr < rows && i0 + fc < a.Ka) {
         ra[i] = *(const chunk_t*)(A + (long)(ids[r0 + rr] / a.a_div) * a.lda + (long)hh * a.a_hoff + i0 + fc);
-        if (scaled && !a.scale_b) ra[i] = scale_chunk(ra[i], gsc[r0 + rr]);
       }
     }
 #pragma unroll
@@ -677,7 +682,6 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       rb[i] = zero_chunk<VEC>();
       if (r0 + rr < rows && j0 + fc < a.Kb) {
         rb[i] = *(const chunk_t*)(Bm + (long)(ids[r0 + rr] / a.b_div) * a.ldb + (long)hh * a.b_hoff + j0 + fc);
-        if (scaled && a.scale_b) rb[i] = scale_chunk(rb[i], gsc[r0 + rr]);
       }
     }
   };
@@ -685,13 +689,17 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     unsigned short* As = smem + stage * Cfg::STAGE_ELEMS;
     unsigned short* Bs = As + BK * LDA;
 #pragma unroll
+    // the gate is applied here, not at the load, so that the load stays in flight while the
+    // previous step is multiplied (rows past the chunk hold zeros and a zero gate)
     for (int i = 0; i < A_N; ++i) {
       const int c = tid + i * 256;
+      if (scaled && !a.scale_b) ra[i] = scale_chunk(ra[i], gsc[min(staged_r0 + c / A_CPR, Cfg::MAX_CHUNK - 1)]);
       *(chunk_t*)(&As[(c / A_CPR) * LDA + (c % A_CPR) * VEC]) = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < B_N; ++i) {
       const int c = tid + i * 256;
+      if (scaled && a.scale_b) rb[i] = scale_chunk(rb[i], gsc[min(staged_r0 + c / B_CPR, Cfg::MAX_CHUNK - 1)]);
       *(chunk_t*)(&Bs[(c / B_CPR) * LDB + (c % B_CPR) * VEC]) = rb[i];
     }
   };
