@@ -82,11 +82,12 @@ struct RowGemmArgs {
   // Segmented reduction, seg_mode:
   //  1  expert sets: perm holds token ids sorted by expert set, offsets the nsets+1 set
   //     boundaries per head (E = nsets); the reduction runs over nseg = k segments of length
-  //     K: segment p reads the same A row scaled by segate[h*gate_hstride + token*nseg + p]
-  //     against B of the p-th (ascending) expert of the set.
+  //     K: segment p reads the A row of sorted position r scaled by
+  //     segate[h*gate_hstride + r*nseg + p] against B of expert set_experts[set*8 + p].
   //  2  concatenation: segment p reads A columns (p/seg_split)*a_wstride + (p%seg_split)*a_sstride
   //     against (p/seg_split ? B2 : B) + (p%seg_split)*b_sstride.
   int seg_mode, nseg, experts;
+  const int* set_experts;
   // TAG_ROUTER only: if not NULL, rownorm[row id] = an upper bound of the Euclidean norm of the A row
   float* rownorm;
   const float* segate;
@@ -198,11 +199,13 @@ struct SetSortArgs {
   const int* idx;      // [sides, H, N, k]
   const float* gate;   // [sides, H, N, k]
   int* setid;          // [sides, H, N] scratch
-  float* gset;         // [sides, H, N, k] gates in ascending-expert order
+  float* gset;         // [sides, H, N, k] scratch: gates in ascending-expert order, by token
+  float* gsort;        // [sides, H, N, k] the same gates in sorted (setperm) order
+  int* setexp;         // [nsets, 8] the ascending experts of every set
   int* setperm;        // [sides, H, N] token ids sorted by set id (stable)
   int* setoff;         // [sides, H, nsets+1]
   int* blockcnt;       // [sides*H, nblk, nsets] scratch
-  int N, H, k, nsets, sides;
+  int N, H, k, E, nsets, sides;
 };
 void launch_set_sort(const SetSortArgs& a, hipStream_t s);
 

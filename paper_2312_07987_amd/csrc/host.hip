@@ -60,7 +60,7 @@ struct Layout {
   size_t total = 0;
   size_t idx, gate, perm, offsets, Q, K, V, ctx, lse, pV;          // saved by forward
   size_t Z, blockcnt, acc32;                                       // forward scratch
-  size_t setid, gset, setperm, setoff, setcnt, yh;                 // expert-set path (bf16 only)
+  size_t setid, gset, gsort, setexp, setperm, setoff, setcnt, yh;                 // expert-set path (bf16 only)
   size_t rh;                                                       // two-stage router scratch (bf16 only)
   size_t wpart;                                                    // per-chunk weight-gradient partial sums (bf16 only)
   size_t u, dctx, dQ, dK, dV, delta, dgate, dz;                    // backward scratch
@@ -141,12 +141,14 @@ Layout make_layout(const sh_shape* s) {
     const size_t ns = count_sets(s->E, s->k);
     L.setid = take(2 * H * N * 4);
     L.gset = take(2 * H * N * k * 4);
+    L.gsort = take(2 * H * N * k * 4);
+    L.setexp = take((size_t)MAX_SETS * 8 * 4);
     L.setperm = take(2 * H * N * 4);
     L.setoff = take(2 * H * (ns + 1) * 4);
     L.setcnt = take(2 * H * (size_t)router_blocks((int)N) * ns * 4);
     L.yh = take((H + 1) * N * dm * esz);   // one partial per head + the routers' share of dx
   } else {
-    L.setid = L.gset = L.setperm = L.setoff = L.setcnt = L.yh = 0;
+    L.setid = L.gset = L.gsort = L.setexp = L.setperm = L.setoff = L.setcnt = L.yh = 0;
   }
   L.rh = L.wpart = 0;
   if (s->dtype == SH_BF16) {
@@ -289,7 +291,8 @@ RowGemmArgs set_rows(const Ctx& c, int side) {
   a.seg_mode = 1;
   a.nseg = c.k;
   a.experts = c.E;
-  a.segate = c.p<float>(c.L.gset) + (size_t)side * c.H * c.N * c.k;
+  a.segate = c.p<float>(c.L.gsort) + (size_t)side * c.H * c.N * c.k;
+  a.set_experts = c.p<int>(c.L.setexp);
   a.gate_hstride = (long)c.N * c.k;
   return a;
 }
@@ -429,6 +432,9 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     sa.gate = c.gate(0);
     sa.setid = c.p<int>(c.L.setid);
     sa.gset = c.p<float>(c.L.gset);
+    sa.gsort = c.p<float>(c.L.gsort);
+    sa.setexp = c.p<int>(c.L.setexp);
+    sa.E = E;
     sa.setperm = c.p<int>(c.L.setperm);
     sa.setoff = c.p<int>(c.L.setoff);
     sa.blockcnt = c.p<int>(c.L.setcnt);

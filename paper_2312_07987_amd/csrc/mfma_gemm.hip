@@ -186,26 +186,10 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
     for (int t = tid; t < BM * nseg; t += 256) {
       int rr = t / nseg, p = t % nseg;
       float g = 0.f;
-      if (rr < rows) g = a.segate[(long)h * a.gate_hstride + (long)a.perm[(long)h * a.M + row0 + rr] * nseg + p];
+      if (rr < rows) g = a.segate[(long)h * a.gate_hstride + (long)(row0 + rr) * nseg + p];
       gsc[rr * 8 + p] = g;
     }
-    if (tid == 0) {
-      // unrank the combination: set id e -> ascending experts x_0 < x_1 < ...
-      int rank = e;
-      for (int p = nseg - 1; p >= 0; --p) {
-        int x = p;
-        while (x + 1 < a.experts) {
-          long v = 1;
-          for (int i = 1; i <= p + 1; ++i) v = v * (x + 1 - (p + 1) + i) / i;   // C(x+1, p+1)
-          if (v > rank) break;
-          ++x;
-        }
-        long v = 1;
-        for (int i = 1; i <= p + 1; ++i) v = v * (x - (p + 1) + i) / i;          // C(x, p+1)
-        rank -= (int)v;
-        bseg[p] = (long)hh * a.b_hstride + (long)x * a.b_estride;
-      }
-    }
+    if (tid < nseg) bseg[tid] = (long)hh * a.b_hstride + (long)a.set_experts[e * 8 + tid] * a.b_estride;
   }
   __syncthreads();
 

@@ -548,12 +548,23 @@ __device__ __forceinline__ int binom(int n, int r) {
 
 __global__ __launch_bounds__(RB) void set_hist_kernel(const int* __restrict__ idx, const float* __restrict__ gate,
                                                       int* __restrict__ setid, float* __restrict__ gset,
-                                                      int* __restrict__ blockcnt, int N, int k, int nsets, int nblk) {
+                                                      int* __restrict__ setexp, int* __restrict__ blockcnt, int N, int k,
+                                                      int E, int nsets, int nblk) {
   __shared__ int cnt[128];
   const int sh_ = blockIdx.y;
   const int n = blockIdx.x * RB + threadIdx.x;
   const bool valid = n < N;
   if (threadIdx.x < 128) cnt[threadIdx.x] = 0;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < nsets) {
+    // the table set id -> ascending experts (combinadic unranking), for the GEMMs that follow
+    int rank = threadIdx.x;
+    for (int p = k - 1; p >= 0; --p) {
+      int x = p;
+      while (x + 1 < E && binom(x + 1, p + 1) <= rank) ++x;
+      rank -= binom(x, p + 1);
+      setexp[threadIdx.x * 8 + p] = x;
+    }
+  }
   __syncthreads();
   int sid = -1;
   if (valid) {
@@ -597,7 +608,8 @@ __global__ __launch_bounds__(RB) void set_hist_kernel(const int* __restrict__ id
 }
 
 __global__ __launch_bounds__(RB) void set_scatter_kernel(const int* __restrict__ setid, const int* __restrict__ base,
-                                                         int* __restrict__ setperm, int N, int nsets, int nblk) {
+                                                         int* __restrict__ setperm, const float* __restrict__ gset,
+                                                         float* __restrict__ gsort, int N, int k, int nsets, int nblk) {
   __shared__ int wcnt[RB / 64][128];
   const int sh_ = blockIdx.y;
   const int n = blockIdx.x * RB + threadIdx.x;
@@ -615,14 +627,15 @@ __global__ __launch_bounds__(RB) void set_scatter_kernel(const int* __restrict__
   int pos = base[((long)sh_ * nblk + blockIdx.x) * nsets + sid] + rk;
   for (int w = 0; w < wave; ++w) pos += wcnt[w][sid];
   setperm[(long)sh_ * N + pos] = n;
+  for (int j = 0; j < k; ++j) gsort[((long)sh_ * N + pos) * k + j] = gset[((long)sh_ * N + n) * k + j];
 }
 
 void launch_set_sort(const SetSortArgs& a, hipStream_t s) {
   const int nblk = router_blocks(a.N);
   dim3 g(nblk, a.sides * a.H);
-  set_hist_kernel<<<g, RB, 0, s>>>(a.idx, a.gate, a.setid, a.gset, a.blockcnt, a.N, a.k, a.nsets, nblk);
+  set_hist_kernel<<<g, RB, 0, s>>>(a.idx, a.gate, a.setid, a.gset, a.setexp, a.blockcnt, a.N, a.k, a.E, a.nsets, nblk);
   scan_kernel<<<a.sides * a.H, 256, 0, s>>>(a.blockcnt, a.setoff, a.nsets, nblk);
-  set_scatter_kernel<<<g, RB, 0, s>>>(a.setid, a.blockcnt, a.setperm, a.N, a.nsets, nblk);
+  set_scatter_kernel<<<g, RB, 0, s>>>(a.setid, a.blockcnt, a.setperm, a.gset, a.gsort, a.N, a.k, a.nsets, nblk);
 }
 
 void launch_dense_routing(int* idx, float* gate, int* perm, int* offsets, int N, int H, hipStream_t s) {
