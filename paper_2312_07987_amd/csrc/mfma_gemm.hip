@@ -125,8 +125,7 @@ struct TileCfg {
   }
 };
 typedef TileCfg<2, 2, 2, 2, 64, 1> CfgSmall;    // 128 x 128
-typedef TileCfg<2, 2, 4, 4, 32, 2> CfgSquare;   // 256 x 256
-typedef TileCfg<4, 1, 4, 4, 32, 2> CfgTall;     // 512 x 128
+typedef TileCfg<2, 2, 2, 4, 64, 1, 2> CfgWide;     // 128 x 256, wave tile 64 x 128, two work-groups per CU
 typedef TileCfg<2, 2, 4, 2, 32, 2, 2> CfgMed;   // 256 x 128, two work-groups per CU
 
 template <class Cfg, int VEC, bool BNT, int TAG, int SEG>
@@ -506,7 +505,7 @@ static void launch_cfg(const RowGemmArgs& a, hipStream_t s) {
 }
 
 // tile shape for a launch: the big tiles pay off when a group has enough rows to fill them
-enum { SHAPE_SMALL, SHAPE_SQUARE, SHAPE_TALL, SHAPE_MED };
+enum { SHAPE_SMALL, SHAPE_WIDE, SHAPE_MED };
 static int g_force_shape = -1;   // experiments only
 void rg_force_shape(int shape) { g_force_shape = shape; }
 static int pick_shape(const RowGemmArgs& a) {
@@ -516,6 +515,7 @@ static int pick_shape(const RowGemmArgs& a) {
   // measured on MI355X: the 256 x 128 tile with two work-groups per CU wins where the rows are
   // dense (its operand traffic per flop is 25 % lower); expert-gathered rows do better with
   // the small tile (more work-groups in flight per CU)
+  if (!a.perm && group_rows >= 4096 && a.Nc >= 512 && a.seg_mode == 2) return SHAPE_WIDE;   // concatenated-K dgrad
   if (!a.perm && group_rows >= 4096 && a.Nc >= 128) return SHAPE_MED;
   return SHAPE_SMALL;
 }
@@ -525,8 +525,7 @@ static int pick_shape(const RowGemmArgs& a) {
 template <bool BNT, int TAG, int SEG>
 static void launch_tagged(const RowGemmArgs& a, hipStream_t s) {
   switch (pick_shape(a)) {
-    case SHAPE_SQUARE: launch_cfg<CfgSquare, 8, BNT, TAG, SEG>(a, s); break;
-    case SHAPE_TALL: launch_cfg<CfgTall, 8, BNT, TAG, SEG>(a, s); break;
+    case SHAPE_WIDE: launch_cfg<CfgWide, 8, BNT, TAG, SEG>(a, s); break;
     case SHAPE_MED: launch_cfg<CfgMed, 8, BNT, TAG, SEG>(a, s); break;
     default: launch_cfg<CfgSmall, 8, BNT, TAG, SEG>(a, s); break;
   }
