@@ -158,7 +158,7 @@ __device__ __forceinline__ void attn_block_map(int L, int ntile, int P, int H, b
 // forward: block = 4 waves x 32 queries, key tiles of KT keys
 // ----------------------------------------------------------------------------------------
 template <int DH, int VEC>
-__global__ __launch_bounds__(256) void mfma_attn_fwd_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_fwd_kernel(AttnArgs a) {
   constexpr int KT = DH > 128 ? 32 : 64;
   constexpr int LDK = DH + 8, LDV = ld_tr(DH);
   constexpr int NKD = DH / 16;   // k steps of Q K^T
@@ -452,7 +452,7 @@ __global__ __launch_bounds__(256) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
 //   dQ^T[d][q] += K^T[d][key] dS^T[key][q]
 // ----------------------------------------------------------------------------------------
 template <int DH, int VEC>
-__global__ __launch_bounds__(256) void mfma_attn_dq_kernel(AttnBwdArgs a) {
+__global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(AttnBwdArgs a) {
   constexpr int KT = DH > 128 ? 32 : 64;
   constexpr bool SEP = DH <= 128;
   constexpr int LDR = SEP ? DH + 8 : ld_tr(DH), LDT = ld_tr(DH);
