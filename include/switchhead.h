@@ -109,8 +109,11 @@ sh_status switchhead_forward(const sh_shape* shape,
  *            dW_S, dW_D, db_S, db_D may be NULL when not wanted; dW_D/db_D are ignored
  *            with shared selection (dW_S then holds the sum of both sides) and all four
  *            are ignored in dense mode.
- * Weight gradients are accumulated with fp32 atomic adds over token chunks: their last
- * bits may differ from run to run.
+ * Determinism: with bf16 storage and the matrix-core kernels, dW_Q, dW_K, dW_V, dW_O are
+ * sums of per-chunk partial results added in a fixed order (bit-identical from run to run);
+ * the small router gradients dW_S, dW_D, db_S, db_D, and every weight gradient of the plain
+ * fp32 kernels, are accumulated with fp32 atomic adds over token chunks, so their last bits
+ * may differ from run to run.
  */
 sh_status switchhead_backward(const sh_shape* shape,
                               const void* x, const void* W_Q, const void* W_K,
