@@ -41,6 +41,10 @@ def step_work(cfg):
         "fwd.q_proj": proj, "fwd.k_proj": proj, "fwd.qk_proj": 2 * proj, "bwd.qk_dgrad": 2 * proj,
         "fwd.v_experts": expert, "fwd.o_experts": expert,
         "fwd.attention": attn, "bwd.attention": 5 * attn // 2,
+        # backward attention = 5 matmuls of attn/2 flops each: S and dP (shared), dV, dK, dQ; the dK/dV
+        # kernel is credited with four of them, the dQ kernel with dQ alone (its recomputation of S and
+        # dP is not algorithmic work)
+        "bwd.attention_dkv": 2 * attn, "bwd.attention_dq": attn // 2,
         "bwd.o_dgrad": expert, "bwd.o_wgrad": expert, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
         "bwd.q_wgrad": proj, "bwd.k_wgrad": proj, "bwd.qk_wgrad": 2 * proj, "bwd.q_dgrad": proj, "bwd.k_dgrad": proj,
         "bwd.router_wgrad": router // 2, "bwd.router_dgrad": router // 2,
@@ -67,7 +71,8 @@ STEP_KERNEL = {
     "bwd.v_dgrad": r"mfma_row_gemm_kernel<.*, 5, 1>", "bwd.qk_dgrad": r"mfma_row_gemm_kernel<.*, 6, 2>",
     "bwd.o_wgrad": r"mfma_wgrad_kernel<.*, 8, 7>", "bwd.v_wgrad": r"mfma_wgrad_kernel<.*, 8, 8>",
     "bwd.qk_wgrad": r"mfma_wgrad_kernel<.*, 8, 9>", "bwd.wgrad_reduce": r"wgrad_reduce_kernel",
-    "fwd.attention": r"mfma_attn_fwd_kernel", "fwd.y_sum": r"sum_heads_kernel", "bwd.dx_cast": r"sum_heads_kernel",
+    "fwd.attention": r"mfma_attn_fwd_kernel", "bwd.attention_dkv": r"mfma_attn_dkv_kernel",
+    "bwd.attention_dq": r"mfma_attn_dq_kernel", "fwd.y_sum": r"sum_heads_kernel", "bwd.dx_cast": r"sum_heads_kernel",
     "fwd.v_combine": r"slot_combine", "bwd.dctx_combine": r"slot_combine", "bwd.dgate_s": r"slot_combine",
 }
 
@@ -94,6 +99,32 @@ def time_loop(fn, steps):
         fn()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def dense_baseline(cfg, steps, warmup):
+    """The same kernels in dense multi-head mode (no routers, E = 1), parameter-matched the way the
+    paper matches its dense baselines (Sec. 3.1): H*E heads whose d_head gives the same number of
+    parameters, rounded up to a multiple of 8."""
+    from paper_2312_07987_amd.inputs import make_inputs
+    from paper_2312_07987_amd.runner import DeviceLayer
+    H, E, dh = cfg["nheads"], cfg["E"], cfg["d_head"]
+    heads = H * E
+    dh_match = ((2 * H + 2 * H * E) * dh + 2 * H * E) / (4.0 * H * E)
+    dh2 = int(-(-dh_match // 8) * 8)
+    dc = dict(cfg, nheads=heads, d_head=dh2, E=1, k=1, bias0=0.0, name="dense")
+    layer = DeviceLayer(dc, make_inputs(dc, seed=1), dense=True)
+
+    def step():
+        layer.forward()
+        layer.backward()
+
+    for _ in range(warmup):
+        step()
+    ms_step = time_loop(step, steps)
+    ms_fwd = time_loop(layer.forward, steps)
+    N = cfg["B"] * cfg["T"]
+    return {"nheads": heads, "d_head": dh2, "d_head_param_matched": dh_match, "fwd_ms": ms_fwd, "fwd_bwd_ms": ms_step,
+            "fwd_tokens_per_s": N / (ms_fwd * 1e-3), "fwd_bwd_tokens_per_s": N / (ms_step * 1e-3)}
 
 
 def cpu_baseline(cfg, budget_tokens):
@@ -129,6 +160,7 @@ def main():
     ap.add_argument("--config", default="c2", help="c1..c4 (c2 = the 262M-model-scale layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=1 << 20, help="token budget of the oracle sample (whole sequences)")
+    ap.add_argument("--no-dense", action="store_true", help="skip the parameter-matched dense multi-head baseline")
     ap.add_argument("--copy-only", action="store_true", help="run a plain 256 MiB device copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -219,6 +251,8 @@ def main():
             "expert_counts_side0_head0": [int(v) for v in (counts[0, 0, 1:] - counts[0, 0, :-1])],
         },
     }
+    if not args.no_dense:
+        out["extra"]["dense_mha"] = dense_baseline(cfg, args.steps, args.warmup)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_tokens)
     print(json.dumps(out))

@@ -130,6 +130,9 @@ struct WgradArgs {
   float* partial;
   int max_chunks;
   int scale_b;   // apply the gate to the rows of Bm instead of A (same product, fewer elements to scale)
+  // Atomic path only: columns j >= kb_store are computed (Bm rows are read Kb wide, e.g. zero padded
+  // to a multiple of 8) but not stored; 0 means Kb.
+  int kb_store;
 };
 void launch_wgrad_reduce(const WgradArgs& a, hipStream_t s);
 
@@ -243,6 +246,10 @@ struct RouterBwdArgs {
   int ld, side_stride;
 };
 void launch_router_bwd(const RouterBwdArgs& a, int bf16, hipStream_t s);
+
+// Step profiler (host.hip): when enabled, records an event on `st`; the time up to the next mark is
+// booked under `label` (a string literal; NULL closes the last step).
+void prof_mark(hipStream_t st, const char* label);
 // both routers' weights as bf16 [side][d_model][HEp], columns HE..HEp-1 zero (W1 unused when sides == 1)
 void launch_pack_router(const void* W0, const void* W1, void* Wp, int dm, int HE, int HEp, int sides, hipStream_t s);
 

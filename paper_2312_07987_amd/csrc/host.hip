@@ -37,7 +37,7 @@ bool g_prof_on = false;
 std::vector<ProfMark> g_marks;
 std::vector<hipEvent_t> g_event_pool;
 
-void prof_mark(hipStream_t st, const char* label) {
+void prof_mark_impl(hipStream_t st, const char* label) {
   if (!g_prof_on) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   hipEvent_t ev;
@@ -53,6 +53,12 @@ void prof_mark(hipStream_t st, const char* label) {
   }
   g_marks.push_back({label, ev});
 }
+
+}  // namespace
+
+void sh::prof_mark(hipStream_t st, const char* label) { prof_mark_impl(st, label); }
+
+namespace {
 
 inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -241,8 +247,9 @@ void wgrad(const Ctx& c, WgradArgs a, bool deterministic = true) {
   }
   // atomic paths add into zeroed outputs
   const int h1 = a.hsplit > 0 ? a.hsplit : a.heads;
-  launch_fill_f32(a.dW, (size_t)h1 * a.E * a.Ka * a.Kb, 0.f, c.st);
-  if (a.hsplit > 0) launch_fill_f32(a.dW2, (size_t)(a.heads - a.hsplit) * a.E * a.Ka * a.Kb, 0.f, c.st);
+  const size_t kb = a.kb_store ? a.kb_store : a.Kb;
+  launch_fill_f32(a.dW, (size_t)h1 * a.E * a.Ka * kb, 0.f, c.st);
+  if (a.hsplit > 0) launch_fill_f32(a.dW2, (size_t)(a.heads - a.hsplit) * a.E * a.Ka * kb, 0.f, c.st);
   if (use_mfma(c) && mfma_wgrad_supported(a)) {
     launch_mfma_wgrad(a, c.st);
     return;
@@ -298,7 +305,7 @@ RowGemmArgs set_rows(const Ctx& c, int side) {
 }
 
 bool sets_usable(const Ctx& c) {
-  return use_mfma(c) && count_sets(c.E, c.k) <= MAX_SETS && c.dm % 8 == 0 && c.dh % 8 == 0;
+  return use_mfma(c) && count_sets(c.E, c.k) <= MAX_SETS && c.dm % 4 == 0 && c.dh % 4 == 0 && ((size_t)c.N * c.dm) % 8 == 0;
 }
 
 RowGemmArgs identity_rows(const Ctx& c, int heads) {
@@ -884,7 +891,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       w.lda = dm;
       w.Ka = dm;
       w.ldb = rb.ld;
-      w.Kb = HE;
+      w.Kb = HEp;        // the padded columns of dz are zero; reading them keeps the rows 16-byte wide
+      w.kb_store = HE;
       w.swa = HE;
       w.chunk = 256;   // tiny output: many short chunks keep the GPU busy, atomics are few
       if (sides == 2 && dWs[0] && dWs[1]) {

@@ -96,14 +96,14 @@ __device__ __forceinline__ bf16x8 global_frag(const unsigned short* row, int d, 
 // from global memory to LDS: load() issues the global loads into registers, store() writes
 // them to one or two LDS tiles (the second with another row stride, for the transposing
 // reads).  Keeping the two apart lets the next tile travel while the current one is used.
-template <int DH, int VEC, int NROWS>
+template <int DH, int VEC, int NROWS, int NT = 256>
 struct RowTile {
-  static constexpr int CPR = DH / VEC, TOTAL = NROWS * CPR, NCH = (TOTAL + 255) / 256;
+  static constexpr int CPR = DH / VEC, TOTAL = NROWS * CPR, NCH = (TOTAL + NT - 1) / NT;
   uint4 r[NCH];   // VEC == 4 uses .x/.y only
   __device__ __forceinline__ void load(const unsigned short* src, long row_stride, int valid_rows, int dh, int tid) {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      const int c = tid + i * 256;
+      const int c = tid + i * NT;
       const int row = c / CPR, d = (c % CPR) * VEC;
       r[i] = make_uint4(0, 0, 0, 0);
       if (c < TOTAL && row < valid_rows && d < dh) {
@@ -120,7 +120,7 @@ struct RowTile {
   __device__ __forceinline__ void store(unsigned short* t0, int ld0, unsigned short* t1, int ld1, int tid) const {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      const int c = tid + i * 256;
+      const int c = tid + i * NT;
       if (c >= TOTAL) continue;
       const int row = c / CPR, d = (c % CPR) * VEC;
       if constexpr (VEC == 8) {
@@ -334,9 +334,9 @@ __device__ __forceinline__ void store_rows_T(unsigned short* dst, const f32x16* 
 //   S[q][key] = Q K^T,  P = exp(S - lse),  dP[q][key] = dO V^T,  dS = P (dP - delta)
 //   dV^T[d][key] += dO^T[d][q] P[q][key],   dK^T[d][key] += Q^T[d][q] dS[q][key]
 // ----------------------------------------------------------------------------------------
-template <int DH, int VEC>
-__global__ __launch_bounds__(256) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
-  constexpr int QT = 32;
+template <int DH, int VEC, int NW>
+__global__ __launch_bounds__(64 * NW) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
+  constexpr int QT = 32, KB = 32 * NW;   // keys per work-group
   constexpr bool SEP = DH <= 128;                       // separate tiles for the two read patterns
   constexpr int LDR = SEP ? DH + 8 : ld_tr(DH), LDT = ld_tr(DH);
   constexpr int NKD = DH / 16, NDB = DH / 32;
@@ -350,8 +350,8 @@ __global__ __launch_bounds__(256) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
   unsigned short* Gt = SEP ? Gt_ : Gr;
 
   int b, h, ktile;
-  attn_block_map(blockIdx.x, (a.T + 127) / 128, a.B * a.H, a.H, a.causal, false, b, h, ktile);
-  const int k0 = ktile * 128;
+  attn_block_map(blockIdx.x, (a.T + KB - 1) / KB, a.B * a.H, a.H, a.causal, false, b, h, ktile);
+  const int k0 = ktile * KB;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
   const int T = a.T, dh = a.dh;
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(256) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
   const float sc = a.scale * 1.44269504088896340736f;
 
   const int qbeg = a.causal ? (k0 / QT) * QT : 0;
-  RowTile<DH, VEC, QT> tq, tg;
+  RowTile<DH, VEC, QT, 64 * NW> tq, tg;
   float nlse = 0.f, ndel = 0.f;
   auto prefetch = [&](int q0) {
     tq.load(Q + (long)q0 * rs, rs, T - q0, dh, tid);
@@ -551,13 +551,20 @@ static void launch_dh(const AttnArgs* f, const AttnBwdArgs* bw, hipStream_t s) {
       mfma_attn_fwd_kernel<DH, 4><<<g, 256, 0, s>>>(*f);
   } else {
     dim3 g(((bw->T + 127) / 128) * bw->H * bw->B);
-    if (attn_vec(bw->dh) == 8) {
-      mfma_attn_dkv_kernel<DH, 8><<<g, 256, 0, s>>>(*bw);
+    prof_mark(s, "bwd.attention_dkv");
+    // four waves (128 keys) per work-group; two-wave work-groups (two per CU where the registers
+    // leave one wave per SIMD) were measured 7 % slower: the Q / dO staging doubles
+    constexpr int NW = 4;
+    dim3 gk(((bw->T + 32 * NW - 1) / (32 * NW)) * bw->H * bw->B);
+    if (attn_vec(bw->dh) == 8)
+      mfma_attn_dkv_kernel<DH, 8, NW><<<gk, 64 * NW, 0, s>>>(*bw);
+    else
+      mfma_attn_dkv_kernel<DH, 4, NW><<<gk, 64 * NW, 0, s>>>(*bw);
+    prof_mark(s, "bwd.attention_dq");
+    if (attn_vec(bw->dh) == 8)
       mfma_attn_dq_kernel<DH, 8><<<g, 256, 0, s>>>(*bw);
-    } else {
-      mfma_attn_dkv_kernel<DH, 4><<<g, 256, 0, s>>>(*bw);
+    else
       mfma_attn_dq_kernel<DH, 4><<<g, 256, 0, s>>>(*bw);
-    }
   }
 }
 

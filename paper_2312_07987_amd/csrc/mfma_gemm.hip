@@ -749,7 +749,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         const int jj = j0 + wn + j * 32 + r;
-        if (jj < a.Kb) atomicAdd(dW + (long)ii * a.swa + jj, acc[i][j][q]);
+        if (jj < (a.kb_store ? a.kb_store : a.Kb)) atomicAdd(dW + (long)ii * a.swa + jj, acc[i][j][q]);
       }
     }
 }

@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void simt_wgrad_kernel(WgradArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int jj = j0 + tx * 4 + j;
-      if (jj < a.Kb) atomicAdd(dW + (long)ii * a.swa + jj, acc[i][j]);
+      if (jj < (a.kb_store ? a.kb_store : a.Kb)) atomicAdd(dW + (long)ii * a.swa + jj, acc[i][j]);
     }
   }
 }
