@@ -604,16 +604,18 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   int* ids = (int*)(smem + 2 * Cfg::STAGE_ELEMS);
   float* gsc = (float*)(ids + Cfg::MAX_CHUNK);
 
-  // unit = (chunk window, head): the output tiles of all its experts share an XCD, because the
-  // experts of a head gather overlapping rows of the token-major operand (every token is in k of the
-  // E groups) and the L2 then fetches each row once; consecutive units go to different XCDs
+  // unit = (chunk window, group); the output tiles of a unit share an XCD (they read the same
+  // rows), consecutive units go to different XCDs.  Coarser units (all experts of a head on one
+  // XCD, to share the gathered rows in its L2) gained nothing and unbalance the XCDs when the
+  // routing is skewed.
   const int ti_ = (a.Ka + BM - 1) / BM, tj = (a.Kb + BN - 1) / BN;
   const int ntile = ti_ * tj;
-  int unit, slot;
-  decode_block(blockIdx.x, a.E * ntile, unit, slot);
-  const int w = unit / a.heads, h = unit % a.heads;
+  const int G = a.heads * a.E;
+  int unit, tile;
+  decode_block(blockIdx.x, ntile, unit, tile);
+  const int w = unit / G, grp = unit % G;
   if (w * a.chunk >= (a.perm ? a.max_group_rows : a.M)) return;
-  const int e = slot / ntile, tile = slot % ntile;
+  const int h = grp / a.E, e = grp % a.E;
   int row0, rows;
   if (a.perm) {
     const int* off = a.offsets + (long)h * (a.E + 1);
@@ -807,7 +809,7 @@ template <class Cfg, int VEC, int TAG>
 static void launch_wg(const WgradArgs& a, hipStream_t s) {
   const int ti = (a.Ka + Cfg::BM - 1) / Cfg::BM, tj = (a.Kb + Cfg::BN - 1) / Cfg::BN;
   const int group_rows = a.perm ? a.max_group_rows : a.M;
-  dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads, a.E * ti * tj));
+  dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads * a.E, ti * tj));
   const size_t lds = Cfg::lds_bytes();
   auto kern = mfma_wgrad_kernel<Cfg, VEC, TAG>;
   if (lds > 64 * 1024) {
