@@ -133,6 +133,9 @@ struct WgradArgs {
   // Atomic path only: columns j >= kb_store are computed (Bm rows are read Kb wide, e.g. zero padded
   // to a multiple of 8) but not stored; 0 means Kb.
   int kb_store;
+  // Atomic path of the MFMA kernel only (hsplit must be 0): columns j >= col_split belong to a second
+  // output dW2 (same shape and swa), as its columns j - col_split; kb_store bounds each block.
+  int col_split;
 };
 void launch_wgrad_reduce(const WgradArgs& a, hipStream_t s);
 

@@ -152,7 +152,7 @@ Layout make_layout(const sh_shape* s) {
     L.setperm = take(2 * H * N * 4);
     L.setoff = take(2 * H * (ns + 1) * 4);
     L.setcnt = take(2 * H * (size_t)router_blocks((int)N) * ns * 4);
-    L.yh = take((H + 1) * N * dm * esz);   // one partial per head + the routers' share of dx
+    L.yh = take((H + 2) * N * dm * esz);   // one partial per head + the Q/K and the routers' shares of dx
   } else {
     L.setid = L.gset = L.gsort = L.setexp = L.setperm = L.setoff = L.setcnt = L.yh = 0;
   }
@@ -705,6 +705,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   // and that overwrites the fp32 dx accumulator; otherwise the accumulator is zeroed and every
   // head adds its part atomically.
   float* dxacc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)dx;
+  bool qk_partial = false;    // the Q/K share of dx sits in a bf16 partial, not in dxacc
+  bool acc_written = false;   // dxacc holds (part of) dx
   {
     prof_mark(c.st, "bwd.qk_wgrad");
     WgradArgs w{};
@@ -751,10 +753,22 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.K = dh;
     a.Nc = dm;
     a.mode = STORE_F32;
+    if (sets && c.bf16) {
+      // with the expert-set path dx is a sum of bf16 partials anyway: this one goes to slot H
+      RowGemmArgs p = a;
+      p.C = c.p<char>(c.L.yh) + (size_t)H * N * dm * 2;
+      p.mode = STORE_T;
+      if (mfma_row_gemm_supported(p)) {
+        a = p;
+        qk_partial = true;
+      }
+    }
     if (use_mfma(c) && mfma_row_gemm_supported(a)) {
       prof_mark(c.st, "bwd.qk_dgrad");
       launch_mfma_row_gemm(a, c.st);
+      acc_written = !qk_partial;
     } else {
+      acc_written = true;
       prof_mark(c.st, "bwd.dx_zero");
       launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
       for (int which = 0; which < 2; ++which) {
@@ -897,13 +911,27 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       w.chunk = 256;   // tiny output: many short chunks keep the GPU busy, atomics are few
       if (sides == 2 && dWs[0] && dWs[1]) {
         prof_mark(c.st, "bwd.router_wgrad");
-        w.heads = 2;
-        w.hsplit = 1;
-        w.Bm = dz0;
-        w.Bm2 = dz0 + (size_t)HEp * esz;
-        w.dW = dWs[0];
-        w.dW2 = dWs[1];
-        wgrad(c, w, false);
+        // one pass over x for both sides: the row of dz holds [side 0 | side 1], HEp columns each
+        WgradArgs w2 = w;
+        w2.heads = 1;
+        w2.Bm = dz0;
+        w2.Kb = 2 * HEp;
+        w2.col_split = HEp;
+        w2.dW = dWs[0];
+        w2.dW2 = dWs[1];
+        if (use_mfma(c) && mfma_wgrad_supported(w2)) {
+          launch_fill_f32(dWs[0], (size_t)dm * HE, 0.f, c.st);
+          launch_fill_f32(dWs[1], (size_t)dm * HE, 0.f, c.st);
+          launch_mfma_wgrad(w2, c.st);
+        } else {
+          w.heads = 2;
+          w.hsplit = 1;
+          w.Bm = dz0;
+          w.Bm2 = dz0 + (size_t)HEp * esz;
+          w.dW = dWs[0];
+          w.dW2 = dWs[1];
+          wgrad(c, w, false);
+        }
       } else {
         for (int sd = 0; sd < sides; ++sd) {
           if (!dWs[sd]) continue;
@@ -933,7 +961,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       a.B2 = Wp + (size_t)dm * HEp;
       a.sbk = 1;
       a.sbn = HEp;
-      a.C = c.p<char>(c.L.yh) + (size_t)H * N * dm * esz;
+      a.C = c.p<char>(c.L.yh) + (size_t)(H + (qk_partial ? 1 : 0)) * N * dm * esz;
       a.ldc = dm;
       a.K = HEp;
       a.Nc = dm;
@@ -945,6 +973,10 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       }
     }
     if (!router_partial) {
+      if (!acc_written) {
+        launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
+        acc_written = true;
+      }
       for (int sd = 0; sd < sides; ++sd) {
         RowGemmArgs a = identity_rows(c, 1);
         a.A = dz0 + (size_t)sd * HEp * esz;
@@ -963,7 +995,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   }
   prof_mark(c.st, "bwd.dx_cast");
   if (sets)
-    launch_sum_heads(c.p<void>(c.L.yh), dxacc, dx, (size_t)N * dm, (size_t)N * dm, router_partial ? H + 1 : H, c.st);
+    launch_sum_heads(c.p<void>(c.L.yh), acc_written ? dxacc : nullptr, dx, (size_t)N * dm, (size_t)N * dm,
+                     H + (qk_partial ? 1 : 0) + (router_partial ? 1 : 0), c.st);
   else if (c.bf16)
     launch_cast_from_f32(dxacc, dx, (size_t)N * dm, 1, c.st);
   prof_mark(c.st, nullptr);

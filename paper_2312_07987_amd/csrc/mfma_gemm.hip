@@ -750,8 +750,13 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       if (ii >= a.Ka) continue;
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        const int jj = j0 + wn + j * 32 + r;
-        if (jj < (a.kb_store ? a.kb_store : a.Kb)) atomicAdd(dW + (long)ii * a.swa + jj, acc[i][j][q]);
+        int jj = j0 + wn + j * 32 + r;
+        float* out = dW;
+        if (a.col_split > 0 && jj >= a.col_split) {   // the right-hand block of columns has its own output
+          jj -= a.col_split;
+          out = a.dW2;
+        }
+        if (jj < (a.kb_store ? a.kb_store : a.Kb)) atomicAdd(out + (long)ii * a.swa + jj, acc[i][j][q]);
       }
     }
 }
