@@ -634,8 +634,8 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     ids[t] = id;
     gsc[t] = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
   }
-  // rows of the last step past the chunk are staged as zeros; give them a zero gate too
-  for (int t = rows + tid; t < rows + BK && t < Cfg::MAX_CHUNK; t += 256) gsc[t] = 0.f;
+  // rows past the chunk that a computed step can touch are staged as zeros; give them a zero gate too
+  for (int t = rows + tid; t < rows + 2 * BK && t < Cfg::MAX_CHUNK; t += 256) gsc[t] = 0.f;
   __syncthreads();
 
   const int i0 = (tile / tj) * BM, j0 = (tile % tj) * BN;
@@ -647,17 +647,22 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
 
   constexpr int A_CPR = BM / VEC, B_CPR = BN / VEC;     // chunks per tile row
   constexpr int A_N = BK * A_CPR / 256, B_N = BK * B_CPR / 256;
-  chunk_t ra[A_N], rb[B_N];
-  int staged_r0 = 0;   // first row of the step that sits in ra / rb
-  auto load_global = [&](int r0) {
-    staged_r0 = r0;
+  // row id -> operand row: ids are divided by a small constant (the k slots of a token share a row);
+  // multiply-high by ceil(2^32 / d) is exact for ids below 2^32 / d
+  const unsigned inv_a = a.a_div > 1 ? 0xFFFFFFFFu / (unsigned)a.a_div + 1u : 0u;
+  const unsigned inv_b = a.b_div > 1 ? 0xFFFFFFFFu / (unsigned)a.b_div + 1u : 0u;
+  auto row_of = [](int id, unsigned inv) { return inv ? (int)__umulhi((unsigned)id, inv) : id; };
+  // two register sets: a step's rows are requested two steps before they are multiplied, so a
+  // load has two steps of the work-group (and of its neighbour on the CU) to arrive
+  chunk_t ra0[A_N], rb0[B_N], ra1[A_N], rb1[B_N];
+  auto load_global = [&](chunk_t (&ra)[A_N], chunk_t (&rb)[B_N], int r0) {
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
       const int c = tid + i * 256;
       const int rr = c / A_CPR, fc = (c % A_CPR) * VEC;
       ra[i] = zero_chunk<VEC>();
       if (r0 + rr < rows && i0 + fc < a.Ka) {
-        ra[i] = *(const chunk_t*)(A + (long)(ids[r0 + rr] / a.a_div) * a.lda + (long)hh * a.a_hoff + i0 + fc);
+        ra[i] = *(const chunk_t*)(A + (long)row_of(ids[r0 + rr], inv_a) * a.lda + (long)hh * a.a_hoff + i0 + fc);
       }
     }
 #pragma unroll
@@ -666,16 +671,16 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       const int rr = c / B_CPR, fc = (c % B_CPR) * VEC;
       rb[i] = zero_chunk<VEC>();
       if (r0 + rr < rows && j0 + fc < a.Kb) {
-        rb[i] = *(const chunk_t*)(Bm + (long)(ids[r0 + rr] / a.b_div) * a.ldb + (long)hh * a.b_hoff + j0 + fc);
+        rb[i] = *(const chunk_t*)(Bm + (long)row_of(ids[r0 + rr], inv_b) * a.ldb + (long)hh * a.b_hoff + j0 + fc);
       }
     }
   };
-  auto store_lds = [&](int stage) {
+  auto store_lds = [&](int stage, chunk_t (&ra)[A_N], chunk_t (&rb)[B_N], int staged_r0) {
     unsigned short* As = smem + stage * Cfg::STAGE_ELEMS;
     unsigned short* Bs = As + BK * LDA;
-#pragma unroll
     // the gate is applied here, not at the load, so that the load stays in flight while the
-    // previous step is multiplied (rows past the chunk hold zeros and a zero gate)
+    // previous steps are multiplied (rows past the chunk hold zeros and a zero gate)
+#pragma unroll
     for (int i = 0; i < A_N; ++i) {
       const int c = tid + i * 256;
       if (scaled && !a.scale_b) ra[i] = scale_chunk(ra[i], gsc[min(staged_r0 + c / A_CPR, Cfg::MAX_CHUNK - 1)]);
@@ -700,12 +705,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
   const int nk = (rows + BK - 1) / BK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int stage = kt & 1;
-    if (kt + 1 < nk) load_global((kt + 1) * BK);
+  auto compute = [&](int stage) {
     const unsigned short* As = smem + stage * Cfg::STAGE_ELEMS;
     const unsigned short* Bs = As + BK * LDA;
 #pragma unroll
@@ -720,7 +720,23 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
 #pragma unroll
         for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_lds(stage ^ 1);
+  };
+  // the loop body is two steps, straight-line: an odd step count is rounded up (rows past the
+  // chunk load as zeros)
+  const int nk2 = (nk + 1) & ~1;
+  load_global(ra0, rb0, 0);
+  load_global(ra1, rb1, BK);
+  store_lds(0, ra0, rb0, 0);
+  __syncthreads();
+  for (int kt = 0; kt < nk2; kt += 2) {
+    // even step: its rows sit in stage 0; set 0 is free for step kt + 2, set 1 holds step kt + 1
+    load_global(ra0, rb0, (kt + 2) * BK);
+    compute(0);
+    store_lds(1, ra1, rb1, (kt + 1) * BK);
+    __syncthreads();
+    load_global(ra1, rb1, (kt + 3) * BK);
+    compute(1);
+    store_lds(0, ra0, rb0, (kt + 2) * BK);
     __syncthreads();
   }
 
