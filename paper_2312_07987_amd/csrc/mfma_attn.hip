@@ -335,7 +335,7 @@ __device__ __forceinline__ void store_rows_T(unsigned short* dst, const f32x16* 
 //   dV^T[d][key] += dO^T[d][q] P[q][key],   dK^T[d][key] += Q^T[d][q] dS[q][key]
 // ----------------------------------------------------------------------------------------
 template <int DH, int VEC, int NW>
-__global__ __launch_bounds__(64 * NW) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
+__global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
   constexpr int QT = 32, KB = 32 * NW;   // keys per work-group
   constexpr bool SEP = DH <= 128;                       // separate tiles for the two read patterns
   constexpr int LDR = SEP ? DH + 8 : ld_tr(DH), LDT = ld_tr(DH);
@@ -402,7 +402,8 @@ __global__ __launch_bounds__(64 * NW) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
     }
     __syncthreads();
     if (q0 + QT < T) prefetch(q0 + QT);
-    if (a.causal && q0 + QT - 1 < wk_first) continue;   // every query of the tile precedes this wave's keys
+    // (a wave whose keys all follow the tile's queries multiplies zeros here: a branch around the
+    //  body costs more registers than the diagonal tiles cost time)
 
     f32x16 S, dP;
 #pragma unroll
