@@ -7,6 +7,10 @@
 
 `stats`:   per-kernel calls / average / share from `rocprofv3 --kernel-trace --stats`.
 `pmc`:     per-kernel average of counter NAME per dispatch from `rocprofv3 --pmc NAME`.
+`mfma`:    python -m paper_2312_07987_amd.prof_summary mfma <counter_collection.csv>: matrix-core
+           utilisation per kernel from one `rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE` run
+           = busy cycles (summed over the chip's 1024 SIMDs) / (active cycles, which rocprofv3 reports
+           summed over the 8 XCDs, x 128 SIMDs per XCD).
 `traffic`: HBM bytes per dispatch of every kernel as JSON, from a `--pmc FETCH_SIZE` and a
            `--pmc WRITE_SIZE` run of the benchmark (counters in KiB), each scaled by what the same
            counter reads for `bench.py --copy-only` (a 256 MiB device copy, 5 launches).
@@ -62,8 +66,20 @@ def traffic(fetch, write, copy_fetch, copy_write, copy_bytes=256 << 20):
     print(json.dumps(out, indent=1))
 
 
+def mfma(path, simds=128):
+    busy = _avg(path, "SQ_VALU_MFMA_BUSY_CYCLES")
+    act = _avg(path, "GRBM_GUI_ACTIVE")
+    print("%-110s %14s %12s %8s" % ("kernel", "mfma_busy/disp", "active_clk", "util_%"))
+    for k in sorted(busy, key=lambda k: -busy[k]):
+        if busy[k] <= 0 or act.get(k, 0) <= 0:
+            continue
+        print("%-110s %14.0f %12.0f %8.1f" % (k[:110], busy[k], act[k], 100.0 * busy[k] / (act[k] * simds)))
+
+
 if __name__ == "__main__":
-    if sys.argv[1] == "stats":
+    if sys.argv[1] == "mfma":
+        mfma(sys.argv[2])
+    elif sys.argv[1] == "stats":
         stats(sys.argv[2])
     elif sys.argv[1] == "traffic":
         traffic(*sys.argv[2:6])
