@@ -178,6 +178,7 @@ struct AttnBwdArgs {
 // ----------------------------------------------------------------------------------------
 // launchers (defined in routing.hip, simt.hip, mfma_*.hip); all enqueue on `s`
 // ----------------------------------------------------------------------------------------
+struct SetSortArgs;
 struct RouterArgs {
   const void* x;          // [N, dm]
   const void* W[2];       // per side [dm, HE]; W[1] == NULL -> one side only
@@ -190,6 +191,9 @@ struct RouterArgs {
   int* blockcnt;          // [sides*H, nblk, E] scratch
   int N, dm, H, E, k, sides;
   int bf16;
+  // if not NULL (and for as many sides), launch_router_hybrid also sorts the tokens by expert set,
+  // sharing the passes of the expert sort; the caller then skips launch_set_sort
+  const SetSortArgs* sets;
 };
 void launch_router(const RouterArgs& a, hipStream_t s);
 // bf16 storage: fp32 matrix-core logits with an fp64 re-evaluation of every decision that

@@ -393,7 +393,28 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
   const int N = c.N, H = c.H, E = c.E, k = c.k, dh = c.dh, dm = c.dm;
   const long hd = (long)H * dh;
 
-  // step 1: routers, top-k, expert-sorted permutation
+  // step 1: routers, top-k, expert-sorted permutation (and, where the expert-set path applies, the
+  // set-sorted one)
+  const bool sets = sets_usable(c);
+  bool sets_sorted = false;
+  SetSortArgs sa{};
+  if (sets) {
+    sa.idx = c.idx(0);
+    sa.gate = c.gate(0);
+    sa.setid = c.p<int>(c.L.setid);
+    sa.gset = c.p<float>(c.L.gset);
+    sa.gsort = c.p<float>(c.L.gsort);
+    sa.setexp = c.p<int>(c.L.setexp);
+    sa.setperm = c.p<int>(c.L.setperm);
+    sa.setoff = c.p<int>(c.L.setoff);
+    sa.blockcnt = c.p<int>(c.L.setcnt);
+    sa.N = N;
+    sa.H = H;
+    sa.k = k;
+    sa.E = E;
+    sa.nsets = count_sets(E, k);
+    sa.sides = 2;
+  }
   prof_mark(c.st, "fwd.router");
   if (c.dense) {
     launch_dense_routing(c.idx(0), c.gate(0), c.perm(0), c.offsets(0), N, H, c.st);
@@ -417,10 +438,15 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     ra.k = k;
     ra.sides = c.shared ? 1 : 2;
     ra.bf16 = c.bf16;
-    if (g_family.load() == 0 && router_hybrid_supported(ra))
+    if (g_family.load() == 0 && router_hybrid_supported(ra)) {
+      if (sets && !c.shared) {   // both sorts in the same three launches
+        ra.sets = &sa;
+        sets_sorted = true;
+      }
       launch_router_hybrid(ra, c.p<char>(c.L.rh), c.st);
-    else
+    } else {
       launch_router(ra, c.st);
+    }
   }
   if (c.dense || c.shared) {
     // one selection serves both sides: the destination tables repeat the source tables
@@ -431,10 +457,8 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     (void)hipMemcpyAsync(c.offsets(1), c.offsets(0), (size_t)H * (E + 1) * 4, hipMemcpyDeviceToDevice, c.st);
   }
 
-  const bool sets = sets_usable(c);
-  if (sets) {
+  if (sets && !sets_sorted) {
     prof_mark(c.st, "fwd.set_sort");
-    SetSortArgs sa{};
     sa.idx = c.idx(0);
     sa.gate = c.gate(0);
     sa.setid = c.p<int>(c.L.setid);

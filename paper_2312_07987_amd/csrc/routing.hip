@@ -119,8 +119,7 @@ __global__ __launch_bounds__(RB) void topk_hist_kernel(const double* __restrict_
 
 // One block per (side, head).  blockcnt[sh][blk][e] (counts) -> in place: first position of
 // bin e for token block blk; offsets[sh][0..E].  One wave per bin, lanes over token blocks.
-__global__ __launch_bounds__(256) void scan_kernel(int* __restrict__ blockcnt, int* __restrict__ offsets, int E,
-                                                   int nblk) {
+__device__ __forceinline__ void scan_body(int* __restrict__ blockcnt, int* __restrict__ offsets, int E, int nblk) {
   __shared__ int tot[129];
   const int sh_ = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -160,9 +159,22 @@ __global__ __launch_bounds__(256) void scan_kernel(int* __restrict__ blockcnt, i
     }
   }
 }
+__global__ __launch_bounds__(256) void scan_kernel(int* __restrict__ blockcnt, int* __restrict__ offsets, int E,
+                                                   int nblk) {
+  scan_body(blockcnt, offsets, E, nblk);
+}
+// the expert table (blockIdx.y == 0) and the set table (blockIdx.y == 1) in one launch
+__global__ __launch_bounds__(256) void scan2_kernel(int* __restrict__ blockcnt, int* __restrict__ offsets, int E,
+                                                    int* __restrict__ setcnt, int* __restrict__ setoff, int nsets,
+                                                    int nblk) {
+  if (blockIdx.y == 0)
+    scan_body(blockcnt, offsets, E, nblk);
+  else
+    scan_body(setcnt, setoff, nsets, nblk);
+}
 
-__global__ __launch_bounds__(RB) void scatter_kernel(const int* __restrict__ idx, const int* __restrict__ base,
-                                                     int* __restrict__ perm, int N, int E, int k, int nblk) {
+__device__ __forceinline__ void scatter_body(const int* __restrict__ idx, const int* __restrict__ base,
+                                             int* __restrict__ perm, int N, int E, int k, int nblk) {
   __shared__ int wcnt[RB / 64][64];
   const int sh_ = blockIdx.y;
   const int n = blockIdx.x * RB + threadIdx.x;
@@ -190,17 +202,22 @@ __global__ __launch_bounds__(RB) void scatter_kernel(const int* __restrict__ idx
     if (lane == 0) wcnt[wave][e] = __popcll(bal);
   }
   __syncthreads();
-  if (!valid) return;
-  const int* bs = base + ((long)sh_ * nblk + blockIdx.x) * E;
+  if (valid) {
+    const int* bs = base + ((long)sh_ * nblk + blockIdx.x) * E;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    if (j < k) {
-      int e = ej[j];
-      int pos = bs[e] + rk[j];
-      for (int w = 0; w < wave; ++w) pos += wcnt[w][e];
-      perm[(long)sh_ * N * k + pos] = n * k + j;
+    for (int j = 0; j < 8; ++j) {
+      if (j < k) {
+        int e = ej[j];
+        int pos = bs[e] + rk[j];
+        for (int w = 0; w < wave; ++w) pos += wcnt[w][e];
+        perm[(long)sh_ * N * k + pos] = n * k + j;
+      }
     }
   }
+}
+__global__ __launch_bounds__(RB) void scatter_kernel(const int* __restrict__ idx, const int* __restrict__ base,
+                                                     int* __restrict__ perm, int N, int E, int k, int nblk) {
+  scatter_body(idx, base, perm, N, E, k, nblk);
 }
 
 __global__ void dense_routing_kernel(int* idx, float* gate, int* perm, int* offsets, int N, int H) {
@@ -238,20 +255,29 @@ __global__ void dense_routing_kernel(int* idx, float* gate, int* perm, int* offs
 // Wt[side][h*E + e][dmp] (zero padded to dmp, a multiple of 1024) for the fp64 recheck.
 __global__ __launch_bounds__(256) void router_prep_kernel(const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
                                                           float* __restrict__ wmax, int* __restrict__ fixcount,
-                                                          unsigned short* __restrict__ Wt, int dm, int dmp, int H, int E) {
+                                                          unsigned short* __restrict__ Wt, unsigned short* __restrict__ Wp,
+                                                          int dm, int dmp, int H, int E, int HEp) {
   __shared__ float red[4];
   const int sh_ = blockIdx.x;
   const int side = sh_ / H, h = sh_ % H;
   const unsigned short* W = (const unsigned short*)(side ? W1 : W0);
   const int HE = H * E;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // this head's columns of the padded copy Wp[side][i][HEp] for the logits GEMM (the last head also
+  // zeroes the padding columns)
+  unsigned short* wp = Wp + (long)side * dm * HEp;
+  if (h == H - 1)
+    for (int t = threadIdx.x; t < dm * (HEp - HE); t += 256) wp[(long)(t / (HEp - HE)) * HEp + HE + t % (HEp - HE)] = 0;
   float mx = 0.f;
   for (int e = 0; e < E; ++e) {
     float s = 0.f;
     unsigned short* wt = Wt + ((long)side * HE + h * E + e) * dmp;
     for (int i = threadIdx.x; i < dmp; i += 256) {
       unsigned short v = 0;
-      if (i < dm) v = W[(long)i * HE + h * E + e];
+      if (i < dm) {
+        v = W[(long)i * HE + h * E + e];
+        wp[(long)i * HEp + h * E + e] = v;
+      }
       wt[i] = v;
       const float f = __uint_as_float((unsigned)v << 16);
       s = fmaf(f, f, s);
@@ -398,8 +424,8 @@ __global__ __launch_bounds__(64 * FIX_WAVES) void fix64_kernel(const bf16_t* __r
   }
 }
 
-__global__ __launch_bounds__(RB) void hist_kernel(const int* __restrict__ idx, int* __restrict__ blockcnt, int N, int E,
-                                                  int k, int nblk) {
+__device__ __forceinline__ void hist_body(const int* __restrict__ idx, int* __restrict__ blockcnt, int N, int E, int k,
+                                          int nblk) {
   __shared__ int cnt[64];
   const int sh_ = blockIdx.y;
   const int n = blockIdx.x * RB + threadIdx.x;
@@ -415,6 +441,10 @@ __global__ __launch_bounds__(RB) void hist_kernel(const int* __restrict__ idx, i
   }
   __syncthreads();
   if (threadIdx.x < E) blockcnt[((long)sh_ * nblk + blockIdx.x) * E + threadIdx.x] = cnt[threadIdx.x];
+}
+__global__ __launch_bounds__(RB) void hist_kernel(const int* __restrict__ idx, int* __restrict__ blockcnt, int N, int E,
+                                                  int k, int nblk) {
+  hist_body(idx, blockcnt, N, E, k, nblk);
 }
 
 // Wp[side][i][c] = W_side[i][c] for c < HE, 0 for HE <= c < HEp (rows padded to 16 bytes)
@@ -461,62 +491,6 @@ bool router_hybrid_supported(const RouterArgs& a) {
   return a.bf16 && a.dm % 4 == 0 && ((uintptr_t)a.x % 16) == 0 && a.H * a.E <= 32;
 }
 
-void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
-  size_t off[7];
-  router_hybrid_bytes(a.N, a.dm, a.H, a.E, off);
-  const int HE = a.H * a.E, HEp = (HE + 7) / 8 * 8;
-  bf16_t* Wp = (bf16_t*)(scratch + off[0]);
-  double* Zs = (double*)(scratch + off[1]);
-  float* xnorm = (float*)(scratch + off[2]);
-  float* wmax = (float*)(scratch + off[3]);
-  int* fixlist = (int*)(scratch + off[4]);
-  int* fixcount = (int*)(scratch + off[5]);
-  unsigned short* Wt = (unsigned short*)(scratch + off[6]);
-  const int dmp = (a.dm + 1023) / 1024 * 1024;
-
-  const long tot = (long)a.sides * a.dm * HEp;
-  pack_router_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], Wp, a.dm, HE,
-                                                                   HEp, a.sides);
-  // stage 1: z32 = x W on the matrix cores, fp32 accumulation, both sides in one launch
-  RowGemmArgs g{};
-  g.heads = a.sides;
-  g.E = 1;
-  g.M = a.N;
-  g.a_div = 1;
-  g.c_div = 1;
-  g.A = a.x;
-  g.lda = a.dm;
-  g.B = Wp;
-  g.b_hstride = (long)a.dm * HEp;
-  g.sbk = HEp;
-  g.sbn = 1;
-  g.C = Zs;
-  g.ldc = HEp;
-  g.c_hoff = (long)a.N * HEp;
-  g.K = a.dm;
-  g.Nc = HEp;
-  g.mode = STORE_F64;
-  g.tag = TAG_ROUTER;
-  g.rownorm = xnorm;   // |x_n| for the error bound, from the tiles the GEMM loads anyway
-  launch_mfma_row_gemm(g, s);
-
-  router_prep_kernel<<<a.sides * a.H, 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], wmax, fixcount, Wt, a.dm, dmp,
-                                                   a.H, a.E);
-  dim3 g1((a.N + SEL_TOK - 1) / SEL_TOK, a.sides);
-  select_kernel<<<g1, 256, (size_t)SEL_TOK * HEp * 8, s>>>(Zs, a.b[0], a.b[1], xnorm, wmax, a.idx, a.gate, fixlist, fixcount,
-                                                            a.N, rg_kstep(), a.H, a.E, a.k, HEp);
-  int fix_blocks = (a.N + FIX_WAVES - 1) / FIX_WAVES;
-  if (fix_blocks > 64) fix_blocks = 64;
-  dim3 g3(fix_blocks, a.sides * a.H);
-  fix64_kernel<<<g3, 64 * FIX_WAVES, 0, s>>>((const bf16_t*)a.x, Wt, a.b[0], a.b[1], fixlist, fixcount, a.Z, a.idx, a.gate,
-                                               a.N, a.dm, dmp, a.H, a.E, a.k);
-  const int nblk = router_blocks(a.N);
-  dim3 g2(nblk, a.sides * a.H);
-  hist_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.N, a.E, a.k, nblk);
-  scan_kernel<<<a.sides * a.H, 256, 0, s>>>(a.blockcnt, a.offsets, a.E, nblk);
-  scatter_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.perm, a.N, a.E, a.k, nblk);
-}
-
 void launch_router(const RouterArgs& a, hipStream_t s) {
   const int HE = a.H * a.E;
   dim3 g((a.N + RT_TOK - 1) / RT_TOK, a.sides, (HE + RT_COL - 1) / RT_COL);
@@ -546,10 +520,10 @@ __device__ __forceinline__ int binom(int n, int r) {
   return (int)v;
 }
 
-__global__ __launch_bounds__(RB) void set_hist_kernel(const int* __restrict__ idx, const float* __restrict__ gate,
-                                                      int* __restrict__ setid, float* __restrict__ gset,
-                                                      int* __restrict__ setexp, int* __restrict__ blockcnt, int N, int k,
-                                                      int E, int nsets, int nblk) {
+__device__ __forceinline__ void set_hist_body(const int* __restrict__ idx, const float* __restrict__ gate,
+                                              int* __restrict__ setid, float* __restrict__ gset,
+                                              int* __restrict__ setexp, int* __restrict__ blockcnt, int N, int k, int E,
+                                              int nsets, int nblk) {
   __shared__ int cnt[128];
   const int sh_ = blockIdx.y;
   const int n = blockIdx.x * RB + threadIdx.x;
@@ -606,10 +580,24 @@ __global__ __launch_bounds__(RB) void set_hist_kernel(const int* __restrict__ id
   __syncthreads();
   if (threadIdx.x < nsets) blockcnt[((long)sh_ * nblk + blockIdx.x) * nsets + threadIdx.x] = cnt[threadIdx.x];
 }
+__global__ __launch_bounds__(RB) void set_hist_kernel(const int* __restrict__ idx, const float* __restrict__ gate,
+                                                      int* __restrict__ setid, float* __restrict__ gset,
+                                                      int* __restrict__ setexp, int* __restrict__ blockcnt, int N, int k,
+                                                      int E, int nsets, int nblk) {
+  set_hist_body(idx, gate, setid, gset, setexp, blockcnt, N, k, E, nsets, nblk);
+}
+// both histograms of a forward pass in one launch
+__global__ __launch_bounds__(RB) void hist2_kernel(const int* __restrict__ idx, const float* __restrict__ gate,
+                                                   int* __restrict__ blockcnt, int* __restrict__ setid,
+                                                   float* __restrict__ gset, int* __restrict__ setexp,
+                                                   int* __restrict__ setcnt, int N, int k, int E, int nsets, int nblk) {
+  hist_body(idx, blockcnt, N, E, k, nblk);
+  set_hist_body(idx, gate, setid, gset, setexp, setcnt, N, k, E, nsets, nblk);
+}
 
-__global__ __launch_bounds__(RB) void set_scatter_kernel(const int* __restrict__ setid, const int* __restrict__ base,
-                                                         int* __restrict__ setperm, const float* __restrict__ gset,
-                                                         float* __restrict__ gsort, int N, int k, int nsets, int nblk) {
+__device__ __forceinline__ void set_scatter_body(const int* __restrict__ setid, const int* __restrict__ base,
+                                                 int* __restrict__ setperm, const float* __restrict__ gset,
+                                                 float* __restrict__ gsort, int N, int k, int nsets, int nblk) {
   __shared__ int wcnt[RB / 64][128];
   const int sh_ = blockIdx.y;
   const int n = blockIdx.x * RB + threadIdx.x;
@@ -629,6 +617,21 @@ __global__ __launch_bounds__(RB) void set_scatter_kernel(const int* __restrict__
   setperm[(long)sh_ * N + pos] = n;
   for (int j = 0; j < k; ++j) gsort[((long)sh_ * N + pos) * k + j] = gset[((long)sh_ * N + n) * k + j];
 }
+__global__ __launch_bounds__(RB) void set_scatter_kernel(const int* __restrict__ setid, const int* __restrict__ base,
+                                                         int* __restrict__ setperm, const float* __restrict__ gset,
+                                                         float* __restrict__ gsort, int N, int k, int nsets, int nblk) {
+  set_scatter_body(setid, base, setperm, gset, gsort, N, k, nsets, nblk);
+}
+// both scatters of a forward pass in one launch (the set scatter last: it may leave early)
+__global__ __launch_bounds__(RB) void scatter2_kernel(const int* __restrict__ idx, const int* __restrict__ base,
+                                                      int* __restrict__ perm, const int* __restrict__ setid,
+                                                      const int* __restrict__ setbase, int* __restrict__ setperm,
+                                                      const float* __restrict__ gset, float* __restrict__ gsort, int N, int E,
+                                                      int k, int nsets, int nblk) {
+  scatter_body(idx, base, perm, N, E, k, nblk);
+  __syncthreads();
+  set_scatter_body(setid, setbase, setperm, gset, gsort, N, k, nsets, nblk);
+}
 
 void launch_set_sort(const SetSortArgs& a, hipStream_t s) {
   const int nblk = router_blocks(a.N);
@@ -641,6 +644,71 @@ void launch_set_sort(const SetSortArgs& a, hipStream_t s) {
 void launch_dense_routing(int* idx, float* gate, int* perm, int* offsets, int N, int H, hipStream_t s) {
   long tot = (long)H * N;
   dense_routing_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>(idx, gate, perm, offsets, N, H);
+}
+
+void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
+  size_t off[7];
+  router_hybrid_bytes(a.N, a.dm, a.H, a.E, off);
+  const int HE = a.H * a.E, HEp = (HE + 7) / 8 * 8;
+  bf16_t* Wp = (bf16_t*)(scratch + off[0]);
+  double* Zs = (double*)(scratch + off[1]);
+  float* xnorm = (float*)(scratch + off[2]);
+  float* wmax = (float*)(scratch + off[3]);
+  int* fixlist = (int*)(scratch + off[4]);
+  int* fixcount = (int*)(scratch + off[5]);
+  unsigned short* Wt = (unsigned short*)(scratch + off[6]);
+  const int dmp = (a.dm + 1023) / 1024 * 1024;
+
+  // per (side, head): largest column norm, queue counter cleared, columns copied out as vectors and
+  // into the padded matrix the GEMM reads
+  router_prep_kernel<<<a.sides * a.H, 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], wmax, fixcount, Wt,
+                                                   (unsigned short*)Wp, a.dm, dmp, a.H, a.E, HEp);
+  // stage 1: z32 = x W on the matrix cores, fp32 accumulation, both sides in one launch
+  RowGemmArgs g{};
+  g.heads = a.sides;
+  g.E = 1;
+  g.M = a.N;
+  g.a_div = 1;
+  g.c_div = 1;
+  g.A = a.x;
+  g.lda = a.dm;
+  g.B = Wp;
+  g.b_hstride = (long)a.dm * HEp;
+  g.sbk = HEp;
+  g.sbn = 1;
+  g.C = Zs;
+  g.ldc = HEp;
+  g.c_hoff = (long)a.N * HEp;
+  g.K = a.dm;
+  g.Nc = HEp;
+  g.mode = STORE_F64;
+  g.tag = TAG_ROUTER;
+  g.rownorm = xnorm;   // |x_n| for the error bound, from the tiles the GEMM loads anyway
+  launch_mfma_row_gemm(g, s);
+
+  dim3 g1((a.N + SEL_TOK - 1) / SEL_TOK, a.sides);
+  select_kernel<<<g1, 256, (size_t)SEL_TOK * HEp * 8, s>>>(Zs, a.b[0], a.b[1], xnorm, wmax, a.idx, a.gate, fixlist, fixcount,
+                                                            a.N, rg_kstep(), a.H, a.E, a.k, HEp);
+  int fix_blocks = (a.N + FIX_WAVES - 1) / FIX_WAVES;
+  if (fix_blocks > 64) fix_blocks = 64;
+  dim3 g3(fix_blocks, a.sides * a.H);
+  fix64_kernel<<<g3, 64 * FIX_WAVES, 0, s>>>((const bf16_t*)a.x, Wt, a.b[0], a.b[1], fixlist, fixcount, a.Z, a.idx, a.gate,
+                                               a.N, a.dm, dmp, a.H, a.E, a.k);
+  const int nblk = router_blocks(a.N);
+  dim3 g2(nblk, a.sides * a.H);
+  if (a.sets && a.sets->sides == a.sides) {
+    // the expert sort and the expert-set sort share their passes over the top-k tables
+    const SetSortArgs& t = *a.sets;
+    hist2_kernel<<<g2, RB, 0, s>>>(a.idx, a.gate, a.blockcnt, t.setid, t.gset, t.setexp, t.blockcnt, a.N, a.k, a.E, t.nsets,
+                                   nblk);
+    scan2_kernel<<<dim3(a.sides * a.H, 2), 256, 0, s>>>(a.blockcnt, a.offsets, a.E, t.blockcnt, t.setoff, t.nsets, nblk);
+    scatter2_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.perm, t.setid, t.blockcnt, t.setperm, t.gset, t.gsort, a.N, a.E,
+                                      a.k, t.nsets, nblk);
+    return;
+  }
+  hist_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.N, a.E, a.k, nblk);
+  scan_kernel<<<a.sides * a.H, 256, 0, s>>>(a.blockcnt, a.offsets, a.E, nblk);
+  scatter_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.perm, a.N, a.E, a.k, nblk);
 }
 
 }  // namespace sh
