@@ -220,6 +220,7 @@ struct SetSortArgs {
 void launch_set_sort(const SetSortArgs& a, hipStream_t s);
 
 void launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
+void launch_zero4_f32(float* p0, size_t n0, float* p1, size_t n1, float* p2, size_t n2, float* p3, size_t n3, hipStream_t s);
 void launch_cast_from_f32(const float* src, void* dst, size_t n, int bf16, hipStream_t s);
 void launch_cast_to_f32(const void* src, float* dst, size_t n, int bf16, hipStream_t s);
 // out[i] = sum_h part[h*hstride + i] (+ add32[i]) for bf16 part/out; n must be a multiple of 8

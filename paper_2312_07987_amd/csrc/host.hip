@@ -896,9 +896,10 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     const int HE = H * E;
     float* dWs[2] = {dW_S, c.shared ? nullptr : dW_D};
     float* dbs[2] = {db_S, c.shared ? nullptr : db_D};
-    for (int sd = 0; sd < sides; ++sd) {
-      if (dbs[sd]) launch_fill_f32(dbs[sd], (size_t)HE, 0.f, c.st);
-    }
+    // the small outputs that are accumulated with atomics are cleared by one launch
+    const bool both_w = sides == 2 && dWs[0] && dWs[1];
+    launch_zero4_f32(dbs[0], dbs[0] ? (size_t)HE : 0, dbs[1], dbs[1] ? (size_t)HE : 0, both_w ? dWs[0] : nullptr,
+                     both_w ? (size_t)dm * HE : 0, both_w ? dWs[1] : nullptr, both_w ? (size_t)dm * HE : 0, c.st);
     RouterBwdArgs rb{};
     rb.idx = c.idx(0);
     rb.gate = c.gate(0);
@@ -944,9 +945,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
         w2.dW = dWs[0];
         w2.dW2 = dWs[1];
         if (use_mfma(c) && mfma_wgrad_supported(w2)) {
-          launch_fill_f32(dWs[0], (size_t)dm * HE, 0.f, c.st);
-          launch_fill_f32(dWs[1], (size_t)dm * HE, 0.f, c.st);
-          launch_mfma_wgrad(w2, c.st);
+          launch_mfma_wgrad(w2, c.st);   // outputs cleared above
         } else {
           w.heads = 2;
           w.hsplit = 1;

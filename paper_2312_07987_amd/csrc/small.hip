@@ -30,6 +30,24 @@ static unsigned grid_for(size_t n, int block) {
   return (unsigned)(g < 1 ? 1 : (g > 65536 ? 65536 : g));
 }
 
+__global__ void zero4_f32_kernel(float* p0, size_t n0, float* p1, size_t n1, float* p2, size_t n2, float* p3, size_t n3) {
+  float* p = blockIdx.y == 0 ? p0 : blockIdx.y == 1 ? p1 : blockIdx.y == 2 ? p2 : p3;
+  const size_t n = blockIdx.y == 0 ? n0 : blockIdx.y == 1 ? n1 : blockIdx.y == 2 ? n2 : n3;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = 0.f;
+}
+
+// clears up to four arrays (NULL / 0 entries are skipped) with one launch
+void launch_zero4_f32(float* p0, size_t n0, float* p1, size_t n1, float* p2, size_t n2, float* p3, size_t n3, hipStream_t s) {
+  size_t mx = n0 > n1 ? n0 : n1;
+  mx = mx > n2 ? mx : n2;
+  mx = mx > n3 ? mx : n3;
+  if (!mx) return;
+  dim3 g(grid_for(mx, 256), 4);
+  zero4_f32_kernel<<<g, 256, 0, s>>>(p0, n0, p1, n1, p2, n2, p3, n3);
+}
+
 void launch_fill_f32(float* p, size_t n, float v, hipStream_t s) {
   if (n) fill_f32_kernel<<<grid_for(n, 256), 256, 0, s>>>(p, n, v);
 }
