@@ -77,6 +77,7 @@ struct RowGemmArgs {
   // Second operand set: heads h >= hsplit (hsplit > 0) use B2 / C2 with head index h - hsplit
   // (queries and keys projected by one launch).
   const void* B2;
+  const void* B3;
   void* C2;
   int hsplit;
   // Segmented reduction, seg_mode:
@@ -85,7 +86,7 @@ struct RowGemmArgs {
   //     K: segment p reads the A row of sorted position r scaled by
   //     segate[h*gate_hstride + r*nseg + p] against B of expert set_experts[set*8 + p].
   //  2  concatenation: segment p reads A columns (p/seg_split)*a_wstride + (p%seg_split)*a_sstride
-  //     against (p/seg_split ? B2 : B) + (p%seg_split)*b_sstride.
+  //     against (B, B2 or B3 for p/seg_split = 0, 1, 2) + (p%seg_split)*b_sstride.
   int seg_mode, nseg, experts;
   const int* set_experts;
   // TAG_ROUTER only: if not NULL, rownorm[row id] = an upper bound of the Euclidean norm of the A row
@@ -252,6 +253,7 @@ struct RouterBwdArgs {
   float* db[2];         // per side [HE] or NULL, atomic add (zeroed by caller)
   int N, H, E, k, sides, shared;
   int ld, side_stride;
+  int pad_to;   // columns sides*side_stride .. pad_to-1 of every row are zeroed too (0: none)
 };
 void launch_router_bwd(const RouterBwdArgs& a, int bf16, hipStream_t s);
 
@@ -260,6 +262,9 @@ void launch_router_bwd(const RouterBwdArgs& a, int bf16, hipStream_t s);
 void prof_mark(hipStream_t st, const char* label);
 // both routers' weights as bf16 [side][d_model][HEp], columns HE..HEp-1 zero (W1 unused when sides == 1)
 void launch_pack_router(const void* W0, const void* W1, void* Wp, int dm, int HE, int HEp, int sides, hipStream_t s);
+// the same weights side by side, bf16 [d_model][width]: columns side*HEp + c, zeros elsewhere
+void launch_pack_router_wide(const void* W0, const void* W1, void* out, int dm, int HE, int HEp, int sides, int width,
+                             hipStream_t s);
 
 void launch_simt_row_gemm(const RowGemmArgs& a, int bf16, hipStream_t s);
 void launch_simt_wgrad(const WgradArgs& a, int bf16, hipStream_t s);

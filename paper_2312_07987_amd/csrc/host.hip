@@ -66,7 +66,8 @@ struct Layout {
   size_t total = 0;
   size_t idx, gate, perm, offsets, Q, K, V, ctx, lse, pV;          // saved by forward
   size_t Z, blockcnt, acc32;                                       // forward scratch
-  size_t setid, gset, gsort, setexp, setperm, setoff, setcnt, yh;                 // expert-set path (bf16 only)
+  size_t setid, gset, gsort, setexp, setperm, setoff, setcnt, yh;
+  size_t dR, wr3;                                                  // wide router dz rows [N, H*dh], routers packed [dm, dh]                 // expert-set path (bf16 only)
   size_t rh;                                                       // two-stage router scratch (bf16 only)
   size_t wpart;                                                    // per-chunk weight-gradient partial sums (bf16 only)
   size_t u, dctx, dQ, dK, dV, delta, dgate, dz;                    // backward scratch
@@ -139,7 +140,9 @@ Layout make_layout(const sh_shape* s) {
   L.dctx = take(N * H * dh * esz);
   L.dQ = take(N * H * dh * esz);
   L.dK = take(N * H * dh * esz);
+  L.dR = take(N * H * dh * esz);   // directly behind dK, same size: a third operand set for the Q/K dgrad GEMM
   L.dV = take(N * H * dh * esz);
+  L.wr3 = take(dm * dh * esz);
   L.delta = take(N * H * 4);
   L.dgate = take(2 * H * N * k * 4);
   L.dz = take(N * 2 * ((H * E + 7) / 8 * 8) * esz);   // each side padded to a multiple of 8 columns
@@ -757,13 +760,21 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.chunk = chunk_dense;
     wgrad(c, w);
   }
-  {
+  // dx += dQ W_Q^T + dK W_K^T (one GEMM over the 2H concatenated segments).  Where the routers' dz fits
+  // into rows of the same shape it rides along as one more segment (dz_S W_S^T + dz_D W_D^T), and the
+  // launch moves behind the router backward kernel.
+  const int HE_r = H * E, HEp_r = (HE_r + 7) / 8 * 8, sides_r = c.shared ? 1 : 2;
+  const bool wide_dz = !c.dense && sides_r * HEp_r <= dh && (c.L.dR - c.L.dK) == (c.L.dK - c.L.dQ);
+  const bool fuse_router = wide_dz && sets && c.bf16 && use_mfma(c);
+  bool router_fused = false;
+  auto run_qk_dgrad = [&](bool with_router) {
     RowGemmArgs a = identity_rows(c, 1);
     a.tag = TAG_QK_DGRAD;
     a.A = c.p<void>(c.L.dQ);
     a.lda = hd;
     a.seg_mode = 2;
-    a.nseg = 2 * H;
+    a.nseg = 2 * H + (with_router ? 1 : 0);
+    a.B3 = c.p<void>(c.L.wr3);
     a.seg_split = H;
     a.a_sstride = dh;
     a.a_wstride = (long)((c.L.dK - c.L.dQ) / (c.bf16 ? 2 : 4));
@@ -791,6 +802,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       prof_mark(c.st, "bwd.qk_dgrad");
       launch_mfma_row_gemm(a, c.st);
       acc_written = !qk_partial;
+      router_fused = with_router;
     } else {
       acc_written = true;
       prof_mark(c.st, "bwd.dx_zero");
@@ -814,7 +826,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
         row_gemm(c, b);
       }
     }
-  }
+  };
+  if (!fuse_router) run_qk_dgrad(false);
 
   // value experts: d(gate_S), dW_V, dx
   {
@@ -904,7 +917,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     rb.idx = c.idx(0);
     rb.gate = c.gate(0);
     rb.dgate = c.p<float>(c.L.dgate);
-    rb.dz = c.p<void>(c.L.dz);
+    rb.dz = c.p<void>(wide_dz ? c.L.dR : c.L.dz);
     rb.db[0] = dbs[0];
     rb.db[1] = dbs[1];
     rb.N = N;
@@ -914,11 +927,16 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     rb.sides = sides;
     rb.shared = c.shared;
     const int HEp = (HE + 7) / 8 * 8;
-    rb.ld = sides * HEp;
+    rb.ld = wide_dz ? (int)hd : sides * HEp;   // wide rows: the shape of a dQ / dK row
     rb.side_stride = HEp;
+    rb.pad_to = wide_dz ? dh : 0;
     launch_router_bwd(rb, c.bf16, c.st);
     const size_t esz = c.bf16 ? 2 : 4;
-    const char* dz0 = c.p<char>(c.L.dz);
+    const char* dz0 = c.p<char>(wide_dz ? c.L.dR : c.L.dz);
+    if (fuse_router) {
+      launch_pack_router_wide(W_S, c.shared ? nullptr : W_D, c.p<void>(c.L.wr3), dm, HE, HEp, sides, dh, c.st);
+      run_qk_dgrad(true);
+    }
     // dW_S / dW_D = x^T dz: one launch for both sides when both are wanted
     {
       WgradArgs w{};
@@ -966,9 +984,9 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
         }
       }
     }
-    // dx += dz_S W_S^T + dz_D W_D^T
-    prof_mark(c.st, "bwd.router_dgrad");
-    if (sets && c.bf16 && use_mfma(c)) {
+    // dx += dz_S W_S^T + dz_D W_D^T, unless it went along with the Q/K input gradient above
+    if (!router_fused) prof_mark(c.st, "bwd.router_dgrad");
+    if (!router_fused && sets && c.bf16 && use_mfma(c)) {
       // both routers packed as [side][d_model][HEp]: one GEMM over the concatenated columns,
       // stored as one more partial of dx
       bf16_t* Wp = (bf16_t*)(c.p<char>(c.L.rh));
@@ -995,7 +1013,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
         router_partial = true;
       }
     }
-    if (!router_partial) {
+    if (!router_partial && !router_fused) {
       if (!acc_written) {
         launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
         acc_written = true;

@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
     if constexpr (SEG == 2) {
       const int which = seg / a.seg_split, sh_ = seg % a.seg_split;
       Ap = A + (long)which * a.a_wstride + (long)sh_ * a.a_sstride;
-      Bp = (const unsigned short*)(which ? a.B2 : a.B) + (long)sh_ * a.b_sstride;
+      Bp = (const unsigned short*)(which == 0 ? a.B : which == 1 ? a.B2 : a.B3) + (long)sh_ * a.b_sstride;
     }
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
@@ -464,6 +464,7 @@ static int row_gemm_vec(const RowGemmArgs& a) {
     bool ok = aligned_to(a.A, bytes) && aligned_to(a.B, bytes) && a.lda % vec == 0 && a.a_hoff % vec == 0 &&
               a.K % vec == 0 && a.b_hstride % vec == 0 && a.b_estride % vec == 0;
     if (a.hsplit > 0 || a.seg_mode == 2) ok = ok && aligned_to(a.B2, bytes);
+    if (a.seg_mode == 2 && a.nseg > 2 * a.seg_split) ok = ok && a.B3 && aligned_to(a.B3, bytes) && a.nseg <= 3 * a.seg_split;
     if (a.seg_mode == 2) ok = ok && a.a_sstride % vec == 0 && a.a_wstride % vec == 0 && a.b_sstride % vec == 0;
     if (a.mode == STORE_T) ok = ok && aligned_to(a.C, bytes) && a.ldc % vec == 0 && a.c_hoff % vec == 0;
     if (nt)

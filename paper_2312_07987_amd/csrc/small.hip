@@ -263,8 +263,15 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(RouterBwdArgs a) {
     T* dz = (T*)a.dz;
     const long base = (long)n * a.ld + (long)side * a.side_stride + (long)h * E;
     for (int e = 0; e < E; ++e) st(dz, base + e, 0.f);
-    if (h == a.H - 1)   // padding columns of this side
+    if (h == a.H - 1) {   // padding columns of this side, and after the last side
       for (int c = HE; c < a.side_stride; ++c) st(dz, (long)n * a.ld + (long)side * a.side_stride + c, 0.f);
+      if (side == a.sides - 1) {
+        int c = a.sides * a.side_stride;
+        if (sizeof(T) == 2 && a.side_stride % 8 == 0 && a.ld % 8 == 0)   // 16-byte pieces of zeros
+          for (; c + 8 <= a.pad_to; c += 8) *(uint4*)((unsigned short*)a.dz + (long)n * a.ld + c) = make_uint4(0, 0, 0, 0);
+        for (; c < a.pad_to; ++c) st(dz, (long)n * a.ld + c, 0.f);
+      }
+    }
     const long o = ((long)sh_ * a.N + n) * k;  // side-major layout [side][H][N][k]
     for (int j = 0; j < k; ++j) {
       int e = a.idx[o + j];
