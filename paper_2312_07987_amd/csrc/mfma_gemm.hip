@@ -125,6 +125,7 @@ struct TileCfg {
   }
 };
 typedef TileCfg<2, 2, 2, 2, 64, 1> CfgSmall;    // 128 x 128
+typedef TileCfg<2, 2, 1, 1, 64, 1> CfgRouter;   // 64 x 64: the router logits have <= 32 columns and want many work-groups
 typedef TileCfg<2, 2, 2, 4, 64, 1, 2> CfgWide;     // 128 x 256, wave tile 64 x 128, two work-groups per CU
 typedef TileCfg<2, 2, 4, 2, 32, 2, 2> CfgMed;   // 256 x 128, two work-groups per CU
 
@@ -563,14 +564,14 @@ void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s) {
         case TAG_V_EXPERTS * 4 + 0: return launch_tagged<false, TAG_V_EXPERTS, 0>(a, s);
         case TAG_O_EXPERTS * 4 + 0: return launch_tagged<false, TAG_O_EXPERTS, 0>(a, s);
         case TAG_O_EXPERTS * 4 + 1: return launch_tagged<false, TAG_O_EXPERTS, 1>(a, s);
-        case TAG_ROUTER * 4 + 0: return launch_cfg<CfgSmall, 8, false, TAG_ROUTER, 0>(a, s);
+        case TAG_ROUTER * 4 + 0: return launch_cfg<CfgRouter, 8, false, TAG_ROUTER, 0>(a, s);
         default: return launch_generic<8, false>(a, s);
       }
     }
   }
   if (nt)
     return launch_generic<4, true>(a, s);
-  if (a.tag == TAG_ROUTER) return launch_cfg<CfgSmall, 4, false, TAG_ROUTER, 0>(a, s);
+  if (a.tag == TAG_ROUTER) return launch_cfg<CfgRouter, 4, false, TAG_ROUTER, 0>(a, s);
   return launch_generic<4, false>(a, s);
 }
 
