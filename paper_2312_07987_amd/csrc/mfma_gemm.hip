@@ -90,6 +90,11 @@ __device__ __forceinline__ uint2 scale_chunk(uint2 c, float g) { return make_uin
 // same rows (the column tiles of a row tile; the same token window of every expert) then
 // meet in one L2 instead of fetching the rows from HBM once per XCD.
 // ----------------------------------------------------------------------------------------
+// Row ids are divided by a small constant (the k slots of a token share a row): multiply-high by
+// ceil(2^32 / d) is exact for ids below 2^32 / d; inv == 0 stands for d == 1.
+__device__ __forceinline__ unsigned div_magic(int d) { return d > 1 ? 0xFFFFFFFFu / (unsigned)d + 1u : 0u; }
+__device__ __forceinline__ int div_by(int id, unsigned inv) { return inv ? (int)__umulhi((unsigned)id, inv) : id; }
+
 __device__ __forceinline__ void decode_block(int L, int per_window, int& w, int& slot) {
   const int S = 8 * per_window;
   const int w8 = L / S, rr = L % S;
@@ -169,6 +174,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
   }
   const bool second = a.hsplit > 0 && h >= a.hsplit;
   const int hh = second ? h - a.hsplit : h;
+  const unsigned inv_adiv = div_magic(a.a_div), inv_cdiv = div_magic(a.c_div);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nseg = SEG ? a.nseg : 1;
@@ -210,7 +216,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
     int c = tid + i * 256;
     int rr = c / A_CPR, kc = (c % A_CPR) * VEC;
     int id = ids[rr];
-    a_off[i] = id >= 0 ? (long)(id / a.a_div) * a.lda + (long)hh * a.a_hoff + kc : -1;
+    a_off[i] = id >= 0 ? (long)div_by(id, inv_adiv) * a.lda + (long)hh * a.a_hoff + kc : -1;
     a_kc[i] = kc;
     a_lds[i] = rr * LDA + kc;
   }
@@ -394,19 +400,21 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
           const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
           const int id = ids[row];
           const int n = n0 + wn + r;
-          if (id >= 0 && n < Nc) ((double*)Cb)[(long)(id / a.c_div) * a.ldc + (long)hh * a.c_hoff + n] = acc64[i][q];
+          if (id >= 0 && n < Nc) ((double*)Cb)[(long)div_by(id, inv_cdiv) * a.ldc + (long)hh * a.c_hoff + n] = acc64[i][q];
         }
     }
     return;
   }
   if (VEC == 8 && a.mode == STORE_T) {
-    // bf16 output: each wave stages 32 rows of its tile in LDS (the operand tiles are dead),
-    // then stores them as 16-byte pieces along the rows
+    // bf16 output: each wave stages 32 rows of its tile in LDS (the operand tiles are dead: the
+    // main loop ends with a barrier), then stores them as 16-byte pieces along the rows.  The
+    // staging area is the wave's own and a wave's LDS operations complete in order, so no
+    // work-group barrier is needed here, only a fixed instruction order.
     constexpr int LDC = Cfg::LDC;
     unsigned short* Cs = smem + wave * 32 * LDC;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
-      __syncthreads();
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const int lr = 8 * (q >> 2) + 4 * g + (q & 3);
@@ -414,14 +422,14 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
 #pragma unroll
         for (int j = 0; j < NJ; ++j) Cs[lr * LDC + j * 32 + r] = f32_to_bf16(acc[i][j][q] * sc);
       }
-      __syncthreads();
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int u = 0; u < 32 * NJ * 4 / 64; ++u) {
         const int c = lane + u * 64;
         const int lr = c / (NJ * 4), cc = (c % (NJ * 4)) * 8;
         const int id = ids[wm + i * 32 + lr];
         if (id < 0 || n0 + wn + cc >= Nc) continue;
-        const long crow = (long)(id / a.c_div) * a.ldc + (long)hh * a.c_hoff;
+        const long crow = (long)div_by(id, inv_cdiv) * a.ldc + (long)hh * a.c_hoff;
         *(uint4*)((unsigned short*)Cb + crow + n0 + wn + cc) = *(const uint4*)(&Cs[lr * LDC + cc]);
       }
     }
@@ -435,7 +443,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
       const int id = ids[row];
       if (id < 0) continue;
       const float sc = SEG == 1 ? 1.f : gsc[row];
-      const long crow = (long)(id / a.c_div) * a.ldc + (long)hh * a.c_hoff;
+      const long crow = (long)div_by(id, inv_cdiv) * a.ldc + (long)hh * a.c_hoff;
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         const int n = n0 + wn + j * 32 + r;
@@ -480,6 +488,8 @@ static int row_gemm_vec(const RowGemmArgs& a) {
 bool mfma_row_gemm_supported(const RowGemmArgs& a) {
   if (a.seg_mode == 1 && (a.nseg < 1 || a.nseg > 8)) return false;
   if (a.tag == TAG_ROUTER && (a.Nc > 32 || a.mode != STORE_F64 || a.seg_mode != 0)) return false;
+  // row ids stay below M; the multiply-high division needs id * divisor < 2^32
+  if ((long)a.M * (a.a_div > a.c_div ? a.a_div : a.c_div) >= (1L << 32)) return false;
   return row_gemm_vec(a) != 0;
 }
 
@@ -651,9 +661,8 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   constexpr int A_N = BK * A_CPR / 256, B_N = BK * B_CPR / 256;
   // row id -> operand row: ids are divided by a small constant (the k slots of a token share a row);
   // multiply-high by ceil(2^32 / d) is exact for ids below 2^32 / d
-  const unsigned inv_a = a.a_div > 1 ? 0xFFFFFFFFu / (unsigned)a.a_div + 1u : 0u;
-  const unsigned inv_b = a.b_div > 1 ? 0xFFFFFFFFu / (unsigned)a.b_div + 1u : 0u;
-  auto row_of = [](int id, unsigned inv) { return inv ? (int)__umulhi((unsigned)id, inv) : id; };
+  const unsigned inv_a = div_magic(a.a_div), inv_b = div_magic(a.b_div);
+  auto row_of = [](int id, unsigned inv) { return div_by(id, inv); };
   // two register sets: a step's rows are requested two steps before they are multiplied, so a
   // load has two steps of the work-group (and of its neighbour on the CU) to arrive
   chunk_t ra0[A_N], rb0[B_N], ra1[A_N], rb1[B_N];
