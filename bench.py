@@ -247,7 +247,10 @@ def main():
             "fwd_frac_of_bf16_peak": lf["fwd"] / (ms_fwd * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "fwd_bwd_frac_of_bf16_peak": lf["fwd_bwd"] / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "step_ms": {n: round(v, 4) for n, v in sorted(per_step.items())},
-            "step_tflops": {n: round(flops[n] / (per_step[n] * 1e-3) / 1e12, 1) for n in sorted(per_step) if n in flops},
+            # with the split backward attention kernels the "bwd.attention" mark covers only the
+            # row-sum (delta) pre-pass, which does none of the matmul work
+            "step_tflops": {n: round(flops[n] / (per_step[n] * 1e-3) / 1e12, 1) for n in sorted(per_step)
+                            if n in flops and not (n == "bwd.attention" and "bwd.attention_dkv" in per_step)},
             "expert_counts_side0_head0": [int(v) for v in (counts[0, 0, 1:] - counts[0, 0, :-1])],
         },
     }

@@ -8,6 +8,9 @@ What it computes, in the paper's notation (Sec. 2.1 and 2.2):
   s_S^h = sigmoid(x W_S^h),  E_S^h = argtopk(s_S^h, k)          source-side router
   s_D^h = sigmoid(x W_D^h),  E_D^h = argtopk(s_D^h, k)          destination-side router
   Q^h = x W_Q^h,  K^h = x W_K^h                                  dense, one copy per head
+    (or, when W_Q and W_K are given as expert banks, the form Sec. 2.2 states before it
+     settles on dense queries and keys:
+     K^h = sum_{e in E_S^h} s_S^h[e] x W_K^{h,e},  Q^h = sum_{e in E_D^h} s_D^h[e] x W_Q^{h,e})
   V^h = sum_{e in E_S^h} s_S^h[e] x W_V^{h,e}                    value experts
   A^h = softmax(Q^h K^h^T / sqrt(d_head))                        Sec. 2.1, first equation
   y   = sum_h sum_{e in E_D^h} s_D^h[e] A^h V^h W_O^{h,e}        output experts
@@ -117,6 +120,9 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
     """One SwitchHead layer call.
 
     x [B,T,dm]; W_Q, W_K [H,dm,dh]; W_V [H,E,dm,dh]; W_O [H,E,dh,dm];
+    W_Q, W_K may instead be expert banks [H,E,dm,dh] (all four projections mixtures of
+    experts, Sec. 2.2): keys mix by the source-side selection, queries by the
+    destination-side selection.
     W_S, W_D [dm, H*E] (column h*E+e); b_S, b_D [H*E] or None.
     W_D None  -> shared selection: the destination side reuses the source side's choice
                  (Sec. 3.5).
@@ -127,7 +133,7 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
     x, W_Q, W_K, W_V, W_O = map(_f64, (x, W_Q, W_K, W_V, W_O))
     B, T, dm = x.shape
     H, E = W_V.shape[0], W_V.shape[1]
-    dh = W_Q.shape[2]
+    dh = W_V.shape[3]
     N = B * T
     x2 = x.reshape(N, dm)
 
@@ -147,9 +153,24 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
             zD = router_logits(x2, W_D, b_D)
             idx_D, g_D, mar_D = select_topk(zD, H, k)
 
-    # step 2: dense per-head queries and keys
-    Q = np.stack([x2 @ W_Q[h] for h in range(H)], axis=1)       # [N,H,dh]
-    K = np.stack([x2 @ W_K[h] for h in range(H)], axis=1)
+    # step 2: queries and keys
+    assert W_Q.ndim == W_K.ndim
+    if W_Q.ndim == 3:
+        # dense, one copy per head
+        Q = np.stack([x2 @ W_Q[h] for h in range(H)], axis=1)       # [N,H,dh]
+        K = np.stack([x2 @ W_K[h] for h in range(H)], axis=1)
+    else:
+        # K^h = sum_{e in E_S} s_S[e] x W_K^{h,e};  Q^h = sum_{e in E_D} s_D[e] x W_Q^{h,e}
+        Q, K = np.zeros((N, H, dh)), np.zeros((N, H, dh))
+        for h in range(H):
+            for j in range(k):
+                for e in range(E):
+                    rows = np.nonzero(idx_D[h, :, j] == e)[0]
+                    if rows.size:
+                        Q[rows, h, :] += g_D[h, rows, j][:, None] * (x2[rows] @ W_Q[h, e])
+                    rows = np.nonzero(idx_S[h, :, j] == e)[0]
+                    if rows.size:
+                        K[rows, h, :] += g_S[h, rows, j][:, None] * (x2[rows] @ W_K[h, e])
 
     # step 3: V^h = sum_{e in E_S} s_S[e] x W_V^{h,e}
     V = np.zeros((N, H, dh))
@@ -205,7 +226,7 @@ def backward(x, W_Q, W_K, W_V, W_O, W_S, W_D, fwd, dy):
     W_S, W_D = _f64(W_S), _f64(W_D)
     B, T, dm = x.shape
     H, E = W_V.shape[0], W_V.shape[1]
-    dh = W_Q.shape[2]
+    dh = W_V.shape[3]
     N = B * T
     k, causal = fwd["k"], fwd["causal"]
     x2, dy2 = x.reshape(N, dm), dy.reshape(N, dm)
@@ -258,11 +279,27 @@ def backward(x, W_Q, W_K, W_V, W_O, W_S, W_D, fwd, dy):
                 dW_V[h, e] += (g * x2[rows]).T @ dV[rows, h, :]
                 dx[rows] += g * (dV[rows, h, :] @ W_V[h, e].T)
 
-    # dense queries and keys
-    for h in range(H):
-        dW_Q[h] = x2.T @ dQ[:, h, :]
-        dW_K[h] = x2.T @ dK[:, h, :]
-        dx += dQ[:, h, :] @ W_Q[h].T + dK[:, h, :] @ W_K[h].T
+    if W_Q.ndim == 3:
+        # dense queries and keys
+        for h in range(H):
+            dW_Q[h] = x2.T @ dQ[:, h, :]
+            dW_K[h] = x2.T @ dK[:, h, :]
+            dx += dQ[:, h, :] @ W_Q[h].T + dK[:, h, :] @ W_K[h].T
+    else:
+        # expert queries (destination-side gates) and keys (source-side gates): same pattern as
+        # the value experts; the gates collect one more term each
+        for W, dW, dP, idx, g_, dg in ((W_Q, dW_Q, dQ, idx_D, g_D, dgD), (W_K, dW_K, dK, idx_S, g_S, dgS)):
+            for h in range(H):
+                for j in range(k):
+                    for e in range(E):
+                        rows = np.nonzero(idx[h, :, j] == e)[0]
+                        if not rows.size:
+                            continue
+                        g = g_[h, rows, j][:, None]
+                        P2 = x2[rows] @ W[h, e]                            # [r, dh]
+                        dg[h, rows, j] += np.sum(P2 * dP[rows, h, :], axis=1)
+                        dW[h, e] += (g * x2[rows]).T @ dP[rows, h, :]
+                        dx[rows] += g * (dP[rows, h, :] @ W[h, e].T)
 
     # routers: g = sigmoid(z) at the selected entries, nothing elsewhere
     dW_S = dW_D = db_S = db_D = None

@@ -59,6 +59,7 @@ def make_inputs(cfg, seed=None, shared_router=False):
     Returns float32 arrays (already rounded to bf16-representable values when
     cfg['dtype'] == 'bf16'): x, W_Q, W_K, W_V, W_O, W_S, W_D, b_S, b_D, dy.
     b_S and b_D are None unless cfg['bias0'] != 0 (then +bias0 on column h*E+0).
+    cfg['qk_experts'] (optional, default 0): W_Q and W_K are expert banks [H,E,dm,dh].
     """
     if seed is None:
         names = [c["name"] for c in CONFIGS]
@@ -71,8 +72,9 @@ def make_inputs(cfg, seed=None, shared_router=False):
 
     t = {}
     t["x"] = draw((B, T, dm), 1.0)
-    t["W_Q"] = draw((H, dm, dh), dm ** -0.5)
-    t["W_K"] = draw((H, dm, dh), dm ** -0.5)
+    qk_shape = (H, E, dm, dh) if cfg.get("qk_experts") else (H, dm, dh)
+    t["W_Q"] = draw(qk_shape, dm ** -0.5)
+    t["W_K"] = draw(qk_shape, dm ** -0.5)
     t["W_V"] = draw((H, E, dm, dh), dm ** -0.5)
     t["W_O"] = draw((H, E, dh, dm), dh ** -0.5)
     t["W_S"] = draw((dm, H * E), dm ** -0.5)

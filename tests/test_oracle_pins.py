@@ -66,8 +66,17 @@ def brute_force_layer(t, k, causal):
     y = [[[0.0] * dm for _ in range(T)] for _ in range(B)]
     for b in range(B):
         for h in range(H):
-            Q = [[sum(x[b][t_][i] * WQ[h][i][d] for i in range(dm)) for d in range(dh)] for t_ in range(T)]
-            K = [[sum(x[b][t_][i] * WK[h][i][d] for i in range(dm)) for d in range(dh)] for t_ in range(T)]
+            if np.ndim(t["W_Q"]) == 3:
+                Q = [[sum(x[b][t_][i] * WQ[h][i][d] for i in range(dm)) for d in range(dh)] for t_ in range(T)]
+                K = [[sum(x[b][t_][i] * WK[h][i][d] for i in range(dm)) for d in range(dh)] for t_ in range(T)]
+            else:   # expert banks: queries by the destination-side gates, keys by the source-side gates
+                Q, K = [], []
+                for t_ in range(T):
+                    mD, mS = gates(x[b][t_], WD, h), gates(x[b][t_], WS, h)
+                    Q.append([sum(mD[e] * sum(x[b][t_][i] * WQ[h][e][i][d] for i in range(dm)) for e in range(E))
+                              for d in range(dh)])
+                    K.append([sum(mS[e] * sum(x[b][t_][i] * WK[h][e][i][d] for i in range(dm)) for e in range(E))
+                              for d in range(dh)])
             V = []
             for t_ in range(T):
                 m = gates(x[b][t_], WS, h)
@@ -132,8 +141,12 @@ def torch_dense_masked(t, idx_S, idx_D, causal, shared=False):
         zD = x @ T64["W_D"] + (0 if T64["b_D"] is None else T64["b_D"])
     gS = torch.sigmoid(zS).reshape(B, T, H, E) * mask_of(idx_S)
     gD = torch.sigmoid(zD).reshape(B, T, H, E) * mask_of(idx_D)
-    Q = torch.einsum("bti,hid->bhtd", x, T64["W_Q"])
-    K = torch.einsum("bti,hid->bhtd", x, T64["W_K"])
+    if T64["W_Q"].dim() == 3:
+        Q = torch.einsum("bti,hid->bhtd", x, T64["W_Q"])
+        K = torch.einsum("bti,hid->bhtd", x, T64["W_K"])
+    else:
+        Q = torch.einsum("bti,heid,bthe->bhtd", x, T64["W_Q"], gD)
+        K = torch.einsum("bti,heid,bthe->bhtd", x, T64["W_K"], gS)
     V = torch.einsum("bti,heid,bthe->bhtd", x, T64["W_V"], gS)
     L = Q @ K.transpose(-1, -2) / math.sqrt(dh)
     if causal:
@@ -445,6 +458,68 @@ def test_dense_mode_gradients_match_textbook_autograd():
 # --------------------------------------------------------------------------------------
 # the input generator (no method arithmetic, but both sides depend on it)
 # --------------------------------------------------------------------------------------
+# --------------------------------------------------------------------------------------
+# all four projections as expert mixtures (Sec. 2.2, before queries and keys are made dense)
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("E,k", [(3, 2), (4, 4)])
+def test_expert_qk_brute_force(E, k, causal):
+    cfg = dict(TINY, E=E, k=k, qk_experts=1)
+    t = _inputs(cfg, seed=31 + E + k)
+    assert t["W_Q"].shape == (2, E, 6, 4)
+    got = _fwd(t, k, causal)["y"]
+    ref = brute_force_layer(t, k, causal)
+    assert np.max(np.abs(got - ref)) < 1e-12 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_expert_qk_with_identical_experts_is_gate_sum_times_dense():
+    """W_Q[h,e] = W for every e  =>  Q^h = (sum of the selected destination gates) x W, and the
+    same for K with the source gates: a rescaling of the dense-query/key layer's Q and K."""
+    cfg = dict(TINY, B=2, T=6, E=4, k=2)
+    t = _inputs(cfg, seed=33)
+    dense = _fwd(t, 2)
+    rep = lambda W: np.repeat(W[:, None], 4, axis=1)
+    f = _fwd(t, 2, W_Q=rep(t["W_Q"]), W_K=rep(t["W_K"]))
+    sD = f["gate_D"].sum(-1).T[:, :, None]     # [N,H,1]
+    sS = f["gate_S"].sum(-1).T[:, :, None]
+    assert np.allclose(f["Q"], sD * dense["Q"], rtol=0, atol=1e-13)
+    assert np.allclose(f["K"], sS * dense["K"], rtol=0, atol=1e-13)
+    assert not np.allclose(f["y"], dense["y"])
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_expert_qk_backward_matches_autograd_and_differences(shared):
+    cfg = dict(TINY, B=2, T=6, d_model=5, nheads=2, d_head=3, E=3, k=2, qk_experts=1, bias0=0.25)
+    t = {n: (None if a is None else a.astype(np.float64))
+         for n, a in make_inputs(cfg, seed=35, shared_router=shared).items()}
+    f = _fwd(t, 2)
+    g = _bwd(t, f)
+    y, leaves = torch_dense_masked(t, f["idx_S"], f["idx_D"], True, shared)
+    assert np.allclose(y.detach().numpy(), f["y"], rtol=0, atol=1e-12)
+    (y * torch.tensor(t["dy"])).sum().backward()
+    for gn, n in zip(GRADS, NAMES):
+        if leaves[n] is None:
+            assert g[gn] is None
+            continue
+        ref = leaves[n].grad.numpy()
+        assert g[gn].shape == ref.shape
+        assert np.max(np.abs(g[gn] - ref)) <= 1e-11 * max(1.0, np.max(np.abs(ref))), gn
+    # central differences on the query and key banks and on x
+    assert min(f["margin_S"].min(), f["margin_D"].min()) > 1e-4
+    rng = np.random.default_rng(1)
+    eps = 1e-6
+    for gn, n in (("dW_Q", "W_Q"), ("dW_K", "W_K"), ("dx", "x")):
+        for _ in range(5):
+            pos = tuple(rng.integers(0, s_) for s_ in t[n].shape)
+            vals = []
+            for sgn in (+1, -1):
+                a2 = t[n].copy()
+                a2[pos] += sgn * eps
+                vals.append(float(np.sum(_fwd(t, 2, **{n: a2})["y"] * t["dy"])))
+            fd = (vals[0] - vals[1]) / (2 * eps)
+            assert abs(fd - g[gn][pos]) < 1e-6 * max(1.0, abs(fd)), (gn, pos, fd, g[gn][pos])
+
+
 def test_bf16_rounding_is_nearest_even():
     a = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -7, 1.0 + 3 * 2 ** -8, -0.3, 3.0e38], dtype=np.float32)
     r = round_to_bf16(a)
