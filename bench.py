@@ -48,6 +48,9 @@ def step_work(cfg):
         "bwd.o_dgrad": expert, "bwd.o_wgrad": expert, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
         "bwd.q_wgrad": proj, "bwd.k_wgrad": proj, "bwd.qk_wgrad": 2 * proj, "bwd.q_dgrad": proj, "bwd.k_dgrad": proj,
         "bwd.router_wgrad": router // 2, "bwd.router_dgrad": router // 2,
+        # query / key expert banks (all-expert form): each step has the shape of its value-expert twin
+        "fwd.q_experts": expert, "fwd.k_experts": expert, "bwd.q_wgrad_e": expert, "bwd.k_wgrad_e": expert,
+        "bwd.q_dgrad_e": expert, "bwd.k_dgrad_e": expert,
     }
     alu = {"fwd.router": router}
     nbytes = {
@@ -109,9 +112,10 @@ def dense_baseline(cfg, steps, warmup):
     from paper_2312_07987_amd.runner import DeviceLayer
     H, E, dh = cfg["nheads"], cfg["E"], cfg["d_head"]
     heads = H * E
-    dh_match = ((2 * H + 2 * H * E) * dh + 2 * H * E) / (4.0 * H * E)
+    qk_mats = 2 * H * E if cfg.get("qk_experts") else 2 * H   # query + key matrices of d_model x d_head
+    dh_match = ((qk_mats + 2 * H * E) * dh + 2 * H * E) / (4.0 * H * E)
     dh2 = int(-(-dh_match // 8) * 8)
-    dc = dict(cfg, nheads=heads, d_head=dh2, E=1, k=1, bias0=0.0, name="dense")
+    dc = dict(cfg, nheads=heads, d_head=dh2, E=1, k=1, bias0=0.0, name="dense", qk_experts=0)
     layer = DeviceLayer(dc, make_inputs(dc, seed=1), dense=True)
 
     def step():
@@ -158,6 +162,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="c2", help="c1..c4 (c2 = the 262M-model-scale layer)")
+    ap.add_argument("--qk-experts", action="store_true",
+                    help="all four projections as expert mixtures (query and key banks like the value bank)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=1 << 20, help="token budget of the oracle sample (whole sequences)")
     ap.add_argument("--no-dense", action="store_true", help="skip the parameter-matched dense multi-head baseline")
@@ -186,6 +192,8 @@ def main():
         return
 
     cfg = config(args.config)
+    if args.qk_experts:
+        cfg["qk_experts"] = 1
     host = make_inputs(cfg)
     layer = DeviceLayer(cfg, host)
     N = cfg["B"] * cfg["T"]
@@ -226,7 +234,7 @@ def main():
     roof["traffic"] = measured_traffic(cfg["name"], dom)
 
     lf = layer_flops(cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
-                     bool(cfg["causal"]))
+                     bool(cfg["causal"]), qk_experts=bool(cfg.get("qk_experts")))
     counts = layer.routing()["offsets"]
     out = {
         "metric": "switchhead_layer_fwd_bwd_tokens_per_s",
@@ -236,9 +244,9 @@ def main():
         "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": "%s: B=%d T=%d d_model=%d nheads=%d d_head=%d E=%d k=%d causal=%d bias0=%g" % (
+        "config": {"workload": "%s: B=%d T=%d d_model=%d nheads=%d d_head=%d E=%d k=%d causal=%d bias0=%g%s" % (
             cfg["name"], cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
-            cfg["causal"], cfg["bias0"]), "tokens_per_step": N},
+            cfg["causal"], cfg["bias0"], " qk_experts=1" if cfg.get("qk_experts") else ""), "tokens_per_step": N},
         "roofline": roof,
         "extra": {
             "fwd_ms": ms_fwd, "fwd_tokens_per_s": N / (ms_fwd * 1e-3),

@@ -56,6 +56,13 @@ typedef struct {
   int32_t causal;   /* 1: key u visible to query t iff u <= t; 0: full attention (the
                        paper's ListOps analysis, Sec. 4, uses the unmasked form)          */
   int32_t dtype;    /* sh_dtype                                                           */
+  int32_t qk_experts; /* 0: SwitchHead proper, one dense W_Q and W_K per head (Sec. 2.2, last
+                       paragraph; Sec. 3.1 finds query/key experts unnecessary).
+                       1: the form Sec. 2.2 states first, all four projections mixtures of
+                       experts: W_Q, W_K (and dW_Q, dW_K) are expert banks
+                       [nheads, E, d_model, d_head] like W_V;
+                       K^h = sum_{e in E_S^h} s_S^h[e] x W_K^{h,e} (source-side selection),
+                       Q^h = sum_{e in E_D^h} s_D^h[e] x W_Q^{h,e} (destination side)      */
 } sh_shape;
 
 /* Bytes of workspace a forward (+ backward) call of this shape needs; 0 if the shape is
@@ -68,6 +75,7 @@ size_t switchhead_workspace_bytes(const sh_shape* shape);
  *   x    [B, T, d_model]                     input
  *   W_Q  [nheads, d_model, d_head]           dense query projection per head
  *   W_K  [nheads, d_model, d_head]           dense key projection per head
+ *        (both [nheads, E, d_model, d_head] when shape->qk_experts == 1)
  *   W_V  [nheads, E, d_model, d_head]        value experts
  *   W_O  [nheads, E, d_head, d_model]        output experts
  *   W_S  [d_model, nheads*E]                 source-side router, column h*E+e.

@@ -239,6 +239,7 @@ struct SlotArgs {
   float* dots;
   float* delta;
   int N, H, k, dh;
+  int dots_add;   // 1: dots[] += the row dots instead of being overwritten
 };
 void launch_slot_combine(const SlotArgs& a, int bf16, hipStream_t s);
 

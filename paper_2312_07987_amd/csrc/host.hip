@@ -65,6 +65,7 @@ inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 struct Layout {
   size_t total = 0;
   size_t idx, gate, perm, offsets, Q, K, V, ctx, lse, pV;          // saved by forward
+  size_t pQ, pK;                                                   // per-slot query / key rows (expert Q/K only)
   size_t Z, blockcnt, acc32;                                       // forward scratch
   size_t setid, gset, gsort, setexp, setperm, setoff, setcnt, yh;
   size_t dR, wr3;                                                  // wide router dz rows [N, H*dh], routers packed [dm, dh]                 // expert-set path (bf16 only)
@@ -103,6 +104,7 @@ sh_status check_shape(const sh_shape* s) {
   if (s->k > s->E) return fail(SH_ERR_INVALID_ARG, "k=%d exceeds E=%d", s->k, s->E);
   if (s->dtype != SH_F32 && s->dtype != SH_BF16) return fail(SH_ERR_INVALID_ARG, "unknown dtype %d", s->dtype);
   if (s->causal != 0 && s->causal != 1) return fail(SH_ERR_INVALID_ARG, "causal must be 0 or 1");
+  if (s->qk_experts != 0 && s->qk_experts != 1) return fail(SH_ERR_INVALID_ARG, "qk_experts must be 0 or 1");
   if (s->E > 64) return fail(SH_ERR_UNSUPPORTED, "E=%d exceeds the limit of 64", s->E);
   if (s->k > 8) return fail(SH_ERR_UNSUPPORTED, "k=%d exceeds the limit of 8", s->k);
   if (s->d_head > 256) return fail(SH_ERR_UNSUPPORTED, "d_head=%d exceeds the limit of 256", s->d_head);
@@ -133,6 +135,11 @@ Layout make_layout(const sh_shape* s) {
   L.ctx = take(N * H * dh * esz);
   L.lse = take(N * H * 4);
   L.pV = take(H * N * k * dh * esz);
+  L.pQ = L.pK = 0;
+  if (s->qk_experts) {
+    L.pQ = take(H * N * k * dh * esz);
+    L.pK = take(H * N * k * dh * esz);
+  }
   L.Z = take(2 * N * H * E * 8);
   L.blockcnt = take(2 * H * (size_t)router_blocks((int)N) * E * 4);
   L.acc32 = take(N * dm * 4);
@@ -155,14 +162,16 @@ Layout make_layout(const sh_shape* s) {
     L.setperm = take(2 * H * N * 4);
     L.setoff = take(2 * H * (ns + 1) * 4);
     L.setcnt = take(2 * H * (size_t)router_blocks((int)N) * ns * 4);
-    L.yh = take((H + 2) * N * dm * esz);   // one partial per head + the Q/K and the routers' shares of dx
+    // partial sums of dx (y in the forward pass): one per head from the value experts, then either one
+    // for the dense Q/K pair or one per head for each of the query and key experts, one for the routers
+    L.yh = take(((s->qk_experts ? 3 * H : H + 1) + 1) * N * dm * esz);
   } else {
     L.setid = L.gset = L.gsort = L.setexp = L.setperm = L.setoff = L.setcnt = L.yh = 0;
   }
   L.rh = L.wpart = 0;
   if (s->dtype == SH_BF16) {
     // groups x chunks-per-group x one expert matrix, fp32 (the dense Q/K pair counts as 2H groups)
-    const size_t groups = H * E > 2 * H ? H * E : 2 * H;
+    const size_t groups = H * E > 2 * H ? H * E : 2 * H;   // expert Q/K banks: H * E groups each, one at a time
     const size_t ce = wgrad_chunk(H * N * k, dm, dh), cd = wgrad_chunk(2 * H * N, dm, dh);
     const size_t cmin = ce < cd ? ce : cd;
     L.wpart = take(groups * ((N + cmin - 1) / cmin) * dm * dh * 4);
@@ -179,7 +188,7 @@ struct Ctx {
   char* ws;
   hipStream_t st;
   int N, H, E, k, dh, dm, bf16;
-  bool dense, shared;
+  bool dense, shared, qk_experts;
   template <typename T>
   T* p(size_t off) const {
     return (T*)(ws + off);
@@ -210,6 +219,7 @@ sh_status make_ctx(Ctx& c, const sh_shape* s, const void* W_S, const void* W_D, 
   c.dh = s->d_head;
   c.dm = s->d_model;
   c.bf16 = s->dtype == SH_BF16;
+  c.qk_experts = s->qk_experts != 0;
   c.dense = W_S == nullptr;
   c.shared = W_S != nullptr && W_D == nullptr;
   if (c.dense && (s->E != 1 || s->k != 1))
@@ -480,6 +490,40 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     launch_set_sort(sa, c.st);
   }
 
+  // step 2, all-expert form: queries mix the destination side's experts, keys the source side's,
+  // each like the value projection of step 3 (per-slot rows, then the gate-weighted sum)
+  if (c.qk_experts) {
+    for (int which = 0; which < 2; ++which) {
+      const int side = which ? 0 : 1;
+      prof_mark(c.st, which ? "fwd.k_experts" : "fwd.q_experts");
+      RowGemmArgs a = perm_rows(c, side);
+      a.tag = TAG_V_EXPERTS;
+      a.A = x;
+      a.lda = dm;
+      a.B = which ? W_K : W_Q;
+      a.b_hstride = (long)E * dm * dh;
+      a.b_estride = (long)dm * dh;
+      a.sbk = dh;
+      a.sbn = 1;
+      a.C = c.p<void>(which ? c.L.pK : c.L.pQ);
+      a.ldc = dh;
+      a.c_hoff = (long)N * k * dh;
+      a.K = dm;
+      a.Nc = dh;
+      a.mode = STORE_T;
+      row_gemm(c, a);
+      prof_mark(c.st, which ? "fwd.k_combine" : "fwd.q_combine");
+      SlotArgs sl{};
+      sl.slots = a.C;
+      sl.gate = c.gate(side);
+      sl.out = c.p<void>(which ? c.L.K : c.L.Q);
+      sl.N = N;
+      sl.H = H;
+      sl.k = k;
+      sl.dh = dh;
+      launch_slot_combine(sl, c.bf16, c.st);
+    }
+  } else
   // step 2: dense queries and keys (one launch for both when the MFMA kernel takes it)
   {
     RowGemmArgs a = identity_rows(c, 2 * H);
@@ -734,7 +778,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   float* dxacc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)dx;
   bool qk_partial = false;    // the Q/K share of dx sits in a bf16 partial, not in dxacc
   bool acc_written = false;   // dxacc holds (part of) dx
-  {
+  if (!c.qk_experts) {
     prof_mark(c.st, "bwd.qk_wgrad");
     WgradArgs w{};
     w.tag = TAG_QK_WGRAD;
@@ -765,7 +809,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   // launch moves behind the router backward kernel.
   const int HE_r = H * E, HEp_r = (HE_r + 7) / 8 * 8, sides_r = c.shared ? 1 : 2;
   const bool wide_dz = !c.dense && sides_r * HEp_r <= dh && (c.L.dR - c.L.dK) == (c.L.dK - c.L.dQ);
-  const bool fuse_router = wide_dz && sets && c.bf16 && use_mfma(c);
+  const bool fuse_router = wide_dz && sets && c.bf16 && use_mfma(c) && !c.qk_experts;
   bool router_fused = false;
   auto run_qk_dgrad = [&](bool with_router) {
     RowGemmArgs a = identity_rows(c, 1);
@@ -827,27 +871,40 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       }
     }
   };
-  if (!fuse_router) run_qk_dgrad(false);
+  if (c.qk_experts) {
+    if (!sets) {   // the expert input gradients below add into the accumulator
+      prof_mark(c.st, "bwd.dx_zero");
+      launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
+      acc_written = true;
+    }
+  } else if (!fuse_router) {
+    run_qk_dgrad(false);
+  }
 
-  // value experts: d(gate_S), dW_V, dx
-  {
-    prof_mark(c.st, "bwd.dgate_s");
+  // A projection P[n,h] = sum_j g[n,h,j] x[n] W[h,e_j] (values; queries and keys in the all-expert
+  // form) given dP: the gates' gradient <x W[h,e_j], dP> from the per-slot rows the forward pass
+  // kept, dW[h,e] = sum_n g x[n]^T dP[n,h], and the projection's share of dx.
+  int yh_used = 0;   // bf16 partials of dx written so far (expert-set path)
+  auto expert_proj_bwd = [&](int side, const void* W, size_t dP, size_t slots, float* dW, bool dots_add,
+                             const char* l_gate, const char* l_wgrad, const char* l_dgrad) {
+    prof_mark(c.st, l_gate);
     SlotArgs sa{};
-    sa.slots = c.p<void>(c.L.pV);
-    sa.gate = c.gate(0);
-    sa.other = c.p<void>(c.L.dV);
-    sa.dots = c.p<float>(c.L.dgate);
+    sa.slots = c.p<void>(slots);
+    sa.gate = c.gate(side);
+    sa.other = c.p<void>(dP);
+    sa.dots = c.p<float>(c.L.dgate) + (size_t)side * H * N * k;
+    sa.dots_add = dots_add;
     sa.N = N;
     sa.H = H;
     sa.k = k;
     sa.dh = dh;
     launch_slot_combine(sa, c.bf16, c.st);
-    prof_mark(c.st, "bwd.v_wgrad");
+    prof_mark(c.st, l_wgrad);
     WgradArgs w{};
     w.tag = TAG_V_WGRAD;
-    w.scale_b = 1;   // gate on the d_head-wide dV rows instead of the d_model-wide x rows
-    w.perm = c.perm(0);
-    w.offsets = c.offsets(0);
+    w.scale_b = 1;   // gate on the d_head-wide dP rows instead of the d_model-wide x rows
+    w.perm = c.perm(side);
+    w.offsets = c.offsets(side);
     w.heads = H;
     w.E = E;
     w.M = N * k;
@@ -858,25 +915,25 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.lda = dm;
     w.a_hoff = 0;
     w.Ka = dm;
-    w.Bm = c.p<void>(c.L.dV);
+    w.Bm = c.p<void>(dP);
     w.ldb = hd;
     w.b_hoff = dh;
     w.Kb = dh;
-    w.dW = dW_V;
+    w.dW = dW;
     w.w_hstride = (long)E * dm * dh;
     w.w_estride = (long)dm * dh;
     w.swa = dh;
-    w.gate = c.gate(0);
+    w.gate = c.gate(side);
     w.gate_hstride = (long)N * k;
     w.chunk = chunk;
     wgrad(c, w);
-    prof_mark(c.st, "bwd.v_dgrad");
-    RowGemmArgs a = sets ? set_rows(c, 0) : perm_rows(c, 0);
+    prof_mark(c.st, l_dgrad);
+    RowGemmArgs a = sets ? set_rows(c, side) : perm_rows(c, side);
     a.tag = TAG_V_DGRAD;
-    a.A = c.p<void>(c.L.dV);
+    a.A = c.p<void>(dP);
     a.lda = hd;
     a.a_hoff = dh;
-    a.B = W_V;
+    a.B = W;
     a.b_hstride = (long)E * dm * dh;
     a.b_estride = (long)dm * dh;
     a.sbk = 1;
@@ -885,21 +942,32 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.Nc = dm;
     if (sets) {
       // per-head partial sums of dx in bf16; they are added to the rest of dx at the end
-      a.C = c.p<void>(c.L.yh);
+      a.C = c.p<char>(c.L.yh) + (size_t)yh_used * N * dm * 2;
       a.ldc = dm;
       a.c_hoff = (long)N * dm;
       a.mode = STORE_T;
       launch_mfma_row_gemm(a, c.st);
+      yh_used += H;
     } else {
       a.c_div = k;
       a.C = dxacc;
       a.ldc = dm;
-      a.gate = c.gate(0);
+      a.gate = c.gate(side);
       a.gate_hstride = (long)N * k;
       a.mode = ATOMIC_F32;
       row_gemm(c, a);
     }
+  };
+  expert_proj_bwd(0, W_V, c.L.dV, c.L.pV, dW_V, false, "bwd.dgate_s", "bwd.v_wgrad", "bwd.v_dgrad");
+  if (c.qk_experts) {
+    // keys add to the source side's gate gradients, queries to the destination side's (written by
+    // the output experts' step above)
+    expert_proj_bwd(0, W_K, c.L.dK, c.L.pK, dW_K, true, "bwd.dgate_k", "bwd.k_wgrad_e", "bwd.k_dgrad_e");
+    expert_proj_bwd(1, W_Q, c.L.dQ, c.L.pQ, dW_Q, true, "bwd.dgate_q", "bwd.q_wgrad_e", "bwd.q_dgrad_e");
   }
+  // slots of the partial-sum buffer taken so far: the experts' above, or the value experts' H and
+  // (once its GEMM has run) the dense Q/K pair's one right behind them
+  auto yh_taken = [&] { return c.qk_experts ? yh_used : H + (qk_partial ? 1 : 0); };
 
   // routers
   bool router_partial = false;
@@ -1002,7 +1070,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       a.B2 = Wp + (size_t)dm * HEp;
       a.sbk = 1;
       a.sbn = HEp;
-      a.C = c.p<char>(c.L.yh) + (size_t)(H + (qk_partial ? 1 : 0)) * N * dm * esz;
+      a.C = c.p<char>(c.L.yh) + (size_t)yh_taken() * N * dm * esz;
       a.ldc = dm;
       a.K = HEp;
       a.Nc = dm;
@@ -1037,7 +1105,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   prof_mark(c.st, "bwd.dx_cast");
   if (sets)
     launch_sum_heads(c.p<void>(c.L.yh), acc_written ? dxacc : nullptr, dx, (size_t)N * dm, (size_t)N * dm,
-                     H + (qk_partial ? 1 : 0) + (router_partial ? 1 : 0), c.st);
+                     yh_taken() + (router_partial ? 1 : 0), c.st);
   else if (c.bf16)
     launch_cast_from_f32(dxacc, dx, (size_t)N * dm, 1, c.st);
   prof_mark(c.st, nullptr);

@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void slot_combine_kernel(SlotArgs a) {
     }
     if (a.dots) {
       dot = wave_sum(dot);
-      if (lane == 0) a.dots[aid] = dot;
+      if (lane == 0) a.dots[aid] = a.dots_add ? a.dots[aid] + dot : dot;
     }
   }
   if (out) {
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(256) void slot_combine_vec_kernel(SlotArgs a) {
     if (a.dots) {
 #pragma unroll
       for (int o = TPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
-      if (valid && lane_in == 0) a.dots[aid] = dot;
+      if (valid && lane_in == 0) a.dots[aid] = a.dots_add ? a.dots[aid] + dot : dot;
     }
   }
   if (a.out && act) {

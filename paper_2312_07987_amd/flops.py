@@ -37,13 +37,13 @@ def mem_switchhead_tables(nheads, d_head, T, C=2):
     return nheads * (4 * T * d_head + 2 * C * T * T + C * T * d_head)
 
 
-def layer_flops(B, T, d_model, nheads, d_head, E, k, causal=True, shared=False, dense=False):
+def layer_flops(B, T, d_model, nheads, d_head, E, k, causal=True, shared=False, dense=False, qk_experts=False):
     """Algorithmic flops of one forward / backward call of this library's layer (no
     positional term, square attention).  Returns a dict of per-step and total counts."""
     N = B * T
     n_routers = 0 if dense else (1 if shared else 2)
     router = 2 * N * d_model * n_routers * nheads * E
-    qk = 2 * (2 * N * d_model * nheads * d_head)
+    qk = 2 * (2 * N * d_model * nheads * d_head) * (k if qk_experts else 1)   # k experts per token when banks
     v = 2 * N * k * d_model * nheads * d_head
     o = v
     pairs = T * (T + 1) // 2 if causal else T * T

@@ -124,6 +124,36 @@ def test_bf16_noncausal_shared_dense():
              dense=True, seed=15)
 
 
+def test_bf16_mac_matched_shapes():
+    """Head counts and widths of the MAC-matched models (Sec. 3.4): 3 heads of 112, 6 heads of 168."""
+    run_case(small("c1", B=2, T=160, nheads=3, d_head=112), seed=16)
+    run_case(small("c2", B=1, T=200, nheads=6, d_head=168), seed=17)
+
+
+@pytest.mark.parametrize("family", [0, 1])
+def test_fp32_expert_queries_and_keys(family):
+    """All four projections as expert mixtures (Sec. 2.2): W_Q, W_K are banks like W_V."""
+    run_case(small("c0", qk_experts=1), family=family)
+    run_case(dict(name="ragqk", dtype="f32", B=3, T=37, d_model=50, nheads=3, d_head=20, E=7, k=3, causal=1, bias0=0.0,
+                  qk_experts=1), family=family, seed=25)
+
+
+def test_fp32_expert_queries_and_keys_shared_selection():
+    run_case(small("c0", qk_experts=1), shared=True, seed=26)
+
+
+@pytest.mark.parametrize("family", [0, 1])
+def test_bf16_expert_queries_and_keys(family):
+    run_case(small("c2", B=3, T=200, d_model=320, nheads=2, d_head=128, qk_experts=1), family=family, seed=27)
+    run_case(small("c1", B=3, T=100, qk_experts=1), family=family, seed=28)
+    run_case(small("c2", B=2, T=130, d_model=256, nheads=2, qk_experts=1), family=family, shared=True, seed=29)
+
+
+def test_full_config_expert_queries_and_keys():
+    """c2 at full size with query and key experts, in the launch configuration bench.py times."""
+    run_case(small("c2", qk_experts=1), seed=30)
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
 def test_full_config(name):
     """The paper-shaped workloads at full size, in the launch configuration bench.py times."""
