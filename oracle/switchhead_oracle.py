@@ -28,7 +28,13 @@ Readings where the paper is silent (all listed in the design notes of the reposi
     single accumulator, bias (if any) added last;
   * gates are not renormalised (non-competitive selection, Sec. 2.2);
   * causal mask: key u is visible to query t iff u <= t; masked logits are -inf;
-  * no positional encoding, dropout, bias or normalisation inside the layer.
+  * no dropout, bias or normalisation inside the layer; no positional encoding unless
+    `rope` is asked for: then queries and keys are rotated as in the rotary position
+    embedding the paper's App. A.5 models use (Su et al., RoFormer): element pair
+    (2i, 2i+1) of every head's query and key at position t (index in its sequence, from 0)
+    turns by the angle t * 10000^(-2i/d), d = the even part of d_head; an odd last element
+    is left as it is.  The paper cites the method without restating it; the adjacent-pair
+    form and base 10000 are the cited paper's own.
 
 Pinned by tests/test_oracle_pins.py against: a dense-masked brute force in pure Python
 loops, the k=E dense mixture, the single-expert case against a textbook concat-form MHA,
@@ -40,7 +46,7 @@ from __future__ import annotations
 
 import numpy as np
 
-__all__ = ["router_logits", "select_topk", "routing_tables", "forward", "backward"]
+__all__ = ["router_logits", "select_topk", "routing_tables", "rotary", "forward", "backward"]
 
 
 def _f64(a):
@@ -104,6 +110,27 @@ def routing_tables(idx, E):
     return perm, offsets, inv
 
 
+def rotary(P, pos, inverse=False):
+    """Rotary position embedding of query or key rows (App. A.5 of the paper, method of
+    Su et al.): P [..., n, d_head] with `pos` [n] the position of each row; the pair
+    (P[2i], P[2i+1]) is turned by the angle pos * 10000^(-2i/d), d = 2*floor(d_head/2).
+    `inverse` turns by the opposite angle (the transpose of the rotation: what the chain
+    rule applies to a gradient)."""
+    P = np.asarray(P, dtype=np.float64)
+    dh = P.shape[-1]
+    half = dh // 2
+    theta = 10000.0 ** (-2.0 * np.arange(half) / (2 * half)) if half else np.zeros(0)
+    ang = np.asarray(pos, dtype=np.float64)[:, None] * theta[None, :]        # [n, half]
+    if inverse:
+        ang = -ang
+    c, s_ = np.cos(ang), np.sin(ang)
+    out = P.copy()
+    a, b = P[..., 0:2 * half:2], P[..., 1:2 * half:2]
+    out[..., 0:2 * half:2] = a * c - b * s_
+    out[..., 1:2 * half:2] = a * s_ + b * c
+    return out
+
+
 def _attention_matrix(Qbh, Kbh, causal):
     """A = softmax(Q K^T / sqrt(d_head)) for one (sequence, head); Sec. 2.1."""
     T, dh = Qbh.shape
@@ -116,7 +143,7 @@ def _attention_matrix(Qbh, Kbh, causal):
     return P / P.sum(axis=-1, keepdims=True)
 
 
-def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, causal=True):
+def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, causal=True, rope=False):
     """One SwitchHead layer call.
 
     x [B,T,dm]; W_Q, W_K [H,dm,dh]; W_V [H,E,dm,dh]; W_O [H,E,dh,dm];
@@ -172,6 +199,13 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
                     if rows.size:
                         K[rows, h, :] += g_S[h, rows, j][:, None] * (x2[rows] @ W_K[h, e])
 
+    # rotary position embedding of queries and keys (App. A.5), position = index in the sequence
+    if rope:
+        pos = np.tile(np.arange(T), B)
+        for h in range(H):
+            Q[:, h, :] = rotary(Q[:, h, :], pos)
+            K[:, h, :] = rotary(K[:, h, :], pos)
+
     # step 3: V^h = sum_{e in E_S} s_S[e] x W_V^{h,e}
     V = np.zeros((N, H, dh))
     for h in range(H):
@@ -208,7 +242,7 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
 
     out = dict(y=y.reshape(B, T, dm), Q=Q, K=K, V=V, ctx=ctx, zS=zS, zD=zD,
                idx_S=idx_S, idx_D=idx_D, gate_S=g_S, gate_D=g_D,
-               margin_S=mar_S, margin_D=mar_D, k=k, causal=causal,
+               margin_S=mar_S, margin_D=mar_D, k=k, causal=causal, rope=bool(rope),
                shared=(W_S is not None and W_D is None), dense=(W_S is None))
     out.update(tabs)
     return out
@@ -264,6 +298,13 @@ def backward(x, W_Q, W_K, W_V, W_O, W_S, W_D, fwd, dy):
             dS = A * (dA - np.sum(dA * A, axis=-1, keepdims=True))
             dQ[sl, h] = (dS @ K[sl, h]) * scale
             dK[sl, h] = (dS.T @ Q[sl, h]) * scale
+
+    # back through the rotation of queries and keys: the transpose of a rotation is the opposite turn
+    if fwd.get("rope"):
+        pos = np.tile(np.arange(T), B)
+        for h in range(H):
+            dQ[:, h, :] = rotary(dQ[:, h, :], pos, inverse=True)
+            dK[:, h, :] = rotary(dK[:, h, :], pos, inverse=True)
 
     # value experts: V[n,h] = sum_j gS * x[n] W_V[h,e_j]
     dgS = np.zeros((H, N, k))

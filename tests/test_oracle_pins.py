@@ -20,11 +20,11 @@ def _inputs(cfg, seed=7):
     return make_inputs(cfg, seed=seed)
 
 
-def _fwd(t, k, causal=True, **over):
+def _fwd(t, k, causal=True, rope=False, **over):
     a = dict(t)
     a.update(over)
     return orc.forward(a["x"], a["W_Q"], a["W_K"], a["W_V"], a["W_O"], a["W_S"], a["W_D"],
-                       a["b_S"], a["b_D"], k=k, causal=causal)
+                       a["b_S"], a["b_D"], k=k, causal=causal, rope=rope)
 
 
 def _bwd(t, fwd, **over):
@@ -36,7 +36,7 @@ def _bwd(t, fwd, **over):
 # --------------------------------------------------------------------------------------
 # independent formulations
 # --------------------------------------------------------------------------------------
-def brute_force_layer(t, k, causal):
+def brute_force_layer(t, k, causal, rope=False):
     """Every expert computed densely for every token, unselected ones multiplied by 0;
     pure Python floats and loops (tiny inputs only).  Selection re-derived here with a
     plain scan: repeatedly take the largest remaining logit, lowest index on ties."""
@@ -77,6 +77,14 @@ def brute_force_layer(t, k, causal):
                               for d in range(dh)])
                     K.append([sum(mS[e] * sum(x[b][t_][i] * WK[h][e][i][d] for i in range(dm)) for e in range(E))
                               for d in range(dh)])
+            if rope:   # turn element pairs (2i, 2i+1) at position t_ by t_ * 10000^(-2i/dh); dh even here
+                for rows in (Q, K):
+                    for t_ in range(T):
+                        for i in range(dh // 2):
+                            ang = t_ * math.pow(10000.0, -2.0 * i / dh)
+                            a_, b_ = rows[t_][2 * i], rows[t_][2 * i + 1]
+                            rows[t_][2 * i] = a_ * math.cos(ang) - b_ * math.sin(ang)
+                            rows[t_][2 * i + 1] = a_ * math.sin(ang) + b_ * math.cos(ang)
             V = []
             for t_ in range(T):
                 m = gates(x[b][t_], WS, h)
@@ -118,7 +126,7 @@ def textbook_mha(x, W_Q, W_K, W_V, W_O, causal):
     return y
 
 
-def torch_dense_masked(t, idx_S, idx_D, causal, shared=False):
+def torch_dense_masked(t, idx_S, idx_D, causal, shared=False, rope=False):
     """Dense-masked SwitchHead in torch float64 with autograd: all experts for all tokens,
     times (selection mask) * sigmoid(logit).  The 0/1 masks are constants."""
     T64 = {n: (None if t[n] is None else torch.tensor(np.asarray(t[n], dtype=np.float64), requires_grad=True))
@@ -148,6 +156,13 @@ def torch_dense_masked(t, idx_S, idx_D, causal, shared=False):
         Q = torch.einsum("bti,heid,bthe->bhtd", x, T64["W_Q"], gD)
         K = torch.einsum("bti,heid,bthe->bhtd", x, T64["W_K"], gS)
     V = torch.einsum("bti,heid,bthe->bhtd", x, T64["W_V"], gS)
+    if rope:   # (p[2i] + i p[2i+1]) * exp(i t theta_i), the complex form of Su et al.
+        theta = torch.tensor([10000.0 ** (-2.0 * i / dh) for i in range(dh // 2)], dtype=torch.float64)
+        phase = torch.polar(torch.ones(T, dh // 2, dtype=torch.float64),
+                            torch.arange(T, dtype=torch.float64)[:, None] * theta[None, :])
+        turn = lambda P: torch.view_as_real(torch.view_as_complex(P.reshape(B, H, T, dh // 2, 2).contiguous()) * phase
+                                            ).reshape(B, H, T, dh)
+        Q, K = turn(Q), turn(K)
     L = Q @ K.transpose(-1, -2) / math.sqrt(dh)
     if causal:
         L = L + torch.triu(torch.full((T, T), float("-inf"), dtype=torch.float64), 1)
@@ -516,6 +531,87 @@ def test_expert_qk_backward_matches_autograd_and_differences(shared):
                 a2 = t[n].copy()
                 a2[pos] += sgn * eps
                 vals.append(float(np.sum(_fwd(t, 2, **{n: a2})["y"] * t["dy"])))
+            fd = (vals[0] - vals[1]) / (2 * eps)
+            assert abs(fd - g[gn][pos]) < 1e-6 * max(1.0, abs(fd)), (gn, pos, fd, g[gn][pos])
+
+
+# --------------------------------------------------------------------------------------
+# rotary position embedding of queries and keys (App. A.5; method of Su et al.)
+# --------------------------------------------------------------------------------------
+def test_rotary_closed_forms():
+    # d_head = 2: theta_0 = 1, so (1, 0) at position t becomes (cos t, sin t)
+    pos = np.array([0, 1, 2, 7])
+    got = orc.rotary(np.tile([1.0, 0.0], (4, 1)), pos)
+    assert np.allclose(got, np.stack([np.cos(pos), np.sin(pos)], axis=1), rtol=0, atol=1e-15)
+    # d_head = 4: the second pair turns a hundred times slower (10000^(-2/4) = 0.01)
+    got = orc.rotary(np.tile([0.0, 0.0, 0.0, 1.0], (4, 1)), pos)
+    assert np.allclose(got[:, 2], -np.sin(0.01 * pos), atol=1e-15) and np.allclose(got[:, 3], np.cos(0.01 * pos), atol=1e-15)
+    assert np.all(got[:, :2] == 0.0)
+    # position 0 is the identity; an odd last element is never touched; lengths are kept
+    P = np.random.default_rng(0).standard_normal((3, 5, 7))
+    R = orc.rotary(P, np.array([0, 3, 11, 12, 500]))
+    assert np.array_equal(R[:, 0], P[:, 0]) and np.array_equal(R[..., 6], P[..., 6])
+    assert np.allclose(np.linalg.norm(R, axis=-1), np.linalg.norm(P, axis=-1), rtol=1e-14)
+    # d = the even part of d_head: with d_head = 7 the pairs use exponents -2i/6
+    assert np.isclose(orc.rotary(np.eye(7)[2:3], np.array([1]))[0, 3], math.sin(10000.0 ** (-2.0 / 6.0)), atol=1e-16)
+
+
+def test_rotary_is_complex_multiplication_and_relative():
+    rng = np.random.default_rng(1)
+    dh, n = 12, 9
+    q, kk = rng.standard_normal((n, dh)), rng.standard_normal((n, dh))
+    pos = rng.integers(0, 2000, n)
+    theta = np.array([math.pow(10000.0, -2.0 * i / dh) for i in range(dh // 2)])
+    ref = (q[:, 0::2] + 1j * q[:, 1::2]) * np.exp(1j * pos[:, None] * theta[None, :])
+    got = orc.rotary(q, pos)
+    assert np.allclose(got[:, 0::2], ref.real, rtol=0, atol=1e-12) and np.allclose(got[:, 1::2], ref.imag, rtol=0, atol=1e-12)
+    # scores depend on the difference of positions only
+    pos2 = rng.integers(0, 2000, n)
+    s0 = np.sum(orc.rotary(q, pos) * orc.rotary(kk, pos2), axis=1)
+    s1 = np.sum(orc.rotary(q, pos + 77) * orc.rotary(kk, pos2 + 77), axis=1)
+    assert np.allclose(s0, s1, rtol=0, atol=1e-10)
+    # the inverse turn is the transpose: <R a, b> = <a, R^-1 b>, and it undoes the turn
+    assert np.allclose(orc.rotary(got, pos, inverse=True), q, rtol=0, atol=1e-12)
+    assert np.allclose(np.sum(got * kk, axis=1), np.sum(q * orc.rotary(kk, pos, inverse=True), axis=1), rtol=0, atol=1e-11)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("qk_experts", [0, 1])
+def test_rotary_layer_brute_force(causal, qk_experts):
+    cfg = dict(TINY, qk_experts=qk_experts)
+    t = _inputs(cfg, seed=41)
+    got = _fwd(t, 2, causal, rope=True)
+    ref = brute_force_layer(t, 2, causal, rope=True)
+    assert np.max(np.abs(got["y"] - ref)) < 1e-12 * max(1.0, np.max(np.abs(ref)))
+    assert np.max(np.abs(got["y"] - _fwd(t, 2, causal)["y"])) > 1e-3      # and it is not a no-op
+    # the first token of every sequence sits at position 0: its query and key are not turned
+    plain = _fwd(t, 2, causal)
+    assert np.array_equal(got["Q"][0::5], plain["Q"][0::5]) and np.array_equal(got["K"][0::5], plain["K"][0::5])
+
+
+@pytest.mark.parametrize("qk_experts", [0, 1])
+def test_rotary_backward_matches_autograd_and_differences(qk_experts):
+    cfg = dict(TINY, B=2, T=6, d_model=5, nheads=2, d_head=4, E=3, k=2, qk_experts=qk_experts, bias0=0.25)
+    t = {n: (None if a is None else a.astype(np.float64)) for n, a in make_inputs(cfg, seed=43).items()}
+    f = _fwd(t, 2, rope=True)
+    g = _bwd(t, f)
+    y, leaves = torch_dense_masked(t, f["idx_S"], f["idx_D"], True, rope=True)
+    assert np.allclose(y.detach().numpy(), f["y"], rtol=0, atol=1e-12)
+    (y * torch.tensor(t["dy"])).sum().backward()
+    for gn, n in zip(GRADS, NAMES):
+        ref = leaves[n].grad.numpy()
+        assert np.max(np.abs(g[gn] - ref)) <= 1e-11 * max(1.0, np.max(np.abs(ref))), gn
+    assert min(f["margin_S"].min(), f["margin_D"].min()) > 1e-4
+    rng = np.random.default_rng(2)
+    eps = 1e-6
+    for gn, n in (("dW_Q", "W_Q"), ("dW_K", "W_K"), ("dx", "x")):
+        for _ in range(5):
+            pos = tuple(rng.integers(0, s_) for s_ in t[n].shape)
+            vals = []
+            for sgn in (+1, -1):
+                a2 = t[n].copy()
+                a2[pos] += sgn * eps
+                vals.append(float(np.sum(_fwd(t, 2, rope=True, **{n: a2})["y"] * t["dy"])))
             fd = (vals[0] - vals[1]) / (2 * eps)
             assert abs(fd - g[gn][pos]) < 1e-6 * max(1.0, abs(fd)), (gn, pos, fd, g[gn][pos])
 
