@@ -62,6 +62,7 @@ def step_work(cfg):
         "fwd.y_cast": N * dm * (4 + es), "bwd.dx_cast": N * dm * (4 + es),
         "bwd.zero_dw": 4 * (2 * H * dm * dh + 2 * H * E * dm * dh),
         "bwd.router": 4 * H * N * k * 4 + N * 2 * H * E * es,
+        "fwd.rope": 4 * N * H * dh * es, "bwd.rope": 4 * N * H * dh * es,   # Q and K (dQ and dK) read and written
     }
     return flops, alu, nbytes
 
@@ -141,7 +142,7 @@ def cpu_baseline(cfg, budget_tokens):
     t = make_inputs(sub)
     t0 = time.perf_counter()
     f = orc.forward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], t["b_S"], t["b_D"],
-                    k=sub["k"], causal=bool(sub["causal"]))
+                    k=sub["k"], causal=bool(sub["causal"]), rope=bool(sub.get("rope")))
     t1 = time.perf_counter()
     orc.backward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], f, t["dy"])
     t2 = time.perf_counter()
@@ -164,6 +165,7 @@ def main():
     ap.add_argument("--config", default="c2", help="c1..c4 (c2 = the 262M-model-scale layer)")
     ap.add_argument("--qk-experts", action="store_true",
                     help="all four projections as expert mixtures (query and key banks like the value bank)")
+    ap.add_argument("--rope", action="store_true", help="rotary position embedding of queries and keys")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=1 << 20, help="token budget of the oracle sample (whole sequences)")
     ap.add_argument("--no-dense", action="store_true", help="skip the parameter-matched dense multi-head baseline")
@@ -194,6 +196,8 @@ def main():
     cfg = config(args.config)
     if args.qk_experts:
         cfg["qk_experts"] = 1
+    if args.rope:
+        cfg["rope"] = 1
     host = make_inputs(cfg)
     layer = DeviceLayer(cfg, host)
     N = cfg["B"] * cfg["T"]
@@ -246,7 +250,7 @@ def main():
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: B=%d T=%d d_model=%d nheads=%d d_head=%d E=%d k=%d causal=%d bias0=%g%s" % (
             cfg["name"], cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
-            cfg["causal"], cfg["bias0"], " qk_experts=1" if cfg.get("qk_experts") else ""), "tokens_per_step": N},
+            cfg["causal"], cfg["bias0"], (" qk_experts=1" if cfg.get("qk_experts") else "") + (" rope=1" if cfg.get("rope") else "")), "tokens_per_step": N},
         "roofline": roof,
         "extra": {
             "fwd_ms": ms_fwd, "fwd_tokens_per_s": N / (ms_fwd * 1e-3),

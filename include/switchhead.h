@@ -63,6 +63,12 @@ typedef struct {
                        [nheads, E, d_model, d_head] like W_V;
                        K^h = sum_{e in E_S^h} s_S^h[e] x W_K^{h,e} (source-side selection),
                        Q^h = sum_{e in E_D^h} s_D^h[e] x W_Q^{h,e} (destination side)      */
+  int32_t rope;     /* 1: rotary position embedding of queries and keys, as in the models of the
+                       paper's App. A.5 (method of Su et al.; square attention, no cache): the
+                       element pair (2i, 2i+1) of every head's query and key at position t (index
+                       in its sequence, from 0) turns by t * 10000^(-2i/d), d = the even part of
+                       d_head; an odd last element stays.  0: no position term (Sec. 2.2 as
+                       written)                                                            */
 } sh_shape;
 
 /* Bytes of workspace a forward (+ backward) call of this shape needs; 0 if the shape is

@@ -225,6 +225,10 @@ void launch_zero4_f32(float* p0, size_t n0, float* p1, size_t n1, float* p2, siz
 void launch_cast_from_f32(const float* src, void* dst, size_t n, int bf16, hipStream_t s);
 void launch_cast_to_f32(const void* src, float* dst, size_t n, int bf16, hipStream_t s);
 // out[i] = sum_h part[h*hstride + i] (+ add32[i]) for bf16 part/out; n must be a multiple of 8
+// Rotary position embedding (App. A.5; Su et al.): tab [T][dh/2] of (cos, sin); apply turns the pairs
+// (2i, 2i+1) of every row of up to two [N, H, dh] tensors in place, position = n % T.
+void launch_rope_table(float2* tab, int T, int dh, hipStream_t s);
+void launch_rope_apply(void* P0, void* P1, const float2* tab, long N, int T, int H, int dh, int inverse, int bf16, hipStream_t s);
 void launch_sum_heads(const void* part, const float* add32, void* out, size_t n, size_t hstride, int H, hipStream_t s);
 
 // out[n,h,:] = sum_j gate[h][n*k+j] * slots[h][n*k+j][:]   (slots [H, N*k, dh], storage type T)

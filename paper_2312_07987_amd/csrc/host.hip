@@ -66,6 +66,7 @@ struct Layout {
   size_t total = 0;
   size_t idx, gate, perm, offsets, Q, K, V, ctx, lse, pV;          // saved by forward
   size_t pQ, pK;                                                   // per-slot query / key rows (expert Q/K only)
+  size_t rope;                                                     // (cos, sin) table [T][dh/2] (rotary embedding only)
   size_t Z, blockcnt, acc32;                                       // forward scratch
   size_t setid, gset, gsort, setexp, setperm, setoff, setcnt, yh;
   size_t dR, wr3;                                                  // wide router dz rows [N, H*dh], routers packed [dm, dh]                 // expert-set path (bf16 only)
@@ -105,6 +106,7 @@ sh_status check_shape(const sh_shape* s) {
   if (s->dtype != SH_F32 && s->dtype != SH_BF16) return fail(SH_ERR_INVALID_ARG, "unknown dtype %d", s->dtype);
   if (s->causal != 0 && s->causal != 1) return fail(SH_ERR_INVALID_ARG, "causal must be 0 or 1");
   if (s->qk_experts != 0 && s->qk_experts != 1) return fail(SH_ERR_INVALID_ARG, "qk_experts must be 0 or 1");
+  if (s->rope != 0 && s->rope != 1) return fail(SH_ERR_INVALID_ARG, "rope must be 0 or 1");
   if (s->E > 64) return fail(SH_ERR_UNSUPPORTED, "E=%d exceeds the limit of 64", s->E);
   if (s->k > 8) return fail(SH_ERR_UNSUPPORTED, "k=%d exceeds the limit of 8", s->k);
   if (s->d_head > 256) return fail(SH_ERR_UNSUPPORTED, "d_head=%d exceeds the limit of 256", s->d_head);
@@ -136,6 +138,7 @@ Layout make_layout(const sh_shape* s) {
   L.lse = take(N * H * 4);
   L.pV = take(H * N * k * dh * esz);
   L.pQ = L.pK = 0;
+  L.rope = s->rope ? take((size_t)s->T * (dh / 2 > 0 ? dh / 2 : 1) * 8) : 0;
   if (s->qk_experts) {
     L.pQ = take(H * N * k * dh * esz);
     L.pK = take(H * N * k * dh * esz);
@@ -559,6 +562,13 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     }
   }
 
+  // rotary position embedding of queries and keys (App. A.5)
+  if (shape->rope) {
+    prof_mark(c.st, "fwd.rope");
+    launch_rope_table(c.p<float2>(c.L.rope), shape->T, dh, c.st);
+    launch_rope_apply(c.p<void>(c.L.Q), c.p<void>(c.L.K), c.p<float2>(c.L.rope), N, shape->T, H, dh, 0, c.bf16, c.st);
+  }
+
   // step 3: value experts, unscaled per-slot results, then the gate-weighted sum over slots
   {
     prof_mark(c.st, "fwd.v_experts");
@@ -769,6 +779,12 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       launch_mfma_attn_bwd(a, c.st);
     else
       launch_simt_attn_bwd(a, c.bf16, c.st);
+  }
+
+  // back through the rotation of queries and keys: gradients take the opposite turn
+  if (shape->rope) {
+    prof_mark(c.st, "bwd.rope");
+    launch_rope_apply(c.p<void>(c.L.dQ), c.p<void>(c.L.dK), c.p<float2>(c.L.rope), N, shape->T, H, dh, 1, c.bf16, c.st);
   }
 
   // dense queries and keys: weight gradients, then dx = dQ W_Q^T + dK W_K^T.  With the MFMA

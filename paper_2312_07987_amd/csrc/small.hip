@@ -104,6 +104,88 @@ void launch_sum_heads(const void* part, const float* add32, void* out, size_t n,
   if (n8) sum_heads_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, s>>>((const unsigned short*)part, add32, (unsigned short*)out, n8, hstride, H);
 }
 
+// ---- rotary position embedding of queries and keys (App. A.5 of the paper; method of Su et al.) ----
+// tab[t][i] = (cos, sin) of t * 10000^(-2i/d), d = 2*half: evaluated in fp64, stored in fp32
+__global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ tab, int T, int half) {
+  const long id = (long)blockIdx.x * 256 + threadIdx.x;
+  if (id >= (long)T * half) return;
+  const int t = (int)(id / half), i = (int)(id % half);
+  const double theta = pow(10000.0, -2.0 * (double)i / (double)(2 * half));
+  double sn, cs;
+  sincos((double)t * theta, &sn, &cs);
+  tab[id] = make_float2((float)cs, (float)sn);
+}
+
+// In place on up to two [N, H, dh] tensors: the pair (2i, 2i+1) of the row of token n (position n % T)
+// turns by +angle (sign = 1) or -angle (sign = -1, the transpose: what a gradient takes).
+template <typename TT>
+__global__ __launch_bounds__(256) void rope_apply_kernel(TT* __restrict__ P0, TT* __restrict__ P1, const float2* __restrict__ tab,
+                                                         long rows, int T, int H, int dh, int half, float sign) {
+  const long id = (long)blockIdx.x * 256 + threadIdx.x;
+  if (id >= rows * half) return;
+  TT* P = blockIdx.y ? P1 : P0;
+  const long row = id / half;
+  const int i = (int)(id % half);
+  const int t = (int)((row / H) % T);
+  const float2 cs = tab[(long)t * half + i];
+  const float c = cs.x, sn = sign * cs.y;
+  const long o = row * dh + 2 * i;
+  const float a = ld(P, o), b = ld(P, o + 1);
+  st(P, o, a * c - b * sn);
+  st(P, o + 1, a * sn + b * c);
+}
+
+// bf16 rows with dh % 8 == 0: 16 bytes (four pairs) per thread
+__global__ __launch_bounds__(256) void rope_apply_vec_kernel(unsigned short* __restrict__ P0, unsigned short* __restrict__ P1,
+                                                             const float2* __restrict__ tab, long rows, int T, int H, int dh,
+                                                             float sign) {
+  const int per_row = dh / 8;
+  const long id = (long)blockIdx.x * 256 + threadIdx.x;
+  if (id >= rows * per_row) return;
+  unsigned short* P = blockIdx.y ? P1 : P0;
+  const long row = id / per_row;
+  const int q = (int)(id % per_row);
+  const int t = (int)((row / H) % T);
+  const float4* tp = (const float4*)(tab + (long)t * (dh / 2) + q * 4);
+  const float4 t0 = tp[0], t1 = tp[1];
+  const float c[4] = {t0.x, t0.z, t1.x, t1.z};
+  const float sn[4] = {sign * t0.y, sign * t0.w, sign * t1.y, sign * t1.w};
+  uint4* ptr = (uint4*)(P + row * dh + q * 8);
+  const uint4 v = *ptr;
+  const unsigned w[4] = {v.x, v.y, v.z, v.w};
+  unsigned o[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const float a = __uint_as_float(w[u] << 16), b = __uint_as_float(w[u] & 0xffff0000u);
+    o[u] = pack_bf16x2(a * c[u] - b * sn[u], a * sn[u] + b * c[u]);
+  }
+  *ptr = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+void launch_rope_table(float2* tab, int T, int dh, hipStream_t s) {
+  const int half = dh / 2;
+  const long n = (long)T * half;
+  if (n) rope_table_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(tab, T, half);
+}
+
+void launch_rope_apply(void* P0, void* P1, const float2* tab, long N, int T, int H, int dh, int inverse, int bf16, hipStream_t s) {
+  const int half = dh / 2;
+  const long rows = N * H;
+  if (!half || !rows) return;
+  const float sign = inverse ? -1.f : 1.f;
+  const unsigned ny = P1 ? 2 : 1;
+  if (bf16 && dh % 8 == 0) {
+    dim3 g((unsigned)((rows * (dh / 8) + 255) / 256), ny);
+    rope_apply_vec_kernel<<<g, 256, 0, s>>>((unsigned short*)P0, (unsigned short*)P1, tab, rows, T, H, dh, sign);
+    return;
+  }
+  dim3 g((unsigned)((rows * half + 255) / 256), ny);
+  if (bf16)
+    rope_apply_kernel<bf16_t><<<g, 256, 0, s>>>((bf16_t*)P0, (bf16_t*)P1, tab, rows, T, H, dh, half, sign);
+  else
+    rope_apply_kernel<float><<<g, 256, 0, s>>>((float*)P0, (float*)P1, tab, rows, T, H, dh, half, sign);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -20,7 +20,7 @@ class DeviceLayer:
         self.tdtype = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
         self.shape = binding.make_shape(cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"],
                                         cfg["E"], cfg["k"], cfg.get("causal", 1), cfg["dtype"],
-                                        cfg.get("qk_experts", 0))
+                                        cfg.get("qk_experts", 0), cfg.get("rope", 0))
         up = lambda a, dt: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(self.dev).to(dt).contiguous()
         self.x = up(host["x"], self.tdtype)
         self.dy = up(host.get("dy"), self.tdtype)

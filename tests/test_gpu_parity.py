@@ -39,7 +39,7 @@ def run_case(cfg, family=0, shared=False, dense=False, backward=True, seed=None,
     finally:
         binding.switchhead_set_kernel_family(prev)
     f = orc.forward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], t["b_S"], t["b_D"],
-                    k=cfg["k"], causal=bool(cfg["causal"]))
+                    k=cfg["k"], causal=bool(cfg["causal"]), rope=bool(cfg.get("rope")))
     tol = TOL[cfg["dtype"]]
     # integer work: exact
     for s, side in enumerate("SD"):
@@ -152,6 +152,29 @@ def test_bf16_expert_queries_and_keys(family):
 def test_full_config_expert_queries_and_keys():
     """c2 at full size with query and key experts, in the launch configuration bench.py times."""
     run_case(small("c2", qk_experts=1), seed=30)
+
+
+@pytest.mark.parametrize("family", [0, 1])
+def test_fp32_rotary_queries_and_keys(family):
+    """Rotary position embedding (App. A.5), fp32: even, odd and ragged head widths, long sequences."""
+    run_case(small("c0", rope=1), family=family)
+    run_case(dict(name="ragrope", dtype="f32", B=2, T=37, d_model=50, nheads=3, d_head=21, E=7, k=3, causal=1, bias0=0.0,
+                  rope=1), family=family, seed=45)
+    run_case(dict(name="longrope", dtype="f32", B=1, T=1500, d_model=32, nheads=1, d_head=16, E=3, k=2, causal=1, bias0=0.0,
+                  rope=1, qk_experts=1), family=family, seed=46)
+
+
+@pytest.mark.parametrize("family", [0, 1])
+def test_bf16_rotary_queries_and_keys(family):
+    # the paper's rotary models: 2 heads of 64 (E=5, k=3, T=512) and 4 heads of 100 (E=4, k=2, T=1024)
+    run_case(small("c1", B=2, T=512, d_head=64, rope=1), family=family, seed=47)
+    run_case(small("c2", B=1, T=1024, nheads=4, d_head=100, E=4, k=2, rope=1), family=family, seed=48)
+    run_case(small("c2", B=2, T=130, d_model=256, nheads=2, rope=1, qk_experts=1, causal=0), family=family, seed=49)
+
+
+def test_full_config_rotary():
+    """c2 at full size with rotary queries and keys, in the launch configuration bench.py times."""
+    run_case(small("c2", rope=1), seed=50)
 
 
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
