@@ -15,6 +15,11 @@ What it computes, in the paper's notation (Sec. 2.1 and 2.2):
   A^h = softmax(Q^h K^h^T / sqrt(d_head))                        Sec. 2.1, first equation
   y   = sum_h sum_{e in E_D^h} s_D^h[e] A^h V^h W_O^{h,e}        output experts
 
+With `T_q` < T the attention is the rectangular one of the paper's Transformer-XL models
+(Sec. 3; App. A.2: keys and values of shape CT x d_head): x holds the cached positions
+followed by the current chunk; keys, values and the source-side selection exist for all T
+positions, queries, the destination-side selection and the output only for the last T_q.
+
 Everything is plain numpy float64, written as the definitions read: no blocking, no
 fusion, no reordering.  The paper gives no backward pass; `backward` is the chain rule
 applied to the six forward steps (the top-k selection is piecewise constant, so only the
@@ -132,18 +137,21 @@ def rotary(P, pos, inverse=False):
 
 
 def _attention_matrix(Qbh, Kbh, causal):
-    """A = softmax(Q K^T / sqrt(d_head)) for one (sequence, head); Sec. 2.1."""
-    T, dh = Qbh.shape
+    """A = softmax(Q K^T / sqrt(d_head)) for one (sequence, head); Sec. 2.1.  With fewer
+    queries than keys the queries are the LAST positions of the sequence (cached context in
+    front, App. A.2): query i sits at position (Tk - Tq) + i and, if causal, sees the keys up
+    to and including its own position."""
+    Tq, dh = Qbh.shape
+    Tk = Kbh.shape[0]
     S = (Qbh @ Kbh.T) / np.sqrt(float(dh))
     if causal:
-        t = np.arange(T)
-        S = np.where(t[None, :] <= t[:, None], S, -np.inf)
+        S = np.where(np.arange(Tk)[None, :] <= (np.arange(Tq) + (Tk - Tq))[:, None], S, -np.inf)
     S = S - S.max(axis=-1, keepdims=True)
     P = np.exp(S)
     return P / P.sum(axis=-1, keepdims=True)
 
 
-def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, causal=True, rope=False):
+def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, causal=True, rope=False, T_q=None):
     """One SwitchHead layer call.
 
     x [B,T,dm]; W_Q, W_K [H,dm,dh]; W_V [H,E,dm,dh]; W_O [H,E,dh,dm];
@@ -155,6 +163,8 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
                  (Sec. 3.5).
     W_S None  -> dense multi-head attention (requires E == 1; every gate is exactly 1;
                  Sec. 2.1, per-head-sum form of the output).
+    T_q (None = T): only the last T_q positions of every sequence are queries; y is
+    [B,T_q,dm], the destination-side tables cover B*T_q tokens, the source side all B*T.
     Returns a dict with y and every intermediate the backward pass and the tests need.
     """
     x, W_Q, W_K, W_V, W_O = map(_f64, (x, W_Q, W_K, W_V, W_O))
@@ -163,47 +173,52 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
     dh = W_V.shape[3]
     N = B * T
     x2 = x.reshape(N, dm)
+    Tq = T if T_q is None else int(T_q)
+    assert 1 <= Tq <= T
+    Nq = B * Tq
+    xq2 = x[:, T - Tq:, :].reshape(Nq, dm)        # the destination (query) tokens
 
-    # step 1: routers (Sec. 2.2)
+    # step 1: routers (Sec. 2.2): source side over every token, destination side over the queries
     if W_S is None:
         assert E == 1 and k == 1
         zS = zD = None
-        idx_S = idx_D = np.zeros((H, N, 1), dtype=np.int32)
-        g_S = g_D = np.ones((H, N, 1))
-        mar_S = mar_D = np.full((H, N), np.inf)
+        idx_S, idx_D = np.zeros((H, N, 1), dtype=np.int32), np.zeros((H, Nq, 1), dtype=np.int32)
+        g_S, g_D = np.ones((H, N, 1)), np.ones((H, Nq, 1))
+        mar_S, mar_D = np.full((H, N), np.inf), np.full((H, Nq), np.inf)
     else:
         zS = router_logits(x2, W_S, b_S)
         idx_S, g_S, mar_S = select_topk(zS, H, k)
-        if W_D is None:
+        if W_D is None and Tq == T:
             zD, idx_D, g_D, mar_D = zS, idx_S, g_S, mar_S
         else:
-            zD = router_logits(x2, W_D, b_D)
+            # shared selection with fewer queries: the same router evaluated on the query tokens
+            zD = router_logits(xq2, W_S if W_D is None else W_D, b_S if W_D is None else b_D)
             idx_D, g_D, mar_D = select_topk(zD, H, k)
 
     # step 2: queries and keys
     assert W_Q.ndim == W_K.ndim
     if W_Q.ndim == 3:
         # dense, one copy per head
-        Q = np.stack([x2 @ W_Q[h] for h in range(H)], axis=1)       # [N,H,dh]
-        K = np.stack([x2 @ W_K[h] for h in range(H)], axis=1)
+        Q = np.stack([xq2 @ W_Q[h] for h in range(H)], axis=1)      # [Nq,H,dh]
+        K = np.stack([x2 @ W_K[h] for h in range(H)], axis=1)       # [N,H,dh]
     else:
         # K^h = sum_{e in E_S} s_S[e] x W_K^{h,e};  Q^h = sum_{e in E_D} s_D[e] x W_Q^{h,e}
-        Q, K = np.zeros((N, H, dh)), np.zeros((N, H, dh))
+        Q, K = np.zeros((Nq, H, dh)), np.zeros((N, H, dh))
         for h in range(H):
             for j in range(k):
                 for e in range(E):
                     rows = np.nonzero(idx_D[h, :, j] == e)[0]
                     if rows.size:
-                        Q[rows, h, :] += g_D[h, rows, j][:, None] * (x2[rows] @ W_Q[h, e])
+                        Q[rows, h, :] += g_D[h, rows, j][:, None] * (xq2[rows] @ W_Q[h, e])
                     rows = np.nonzero(idx_S[h, :, j] == e)[0]
                     if rows.size:
                         K[rows, h, :] += g_S[h, rows, j][:, None] * (x2[rows] @ W_K[h, e])
 
     # rotary position embedding of queries and keys (App. A.5), position = index in the sequence
     if rope:
-        pos = np.tile(np.arange(T), B)
+        pos, posq = np.tile(np.arange(T), B), np.tile(np.arange(T - Tq, T), B)
         for h in range(H):
-            Q[:, h, :] = rotary(Q[:, h, :], pos)
+            Q[:, h, :] = rotary(Q[:, h, :], posq)
             K[:, h, :] = rotary(K[:, h, :], pos)
 
     # step 3: V^h = sum_{e in E_S} s_S[e] x W_V^{h,e}
@@ -216,15 +231,15 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
                     V[rows, h, :] += g_S[h, rows, j][:, None] * (x2[rows] @ W_V[h, e])
 
     # step 4: one attention matrix per (sequence, head)
-    ctx = np.zeros((N, H, dh))
+    ctx = np.zeros((Nq, H, dh))
     for b in range(B):
-        sl = slice(b * T, (b + 1) * T)
+        sl, sq = slice(b * T, (b + 1) * T), slice(b * Tq, (b + 1) * Tq)
         for h in range(H):
-            A = _attention_matrix(Q[sl, h], K[sl, h], causal)
-            ctx[sl, h, :] = A @ V[sl, h]
+            A = _attention_matrix(Q[sq, h], K[sl, h], causal)
+            ctx[sq, h, :] = A @ V[sl, h]
 
     # step 5: y = sum_h sum_{e in E_D} s_D[e] (A V) W_O^{h,e}
-    y = np.zeros((N, dm))
+    y = np.zeros((Nq, dm))
     for h in range(H):
         for j in range(k):
             for e in range(E):
@@ -240,10 +255,12 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
         tabs["offsets_" + name] = np.stack(of)
         tabs["inv_" + name] = np.stack(iv)
 
-    out = dict(y=y.reshape(B, T, dm), Q=Q, K=K, V=V, ctx=ctx, zS=zS, zD=zD,
+    out = dict(y=y.reshape(B, Tq, dm), T_q=Tq, Q=Q, K=K, V=V, ctx=ctx, zS=zS, zD=zD,
                idx_S=idx_S, idx_D=idx_D, gate_S=g_S, gate_D=g_D,
                margin_S=mar_S, margin_D=mar_D, k=k, causal=causal, rope=bool(rope),
                shared=(W_S is not None and W_D is None), dense=(W_S is None))
+    # (with shared selection and T_q < T the destination tables are the source router's, evaluated on
+    #  the query tokens: the same numbers as the source tables' rows of those tokens)
     out.update(tabs)
     return out
 
@@ -263,7 +280,11 @@ def backward(x, W_Q, W_K, W_V, W_O, W_S, W_D, fwd, dy):
     dh = W_V.shape[3]
     N = B * T
     k, causal = fwd["k"], fwd["causal"]
-    x2, dy2 = x.reshape(N, dm), dy.reshape(N, dm)
+    Tq = fwd.get("T_q", T)
+    Nq = B * Tq
+    qrows = (np.arange(B)[:, None] * T + np.arange(T - Tq, T)[None, :]).reshape(-1)   # query tokens' rows of x
+    x2, dy2 = x.reshape(N, dm), dy.reshape(Nq, dm)
+    xq2 = x2[qrows]
     Q, K, V, ctx = fwd["Q"], fwd["K"], fwd["V"], fwd["ctx"]
     idx_S, idx_D, g_S, g_D = fwd["idx_S"], fwd["idx_D"], fwd["gate_S"], fwd["gate_D"]
 
@@ -272,8 +293,8 @@ def backward(x, W_Q, W_K, W_V, W_O, W_S, W_D, fwd, dy):
     dW_V, dW_O = np.zeros_like(W_V), np.zeros_like(W_O)
 
     # output experts: y[n] = sum_h sum_j gD * ctx[n,h] W_O[h,e_j]
-    dgD = np.zeros((H, N, k))
-    dctx = np.zeros((N, H, dh))
+    dgD = np.zeros((H, Nq, k))
+    dctx = np.zeros((Nq, H, dh))
     for h in range(H):
         for j in range(k):
             for e in range(E):
@@ -290,20 +311,20 @@ def backward(x, W_Q, W_K, W_V, W_O, W_S, W_D, fwd, dy):
     dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
     scale = 1.0 / np.sqrt(float(dh))
     for b in range(B):
-        sl = slice(b * T, (b + 1) * T)
+        sl, sq = slice(b * T, (b + 1) * T), slice(b * Tq, (b + 1) * Tq)
         for h in range(H):
-            A = _attention_matrix(Q[sl, h], K[sl, h], causal)
-            dV[sl, h] = A.T @ dctx[sl, h]
-            dA = dctx[sl, h] @ V[sl, h].T
+            A = _attention_matrix(Q[sq, h], K[sl, h], causal)
+            dV[sl, h] = A.T @ dctx[sq, h]
+            dA = dctx[sq, h] @ V[sl, h].T
             dS = A * (dA - np.sum(dA * A, axis=-1, keepdims=True))
-            dQ[sl, h] = (dS @ K[sl, h]) * scale
-            dK[sl, h] = (dS.T @ Q[sl, h]) * scale
+            dQ[sq, h] = (dS @ K[sl, h]) * scale
+            dK[sl, h] = (dS.T @ Q[sq, h]) * scale
 
     # back through the rotation of queries and keys: the transpose of a rotation is the opposite turn
     if fwd.get("rope"):
-        pos = np.tile(np.arange(T), B)
+        pos, posq = np.tile(np.arange(T), B), np.tile(np.arange(T - Tq, T), B)
         for h in range(H):
-            dQ[:, h, :] = rotary(dQ[:, h, :], pos, inverse=True)
+            dQ[:, h, :] = rotary(dQ[:, h, :], posq, inverse=True)
             dK[:, h, :] = rotary(dK[:, h, :], pos, inverse=True)
 
     # value experts: V[n,h] = sum_j gS * x[n] W_V[h,e_j]
@@ -323,13 +344,16 @@ def backward(x, W_Q, W_K, W_V, W_O, W_S, W_D, fwd, dy):
     if W_Q.ndim == 3:
         # dense queries and keys
         for h in range(H):
-            dW_Q[h] = x2.T @ dQ[:, h, :]
+            dW_Q[h] = xq2.T @ dQ[:, h, :]
             dW_K[h] = x2.T @ dK[:, h, :]
-            dx += dQ[:, h, :] @ W_Q[h].T + dK[:, h, :] @ W_K[h].T
+            dx += dK[:, h, :] @ W_K[h].T
+            dx[qrows] += dQ[:, h, :] @ W_Q[h].T
     else:
         # expert queries (destination-side gates) and keys (source-side gates): same pattern as
         # the value experts; the gates collect one more term each
-        for W, dW, dP, idx, g_, dg in ((W_Q, dW_Q, dQ, idx_D, g_D, dgD), (W_K, dW_K, dK, idx_S, g_S, dgS)):
+        allrows = np.arange(N)
+        for W, dW, dP, idx, g_, dg, xs, xrow in ((W_Q, dW_Q, dQ, idx_D, g_D, dgD, xq2, qrows),
+                                                 (W_K, dW_K, dK, idx_S, g_S, dgS, x2, allrows)):
             for h in range(H):
                 for j in range(k):
                     for e in range(E):
@@ -337,30 +361,33 @@ def backward(x, W_Q, W_K, W_V, W_O, W_S, W_D, fwd, dy):
                         if not rows.size:
                             continue
                         g = g_[h, rows, j][:, None]
-                        P2 = x2[rows] @ W[h, e]                            # [r, dh]
+                        P2 = xs[rows] @ W[h, e]                            # [r, dh]
                         dg[h, rows, j] += np.sum(P2 * dP[rows, h, :], axis=1)
-                        dW[h, e] += (g * x2[rows]).T @ dP[rows, h, :]
-                        dx[rows] += g * (dP[rows, h, :] @ W[h, e].T)
+                        dW[h, e] += (g * xs[rows]).T @ dP[rows, h, :]
+                        dx[xrow[rows]] += g * (dP[rows, h, :] @ W[h, e].T)
 
     # routers: g = sigmoid(z) at the selected entries, nothing elsewhere
     dW_S = dW_D = db_S = db_D = None
     if not fwd["dense"]:
         def dz_of(idx, g, dg):
-            dz = np.zeros((N, H * E))
+            n = idx.shape[1]
+            dz = np.zeros((n, H * E))
             for h in range(H):
                 for j in range(k):
-                    dz[np.arange(N), h * E + idx[h, :, j]] += dg[h, :, j] * g[h, :, j] * (1.0 - g[h, :, j])
+                    dz[np.arange(n), h * E + idx[h, :, j]] += dg[h, :, j] * g[h, :, j] * (1.0 - g[h, :, j])
             return dz
         dzS = dz_of(idx_S, g_S, dgS)
         dzD = dz_of(idx_D, g_D, dgD)
         if fwd["shared"]:
-            dzS = dzS + dzD
-            dW_S, db_S = x2.T @ dzS, dzS.sum(axis=0)
+            # one router serves both sides: its gradient collects both (the query tokens' rows twice)
+            dW_S, db_S = x2.T @ dzS + xq2.T @ dzD, dzS.sum(axis=0) + dzD.sum(axis=0)
             dx += dzS @ W_S.T
+            dx[qrows] += dzD @ W_S.T
         else:
             dW_S, db_S = x2.T @ dzS, dzS.sum(axis=0)
-            dW_D, db_D = x2.T @ dzD, dzD.sum(axis=0)
-            dx += dzS @ W_S.T + dzD @ W_D.T
+            dW_D, db_D = xq2.T @ dzD, dzD.sum(axis=0)
+            dx += dzS @ W_S.T
+            dx[qrows] += dzD @ W_D.T
 
     return dict(dx=dx.reshape(B, T, dm), dW_Q=dW_Q, dW_K=dW_K, dW_V=dW_V, dW_O=dW_O,
                 dW_S=dW_S, dW_D=dW_D, db_S=db_S, db_D=db_D,

@@ -20,11 +20,11 @@ def _inputs(cfg, seed=7):
     return make_inputs(cfg, seed=seed)
 
 
-def _fwd(t, k, causal=True, rope=False, **over):
+def _fwd(t, k, causal=True, rope=False, T_q=None, **over):
     a = dict(t)
     a.update(over)
     return orc.forward(a["x"], a["W_Q"], a["W_K"], a["W_V"], a["W_O"], a["W_S"], a["W_D"],
-                       a["b_S"], a["b_D"], k=k, causal=causal, rope=rope)
+                       a["b_S"], a["b_D"], k=k, causal=causal, rope=rope, T_q=T_q)
 
 
 def _bwd(t, fwd, **over):
@@ -36,7 +36,7 @@ def _bwd(t, fwd, **over):
 # --------------------------------------------------------------------------------------
 # independent formulations
 # --------------------------------------------------------------------------------------
-def brute_force_layer(t, k, causal, rope=False):
+def brute_force_layer(t, k, causal, rope=False, T_q=None):
     """Every expert computed densely for every token, unselected ones multiplied by 0;
     pure Python floats and loops (tiny inputs only).  Selection re-derived here with a
     plain scan: repeatedly take the largest remaining logit, lowest index on ties."""
@@ -64,6 +64,7 @@ def brute_force_layer(t, k, causal, rope=False):
         return m
 
     y = [[[0.0] * dm for _ in range(T)] for _ in range(B)]
+    first_q = 0 if T_q is None else T - T_q     # positions before it are cached context: keys and values only
     for b in range(B):
         for h in range(H):
             if np.ndim(t["W_Q"]) == 3:
@@ -90,7 +91,7 @@ def brute_force_layer(t, k, causal, rope=False):
                 m = gates(x[b][t_], WS, h)
                 V.append([sum(m[e] * sum(x[b][t_][i] * WV[h][e][i][d] for i in range(dm)) for e in range(E))
                           for d in range(dh)])
-            for t_ in range(T):
+            for t_ in range(first_q, T):
                 last = t_ if causal else T - 1
                 logit = [sum(Q[t_][d] * K[u][d] for d in range(dh)) / math.sqrt(dh) for u in range(last + 1)]
                 mx = max(logit)
@@ -102,7 +103,7 @@ def brute_force_layer(t, k, causal, rope=False):
                     if m[e] != 0.0:
                         for cc in range(dm):
                             y[b][t_][cc] += m[e] * sum(c[d] * WO[h][e][d][cc] for d in range(dh))
-    return np.array(y)
+    return np.array(y)[:, first_q:, :]
 
 
 def textbook_mha(x, W_Q, W_K, W_V, W_O, causal):
@@ -614,6 +615,56 @@ def test_rotary_backward_matches_autograd_and_differences(qk_experts):
                 vals.append(float(np.sum(_fwd(t, 2, rope=True, **{n: a2})["y"] * t["dy"])))
             fd = (vals[0] - vals[1]) / (2 * eps)
             assert abs(fd - g[gn][pos]) < 1e-6 * max(1.0, abs(fd)), (gn, pos, fd, g[gn][pos])
+
+
+# --------------------------------------------------------------------------------------
+# fewer queries than keys: the Transformer-XL-style attention over a cached context (App. A.2)
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("variant", [dict(), dict(qk_experts=1), dict(rope=1), dict(shared=1)])
+def test_fewer_queries_equal_the_last_rows_of_the_square_layer(causal, variant):
+    """Dropping the queries of the cached positions changes nothing for the remaining ones: output,
+    selections and every gradient (upstream gradient zero on the dropped rows) are those of the
+    square layer, which the pins above hold in place."""
+    v = dict(variant)
+    shared, rope = bool(v.pop("shared", 0)), bool(v.pop("rope", 0))
+    cfg = dict(TINY, B=2, T=7, d_model=6, nheads=2, d_head=4, E=4, k=2, bias0=0.25, **v)
+    t = {n: (None if a is None else a.astype(np.float64)) for n, a in make_inputs(cfg, seed=51, shared_router=shared).items()}
+    Tq, T = 3, 7
+    sq = _fwd(t, 2, causal, rope=rope)
+    re = _fwd(t, 2, causal, rope=rope, T_q=Tq)
+    qrows = (np.arange(2)[:, None] * T + np.arange(T - Tq, T)[None, :]).reshape(-1)
+    assert re["y"].shape == (2, Tq, 6)
+    assert np.allclose(re["y"], sq["y"][:, T - Tq:], rtol=0, atol=1e-13)
+    assert np.array_equal(re["idx_D"], sq["idx_D"][:, qrows]) and np.array_equal(re["idx_S"], sq["idx_S"])
+    assert np.allclose(re["Q"], sq["Q"][qrows], rtol=0, atol=1e-13) and np.allclose(re["K"], sq["K"], rtol=0, atol=1e-13)
+    assert np.allclose(re["ctx"], sq["ctx"][qrows], rtol=0, atol=1e-13)
+    assert re["perm_D"].shape == (2, 2 * Tq * 2) and re["offsets_D"][:, -1].tolist() == [2 * Tq * 2] * 2
+    dy_q = t["dy"][:, T - Tq:]
+    dy_pad = np.zeros_like(t["dy"])
+    dy_pad[:, T - Tq:] = dy_q
+    g_re = _bwd(t, re, dy=dy_q)
+    g_sq = _bwd(t, sq, dy=dy_pad)
+    for gn in GRADS:
+        if g_sq[gn] is None:
+            assert g_re[gn] is None
+            continue
+        assert g_re[gn].shape == g_sq[gn].shape
+        assert np.max(np.abs(g_re[gn] - g_sq[gn])) <= 1e-12 * max(1.0, np.max(np.abs(g_sq[gn]))), gn
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_fewer_queries_brute_force_and_single_query(causal):
+    cfg = dict(TINY, qk_experts=0)
+    t = _inputs(cfg, seed=53)
+    got = _fwd(t, 2, causal, rope=True, T_q=2)
+    ref = brute_force_layer(t, 2, causal, rope=True, T_q=2)
+    assert ref.shape == (2, 2, 6)
+    assert np.max(np.abs(got["y"] - ref)) < 1e-12 * max(1.0, np.max(np.abs(ref)))
+    # one query at the last position sees every key either way
+    a = _fwd(t, 2, True, T_q=1)["y"]
+    b = _fwd(t, 2, False, T_q=1)["y"]
+    assert np.array_equal(a, b)
 
 
 def test_bf16_rounding_is_nearest_even():
