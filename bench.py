@@ -30,27 +30,31 @@ def step_work(cfg):
     """Algorithmic flops (MFMA-bound steps) and bytes (HBM-bound steps) per launch of each step."""
     B, T, dm, H, dh, E, k = (cfg[s] for s in ("B", "T", "d_model", "nheads", "d_head", "E", "k"))
     N = B * T
+    Tq = cfg.get("T_q") or T              # queries per sequence (destination-side tokens)
+    Nq = B * Tq
     es = 2 if cfg["dtype"] == "bf16" else 4
-    pairs = T * (T + 1) // 2 if cfg["causal"] else T * T
+    pairs = Tq * (T - Tq) + Tq * (Tq + 1) // 2 if cfg["causal"] else Tq * T
     proj = 2 * N * dm * H * dh
+    proj_q = 2 * Nq * dm * H * dh
     expert = 2 * N * k * dm * H * dh
+    expert_q = 2 * Nq * k * dm * H * dh
     attn = 4 * B * H * dh * pairs
-    router = 2 * N * dm * 2 * H * E
+    router = 2 * (N + Nq) * dm * H * E
     slots = N * H * k * dh * 4
     flops = {
-        "fwd.q_proj": proj, "fwd.k_proj": proj, "fwd.qk_proj": 2 * proj, "bwd.qk_dgrad": 2 * proj,
-        "fwd.v_experts": expert, "fwd.o_experts": expert,
+        "fwd.q_proj": proj_q, "fwd.k_proj": proj, "fwd.qk_proj": 2 * proj, "bwd.qk_dgrad": proj + (proj if Tq == T else 0),
+        "fwd.v_experts": expert, "fwd.o_experts": expert_q,
         "fwd.attention": attn, "bwd.attention": 5 * attn // 2,
         # backward attention = 5 matmuls of attn/2 flops each: S and dP (shared), dV, dK, dQ; the dK/dV
         # kernel is credited with four of them, the dQ kernel with dQ alone (its recomputation of S and
         # dP is not algorithmic work)
         "bwd.attention_dkv": 2 * attn, "bwd.attention_dq": attn // 2,
-        "bwd.o_dgrad": expert, "bwd.o_wgrad": expert, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
-        "bwd.q_wgrad": proj, "bwd.k_wgrad": proj, "bwd.qk_wgrad": 2 * proj, "bwd.q_dgrad": proj, "bwd.k_dgrad": proj,
+        "bwd.o_dgrad": expert_q, "bwd.o_wgrad": expert_q, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
+        "bwd.q_wgrad": proj_q, "bwd.k_wgrad": proj, "bwd.qk_wgrad": proj + proj_q, "bwd.q_dgrad": proj_q, "bwd.k_dgrad": proj,
         "bwd.router_wgrad": router // 2, "bwd.router_dgrad": router // 2,
         # query / key expert banks (all-expert form): each step has the shape of its value-expert twin
-        "fwd.q_experts": expert, "fwd.k_experts": expert, "bwd.q_wgrad_e": expert, "bwd.k_wgrad_e": expert,
-        "bwd.q_dgrad_e": expert, "bwd.k_dgrad_e": expert,
+        "fwd.q_experts": expert_q, "fwd.k_experts": expert, "bwd.q_wgrad_e": expert_q, "bwd.k_wgrad_e": expert,
+        "bwd.q_dgrad_e": expert_q, "bwd.k_dgrad_e": expert,
     }
     alu = {"fwd.router": router}
     nbytes = {
@@ -142,9 +146,10 @@ def cpu_baseline(cfg, budget_tokens):
     t = make_inputs(sub)
     t0 = time.perf_counter()
     f = orc.forward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], t["b_S"], t["b_D"],
-                    k=sub["k"], causal=bool(sub["causal"]), rope=bool(sub.get("rope")))
+                    k=sub["k"], causal=bool(sub["causal"]), rope=bool(sub.get("rope")), T_q=sub.get("T_q"))
     t1 = time.perf_counter()
-    orc.backward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], f, t["dy"])
+    orc.backward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], f,
+                 t["dy"][:, sub["T"] - (sub.get("T_q") or sub["T"]):])
     t2 = time.perf_counter()
     try:
         from threadpoolctl import threadpool_info
@@ -166,6 +171,9 @@ def main():
     ap.add_argument("--qk-experts", action="store_true",
                     help="all four projections as expert mixtures (query and key banks like the value bank)")
     ap.add_argument("--rope", action="store_true", help="rotary position embedding of queries and keys")
+    ap.add_argument("--context", type=int, default=1,
+                    help="C >= 1: keys and values over C chunks of the config's T positions (C - 1 cached chunks in "
+                         "front), queries for the last chunk only; tokens/s counts the current chunk's tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=1 << 20, help="token budget of the oracle sample (whole sequences)")
     ap.add_argument("--no-dense", action="store_true", help="skip the parameter-matched dense multi-head baseline")
@@ -198,9 +206,12 @@ def main():
         cfg["qk_experts"] = 1
     if args.rope:
         cfg["rope"] = 1
+    if args.context > 1:
+        cfg["T_q"] = cfg["T"]
+        cfg["T"] = args.context * cfg["T"]
     host = make_inputs(cfg)
     layer = DeviceLayer(cfg, host)
-    N = cfg["B"] * cfg["T"]
+    N = cfg["B"] * (cfg.get("T_q") or cfg["T"])   # tokens that get an output
 
     def step():
         layer.forward()
@@ -238,7 +249,7 @@ def main():
     roof["traffic"] = measured_traffic(cfg["name"], dom)
 
     lf = layer_flops(cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
-                     bool(cfg["causal"]), qk_experts=bool(cfg.get("qk_experts")))
+                     bool(cfg["causal"]), qk_experts=bool(cfg.get("qk_experts")), T_q=cfg.get("T_q"))
     counts = layer.routing()["offsets"]
     out = {
         "metric": "switchhead_layer_fwd_bwd_tokens_per_s",
@@ -250,7 +261,8 @@ def main():
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: B=%d T=%d d_model=%d nheads=%d d_head=%d E=%d k=%d causal=%d bias0=%g%s" % (
             cfg["name"], cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
-            cfg["causal"], cfg["bias0"], (" qk_experts=1" if cfg.get("qk_experts") else "") + (" rope=1" if cfg.get("rope") else "")), "tokens_per_step": N},
+            cfg["causal"], cfg["bias0"], (" qk_experts=1" if cfg.get("qk_experts") else "") + (" rope=1" if cfg.get("rope") else "") +
+            (" T_q=%d" % cfg["T_q"] if cfg.get("T_q") else "")), "tokens_per_step": N},
         "roofline": roof,
         "extra": {
             "fwd_ms": ms_fwd, "fwd_tokens_per_s": N / (ms_fwd * 1e-3),

@@ -69,6 +69,21 @@ typedef struct {
                        in its sequence, from 0) turns by t * 10000^(-2i/d), d = the even part of
                        d_head; an odd last element stays.  0: no position term (Sec. 2.2 as
                        written)                                                            */
+  int32_t T_q;      /* queries per sequence; 0 or T: every position is a query (square attention).
+                       0 < T_q < T: attention over a cached context as in the paper's
+                       Transformer-XL models (Sec. 3; App. A.2, keys and values of shape CT x d_head):
+                       x holds the cached positions followed by the current chunk; keys, values
+                       and the source-side selection are computed for all T positions, queries,
+                       the destination-side selection and the output only for the last T_q;
+                       query i sees keys u <= (T - T_q) + i when causal, and rotary positions
+                       count from the start of x.  Then y and dy are [B, T_q, d_model]; dx stays
+                       [B, T, d_model] and is the full gradient (a trainer that treats the cache
+                       as constant ignores its first T - T_q rows); in the routing tables and
+                       intermediates the destination-side blocks and Q, ctx keep their place but
+                       hold B*T_q tokens, packed at the front of the block.  With shared
+                       selection the one router is evaluated on the query tokens for the
+                       destination side, and its gradients collect both sides.  No relative
+                       position term is added (the paper does not define one)               */
 } sh_shape;
 
 /* Bytes of workspace a forward (+ backward) call of this shape needs; 0 if the shape is

@@ -23,7 +23,7 @@ EXPORTS = ("switchhead_workspace_bytes", "switchhead_forward", "switchhead_backw
 
 class sh_shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("B", "T", "d_model", "nheads", "d_head", "E", "k", "causal", "dtype", "qk_experts", "rope")]
+                ("B", "T", "d_model", "nheads", "d_head", "E", "k", "causal", "dtype", "qk_experts", "rope", "T_q")]
 
 
 class SwitchHeadError(RuntimeError):
@@ -73,9 +73,9 @@ def lib():
     return L
 
 
-def make_shape(B, T, d_model, nheads, d_head, E, k, causal=1, dtype="bf16", qk_experts=0, rope=0):
+def make_shape(B, T, d_model, nheads, d_head, E, k, causal=1, dtype="bf16", qk_experts=0, rope=0, T_q=0):
     code = {"f32": SH_F32, "fp32": SH_F32, "bf16": SH_BF16}[dtype] if isinstance(dtype, str) else int(dtype)
-    return sh_shape(B, T, d_model, nheads, d_head, E, k, int(causal), code, int(qk_experts), int(rope))
+    return sh_shape(B, T, d_model, nheads, d_head, E, k, int(causal), code, int(qk_experts), int(rope), int(T_q))
 
 
 def _ptr(t):

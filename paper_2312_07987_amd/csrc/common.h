@@ -166,6 +166,9 @@ struct AttnArgs {
   float* lse;
   int B, T, H, dh, causal;
   float scale;  // 1/sqrt(dh)
+  // queries per sequence; 0 = T.  With Tq < T the queries are the last Tq positions (cached context in
+  // front): Q, O, lse have Tq rows per sequence, K, V have T, and query i sees keys <= i + (T - Tq).
+  int Tq;
 };
 
 struct AttnBwdArgs {
@@ -174,6 +177,7 @@ struct AttnBwdArgs {
   void *dQ, *dK, *dV;
   int B, T, H, dh, causal;
   float scale;
+  int Tq;   // as in AttnArgs: Q, dO, dQ, lse, delta have Tq rows per sequence, K, V, dK, dV have T
 };
 
 // ----------------------------------------------------------------------------------------
@@ -228,7 +232,11 @@ void launch_cast_to_f32(const void* src, float* dst, size_t n, int bf16, hipStre
 // Rotary position embedding (App. A.5; Su et al.): tab [T][dh/2] of (cos, sin); apply turns the pairs
 // (2i, 2i+1) of every row of up to two [N, H, dh] tensors in place, position = n % T.
 void launch_rope_table(float2* tab, int T, int dh, hipStream_t s);
-void launch_rope_apply(void* P0, void* P1, const float2* tab, long N, int T, int H, int dh, int inverse, int bf16, hipStream_t s);
+// (T rows per sequence, the first of them at position pos0)
+void launch_rope_apply(void* P0, void* P1, const float2* tab, long N, int T, int pos0, int H, int dh, int inverse, int bf16,
+                       hipStream_t s);
+// out [B, T, dm] (storage type) += add [B, Tq, dm] (fp32) on the last Tq rows of every sequence
+void launch_add_query_rows(void* out, const float* add, long rows, int T, int Tq, int dm, int bf16, hipStream_t s);
 void launch_sum_heads(const void* part, const float* add32, void* out, size_t n, size_t hstride, int H, hipStream_t s);
 
 // out[n,h,:] = sum_j gate[h][n*k+j] * slots[h][n*k+j][:]   (slots [H, N*k, dh], storage type T)

@@ -67,6 +67,7 @@ struct Layout {
   size_t idx, gate, perm, offsets, Q, K, V, ctx, lse, pV;          // saved by forward
   size_t pQ, pK;                                                   // per-slot query / key rows (expert Q/K only)
   size_t rope;                                                     // (cos, sin) table [T][dh/2] (rotary embedding only)
+  size_t xq, accq;   // fewer queries than keys only: the query tokens' rows of x; their fp32 share of dx
   size_t Z, blockcnt, acc32;                                       // forward scratch
   size_t setid, gset, gsort, setexp, setperm, setoff, setcnt, yh;
   size_t dR, wr3;                                                  // wide router dz rows [N, H*dh], routers packed [dm, dh]                 // expert-set path (bf16 only)
@@ -107,6 +108,7 @@ sh_status check_shape(const sh_shape* s) {
   if (s->causal != 0 && s->causal != 1) return fail(SH_ERR_INVALID_ARG, "causal must be 0 or 1");
   if (s->qk_experts != 0 && s->qk_experts != 1) return fail(SH_ERR_INVALID_ARG, "qk_experts must be 0 or 1");
   if (s->rope != 0 && s->rope != 1) return fail(SH_ERR_INVALID_ARG, "rope must be 0 or 1");
+  if (s->T_q < 0 || s->T_q > s->T) return fail(SH_ERR_INVALID_ARG, "T_q=%d must lie in 0..T=%d", s->T_q, s->T);
   if (s->E > 64) return fail(SH_ERR_UNSUPPORTED, "E=%d exceeds the limit of 64", s->E);
   if (s->k > 8) return fail(SH_ERR_UNSUPPORTED, "k=%d exceeds the limit of 8", s->k);
   if (s->d_head > 256) return fail(SH_ERR_UNSUPPORTED, "d_head=%d exceeds the limit of 256", s->d_head);
@@ -139,6 +141,12 @@ Layout make_layout(const sh_shape* s) {
   L.pV = take(H * N * k * dh * esz);
   L.pQ = L.pK = 0;
   L.rope = s->rope ? take((size_t)s->T * (dh / 2 > 0 ? dh / 2 : 1) * 8) : 0;
+  L.xq = L.accq = 0;
+  if (s->T_q > 0 && s->T_q < s->T) {
+    const size_t Nq = (size_t)s->B * s->T_q;
+    L.xq = take(Nq * dm * esz);
+    L.accq = take(Nq * dm * 4);
+  }
   if (s->qk_experts) {
     L.pQ = take(H * N * k * dh * esz);
     L.pK = take(H * N * k * dh * esz);
@@ -191,7 +199,10 @@ struct Ctx {
   char* ws;
   hipStream_t st;
   int N, H, E, k, dh, dm, bf16;
+  int Tq, Nq;   // queries per sequence and in all; Tq < T: only the last Tq positions are destinations
+  bool rect;    // Tq < T
   bool dense, shared, qk_experts;
+  int n(int side) const { return side ? Nq : N; }   // tokens of the source (0) / destination (1) side
   template <typename T>
   T* p(size_t off) const {
     return (T*)(ws + off);
@@ -216,6 +227,9 @@ sh_status make_ctx(Ctx& c, const sh_shape* s, const void* W_S, const void* W_D, 
   c.ws = (char*)ws;
   c.st = (hipStream_t)stream;
   c.N = s->B * s->T;
+  c.Tq = s->T_q > 0 ? s->T_q : s->T;
+  c.Nq = s->B * c.Tq;
+  c.rect = c.Tq != s->T;
   c.H = s->nheads;
   c.E = s->E;
   c.k = s->k;
@@ -247,7 +261,7 @@ void row_gemm(const Ctx& c, const RowGemmArgs& a) {
 
 // Weight gradient of one step.  MFMA family: per-chunk partial sums + a reduction (deterministic,
 // the outputs need no zero fill); otherwise atomic adds into zeroed outputs.
-void wgrad(const Ctx& c, WgradArgs a, bool deterministic = true) {
+void wgrad(const Ctx& c, WgradArgs a, bool deterministic = true, bool zero = true) {
   if (use_mfma(c)) {
     WgradArgs b = a;
     if (deterministic) {
@@ -264,8 +278,10 @@ void wgrad(const Ctx& c, WgradArgs a, bool deterministic = true) {
   // atomic paths add into zeroed outputs
   const int h1 = a.hsplit > 0 ? a.hsplit : a.heads;
   const size_t kb = a.kb_store ? a.kb_store : a.Kb;
-  launch_fill_f32(a.dW, (size_t)h1 * a.E * a.Ka * kb, 0.f, c.st);
-  if (a.hsplit > 0) launch_fill_f32(a.dW2, (size_t)(a.heads - a.hsplit) * a.E * a.Ka * kb, 0.f, c.st);
+  if (zero) {
+    launch_fill_f32(a.dW, (size_t)h1 * a.E * a.Ka * kb, 0.f, c.st);
+    if (a.hsplit > 0) launch_fill_f32(a.dW2, (size_t)(a.heads - a.hsplit) * a.E * a.Ka * kb, 0.f, c.st);
+  }
   if (use_mfma(c) && mfma_wgrad_supported(a)) {
     launch_mfma_wgrad(a, c.st);
     return;
@@ -292,8 +308,8 @@ RowGemmArgs perm_rows(const Ctx& c, int side) {
   a.offsets = c.offsets(side);
   a.heads = c.H;
   a.E = c.E;
-  a.M = c.N * c.k;
-  a.max_group_rows = c.N;
+  a.M = c.n(side) * c.k;
+  a.max_group_rows = c.n(side);
   a.a_div = c.k;
   a.c_div = 1;
   return a;
@@ -307,28 +323,29 @@ RowGemmArgs set_rows(const Ctx& c, int side) {
   a.offsets = c.p<int>(c.L.setoff) + (size_t)side * c.H * (ns + 1);
   a.heads = c.H;
   a.E = ns;
-  a.M = c.N;
+  a.M = c.n(side);
   a.a_div = 1;
   a.c_div = 1;
-  a.max_group_rows = c.N;
+  a.max_group_rows = c.n(side);
   a.seg_mode = 1;
   a.nseg = c.k;
   a.experts = c.E;
   a.segate = c.p<float>(c.L.gsort) + (size_t)side * c.H * c.N * c.k;
   a.set_experts = c.p<int>(c.L.setexp);
-  a.gate_hstride = (long)c.N * c.k;
+  a.gate_hstride = (long)c.n(side) * c.k;
   return a;
 }
 
 bool sets_usable(const Ctx& c) {
-  return use_mfma(c) && count_sets(c.E, c.k) <= MAX_SETS && c.dm % 4 == 0 && c.dh % 4 == 0 && ((size_t)c.N * c.dm) % 8 == 0;
+  return use_mfma(c) && count_sets(c.E, c.k) <= MAX_SETS && c.dm % 4 == 0 && c.dh % 4 == 0 &&
+         ((size_t)c.N * c.dm) % 8 == 0 && ((size_t)c.Nq * c.dm) % 8 == 0;
 }
 
-RowGemmArgs identity_rows(const Ctx& c, int heads) {
+RowGemmArgs identity_rows(const Ctx& c, int heads, int side = 0) {
   RowGemmArgs a{};
   a.heads = heads;
   a.E = 1;
-  a.M = c.N;
+  a.M = c.n(side);
   a.a_div = 1;
   a.c_div = 1;
   return a;
@@ -432,7 +449,65 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     sa.sides = 2;
   }
   prof_mark(c.st, "fwd.router");
-  if (c.dense) {
+  const void* xq = x;   // the destination (query) tokens' rows of x
+  if (c.rect) {
+    // Fewer queries than keys: the query tokens' rows (the last T_q of every sequence) are copied into
+    // one block, and each side is routed on its own tokens.  Shared selection evaluates the one router
+    // on the query rows again, which gives the source side's numbers for those tokens.
+    const size_t esz = c.bf16 ? 2 : 4, rowb = (size_t)dm * esz;
+    xq = c.p<void>(c.L.xq);
+    if (hipMemcpy2DAsync(c.p<void>(c.L.xq), (size_t)c.Tq * rowb, (const char*)x + (size_t)(shape->T - c.Tq) * rowb,
+                         (size_t)shape->T * rowb, (size_t)c.Tq * rowb, (size_t)shape->B, hipMemcpyDeviceToDevice,
+                         c.st) != hipSuccess)
+      return fail(SH_ERR_HIP, "switchhead_forward: copy of the query rows failed");
+    const int nblk = router_blocks(N), ns = count_sets(E, k);
+    for (int side = 0; side < 2; ++side) {
+      const int n = c.n(side);
+      if (c.dense) {
+        launch_dense_routing(c.idx(side), c.gate(side), c.perm(side), c.offsets(side), n, H, c.st);
+        continue;
+      }
+      const bool own = side == 1 && !c.shared;   // the destination side's own router
+      RouterArgs ra{};
+      ra.x = side ? xq : x;
+      ra.W[0] = own ? W_D : W_S;
+      ra.b[0] = own ? b_D : b_S;
+      ra.Z = c.p<double>(c.L.Z) + (size_t)side * N * H * E;
+      ra.idx = c.idx(side);
+      ra.gate = c.gate(side);
+      ra.perm = c.perm(side);
+      ra.offsets = c.offsets(side);
+      ra.blockcnt = c.p<int>(c.L.blockcnt) + (size_t)side * H * nblk * E;
+      ra.N = n;
+      ra.dm = dm;
+      ra.H = H;
+      ra.E = E;
+      ra.k = k;
+      ra.sides = 1;
+      ra.bf16 = c.bf16;
+      SetSortArgs s1 = sa;
+      if (sets) {
+        s1.idx = c.idx(side);
+        s1.gate = c.gate(side);
+        s1.setid = sa.setid + (size_t)side * H * N;
+        s1.gset = sa.gset + (size_t)side * H * N * k;
+        s1.gsort = sa.gsort + (size_t)side * H * N * k;
+        s1.setperm = sa.setperm + (size_t)side * H * N;
+        s1.setoff = sa.setoff + (size_t)side * H * (ns + 1);
+        s1.blockcnt = sa.blockcnt + (size_t)side * H * nblk * ns;
+        s1.N = n;
+        s1.sides = 1;
+      }
+      if (g_family.load() == 0 && router_hybrid_supported(ra)) {
+        if (sets) ra.sets = &s1;
+        launch_router_hybrid(ra, c.p<char>(c.L.rh), c.st);
+      } else {
+        launch_router(ra, c.st);
+        if (sets) launch_set_sort(s1, c.st);
+      }
+    }
+    sets_sorted = true;
+  } else if (c.dense) {
     launch_dense_routing(c.idx(0), c.gate(0), c.perm(0), c.offsets(0), N, H, c.st);
   } else {
     RouterArgs ra{};
@@ -464,7 +539,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
       launch_router(ra, c.st);
     }
   }
-  if (c.dense || c.shared) {
+  if ((c.dense || c.shared) && !c.rect) {
     // one selection serves both sides: the destination tables repeat the source tables
     const size_t n1 = (size_t)H * N * k * 4;
     (void)hipMemcpyAsync(c.idx(1), c.idx(0), n1, hipMemcpyDeviceToDevice, c.st);
@@ -508,9 +583,10 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
       a.b_estride = (long)dm * dh;
       a.sbk = dh;
       a.sbn = 1;
+      a.A = side ? xq : x;
       a.C = c.p<void>(which ? c.L.pK : c.L.pQ);
       a.ldc = dh;
-      a.c_hoff = (long)N * k * dh;
+      a.c_hoff = (long)c.n(side) * k * dh;
       a.K = dm;
       a.Nc = dh;
       a.mode = STORE_T;
@@ -520,7 +596,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
       sl.slots = a.C;
       sl.gate = c.gate(side);
       sl.out = c.p<void>(which ? c.L.K : c.L.Q);
-      sl.N = N;
+      sl.N = c.n(side);
       sl.H = H;
       sl.k = k;
       sl.dh = dh;
@@ -547,7 +623,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     a.K = dm;
     a.Nc = dh;
     a.mode = STORE_T;
-    if (use_mfma(c) && mfma_row_gemm_supported(a)) {
+    if (!c.rect && use_mfma(c) && mfma_row_gemm_supported(a)) {
       prof_mark(c.st, "fwd.qk_proj");
       launch_mfma_row_gemm(a, c.st);
     } else {
@@ -555,6 +631,8 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
       a.hsplit = 0;
       for (int which = 0; which < 2; ++which) {
         prof_mark(c.st, which ? "fwd.k_proj" : "fwd.q_proj");
+        a.A = which ? x : xq;              // keys from every token, queries from the destination tokens
+        a.M = c.n(which ? 0 : 1);
         a.B = which ? W_K : W_Q;
         a.C = c.p<void>(which ? c.L.K : c.L.Q);
         row_gemm(c, a);
@@ -566,7 +644,12 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
   if (shape->rope) {
     prof_mark(c.st, "fwd.rope");
     launch_rope_table(c.p<float2>(c.L.rope), shape->T, dh, c.st);
-    launch_rope_apply(c.p<void>(c.L.Q), c.p<void>(c.L.K), c.p<float2>(c.L.rope), N, shape->T, H, dh, 0, c.bf16, c.st);
+    if (c.rect) {   // query i of a sequence sits at position (T - T_q) + i
+      launch_rope_apply(c.p<void>(c.L.Q), nullptr, c.p<float2>(c.L.rope), c.Nq, c.Tq, shape->T - c.Tq, H, dh, 0, c.bf16, c.st);
+      launch_rope_apply(c.p<void>(c.L.K), nullptr, c.p<float2>(c.L.rope), N, shape->T, 0, H, dh, 0, c.bf16, c.st);
+    } else {
+      launch_rope_apply(c.p<void>(c.L.Q), c.p<void>(c.L.K), c.p<float2>(c.L.rope), N, shape->T, 0, H, dh, 0, c.bf16, c.st);
+    }
   }
 
   // step 3: value experts, unscaled per-slot results, then the gate-weighted sum over slots
@@ -615,6 +698,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     a.dh = dh;
     a.causal = shape->causal;
     a.scale = 1.0f / sqrtf((float)dh);
+    a.Tq = c.Tq;
     if (use_mfma(c) && mfma_attn_supported(shape->T, dh))
       launch_mfma_attn_fwd(a, c.st);
     else
@@ -637,21 +721,21 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     a.sbn = 1;
     a.C = H == 1 ? y : c.p<void>(c.L.yh);
     a.ldc = dm;
-    a.c_hoff = (long)N * dm;
+    a.c_hoff = (long)c.Nq * dm;
     a.K = dh;
     a.Nc = dm;
     a.mode = STORE_T;
     launch_mfma_row_gemm(a, c.st);
     if (H > 1) {
       prof_mark(c.st, "fwd.y_sum");
-      launch_sum_heads(c.p<void>(c.L.yh), nullptr, y, (size_t)N * dm, (size_t)N * dm, H, c.st);
+      launch_sum_heads(c.p<void>(c.L.yh), nullptr, y, (size_t)c.Nq * dm, (size_t)c.Nq * dm, H, c.st);
     }
   } else
   // fallback: expert-sorted rows, gate-scaled, summed over heads and slots with fp32 atomics
   {
     prof_mark(c.st, "fwd.y_zero");
     float* acc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)y;
-    launch_fill_f32(acc, (size_t)N * dm, 0.f, c.st);
+    launch_fill_f32(acc, (size_t)c.Nq * dm, 0.f, c.st);
     prof_mark(c.st, "fwd.o_experts");
     RowGemmArgs a = perm_rows(c, 1);
     a.tag = TAG_O_EXPERTS;
@@ -668,13 +752,13 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     a.ldc = dm;
     a.c_hoff = 0;
     a.gate = c.gate(1);
-    a.gate_hstride = (long)N * k;
+    a.gate_hstride = (long)c.Nq * k;
     a.K = dh;
     a.Nc = dm;
     a.mode = ATOMIC_F32;
     row_gemm(c, a);
     prof_mark(c.st, "fwd.y_cast");
-    if (c.bf16) launch_cast_from_f32(acc, y, (size_t)N * dm, 1, c.st);
+    if (c.bf16) launch_cast_from_f32(acc, y, (size_t)c.Nq * dm, 1, c.st);
   }
   prof_mark(c.st, nullptr);
   return check_launch("switchhead_forward");
@@ -694,6 +778,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   const int chunk = wgrad_chunk((size_t)H * N * k, dm, dh);         // expert-sorted operands
   const int chunk_dense = wgrad_chunk((size_t)2 * H * N, dm, dh);   // fused dense Q/K
   const bool sets = sets_usable(c);
+  const int Nq = c.Nq;
+  const void* xq = c.rect ? c.p<void>(c.L.xq) : x;   // the query tokens' rows of x (copied by forward)
 
   // output experts: u[h][a][:] = dy[n] W_O[h,e]^T (unscaled), then dctx, d(gate_D), delta
   {
@@ -709,7 +795,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.sbn = dm;
     a.C = c.p<void>(c.L.u);
     a.ldc = dh;
-    a.c_hoff = (long)N * k * dh;
+    a.c_hoff = (long)Nq * k * dh;
     a.K = dm;
     a.Nc = dh;
     a.mode = STORE_T;
@@ -722,7 +808,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     sa.out = c.p<void>(c.L.dctx);
     sa.dots = c.p<float>(c.L.dgate) + (size_t)H * N * k;
     sa.delta = c.p<float>(c.L.delta);
-    sa.N = N;
+    sa.N = Nq;
     sa.H = H;
     sa.k = k;
     sa.dh = dh;
@@ -734,8 +820,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.offsets = c.offsets(1);
     w.heads = H;
     w.E = E;
-    w.M = N * k;
-    w.max_group_rows = N;
+    w.M = Nq * k;
+    w.max_group_rows = Nq;
     w.a_div = k;
     w.b_div = k;
     w.A = c.p<void>(c.L.ctx);
@@ -751,7 +837,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.w_estride = (long)dh * dm;
     w.swa = dm;
     w.gate = c.gate(1);
-    w.gate_hstride = (long)N * k;
+    w.gate_hstride = (long)Nq * k;
     w.chunk = chunk;
     wgrad(c, w);
   }
@@ -775,6 +861,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.dh = dh;
     a.causal = shape->causal;
     a.scale = 1.0f / sqrtf((float)dh);
+    a.Tq = c.Tq;
     if (use_mfma(c) && mfma_attn_supported(shape->T, dh))
       launch_mfma_attn_bwd(a, c.st);
     else
@@ -784,7 +871,12 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   // back through the rotation of queries and keys: gradients take the opposite turn
   if (shape->rope) {
     prof_mark(c.st, "bwd.rope");
-    launch_rope_apply(c.p<void>(c.L.dQ), c.p<void>(c.L.dK), c.p<float2>(c.L.rope), N, shape->T, H, dh, 1, c.bf16, c.st);
+    if (c.rect) {
+      launch_rope_apply(c.p<void>(c.L.dQ), nullptr, c.p<float2>(c.L.rope), c.Nq, c.Tq, shape->T - c.Tq, H, dh, 1, c.bf16, c.st);
+      launch_rope_apply(c.p<void>(c.L.dK), nullptr, c.p<float2>(c.L.rope), N, shape->T, 0, H, dh, 1, c.bf16, c.st);
+    } else {
+      launch_rope_apply(c.p<void>(c.L.dQ), c.p<void>(c.L.dK), c.p<float2>(c.L.rope), N, shape->T, 0, H, dh, 1, c.bf16, c.st);
+    }
   }
 
   // dense queries and keys: weight gradients, then dx = dQ W_Q^T + dK W_K^T.  With the MFMA
@@ -818,14 +910,52 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.w_hstride = (long)dm * dh;
     w.swa = dh;
     w.chunk = chunk_dense;
-    wgrad(c, w);
+    if (!c.rect) {
+      wgrad(c, w);
+    } else {   // queries and keys come from different token sets: one launch each
+      w.heads = H;
+      w.hsplit = 0;
+      w.A = xq;
+      w.M = Nq;
+      wgrad(c, w);
+      prof_mark(c.st, "bwd.qk_wgrad");
+      w.A = x;
+      w.M = N;
+      w.Bm = c.p<void>(c.L.dK);
+      w.dW = dW_K;
+      wgrad(c, w);
+    }
+  }
+  // the query tokens' own share of dx (fewer queries than keys): fp32, added to their rows at the end
+  float* accq = c.rect ? c.p<float>(c.L.accq) : nullptr;
+  if (c.rect) {
+    prof_mark(c.st, "bwd.dx_zero");
+    launch_fill_f32(accq, (size_t)Nq * dm, 0.f, c.st);
+    if (!c.qk_experts) {
+      prof_mark(c.st, "bwd.q_dgrad");
+      RowGemmArgs b = identity_rows(c, H, 1);
+      b.tag = TAG_QK_DGRAD;
+      b.A = c.p<void>(c.L.dQ);
+      b.lda = hd;
+      b.a_hoff = dh;
+      b.B = W_Q;
+      b.b_hstride = (long)dm * dh;
+      b.sbk = 1;
+      b.sbn = dh;
+      b.C = accq;
+      b.ldc = dm;
+      b.K = dh;
+      b.Nc = dm;
+      b.mode = ATOMIC_F32;
+      row_gemm(c, b);
+    }
   }
   // dx += dQ W_Q^T + dK W_K^T (one GEMM over the 2H concatenated segments).  Where the routers' dz fits
   // into rows of the same shape it rides along as one more segment (dz_S W_S^T + dz_D W_D^T), and the
   // launch moves behind the router backward kernel.
   const int HE_r = H * E, HEp_r = (HE_r + 7) / 8 * 8, sides_r = c.shared ? 1 : 2;
   const bool wide_dz = !c.dense && sides_r * HEp_r <= dh && (c.L.dR - c.L.dK) == (c.L.dK - c.L.dQ);
-  const bool fuse_router = wide_dz && sets && c.bf16 && use_mfma(c) && !c.qk_experts;
+  const bool fuse_router = wide_dz && sets && c.bf16 && use_mfma(c) && !c.qk_experts && !c.rect;
   bool router_fused = false;
   auto run_qk_dgrad = [&](bool with_router) {
     RowGemmArgs a = identity_rows(c, 1);
@@ -840,6 +970,11 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.a_wstride = (long)((c.L.dK - c.L.dQ) / (c.bf16 ? 2 : 4));
     a.B = W_Q;
     a.B2 = W_K;
+    if (c.rect) {   // the keys' segments alone: the queries' share went to the query rows' accumulator
+      a.A = c.p<void>(c.L.dK);
+      a.nseg = H;
+      a.B = W_K;
+    }
     a.b_sstride = (long)dm * dh;
     a.sbk = 1;
     a.sbn = dh;
@@ -867,7 +1002,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       acc_written = true;
       prof_mark(c.st, "bwd.dx_zero");
       launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
-      for (int which = 0; which < 2; ++which) {
+      for (int which = c.rect ? 1 : 0; which < 2; ++which) {
         prof_mark(c.st, which ? "bwd.k_dgrad" : "bwd.q_dgrad");
         RowGemmArgs b = identity_rows(c, H);
         b.tag = TAG_QK_DGRAD;
@@ -901,6 +1036,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   // form) given dP: the gates' gradient <x W[h,e_j], dP> from the per-slot rows the forward pass
   // kept, dW[h,e] = sum_n g x[n]^T dP[n,h], and the projection's share of dx.
   int yh_used = 0;   // bf16 partials of dx written so far (expert-set path)
+  const bool sets_path = sets;
   auto expert_proj_bwd = [&](int side, const void* W, size_t dP, size_t slots, float* dW, bool dots_add,
                              const char* l_gate, const char* l_wgrad, const char* l_dgrad) {
     prof_mark(c.st, l_gate);
@@ -910,7 +1046,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     sa.other = c.p<void>(dP);
     sa.dots = c.p<float>(c.L.dgate) + (size_t)side * H * N * k;
     sa.dots_add = dots_add;
-    sa.N = N;
+    sa.N = c.n(side);
     sa.H = H;
     sa.k = k;
     sa.dh = dh;
@@ -923,11 +1059,11 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.offsets = c.offsets(side);
     w.heads = H;
     w.E = E;
-    w.M = N * k;
-    w.max_group_rows = N;
+    w.M = c.n(side) * k;
+    w.max_group_rows = c.n(side);
     w.a_div = k;
     w.b_div = k;
-    w.A = x;
+    w.A = side ? xq : x;
     w.lda = dm;
     w.a_hoff = 0;
     w.Ka = dm;
@@ -940,10 +1076,12 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.w_estride = (long)dm * dh;
     w.swa = dh;
     w.gate = c.gate(side);
-    w.gate_hstride = (long)N * k;
+    w.gate_hstride = (long)c.n(side) * k;
     w.chunk = chunk;
     wgrad(c, w);
     prof_mark(c.st, l_dgrad);
+    const bool to_accq = c.rect && side == 1;   // rows of the query tokens: their own fp32 accumulator
+    const bool sets = sets_path && !to_accq;
     RowGemmArgs a = sets ? set_rows(c, side) : perm_rows(c, side);
     a.tag = TAG_V_DGRAD;
     a.A = c.p<void>(dP);
@@ -966,10 +1104,10 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       yh_used += H;
     } else {
       a.c_div = k;
-      a.C = dxacc;
+      a.C = to_accq ? accq : dxacc;
       a.ldc = dm;
       a.gate = c.gate(side);
-      a.gate_hstride = (long)N * k;
+      a.gate_hstride = (long)c.n(side) * k;
       a.mode = ATOMIC_F32;
       row_gemm(c, a);
     }
@@ -987,7 +1125,78 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
 
   // routers
   bool router_partial = false;
-  if (!c.dense) {
+  if (!c.dense && c.rect) {
+    // fewer queries than keys: each side has its own tokens, so every step runs once per side; the
+    // destination side's input gradient goes to the query rows' accumulator
+    prof_mark(c.st, "bwd.router");
+    const int HE = H * E, HEp = (HE + 7) / 8 * 8;
+    const size_t esz = c.bf16 ? 2 : 4;
+    launch_zero4_f32(db_S, db_S ? (size_t)HE : 0, c.shared ? nullptr : db_D, (!c.shared && db_D) ? (size_t)HE : 0, nullptr, 0,
+                     nullptr, 0, c.st);
+    for (int side = 0; side < 2; ++side) {
+      const bool own = side == 1 && !c.shared;
+      const void* W = own ? W_D : W_S;
+      float* dW = own ? dW_D : dW_S;
+      char* dzs = c.p<char>(c.L.dz) + (size_t)side * N * HEp * esz;
+      RouterBwdArgs rb{};
+      rb.idx = c.idx(side);
+      rb.gate = c.gate(side);
+      rb.dgate = c.p<float>(c.L.dgate) + (size_t)side * H * N * k;
+      rb.dz = dzs;
+      rb.db[0] = own ? db_D : db_S;
+      rb.N = c.n(side);
+      rb.H = H;
+      rb.E = E;
+      rb.k = k;
+      rb.sides = 1;
+      rb.shared = 0;
+      rb.ld = HEp;
+      rb.side_stride = HEp;
+      rb.pad_to = 0;
+      launch_router_bwd(rb, c.bf16, c.st);
+      if (dW) {
+        prof_mark(c.st, "bwd.router_wgrad");
+        WgradArgs w{};
+        w.heads = 1;
+        w.E = 1;
+        w.M = c.n(side);
+        w.a_div = 1;
+        w.b_div = 1;
+        w.A = side ? xq : x;
+        w.lda = dm;
+        w.Ka = dm;
+        w.Bm = dzs;
+        w.ldb = HEp;
+        w.Kb = HEp;
+        w.kb_store = HE;
+        w.swa = HE;
+        w.chunk = 256;
+        w.dW = dW;
+        wgrad(c, w, false, /*zero=*/!(c.shared && side == 1));   // shared selection: both sides add into dW_S
+      }
+      prof_mark(c.st, "bwd.router_dgrad");
+      RowGemmArgs a = identity_rows(c, 1, side);
+      a.A = dzs;
+      a.lda = HEp;
+      a.B = W;
+      a.sbk = 1;
+      a.sbn = HE;
+      a.ldc = dm;
+      a.K = HE;
+      a.Nc = dm;
+      a.mode = ATOMIC_F32;
+      if (side == 1) {
+        a.C = accq;
+      } else {
+        if (!acc_written) {
+          launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
+          acc_written = true;
+        }
+        a.C = dxacc;
+      }
+      row_gemm(c, a);
+    }
+  } else if (!c.dense) {
     prof_mark(c.st, "bwd.router");
     const int sides = c.shared ? 1 : 2;
     const int HE = H * E;
@@ -1124,6 +1333,10 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
                      yh_taken() + (router_partial ? 1 : 0), c.st);
   else if (c.bf16)
     launch_cast_from_f32(dxacc, dx, (size_t)N * dm, 1, c.st);
+  if (c.rect) {
+    prof_mark(c.st, "bwd.dx_query_rows");
+    launch_add_query_rows(dx, accq, Nq, shape->T, c.Tq, dm, c.bf16, c.st);
+  }
   prof_mark(c.st, nullptr);
   return check_launch("switchhead_backward");
 }

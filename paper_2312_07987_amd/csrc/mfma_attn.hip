@@ -167,22 +167,25 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_fwd_kernel(A
   __shared__ __attribute__((aligned(16))) unsigned short Vs[KT * LDV];
 
   int b, h, qt;
-  attn_block_map(blockIdx.x, (a.T + 127) / 128, a.B * a.H, a.H, a.causal, true, b, h, qt);
+  const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
+  const int off = T - Tq;   // position of query 0 among the keys
+  attn_block_map(blockIdx.x, (Tq + 127) / 128, a.B * a.H, a.H, a.causal, true, b, h, qt);
   const int q0 = qt * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
-  const int T = a.T, dh = a.dh;
   const long rs = (long)a.H * dh;
   const long base = ((long)b * T) * rs + (long)h * dh;
-  const unsigned short* Q = (const unsigned short*)a.Q + base;
+  const long qbase = ((long)b * Tq) * rs + (long)h * dh;
+  const unsigned short* Q = (const unsigned short*)a.Q + qbase;
   const unsigned short* K = (const unsigned short*)a.K + base;
   const unsigned short* V = (const unsigned short*)a.V + base;
 
   const int q = q0 + wave * 32 + r;             // this lane's query
-  const int wq_last = q0 + wave * 32 + 31;
+  const int qpos = q + off;                     // its position among the keys
+  const int wq_last = q0 + wave * 32 + 31 + off;
   bf16x8 qf[NKD];
 #pragma unroll
-  for (int kk = 0; kk < NKD; ++kk) qf[kk] = global_frag<VEC>(Q + (long)q * rs, kk * 16 + 8 * g, dh, q < T);
+  for (int kk = 0; kk < NKD; ++kk) qf[kk] = global_frag<VEC>(Q + (long)q * rs, kk * 16 + 8 * g, dh, q < Tq);
 
   f32x16 o[NDB];
 #pragma unroll
@@ -192,7 +195,7 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_fwd_kernel(A
   float m = -INFINITY, l = 0.f;
   const float sc = a.scale * 1.44269504088896340736f;   // logits in log2 units
 
-  const int kend = a.causal ? min(T, q0 + 128) : T;
+  const int kend = a.causal ? min(T, q0 + 128 + off) : T;
   RowTile<DH, VEC, KT> tk, tv;
   tk.load(K, rs, T, dh, tid);
   tv.load(V, rs, T, dh, tid);
@@ -220,14 +223,14 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_fwd_kernel(A
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[kb][i] = acc[i];
     }
-    const bool need_mask = (a.causal && k0 + KT - 1 > q0 + wave * 32) || (k0 + KT > T);
+    const bool need_mask = (a.causal && k0 + KT - 1 > q0 + wave * 32 + off) || (k0 + KT > T);
     if (need_mask) {
 #pragma unroll
       for (int kb = 0; kb < KT / 32; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int key = k0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-          if (key >= T || (a.causal && key > q)) s[kb][i] = -INFINITY;
+          if (key >= T || (a.causal && key > qpos)) s[kb][i] = -INFINITY;
         }
     }
     float mt = -INFINITY;
@@ -269,9 +272,9 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_fwd_kernel(A
   }
 
   l += __shfl_xor(l, 32, 64);
-  if (q < T) {
+  if (q < Tq) {
     const float inv = 1.f / l;
-    unsigned short* O = (unsigned short*)a.O + base + (long)q * rs;
+    unsigned short* O = (unsigned short*)a.O + qbase + (long)q * rs;
 #pragma unroll
     for (int d = 0; d < NDB; ++d)
 #pragma unroll
@@ -284,7 +287,7 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_fwd_kernel(A
           *(uint2*)(O + dd) = w;
         }
       }
-    if (g == 0) a.lse[((long)b * a.H + h) * T + q] = (m + log2f(l)) * 0.69314718055994530942f;
+    if (g == 0) a.lse[((long)b * a.H + h) * Tq + q] = (m + log2f(l)) * 0.69314718055994530942f;
   }
 }
 
@@ -354,15 +357,17 @@ __global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kerne
   const int k0 = ktile * KB;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
-  const int T = a.T, dh = a.dh;
+  const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
+  const int off = T - Tq;   // position of query 0 among the keys
   const long rs = (long)a.H * dh;
   const long base = ((long)b * T) * rs + (long)h * dh;
-  const unsigned short* Q = (const unsigned short*)a.Q + base;
+  const long qbase = ((long)b * Tq) * rs + (long)h * dh;
+  const unsigned short* Q = (const unsigned short*)a.Q + qbase;
   const unsigned short* K = (const unsigned short*)a.K + base;
   const unsigned short* V = (const unsigned short*)a.V + base;
-  const unsigned short* dO = (const unsigned short*)a.dO + base;
-  const float* lse = a.lse + ((long)b * a.H + h) * T;
-  const float* delta = a.delta + (long)b * T * a.H + h;
+  const unsigned short* dO = (const unsigned short*)a.dO + qbase;
+  const float* lse = a.lse + ((long)b * a.H + h) * Tq;
+  const float* delta = a.delta + (long)b * Tq * a.H + h;
 
   const int key = k0 + wave * 32 + r;
   const int wk_first = k0 + wave * 32;
@@ -379,20 +384,20 @@ __global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kerne
     for (int i = 0; i < 16; ++i) accK[d][i] = accV[d][i] = 0.f;
   const float sc = a.scale * 1.44269504088896340736f;
 
-  const int qbeg = a.causal ? (k0 / QT) * QT : 0;
+  const int qbeg = a.causal ? (max(k0 - off, 0) / QT) * QT : 0;   // first query tile that sees a key of this tile
   RowTile<DH, VEC, QT, 64 * NW> tq, tg;
   float nlse = 0.f, ndel = 0.f;
   auto prefetch = [&](int q0) {
-    tq.load(Q + (long)q0 * rs, rs, T - q0, dh, tid);
-    tg.load(dO + (long)q0 * rs, rs, T - q0, dh, tid);
+    tq.load(Q + (long)q0 * rs, rs, Tq - q0, dh, tid);
+    tg.load(dO + (long)q0 * rs, rs, Tq - q0, dh, tid);
     if (tid < QT) {
-      const bool ok = q0 + tid < T;
+      const bool ok = q0 + tid < Tq;
       nlse = ok ? lse[q0 + tid] * 1.44269504088896340736f : 0.f;
       ndel = ok ? delta[(long)(q0 + tid) * a.H] : 0.f;
     }
   };
-  if (qbeg < T) prefetch(qbeg);
-  for (int q0 = qbeg; q0 < T; q0 += QT) {
+  if (qbeg < Tq) prefetch(qbeg);
+  for (int q0 = qbeg; q0 < Tq; q0 += QT) {
     __syncthreads();
     tq.store(Qr, LDR, Qt, LDT, tid);
     tg.store(Gr, LDR, Gt, LDT, tid);
@@ -401,7 +406,7 @@ __global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kerne
       del_s[tid] = ndel;
     }
     __syncthreads();
-    if (q0 + QT < T) prefetch(q0 + QT);
+    if (q0 + QT < Tq) prefetch(q0 + QT);
     // (a wave whose keys all follow the tile's queries multiplies zeros here: a branch around the
     //  body costs more registers than the diagonal tiles cost time)
 
@@ -423,7 +428,7 @@ __global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kerne
       for (int t = 0; t < 4; ++t) {
         const int i = 4 * i4 + t;
         const int qq = q0 + 8 * i4 + 4 * g + t;
-        const bool vis = qq < T && key < T && (!a.causal || key <= qq);
+        const bool vis = qq < Tq && key < T && (!a.causal || key <= qq + off);
         const float pv = vis ? __builtin_amdgcn_exp2f(fmaf(S[i], sc, -Lv[t])) : 0.f;
         p[i] = pv;
         ds[i] = pv * (dP[i] - Dv[t]);
@@ -464,28 +469,31 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
   unsigned short* Kt = SEP ? Kt_ : Kr;
 
   int b, h, qt;
-  attn_block_map(blockIdx.x, (a.T + 127) / 128, a.B * a.H, a.H, a.causal, true, b, h, qt);
+  const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
+  const int off = T - Tq;   // position of query 0 among the keys
+  attn_block_map(blockIdx.x, (Tq + 127) / 128, a.B * a.H, a.H, a.causal, true, b, h, qt);
   const int q0 = qt * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
-  const int T = a.T, dh = a.dh;
   const long rs = (long)a.H * dh;
   const long base = ((long)b * T) * rs + (long)h * dh;
-  const unsigned short* Q = (const unsigned short*)a.Q + base;
+  const long qbase = ((long)b * Tq) * rs + (long)h * dh;
+  const unsigned short* Q = (const unsigned short*)a.Q + qbase;
   const unsigned short* K = (const unsigned short*)a.K + base;
   const unsigned short* V = (const unsigned short*)a.V + base;
-  const unsigned short* dO = (const unsigned short*)a.dO + base;
+  const unsigned short* dO = (const unsigned short*)a.dO + qbase;
 
   const int q = q0 + wave * 32 + r;
-  const int wq_last = q0 + wave * 32 + 31;
+  const int qpos = q + off;
+  const int wq_last = q0 + wave * 32 + 31 + off;
   bf16x8 qf[NKD], gf[NKD];
 #pragma unroll
   for (int kk = 0; kk < NKD; ++kk) {
-    qf[kk] = global_frag<VEC>(Q + (long)q * rs, kk * 16 + 8 * g, dh, q < T);
-    gf[kk] = global_frag<VEC>(dO + (long)q * rs, kk * 16 + 8 * g, dh, q < T);
+    qf[kk] = global_frag<VEC>(Q + (long)q * rs, kk * 16 + 8 * g, dh, q < Tq);
+    gf[kk] = global_frag<VEC>(dO + (long)q * rs, kk * 16 + 8 * g, dh, q < Tq);
   }
-  const float lse2 = q < T ? a.lse[((long)b * a.H + h) * T + q] * 1.44269504088896340736f : 0.f;
-  const float del = q < T ? a.delta[((long)b * T + q) * a.H + h] : 0.f;
+  const float lse2 = q < Tq ? a.lse[((long)b * a.H + h) * Tq + q] * 1.44269504088896340736f : 0.f;
+  const float del = q < Tq ? a.delta[((long)b * Tq + q) * a.H + h] : 0.f;
   f32x16 acc[NDB];
 #pragma unroll
   for (int d = 0; d < NDB; ++d)
@@ -493,7 +501,7 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
     for (int i = 0; i < 16; ++i) acc[d][i] = 0.f;
   const float sc = a.scale * 1.44269504088896340736f;
 
-  const int kend = a.causal ? min(T, q0 + 128) : T;
+  const int kend = a.causal ? min(T, q0 + 128 + off) : T;
   RowTile<DH, VEC, KT> tk, tv;
   tk.load(K, rs, T, dh, tid);
   tv.load(V, rs, T, dh, tid);
@@ -521,7 +529,7 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int key = k0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-        const bool vis = key < T && (!a.causal || key <= q);
+        const bool vis = key < T && (!a.causal || key <= qpos);
         const float pv = vis ? __builtin_amdgcn_exp2f(fmaf(S[i], sc, -lse2)) : 0.f;
         ds[i] = pv * (dP[i] - del);
       }
@@ -535,7 +543,7 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
       }
     }
   }
-  if (q < T) store_rows_T<NDB>((unsigned short*)a.dQ + base + (long)q * rs, acc, a.scale, g, dh);
+  if (q < Tq) store_rows_T<NDB>((unsigned short*)a.dQ + qbase + (long)q * rs, acc, a.scale, g, dh);
 }
 
 static int attn_vec(int dh) { return dh % 8 == 0 ? 8 : (dh % 4 == 0 ? 4 : 0); }
@@ -545,13 +553,13 @@ bool mfma_attn_supported(int T, int dh) { return T >= 1 && dh >= 4 && dh <= 256 
 template <int DH>
 static void launch_dh(const AttnArgs* f, const AttnBwdArgs* bw, hipStream_t s) {
   if (f) {
-    dim3 g(((f->T + 127) / 128) * f->H * f->B);
+    dim3 g((((f->Tq > 0 ? f->Tq : f->T) + 127) / 128) * f->H * f->B);
     if (attn_vec(f->dh) == 8)
       mfma_attn_fwd_kernel<DH, 8><<<g, 256, 0, s>>>(*f);
     else
       mfma_attn_fwd_kernel<DH, 4><<<g, 256, 0, s>>>(*f);
   } else {
-    dim3 g(((bw->T + 127) / 128) * bw->H * bw->B);
+    dim3 g((((bw->Tq > 0 ? bw->Tq : bw->T) + 127) / 128) * bw->H * bw->B);
     prof_mark(s, "bwd.attention_dkv");
     // four waves (128 keys) per work-group; two-wave work-groups (two per CU where the registers
     // leave one wave per SIMD) were measured 7 % slower: the Q / dO staging doubles

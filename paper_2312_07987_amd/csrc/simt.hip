@@ -242,10 +242,11 @@ __global__ __launch_bounds__(256) void simt_attn_fwd_kernel(AttnArgs a, int KT) 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int parts = 64 / KT, key_l = lane % KT, part = lane / KT;
   const long rs = (long)a.H * dh;  // row stride
-  const T* Q = (const T*)a.Q + ((long)b * a.T) * rs + (long)h * dh;
+  const int Tq = a.Tq > 0 ? a.Tq : a.T, off = a.T - Tq;   // query i sits at key position off + i
+  const T* Q = (const T*)a.Q + ((long)b * Tq) * rs + (long)h * dh;
   const T* K = (const T*)a.K + ((long)b * a.T) * rs + (long)h * dh;
   const T* V = (const T*)a.V + ((long)b * a.T) * rs + (long)h * dh;
-  T* O = (T*)a.O + ((long)b * a.T) * rs + (long)h * dh;
+  T* O = (T*)a.O + ((long)b * Tq) * rs + (long)h * dh;
 
   float m[QPW], l[QPW], acc[QPW][4];
 #pragma unroll
@@ -255,8 +256,8 @@ __global__ __launch_bounds__(256) void simt_attn_fwd_kernel(AttnArgs a, int KT) 
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[i][c] = 0.f;
   }
-  const int qlast = min(q0 + RPB, a.T) - 1;
-  const int kend = a.causal ? qlast + 1 : a.T;
+  const int qlast = min(q0 + RPB, Tq) - 1;
+  const int kend = a.causal ? qlast + off + 1 : a.T;
 
   for (int k0 = 0; k0 < kend; k0 += KT) {
     __syncthreads();
@@ -270,13 +271,13 @@ __global__ __launch_bounds__(256) void simt_attn_fwd_kernel(AttnArgs a, int KT) 
     for (int i = 0; i < QPW; ++i) {
       const int q = q0 + wave * QPW + i;  // block-uniform control flow below
       __syncthreads();
-      for (int d = lane; d < dh; d += 64) qs[wave * dh + d] = q < a.T ? ld(Q, (long)q * rs + d) : 0.f;
+      for (int d = lane; d < dh; d += 64) qs[wave * dh + d] = q < Tq ? ld(Q, (long)q * rs + d) : 0.f;
       __syncthreads();
       float s = 0.f;
       for (int d = part; d < dh; d += parts) s = fmaf(qs[wave * dh + d], Ks[key_l * ldt + d], s);
       s = part_sum(s, KT) * a.scale;
       const int key = k0 + key_l;
-      const bool vis = key < a.T && q < a.T && (!a.causal || key <= q);
+      const bool vis = key < a.T && q < Tq && (!a.causal || key <= q + off);
       float sm = vis ? s : -INFINITY;
       float mn = fmaxf(m[i], wmax(sm));
       float p = (vis && mn > -INFINITY) ? __expf(sm - mn) : 0.f;
@@ -299,14 +300,14 @@ __global__ __launch_bounds__(256) void simt_attn_fwd_kernel(AttnArgs a, int KT) 
 #pragma unroll
   for (int i = 0; i < QPW; ++i) {
     const int q = q0 + wave * QPW + i;
-    if (q >= a.T) continue;
+    if (q >= Tq) continue;
     float inv = 1.f / l[i];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       int d = lane + 64 * c;
       if (d < dh) st(O, (long)q * rs + d, acc[i][c] * inv);
     }
-    if (lane == 0) a.lse[((long)b * a.H + h) * a.T + q] = m[i] + logf(l[i]);
+    if (lane == 0) a.lse[((long)b * a.H + h) * Tq + q] = m[i] + logf(l[i]);
   }
 }
 
@@ -325,20 +326,22 @@ __global__ __launch_bounds__(256) void simt_attn_dq_kernel(AttnBwdArgs a, int KT
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int parts = 64 / KT, key_l = lane % KT, part = lane / KT;
   const long rs = (long)a.H * dh;
+  const int Tq = a.Tq > 0 ? a.Tq : a.T, off = a.T - Tq;
   const long base = ((long)b * a.T) * rs + (long)h * dh;
-  const T* Q = (const T*)a.Q + base;
+  const long qbase = ((long)b * Tq) * rs + (long)h * dh;
+  const T* Q = (const T*)a.Q + qbase;
   const T* K = (const T*)a.K + base;
   const T* V = (const T*)a.V + base;
-  const T* dO = (const T*)a.dO + base;
-  T* dQ = (T*)a.dQ + base;
+  const T* dO = (const T*)a.dO + qbase;
+  T* dQ = (T*)a.dQ + qbase;
 
   float acc[QPW][4];
 #pragma unroll
   for (int i = 0; i < QPW; ++i)
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[i][c] = 0.f;
-  const int qlast = min(q0 + RPB, a.T) - 1;
-  const int kend = a.causal ? qlast + 1 : a.T;
+  const int qlast = min(q0 + RPB, Tq) - 1;
+  const int kend = a.causal ? qlast + off + 1 : a.T;
 
   for (int k0 = 0; k0 < kend; k0 += KT) {
     __syncthreads();
@@ -351,7 +354,7 @@ __global__ __launch_bounds__(256) void simt_attn_dq_kernel(AttnBwdArgs a, int KT
 #pragma unroll
     for (int i = 0; i < QPW; ++i) {
       const int q = q0 + wave * QPW + i;
-      const bool qok = q < a.T;
+      const bool qok = q < Tq;
       __syncthreads();
       for (int d = lane; d < dh; d += 64) {
         qs[wave * dh + d] = qok ? ld(Q, (long)q * rs + d) : 0.f;
@@ -366,11 +369,11 @@ __global__ __launch_bounds__(256) void simt_attn_dq_kernel(AttnBwdArgs a, int KT
       s = part_sum(s, KT) * a.scale;
       dp = part_sum(dp, KT);
       const int key = k0 + key_l;
-      const bool vis = key < a.T && qok && (!a.causal || key <= q);
+      const bool vis = key < a.T && qok && (!a.causal || key <= q + off);
       float ds = 0.f;
       if (vis) {
-        float lse = a.lse[((long)b * a.H + h) * a.T + q];
-        float dl = a.delta[((long)b * a.T + q) * a.H + h];
+        float lse = a.lse[((long)b * a.H + h) * Tq + q];
+        float dl = a.delta[((long)b * Tq + q) * a.H + h];
         ds = __expf(s - lse) * (dp - dl) * a.scale;
       }
       if (part == 0) ps[wave * 64 + key_l] = ds;
@@ -389,7 +392,7 @@ __global__ __launch_bounds__(256) void simt_attn_dq_kernel(AttnBwdArgs a, int KT
 #pragma unroll
   for (int i = 0; i < QPW; ++i) {
     const int q = q0 + wave * QPW + i;
-    if (q >= a.T) continue;
+    if (q >= Tq) continue;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       int d = lane + 64 * c;
@@ -416,11 +419,13 @@ __global__ __launch_bounds__(256) void simt_attn_dkv_kernel(AttnBwdArgs a, int K
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int parts = 64 / KT, q_l = lane % KT, part = lane / KT;
   const long rs = (long)a.H * dh;
+  const int Tq = a.Tq > 0 ? a.Tq : a.T, off = a.T - Tq;
   const long base = ((long)b * a.T) * rs + (long)h * dh;
-  const T* Q = (const T*)a.Q + base;
+  const long qbase = ((long)b * Tq) * rs + (long)h * dh;
+  const T* Q = (const T*)a.Q + qbase;
   const T* K = (const T*)a.K + base;
   const T* V = (const T*)a.V + base;
-  const T* dO = (const T*)a.dO + base;
+  const T* dO = (const T*)a.dO + qbase;
   T* dK = (T*)a.dK + base;
   T* dV = (T*)a.dV + base;
 
@@ -429,20 +434,20 @@ __global__ __launch_bounds__(256) void simt_attn_dkv_kernel(AttnBwdArgs a, int K
   for (int i = 0; i < QPW; ++i)
 #pragma unroll
     for (int c = 0; c < 4; ++c) ak[i][c] = av[i][c] = 0.f;
-  const int qbeg = a.causal ? (u0 / KT) * KT : 0;
+  const int qbeg = a.causal ? (max(u0 - off, 0) / KT) * KT : 0;
 
-  for (int qt = qbeg; qt < a.T; qt += KT) {
+  for (int qt = qbeg; qt < Tq; qt += KT) {
     __syncthreads();
     for (int t = tid; t < KT * dh; t += 256) {
       int r = t / dh, d = t % dh;
-      bool ok = qt + r < a.T;
+      bool ok = qt + r < Tq;
       Qs[r * ldt + d] = ok ? ld(Q, (long)(qt + r) * rs + d) : 0.f;
       Gs[r * ldt + d] = ok ? ld(dO, (long)(qt + r) * rs + d) : 0.f;
     }
     if (tid < KT) {
-      bool ok = qt + tid < a.T;
-      ls[tid] = ok ? a.lse[((long)b * a.H + h) * a.T + qt + tid] : 0.f;
-      dl[tid] = ok ? a.delta[((long)b * a.T + qt + tid) * a.H + h] : 0.f;
+      bool ok = qt + tid < Tq;
+      ls[tid] = ok ? a.lse[((long)b * a.H + h) * Tq + qt + tid] : 0.f;
+      dl[tid] = ok ? a.delta[((long)b * Tq + qt + tid) * a.H + h] : 0.f;
     }
 #pragma unroll
     for (int i = 0; i < QPW; ++i) {
@@ -462,7 +467,7 @@ __global__ __launch_bounds__(256) void simt_attn_dkv_kernel(AttnBwdArgs a, int K
       s = part_sum(s, KT) * a.scale;
       dp = part_sum(dp, KT);
       const int q = qt + q_l;
-      const bool vis = q < a.T && uok && (!a.causal || u <= q);
+      const bool vis = q < Tq && uok && (!a.causal || u <= q + off);
       float p = 0.f, ds = 0.f;
       if (vis) {
         p = __expf(s - ls[q_l]);
@@ -508,7 +513,7 @@ static int attn_kt(int dh) { return dh > 128 ? 16 : 32; }
 void launch_simt_attn_fwd(const AttnArgs& a, int bf16, hipStream_t s) {
   const int KT = attn_kt(a.dh);
   size_t lds = sizeof(float) * ((size_t)2 * KT * (a.dh + 1) + 4 * a.dh + 4 * 64);
-  dim3 g((a.T + RPB - 1) / RPB, a.H, a.B);
+  dim3 g(((a.Tq > 0 ? a.Tq : a.T) + RPB - 1) / RPB, a.H, a.B);
   if (bf16)
     simt_attn_fwd_kernel<bf16_t><<<g, 256, lds, s>>>(a, KT);
   else
@@ -517,14 +522,15 @@ void launch_simt_attn_fwd(const AttnArgs& a, int bf16, hipStream_t s) {
 
 void launch_simt_attn_bwd(const AttnBwdArgs& a, int bf16, hipStream_t s) {
   const int KT = attn_kt(a.dh);
-  dim3 g((a.T + RPB - 1) / RPB, a.H, a.B);
+  dim3 g((a.T + RPB - 1) / RPB, a.H, a.B);                             // keys
+  dim3 gq(((a.Tq > 0 ? a.Tq : a.T) + RPB - 1) / RPB, a.H, a.B);       // queries
   size_t lds_q = sizeof(float) * ((size_t)2 * KT * (a.dh + 1) + 8 * a.dh + 4 * 64);
   size_t lds_kv = sizeof(float) * ((size_t)2 * KT * (a.dh + 1) + 8 * a.dh + 8 * 64 + 128);
   if (bf16) {
-    simt_attn_dq_kernel<bf16_t><<<g, 256, lds_q, s>>>(a, KT);
+    simt_attn_dq_kernel<bf16_t><<<gq, 256, lds_q, s>>>(a, KT);
     simt_attn_dkv_kernel<bf16_t><<<g, 256, lds_kv, s>>>(a, KT);
   } else {
-    simt_attn_dq_kernel<float><<<g, 256, lds_q, s>>>(a, KT);
+    simt_attn_dq_kernel<float><<<gq, 256, lds_q, s>>>(a, KT);
     simt_attn_dkv_kernel<float><<<g, 256, lds_kv, s>>>(a, KT);
   }
 }

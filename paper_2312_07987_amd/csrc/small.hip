@@ -120,13 +120,13 @@ __global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ ta
 // turns by +angle (sign = 1) or -angle (sign = -1, the transpose: what a gradient takes).
 template <typename TT>
 __global__ __launch_bounds__(256) void rope_apply_kernel(TT* __restrict__ P0, TT* __restrict__ P1, const float2* __restrict__ tab,
-                                                         long rows, int T, int H, int dh, int half, float sign) {
+                                                         long rows, int T, int pos0, int H, int dh, int half, float sign) {
   const long id = (long)blockIdx.x * 256 + threadIdx.x;
   if (id >= rows * half) return;
   TT* P = blockIdx.y ? P1 : P0;
   const long row = id / half;
   const int i = (int)(id % half);
-  const int t = (int)((row / H) % T);
+  const int t = pos0 + (int)((row / H) % T);
   const float2 cs = tab[(long)t * half + i];
   const float c = cs.x, sn = sign * cs.y;
   const long o = row * dh + 2 * i;
@@ -137,15 +137,15 @@ __global__ __launch_bounds__(256) void rope_apply_kernel(TT* __restrict__ P0, TT
 
 // bf16 rows with dh % 8 == 0: 16 bytes (four pairs) per thread
 __global__ __launch_bounds__(256) void rope_apply_vec_kernel(unsigned short* __restrict__ P0, unsigned short* __restrict__ P1,
-                                                             const float2* __restrict__ tab, long rows, int T, int H, int dh,
-                                                             float sign) {
+                                                             const float2* __restrict__ tab, long rows, int T, int pos0, int H,
+                                                             int dh, float sign) {
   const int per_row = dh / 8;
   const long id = (long)blockIdx.x * 256 + threadIdx.x;
   if (id >= rows * per_row) return;
   unsigned short* P = blockIdx.y ? P1 : P0;
   const long row = id / per_row;
   const int q = (int)(id % per_row);
-  const int t = (int)((row / H) % T);
+  const int t = pos0 + (int)((row / H) % T);
   const float4* tp = (const float4*)(tab + (long)t * (dh / 2) + q * 4);
   const float4 t0 = tp[0], t1 = tp[1];
   const float c[4] = {t0.x, t0.z, t1.x, t1.z};
@@ -168,7 +168,8 @@ void launch_rope_table(float2* tab, int T, int dh, hipStream_t s) {
   if (n) rope_table_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(tab, T, half);
 }
 
-void launch_rope_apply(void* P0, void* P1, const float2* tab, long N, int T, int H, int dh, int inverse, int bf16, hipStream_t s) {
+void launch_rope_apply(void* P0, void* P1, const float2* tab, long N, int T, int pos0, int H, int dh, int inverse, int bf16,
+                       hipStream_t s) {
   const int half = dh / 2;
   const long rows = N * H;
   if (!half || !rows) return;
@@ -176,14 +177,37 @@ void launch_rope_apply(void* P0, void* P1, const float2* tab, long N, int T, int
   const unsigned ny = P1 ? 2 : 1;
   if (bf16 && dh % 8 == 0) {
     dim3 g((unsigned)((rows * (dh / 8) + 255) / 256), ny);
-    rope_apply_vec_kernel<<<g, 256, 0, s>>>((unsigned short*)P0, (unsigned short*)P1, tab, rows, T, H, dh, sign);
+    rope_apply_vec_kernel<<<g, 256, 0, s>>>((unsigned short*)P0, (unsigned short*)P1, tab, rows, T, pos0, H, dh, sign);
     return;
   }
   dim3 g((unsigned)((rows * half + 255) / 256), ny);
   if (bf16)
-    rope_apply_kernel<bf16_t><<<g, 256, 0, s>>>((bf16_t*)P0, (bf16_t*)P1, tab, rows, T, H, dh, half, sign);
+    rope_apply_kernel<bf16_t><<<g, 256, 0, s>>>((bf16_t*)P0, (bf16_t*)P1, tab, rows, T, pos0, H, dh, half, sign);
   else
-    rope_apply_kernel<float><<<g, 256, 0, s>>>((float*)P0, (float*)P1, tab, rows, T, H, dh, half, sign);
+    rope_apply_kernel<float><<<g, 256, 0, s>>>((float*)P0, (float*)P1, tab, rows, T, pos0, H, dh, half, sign);
+}
+
+// out[(n / Tq) * T + (T - Tq) + n % Tq][:] += add[n][:] for the B*Tq rows of `add` (fp32): the rows of
+// the last Tq positions of every sequence take one more term.  One thread per element.
+template <typename TT>
+__global__ __launch_bounds__(256) void add_query_rows_kernel(TT* __restrict__ out, const float* __restrict__ add, long rows, int T,
+                                                             int Tq, int dm) {
+  const long id = (long)blockIdx.x * 256 + threadIdx.x;
+  if (id >= rows * dm) return;
+  const long n = id / dm;
+  const int c = (int)(id % dm);
+  const long o = ((n / Tq) * T + (T - Tq) + n % Tq) * dm + c;
+  st(out, o, ld(out, o) + add[id]);
+}
+
+void launch_add_query_rows(void* out, const float* add, long rows, int T, int Tq, int dm, int bf16, hipStream_t s) {
+  const long n = rows * dm;
+  if (!n) return;
+  const unsigned g = (unsigned)((n + 255) / 256);
+  if (bf16)
+    add_query_rows_kernel<bf16_t><<<g, 256, 0, s>>>((bf16_t*)out, add, rows, T, Tq, dm);
+  else
+    add_query_rows_kernel<float><<<g, 256, 0, s>>>((float*)out, add, rows, T, Tq, dm);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

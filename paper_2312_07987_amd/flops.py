@@ -37,16 +37,22 @@ def mem_switchhead_tables(nheads, d_head, T, C=2):
     return nheads * (4 * T * d_head + 2 * C * T * T + C * T * d_head)
 
 
-def layer_flops(B, T, d_model, nheads, d_head, E, k, causal=True, shared=False, dense=False, qk_experts=False):
+def layer_flops(B, T, d_model, nheads, d_head, E, k, causal=True, shared=False, dense=False, qk_experts=False, T_q=None):
     """Algorithmic flops of one forward / backward call of this library's layer (no
-    positional term, square attention).  Returns a dict of per-step and total counts."""
-    N = B * T
-    n_routers = 0 if dense else (1 if shared else 2)
-    router = 2 * N * d_model * n_routers * nheads * E
-    qk = 2 * (2 * N * d_model * nheads * d_head) * (k if qk_experts else 1)   # k experts per token when banks
+    positional term).  T_q < T: queries, destination-side routing and output only for the last
+    T_q positions of every sequence (attention over a cached context).  Returns a dict of
+    per-step and total counts."""
+    Tq = T if not T_q else T_q
+    N, Nq = B * T, B * Tq
+    if dense:
+        router = 0
+    else:   # source router over every token, destination router (or the shared one again) over the queries
+        router = 2 * d_model * nheads * E * ((N if shared and Tq == T else N + Nq))
+    kq = k if qk_experts else 1   # k experts per token when queries and keys are banks
+    qk = 2 * (N + Nq) * d_model * nheads * d_head * kq
     v = 2 * N * k * d_model * nheads * d_head
-    o = v
-    pairs = T * (T + 1) // 2 if causal else T * T
+    o = 2 * Nq * k * d_model * nheads * d_head
+    pairs = Tq * (T - Tq) + Tq * (Tq + 1) // 2 if causal else Tq * T
     attn = 4 * B * nheads * d_head * pairs
     fwd = router + qk + v + o + attn
     bwd = 2 * (router + qk + v + o) + (5 * attn) // 2

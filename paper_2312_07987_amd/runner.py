@@ -20,10 +20,12 @@ class DeviceLayer:
         self.tdtype = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
         self.shape = binding.make_shape(cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"],
                                         cfg["E"], cfg["k"], cfg.get("causal", 1), cfg["dtype"],
-                                        cfg.get("qk_experts", 0), cfg.get("rope", 0))
+                                        cfg.get("qk_experts", 0), cfg.get("rope", 0), cfg.get("T_q", 0))
         up = lambda a, dt: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(self.dev).to(dt).contiguous()
+        self.Tq = cfg.get("T_q", 0) or cfg["T"]      # queries per sequence (the last Tq positions)
         self.x = up(host["x"], self.tdtype)
-        self.dy = up(host.get("dy"), self.tdtype)
+        dy = host.get("dy")
+        self.dy = up(None if dy is None else dy[:, cfg["T"] - self.Tq:], self.tdtype)
         self.W = {n: up(host.get(n), self.tdtype) for n in _W}
         if dense:
             self.W["W_S"] = self.W["W_D"] = None
@@ -33,7 +35,7 @@ class DeviceLayer:
         if nbytes == 0:
             raise binding.SwitchHeadError(-1, binding.switchhead_last_error())
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
-        self.y = torch.empty_like(self.x)
+        self.y = torch.empty((cfg["B"], self.Tq, cfg["d_model"]), dtype=self.tdtype, device=self.dev)
         self.dx = torch.empty_like(self.x)
         f32 = lambda t: None if t is None else torch.empty(t.shape, dtype=torch.float32, device=self.dev)
         self.dW = {n: f32(self.W[n]) for n in _W}
@@ -61,7 +63,14 @@ class DeviceLayer:
         off = torch.empty((2, H, E + 1), dtype=torch.int32, device=self.dev)
         binding.switchhead_get_routing(self.shape, self.ws, idx, gate, perm, off)
         torch.cuda.synchronize()
-        return dict(idx=idx.cpu().numpy(), gate=gate.cpu().numpy(), perm=perm.cpu().numpy(), offsets=off.cpu().numpy())
+        out = dict(idx=idx.cpu().numpy(), gate=gate.cpu().numpy(), perm=perm.cpu().numpy(), offsets=off.cpu().numpy())
+        if self.Tq != c["T"]:
+            # the destination side's block holds B*Tq tokens packed at its front
+            Nq = c["B"] * self.Tq
+            out["idx_D"] = out["idx"][1].reshape(-1)[:H * Nq * k].reshape(H, Nq, k)
+            out["gate_D"] = out["gate"][1].reshape(-1)[:H * Nq * k].reshape(H, Nq, k)
+            out["perm_D"] = out["perm"][1].reshape(-1)[:H * Nq * k].reshape(H, Nq * k)
+        return out
 
     def intermediates(self):
         c = self.cfg
@@ -71,6 +80,10 @@ class DeviceLayer:
         binding.switchhead_get_intermediates(self.shape, self.ws, bufs["Q"], bufs["K"], bufs["V"], bufs["ctx"], lse)
         torch.cuda.synchronize()
         out = {n: t.cpu().numpy() for n, t in bufs.items()}
+        if self.Tq != c["T"]:
+            Nq = c["B"] * self.Tq
+            for n in ("Q", "ctx"):
+                out[n] = out[n].reshape(-1)[:Nq * H * dh].reshape(Nq, H, dh)
         out["lse"] = lse.cpu().numpy()
         return out
 

@@ -42,6 +42,7 @@ def test_workspace_bytes_and_shape_errors(lib):
                       (binding.make_shape(2, 64, 64, 2, 32, 4, 2, 2, "f32"), "causal"),
                       (binding.make_shape(2, 64, 64, 2, 32, 4, 2, 1, "f32", qk_experts=2), "qk_experts"),
                       (binding.make_shape(2, 64, 64, 2, 32, 4, 2, 1, "f32", rope=3), "rope"),
+                      (binding.make_shape(2, 64, 64, 2, 32, 4, 2, 1, "f32", T_q=65), "T_q"),
                       (binding.make_shape(2, 64, 64, 2, 32, 4, 2, 1, 7), "dtype")):
         assert binding.switchhead_workspace_bytes(bad) == 0
         assert word in binding.switchhead_last_error()

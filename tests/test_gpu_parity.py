@@ -39,7 +39,12 @@ def run_case(cfg, family=0, shared=False, dense=False, backward=True, seed=None,
     finally:
         binding.switchhead_set_kernel_family(prev)
     f = orc.forward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], t["b_S"], t["b_D"],
-                    k=cfg["k"], causal=bool(cfg["causal"]), rope=bool(cfg.get("rope")))
+                    k=cfg["k"], causal=bool(cfg["causal"]), rope=bool(cfg.get("rope")), T_q=cfg.get("T_q") or None)
+    Tq = cfg.get("T_q") or cfg["T"]
+    if Tq != cfg["T"]:   # fewer queries than keys: the destination side's tables hold B*Tq tokens
+        routing = dict(routing)
+        for nm in ("idx", "gate", "perm"):
+            routing[nm] = [routing[nm][0], routing[nm + "_D"]]
     tol = TOL[cfg["dtype"]]
     # integer work: exact
     for s, side in enumerate("SD"):
@@ -56,7 +61,7 @@ def run_case(cfg, family=0, shared=False, dense=False, backward=True, seed=None,
     print("  y err %.3e" % e, flush=True)
     assert e < tol
     if backward:
-        b = orc.backward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], f, t["dy"])
+        b = orc.backward(t["x"], t["W_Q"], t["W_K"], t["W_V"], t["W_O"], t["W_S"], t["W_D"], f, t["dy"][:, cfg["T"] - Tq:])
         errs = {}
         for n in GRADS:
             if b[n] is None:
@@ -175,6 +180,33 @@ def test_bf16_rotary_queries_and_keys(family):
 def test_full_config_rotary():
     """c2 at full size with rotary queries and keys, in the launch configuration bench.py times."""
     run_case(small("c2", rope=1), seed=50)
+
+
+@pytest.mark.parametrize("family", [0, 1])
+def test_fp32_fewer_queries_than_keys(family):
+    """Attention over a cached context (App. A.2): queries for the last T_q positions only."""
+    run_case(small("c0", T_q=32), family=family)
+    run_case(dict(name="ragxl", dtype="f32", B=3, T=37, d_model=50, nheads=3, d_head=20, E=7, k=3, causal=1, bias0=0.0,
+                  T_q=13, rope=1), family=family, seed=55)
+    run_case(dict(name="ragxl2", dtype="f32", B=2, T=45, d_model=32, nheads=2, d_head=16, E=4, k=2, causal=0, bias0=0.0,
+                  T_q=1, qk_experts=1), family=family, seed=56)
+    run_case(small("c0", T_q=40), family=family, shared=True, seed=57)
+    run_case(dict(name="densexl", dtype="f32", B=2, T=48, d_model=64, nheads=4, d_head=16, E=1, k=1, causal=1, bias0=0.0,
+                  T_q=16), family=family, dense=True, seed=58)
+
+
+@pytest.mark.parametrize("family", [0, 1])
+def test_bf16_fewer_queries_than_keys(family):
+    run_case(small("c2", B=3, T=400, d_model=320, nheads=2, d_head=128, T_q=200), family=family, seed=59)
+    run_case(small("c1", B=3, T=200, T_q=100, rope=1), family=family, seed=60)
+    run_case(small("c2", B=2, T=260, d_model=256, nheads=2, T_q=130, qk_experts=1), family=family, seed=61)
+    run_case(small("c2", B=2, T=260, d_model=256, nheads=2, T_q=77, causal=0), family=family, shared=True, seed=62)
+
+
+def test_full_config_cached_context():
+    """The paper's main setting at c2's sizes: a context twice the current chunk (T = 2 * 512 keys, 512
+    queries per sequence), in the launch configuration bench.py times."""
+    run_case(small("c2", T=1024, T_q=512), seed=63)
 
 
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
