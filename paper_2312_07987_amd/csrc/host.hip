@@ -928,7 +928,33 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   }
   // the query tokens' own share of dx (fewer queries than keys): fp32, added to their rows at the end
   float* accq = c.rect ? c.p<float>(c.L.accq) : nullptr;
-  if (c.rect) {
+  bool accq_set = false;
+  if (c.rect && !c.qk_experts) {
+    // dQ W_Q^T as one GEMM over the H concatenated head segments that overwrites the accumulator
+    RowGemmArgs a = identity_rows(c, 1, 1);
+    a.tag = TAG_QK_DGRAD;
+    a.A = c.p<void>(c.L.dQ);
+    a.lda = hd;
+    a.seg_mode = 2;
+    a.nseg = H;
+    a.seg_split = H;
+    a.a_sstride = dh;
+    a.B = W_Q;
+    a.b_sstride = (long)dm * dh;
+    a.sbk = 1;
+    a.sbn = dh;
+    a.C = accq;
+    a.ldc = dm;
+    a.K = dh;
+    a.Nc = dm;
+    a.mode = STORE_F32;
+    if (use_mfma(c) && mfma_row_gemm_supported(a)) {
+      prof_mark(c.st, "bwd.q_dgrad");
+      launch_mfma_row_gemm(a, c.st);
+      accq_set = true;
+    }
+  }
+  if (c.rect && !accq_set) {
     prof_mark(c.st, "bwd.dx_zero");
     launch_fill_f32(accq, (size_t)Nq * dm, 0.f, c.st);
     if (!c.qk_experts) {
@@ -1188,6 +1214,27 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       if (side == 1) {
         a.C = accq;
       } else {
+        if (sets && c.bf16 && use_mfma(c)) {
+          // the router packed as [d_model][HEp]: one GEMM, stored as one more bf16 partial of dx
+          bf16_t* Wp = (bf16_t*)(c.p<char>(c.L.rh));
+          RowGemmArgs p = a;
+          p.tag = TAG_QK_DGRAD;
+          p.seg_mode = 2;
+          p.nseg = 1;
+          p.seg_split = 1;
+          p.a_wstride = HEp;
+          p.B = Wp;
+          p.sbn = HEp;
+          p.K = HEp;
+          p.C = c.p<char>(c.L.yh) + (size_t)yh_taken() * N * dm * esz;
+          p.mode = STORE_T;
+          if (mfma_row_gemm_supported(p)) {
+            launch_pack_router(W, nullptr, Wp, dm, HE, HEp, 1, c.st);
+            launch_mfma_row_gemm(p, c.st);
+            router_partial = true;
+            continue;
+          }
+        }
         if (!acc_written) {
           launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
           acc_written = true;
