@@ -134,19 +134,22 @@ struct RowTile {
   }
 };
 
-// Work-group -> (sequence, head, tile).  All work-groups of a launch are resident at once
-// (two per CU), so under a causal mask the order decides the balance: the first half of the
-// grid holds the heavy tiles in descending order, the second half the light tiles in
-// ascending order, and the CU that got the r-th heaviest tile also gets the r-th lightest.
+// Work-group -> (sequence, head, tile).  Under a causal mask the tiles differ in weight and the
+// order decides the balance.  Where all work-groups of a launch are resident at once (`resident`
+// per CU on 256 CUs) the first half of the grid holds the heavy tiles in descending order, the
+// second half the light tiles in ascending order, and the CU that got the r-th heaviest tile also
+// gets the r-th lightest.  A larger grid is handed out as CUs become free, so the tiles simply come
+// heaviest first (longest-processing-time order): whichever CU frees up first takes the largest
+// piece left.
 // Consecutive ids go to different XCDs; id % 8 = (b*H + h) % 8 keeps all tiles of one
 // (sequence, head) on one XCD, whose L2 then serves the K/V re-reads.
-__device__ __forceinline__ void attn_block_map(int L, int ntile, int P, int H, bool causal, bool heavy_is_high, int& b,
-                                               int& h, int& tile) {
+__device__ __forceinline__ void attn_block_map(int L, int ntile, int P, int H, bool causal, bool heavy_is_high, int resident,
+                                               int& b, int& h, int& tile) {
   const int rank = L / P, pair = L % P;
   b = pair / H;
   h = pair % H;
   int t = rank;   // index counted from the heavy end
-  if (causal) {
+  if (causal && (long)ntile * P <= 256L * resident) {
     const int nheavy = (ntile + 1) / 2;
     t = rank < nheavy ? rank : ntile - 1 - (rank - nheavy);
   }
@@ -169,7 +172,7 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_fwd_kernel(A
   int b, h, qt;
   const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
   const int off = T - Tq;   // position of query 0 among the keys
-  attn_block_map(blockIdx.x, (Tq + 127) / 128, a.B * a.H, a.H, a.causal, true, b, h, qt);
+  attn_block_map(blockIdx.x, (Tq + 127) / 128, a.B * a.H, a.H, a.causal, true, DH <= 128 ? 2 : 1, b, h, qt);
   const int q0 = qt * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
@@ -353,7 +356,7 @@ __global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kerne
   unsigned short* Gt = SEP ? Gt_ : Gr;
 
   int b, h, ktile;
-  attn_block_map(blockIdx.x, (a.T + KB - 1) / KB, a.B * a.H, a.H, a.causal, false, b, h, ktile);
+  attn_block_map(blockIdx.x, (a.T + KB - 1) / KB, a.B * a.H, a.H, a.causal, false, DH <= 96 ? 2 : 1, b, h, ktile);
   const int k0 = ktile * KB;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
@@ -390,19 +393,25 @@ __global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kerne
   auto prefetch = [&](int q0) {
     tq.load(Q + (long)q0 * rs, rs, Tq - q0, dh, tid);
     tg.load(dO + (long)q0 * rs, rs, Tq - q0, dh, tid);
-    if (tid < QT) {
-      const bool ok = q0 + tid < Tq;
-      nlse = ok ? lse[q0 + tid] * 1.44269504088896340736f : 0.f;
-      ndel = ok ? delta[(long)(q0 + tid) * a.H] : 0.f;
-    }
+    // the softmax statistics of the tile's queries: loaded by every thread from a clamped index and
+    // left untouched until they are stored, so that neither a branch nor arithmetic on the loaded
+    // value makes the wave wait for this prefetch before it multiplies the current tile (rows past
+    // the end repeat the last query: their probabilities are masked to zero below)
+    const int qi = min(q0 + (tid & (QT - 1)), Tq - 1);
+    nlse = lse[qi];
+    ndel = delta[(long)qi * a.H];
   };
   if (qbeg < Tq) prefetch(qbeg);
+  // Every load issued so far (the K / V rows held in registers, the first tile) completes here.  Without
+  // this the compiler, which cannot tell the first trip of the loop from the others, waits for ALL
+  // outstanding loads, the prefetch of the next tile included, before the first product of every trip.
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
   for (int q0 = qbeg; q0 < Tq; q0 += QT) {
     __syncthreads();
     tq.store(Qr, LDR, Qt, LDT, tid);
     tg.store(Gr, LDR, Gt, LDT, tid);
     if (tid < QT) {
-      lse_s[tid] = nlse;
+      lse_s[tid] = nlse * 1.44269504088896340736f;
       del_s[tid] = ndel;
     }
     __syncthreads();
@@ -429,7 +438,8 @@ __global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kerne
         const int i = 4 * i4 + t;
         const int qq = q0 + 8 * i4 + 4 * g + t;
         const bool vis = qq < Tq && key < T && (!a.causal || key <= qq + off);
-        const float pv = vis ? __builtin_amdgcn_exp2f(fmaf(S[i], sc, -Lv[t])) : 0.f;
+        // the mask caps the argument (exp2(-inf) = 0): nothing is left that a branch could skip
+        const float pv = __builtin_amdgcn_exp2f(fminf(fmaf(S[i], sc, -Lv[t]), vis ? INFINITY : -INFINITY));
         p[i] = pv;
         ds[i] = pv * (dP[i] - Dv[t]);
       }
@@ -471,7 +481,7 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
   int b, h, qt;
   const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
   const int off = T - Tq;   // position of query 0 among the keys
-  attn_block_map(blockIdx.x, (Tq + 127) / 128, a.B * a.H, a.H, a.causal, true, b, h, qt);
+  attn_block_map(blockIdx.x, (Tq + 127) / 128, a.B * a.H, a.H, a.causal, true, DH <= 128 ? 2 : 1, b, h, qt);
   const int q0 = qt * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
@@ -530,7 +540,7 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
       for (int i = 0; i < 16; ++i) {
         const int key = k0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
         const bool vis = key < T && (!a.causal || key <= qpos);
-        const float pv = vis ? __builtin_amdgcn_exp2f(fmaf(S[i], sc, -lse2)) : 0.f;
+        const float pv = __builtin_amdgcn_exp2f(fminf(fmaf(S[i], sc, -lse2), vis ? INFINITY : -INFINITY));
         ds[i] = pv * (dP[i] - del);
       }
 #pragma unroll
