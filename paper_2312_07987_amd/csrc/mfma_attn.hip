@@ -428,20 +428,38 @@ __global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kerne
       dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Gr[r * LDR + kk * 16 + 8 * g]), vf[kk], dP, 0, 0, 0);
     }
     float p[16], ds[16];
+    // wave-uniform: most tiles lie wholly inside the visible region and need no per-element test
+    const bool need_mask = q0 + QT > Tq || wk_first + 32 > T || (a.causal && wk_first + 31 > q0 + off);
+    if (need_mask) {
 #pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      const float4 L = *(const float4*)&lse_s[8 * i4 + 4 * g];
-      const float4 D = *(const float4*)&del_s[8 * i4 + 4 * g];
-      const float Lv[4] = {L.x, L.y, L.z, L.w}, Dv[4] = {D.x, D.y, D.z, D.w};
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const float4 L = *(const float4*)&lse_s[8 * i4 + 4 * g];
+        const float4 D = *(const float4*)&del_s[8 * i4 + 4 * g];
+        const float Lv[4] = {L.x, L.y, L.z, L.w}, Dv[4] = {D.x, D.y, D.z, D.w};
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int i = 4 * i4 + t;
-        const int qq = q0 + 8 * i4 + 4 * g + t;
-        const bool vis = qq < Tq && key < T && (!a.causal || key <= qq + off);
-        // the mask caps the argument (exp2(-inf) = 0): nothing is left that a branch could skip
-        const float pv = __builtin_amdgcn_exp2f(fminf(fmaf(S[i], sc, -Lv[t]), vis ? INFINITY : -INFINITY));
-        p[i] = pv;
-        ds[i] = pv * (dP[i] - Dv[t]);
+        for (int t = 0; t < 4; ++t) {
+          const int i = 4 * i4 + t;
+          const int qq = q0 + 8 * i4 + 4 * g + t;
+          const bool vis = qq < Tq && key < T && (!a.causal || key <= qq + off);
+          // the mask caps the argument (exp2(-inf) = 0): nothing is left that a branch could skip
+          const float pv = __builtin_amdgcn_exp2f(fminf(fmaf(S[i], sc, -Lv[t]), vis ? INFINITY : -INFINITY));
+          p[i] = pv;
+          ds[i] = pv * (dP[i] - Dv[t]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const float4 L = *(const float4*)&lse_s[8 * i4 + 4 * g];
+        const float4 D = *(const float4*)&del_s[8 * i4 + 4 * g];
+        const float Lv[4] = {L.x, L.y, L.z, L.w}, Dv[4] = {D.x, D.y, D.z, D.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int i = 4 * i4 + t;
+          const float pv = __builtin_amdgcn_exp2f(fmaf(S[i], sc, -Lv[t]));
+          p[i] = pv;
+          ds[i] = pv * (dP[i] - Dv[t]);
+        }
       }
     }
 #pragma unroll

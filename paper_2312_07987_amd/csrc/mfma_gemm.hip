@@ -607,7 +607,11 @@ typedef WgCfg<2, 2, 2, 2, 1> WgSmall;   // 128 x 128
 typedef WgCfg<1, 4, 4, 2, 2> WgWide;    // 128 x 256, wave tile 128 x 64, two work-groups per CU
 typedef WgCfg<4, 1, 2, 4, 2> WgTall;    // 256 x 128, wave tile 64 x 128, two work-groups per CU
 
-template <class Cfg, int VEC, int TAG>
+// FULL: both feature counts are multiples of the tile, so every load is issued without a condition
+// (rows past the chunk repeat its last row and are zeroed on their way into LDS).  With the loads of a
+// step a fixed number, the wait before a step is staged names exactly the loads of that step and
+// leaves the younger ones of the next step in flight; a branch around a load makes it wait for all.
+template <class Cfg, int VEC, int TAG, bool FULL = false>
 __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NJ = Cfg::NJ;
   constexpr int LDA = Cfg::LDA, LDB = Cfg::LDB;
@@ -671,6 +675,10 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     for (int i = 0; i < A_N; ++i) {
       const int c = tid + i * 256;
       const int rr = c / A_CPR, fc = (c % A_CPR) * VEC;
+      if constexpr (FULL) {
+        ra[i] = *(const chunk_t*)(A + (long)row_of(ids[min(r0 + rr, rows - 1)], inv_a) * a.lda + (long)hh * a.a_hoff + i0 + fc);
+        continue;
+      }
       ra[i] = zero_chunk<VEC>();
       if (r0 + rr < rows && i0 + fc < a.Ka) {
         ra[i] = *(const chunk_t*)(A + (long)row_of(ids[r0 + rr], inv_a) * a.lda + (long)hh * a.a_hoff + i0 + fc);
@@ -680,6 +688,10 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     for (int i = 0; i < B_N; ++i) {
       const int c = tid + i * 256;
       const int rr = c / B_CPR, fc = (c % B_CPR) * VEC;
+      if constexpr (FULL) {
+        rb[i] = *(const chunk_t*)(Bm + (long)row_of(ids[min(r0 + rr, rows - 1)], inv_b) * a.ldb + (long)hh * a.b_hoff + j0 + fc);
+        continue;
+      }
       rb[i] = zero_chunk<VEC>();
       if (r0 + rr < rows && j0 + fc < a.Kb) {
         rb[i] = *(const chunk_t*)(Bm + (long)row_of(ids[r0 + rr], inv_b) * a.ldb + (long)hh * a.b_hoff + j0 + fc);
@@ -701,6 +713,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     for (int i = 0; i < B_N; ++i) {
       const int c = tid + i * 256;
       if (scaled && a.scale_b) rb[i] = scale_chunk(rb[i], gsc[min(staged_r0 + c / B_CPR, Cfg::MAX_CHUNK - 1)]);
+      if constexpr (FULL) rb[i] = staged_r0 + c / B_CPR < rows ? rb[i] : zero_chunk<VEC>();   // repeated rows count for nothing
       *(chunk_t*)(&Bs[(c / B_CPR) * LDB + (c % B_CPR) * VEC]) = rb[i];
     }
   };
@@ -843,11 +856,13 @@ static void launch_wg(const WgradArgs& a, hipStream_t s) {
   const int group_rows = a.perm ? a.max_group_rows : a.M;
   dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads * a.E, ti * tj));
   const size_t lds = Cfg::lds_bytes();
-  auto kern = mfma_wgrad_kernel<Cfg, VEC, TAG>;
+  const bool full = a.Ka % Cfg::BM == 0 && a.Kb % Cfg::BN == 0;
+  auto kern = full ? mfma_wgrad_kernel<Cfg, VEC, TAG, true> : mfma_wgrad_kernel<Cfg, VEC, TAG, false>;
   if (lds > 64 * 1024) {
     static bool raised = false;
     if (!raised) {
-      (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       raised = true;
     }
   }
