@@ -77,8 +77,8 @@ STEP_KERNEL = {
     "fwd.qk_proj": r"mfma_row_gemm_kernel<.*, 1, 0>", "fwd.v_experts": r"mfma_row_gemm_kernel<.*, 2, 0>",
     "fwd.o_experts": r"mfma_row_gemm_kernel<.*, 3, 1>", "bwd.o_dgrad": r"mfma_row_gemm_kernel<.*, 4, 0>",
     "bwd.v_dgrad": r"mfma_row_gemm_kernel<.*, 5, 1>", "bwd.qk_dgrad": r"mfma_row_gemm_kernel<.*, 6, 2>",
-    "bwd.o_wgrad": r"mfma_wgrad_kernel<.*, 8, 7>", "bwd.v_wgrad": r"mfma_wgrad_kernel<.*, 8, 8>",
-    "bwd.qk_wgrad": r"mfma_wgrad_kernel<.*, 8, 9>", "bwd.wgrad_reduce": r"wgrad_reduce_kernel",
+    "bwd.o_wgrad": r"mfma_wgrad_kernel<.*, 8, 7(, \w+)?>", "bwd.v_wgrad": r"mfma_wgrad_kernel<.*, 8, 8(, \w+)?>",
+    "bwd.qk_wgrad": r"mfma_wgrad_kernel<.*, 8, 9(, \w+)?>", "bwd.wgrad_reduce": r"wgrad_reduce_kernel",
     "fwd.attention": r"mfma_attn_fwd_kernel", "bwd.attention_dkv": r"mfma_attn_dkv_kernel",
     "bwd.attention_dq": r"mfma_attn_dq_kernel", "fwd.y_sum": r"sum_heads_kernel", "bwd.dx_cast": r"sum_heads_kernel",
     "fwd.v_combine": r"slot_combine", "bwd.dctx_combine": r"slot_combine", "bwd.dgate_s": r"slot_combine",

@@ -554,10 +554,12 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
         dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Vr[(kb * 32 + r) * LDR + kk * 16 + 8 * g]), gf[kk], dP, 0, 0, 0);
       }
       float ds[16];
+      // key of element i = k0 + kb*32 + 4g + (8*(i/4) + i%4): visible iff that constant offset is at most
+      // `lim` (one compare per element); the mask caps the exponent's argument, exp2(-inf) = 0
+      const int lim = (a.causal ? min(T - 1, qpos) : T - 1) - (k0 + kb * 32 + 4 * g);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int key = k0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-        const bool vis = key < T && (!a.causal || key <= qpos);
+        const bool vis = 8 * (i >> 2) + (i & 3) <= lim;
         const float pv = __builtin_amdgcn_exp2f(fminf(fmaf(S[i], sc, -lse2), vis ? INFINITY : -INFINITY));
         ds[i] = pv * (dP[i] - del);
       }

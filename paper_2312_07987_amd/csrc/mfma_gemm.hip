@@ -611,8 +611,12 @@ typedef WgCfg<4, 1, 2, 4, 2> WgTall;    // 256 x 128, wave tile 64 x 128, two wo
 // (rows past the chunk repeat its last row and are zeroed on their way into LDS).  With the loads of a
 // step a fixed number, the wait before a step is staged names exactly the loads of that step and
 // leaves the younger ones of the next step in flight; a branch around a load makes it wait for all.
-template <class Cfg, int VEC, int TAG, bool FULL = false>
+// MODE 0 is the general form; 1..3 are FULL with the gate fixed at compile time (1 none, 2 on the rows
+// of A, 3 on the rows of Bm) and with the operand row (the row id divided by the shared a_div = b_div)
+// kept in LDS instead of the id, which takes the division out of every load's address.
+template <class Cfg, int VEC, int TAG, int MODE = 0>
 __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a) {
+  constexpr bool FULL = MODE != 0;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NJ = Cfg::NJ;
   constexpr int LDA = Cfg::LDA, LDB = Cfg::LDB;
   typedef typename Chunk<VEC>::type chunk_t;
@@ -647,7 +651,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int t = tid; t < rows; t += 256) {
     int id = a.perm ? a.perm[(long)h * a.M + row0 + t] : row0 + t;
-    ids[t] = id;
+    ids[t] = FULL ? div_by(id, div_magic(a.a_div)) : id;
     gsc[t] = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
   }
   // rows past the chunk that a computed step can touch are staged as zeros; give them a zero gate too
@@ -666,7 +670,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   // row id -> operand row: ids are divided by a small constant (the k slots of a token share a row);
   // multiply-high by ceil(2^32 / d) is exact for ids below 2^32 / d
   const unsigned inv_a = div_magic(a.a_div), inv_b = div_magic(a.b_div);
-  auto row_of = [](int id, unsigned inv) { return div_by(id, inv); };
+  auto row_of = [](int id, unsigned inv) { return FULL ? id : div_by(id, inv); };   // FULL: already divided
   // two register sets: a step's rows are requested two steps before they are multiplied, so a
   // load has two steps of the work-group (and of its neighbour on the CU) to arrive
   chunk_t ra0[A_N], rb0[B_N], ra1[A_N], rb1[B_N];
@@ -706,15 +710,17 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
       const int c = tid + i * 256;
-      if (scaled && !a.scale_b) ra[i] = scale_chunk(ra[i], gsc[min(staged_r0 + c / A_CPR, Cfg::MAX_CHUNK - 1)]);
-      *(chunk_t*)(&As[(c / A_CPR) * LDA + (c % A_CPR) * VEC]) = ra[i];
+      chunk_t v = ra[i];   // a copy: the register sets themselves are only ever written by the loads
+      if (MODE == 2 || (MODE == 0 && scaled && !a.scale_b)) v = scale_chunk(v, gsc[min(staged_r0 + c / A_CPR, Cfg::MAX_CHUNK - 1)]);
+      *(chunk_t*)(&As[(c / A_CPR) * LDA + (c % A_CPR) * VEC]) = v;
     }
 #pragma unroll
     for (int i = 0; i < B_N; ++i) {
       const int c = tid + i * 256;
-      if (scaled && a.scale_b) rb[i] = scale_chunk(rb[i], gsc[min(staged_r0 + c / B_CPR, Cfg::MAX_CHUNK - 1)]);
-      if constexpr (FULL) rb[i] = staged_r0 + c / B_CPR < rows ? rb[i] : zero_chunk<VEC>();   // repeated rows count for nothing
-      *(chunk_t*)(&Bs[(c / B_CPR) * LDB + (c % B_CPR) * VEC]) = rb[i];
+      chunk_t v = rb[i];
+      if (MODE == 3 || (MODE == 0 && scaled && a.scale_b)) v = scale_chunk(v, gsc[min(staged_r0 + c / B_CPR, Cfg::MAX_CHUNK - 1)]);
+      if constexpr (FULL) v = staged_r0 + c / B_CPR < rows ? v : zero_chunk<VEC>();   // repeated rows count for nothing
+      *(chunk_t*)(&Bs[(c / B_CPR) * LDB + (c % B_CPR) * VEC]) = v;
     }
   };
 
@@ -856,13 +862,18 @@ static void launch_wg(const WgradArgs& a, hipStream_t s) {
   const int group_rows = a.perm ? a.max_group_rows : a.M;
   dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads * a.E, ti * tj));
   const size_t lds = Cfg::lds_bytes();
-  const bool full = a.Ka % Cfg::BM == 0 && a.Kb % Cfg::BN == 0;
-  auto kern = full ? mfma_wgrad_kernel<Cfg, VEC, TAG, true> : mfma_wgrad_kernel<Cfg, VEC, TAG, false>;
+  const bool full = a.Ka % Cfg::BM == 0 && a.Kb % Cfg::BN == 0 && a.a_div == a.b_div;
+  const int mode = !full ? 0 : (a.gate == nullptr ? 1 : (a.scale_b ? 3 : 2));
+  auto kern = mode == 0 ? mfma_wgrad_kernel<Cfg, VEC, TAG, 0>
+            : mode == 1 ? mfma_wgrad_kernel<Cfg, VEC, TAG, 1>
+            : mode == 2 ? mfma_wgrad_kernel<Cfg, VEC, TAG, 2> : mfma_wgrad_kernel<Cfg, VEC, TAG, 3>;
   if (lds > 64 * 1024) {
     static bool raised = false;
     if (!raised) {
-      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       raised = true;
     }
   }
