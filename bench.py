@@ -74,9 +74,9 @@ def step_work(cfg):
 # Which kernel a profiled step launches, as a pattern on the kernel name rocprofv3 reports
 # (row GEMM: "..., <B transposed>, <tag>, <segment mode>>"; weight gradient: "..., <vec>, <tag>>").
 STEP_KERNEL = {
-    "fwd.qk_proj": r"mfma_row_gemm_kernel<.*, 1, 0>", "fwd.v_experts": r"mfma_row_gemm_kernel<.*, 2, 0>",
-    "fwd.o_experts": r"mfma_row_gemm_kernel<.*, 3, 1>", "bwd.o_dgrad": r"mfma_row_gemm_kernel<.*, 4, 0>",
-    "bwd.v_dgrad": r"mfma_row_gemm_kernel<.*, 5, 1>", "bwd.qk_dgrad": r"mfma_row_gemm_kernel<.*, 6, 2>",
+    "fwd.qk_proj": r"mfma_row_gemm_kernel<.*, 1, 0(, \w+)?>", "fwd.v_experts": r"mfma_row_gemm_kernel<.*, 2, 0(, \w+)?>",
+    "fwd.o_experts": r"mfma_row_gemm_kernel<.*, 3, 1(, \w+)?>", "bwd.o_dgrad": r"mfma_row_gemm_kernel<.*, 4, 0(, \w+)?>",
+    "bwd.v_dgrad": r"mfma_row_gemm_kernel<.*, 5, 1(, \w+)?>", "bwd.qk_dgrad": r"mfma_row_gemm_kernel<.*, 6, 2(, \w+)?>",
     "bwd.o_wgrad": r"mfma_wgrad_kernel<.*, 8, 7(, \w+)?>", "bwd.v_wgrad": r"mfma_wgrad_kernel<.*, 8, 8(, \w+)?>",
     "bwd.qk_wgrad": r"mfma_wgrad_kernel<.*, 8, 9(, \w+)?>", "bwd.wgrad_reduce": r"wgrad_reduce_kernel",
     "fwd.attention": r"mfma_attn_fwd_kernel", "bwd.attention_dkv": r"mfma_attn_dkv_kernel",
