@@ -95,6 +95,37 @@ __device__ __forceinline__ uint2 scale_chunk(uint2 c, float g) { return make_uin
 __device__ __forceinline__ unsigned div_magic(int d) { return d > 1 ? 0xFFFFFFFFu / (unsigned)d + 1u : 0u; }
 __device__ __forceinline__ int div_by(int id, unsigned inv) { return inv ? (int)__umulhi((unsigned)id, inv) : id; }
 
+// The tile-th row tile of a head whose groups (experts or expert sets, at most 128) start at off[0..E]:
+// every lane takes the groups `lane` and `lane + 64`, a wave prefix sum of their tile counts finds the
+// group in one round of loads (a serial scan pays one dependent scalar load per group).  Returns false
+// past the last tile.  All lanes get the same answer.
+__device__ __forceinline__ bool find_tile_wave(const int* off, int E, int bm, int tile, int lane, int& e, int& row0, int& rows) {
+  const int b0 = off[min(lane, E)], e0 = off[min(lane + 1, E)];
+  const int b1 = off[min(lane + 64, E)], e1 = off[min(lane + 65, E)];
+  const int c0 = (e0 - b0 + bm - 1) / bm, c1 = (e1 - b1 + bm - 1) / bm;   // 0 for lanes past the last group
+  int p0 = c0, p1 = c1;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int u0 = __shfl_up(p0, d, 64), u1 = __shfl_up(p1, d, 64);
+    if (lane >= d) {
+      p0 += u0;
+      p1 += u1;
+    }
+  }
+  const int total0 = __shfl(p0, 63, 64);
+  p1 += total0;
+  const unsigned long long m0 = __ballot(tile < p0), m1 = __ballot(tile < p1);
+  if (!(m0 | m1)) return false;
+  const bool low = m0 != 0;
+  const int src = low ? __builtin_ctzll(m0) : __builtin_ctzll(m1);
+  e = low ? src : src + 64;
+  const int first = __shfl(low ? p0 - c0 : p1 - c1, src, 64);   // tiles before this group
+  const int beg = __shfl(low ? b0 : b1, src, 64), end = __shfl(low ? e0 : e1, src, 64);
+  row0 = beg + (tile - first) * bm;
+  rows = end - row0 < bm ? end - row0 : bm;
+  return true;
+}
+
 __device__ __forceinline__ void decode_block(int L, int per_window, int& w, int& slot) {
   const int S = 8 * per_window;
   const int w8 = L / S, rr = L % S;
@@ -153,7 +184,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
     const int tph = (a.M + BM - 1) / BM + a.E;   // upper bound of the row tiles of one head
     h = w / tph;
     if (h >= a.heads) return;
-    if (!find_tile(a.offsets + (long)h * (a.E + 1), a.E, BM, w % tph, e, row0, rows)) return;
+    if (!find_tile_wave(a.offsets + (long)h * (a.E + 1), a.E, BM, w % tph, threadIdx.x & 63, e, row0, rows)) return;
   } else {
     decode_block(blockIdx.x, a.heads * a.E * ncol, w, slot);
     const int grp = slot / ncol;
@@ -178,24 +209,40 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nseg = SEG ? a.nseg : 1;
-  for (int t = tid; t < BM; t += 256) {
-    int id = -1;
-    float g = 0.f;
-    if (t < rows) {
-      id = a.perm ? a.perm[(long)h * a.M + row0 + t] : row0 + t;
-      if constexpr (SEG != 1) g = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
-    }
-    ids[t] = id;
-    if constexpr (SEG != 1) gsc[t] = g;
-  }
   if constexpr (SEG == 1) {
-    for (int t = tid; t < BM * nseg; t += 256) {
-      int rr = t / nseg, p = t % nseg;
-      float g = 0.f;
-      if (rr < rows) g = a.segate[(long)h * a.gate_hstride + (long)(row0 + rr) * nseg + p];
-      gsc[rr * 8 + p] = g;
+    // the rows' ids, their gates and the segments' experts are independent loads: all are requested
+    // before the first is waited for
+    constexpr int GS = (BM * 8 + 255) / 256;
+    float gv[GS];
+#pragma unroll
+    for (int u = 0; u < GS; ++u) {
+      const int t = tid + u * 256, rr = t / nseg, p = t % nseg;
+      gv[u] = 0.f;
+      if (t < BM * nseg && rr < rows) gv[u] = a.segate[(long)h * a.gate_hstride + (long)(row0 + rr) * nseg + p];
     }
-    if (tid < nseg) bseg[tid] = (long)hh * a.b_hstride + (long)a.set_experts[e * 8 + tid] * a.b_estride;
+    static_assert(BM <= 256, "one row id per thread");
+    int idv = -1;
+    if (tid < rows) idv = a.perm ? a.perm[(long)h * a.M + row0 + tid] : row0 + tid;
+    long bs = 0;
+    if (tid < nseg) bs = (long)hh * a.b_hstride + (long)a.set_experts[e * 8 + tid] * a.b_estride;
+    if (tid < BM) ids[tid] = idv;
+#pragma unroll
+    for (int u = 0; u < GS; ++u) {
+      const int t = tid + u * 256;
+      if (t < BM * nseg) gsc[(t / nseg) * 8 + t % nseg] = gv[u];
+    }
+    if (tid < nseg) bseg[tid] = bs;
+  } else {
+    for (int t = tid; t < BM; t += 256) {
+      int id = -1;
+      float g = 0.f;
+      if (t < rows) {
+        id = a.perm ? a.perm[(long)h * a.M + row0 + t] : row0 + t;
+        g = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
+      }
+      ids[t] = id;
+      gsc[t] = g;
+    }
   }
   __syncthreads();
 
@@ -486,7 +533,7 @@ static int row_gemm_vec(const RowGemmArgs& a) {
 }
 
 bool mfma_row_gemm_supported(const RowGemmArgs& a) {
-  if (a.seg_mode == 1 && (a.nseg < 1 || a.nseg > 8)) return false;
+  if (a.seg_mode == 1 && (a.nseg < 1 || a.nseg > 8 || a.E > 128)) return false;   // the tile lookup covers 128 groups
   if (a.tag == TAG_ROUTER && (a.Nc > 32 || a.mode != STORE_F64 || a.seg_mode != 0)) return false;
   // row ids stay below M; the multiply-high division needs id * divisor < 2^32
   if ((long)a.M * (a.a_div > a.c_div ? a.a_div : a.c_div) >= (1L << 32)) return false;
