@@ -250,48 +250,41 @@ __global__ void dense_routing_kernel(int* idx, float* gate, int* perm, int* offs
 // the fp32-level gaps that send an entry here -- and gives bit-identical sums for identical
 // columns, so ties still resolve to the lower index.
 // ----------------------------------------------------------------------------------------
-// Per (side, head) work-group: the largest column norm of the head's router (for the error bound),
-// the queue counter cleared, and the head's columns copied out as contiguous vectors
-// Wt[side][h*E + e][dmp] (zero padded to dmp, a multiple of 1024) for the fp64 recheck.
+// Per (side, head, expert) work-group: the squared norm of that router column (the error bound takes
+// the largest of a head's), the head's queue counter cleared, the column copied out as a contiguous
+// vector Wt[side][h*E + e][dmp] (zero padded to dmp, a multiple of 1024) for the fp64 recheck and into
+// the padded matrix Wp[side][i][HEp] the logits GEMM reads (the last column also zeroes the padding).
 __global__ __launch_bounds__(256) void router_prep_kernel(const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
-                                                          float* __restrict__ wmax, int* __restrict__ fixcount,
+                                                          float* __restrict__ wnorm2, int* __restrict__ fixcount,
                                                           unsigned short* __restrict__ Wt, unsigned short* __restrict__ Wp,
                                                           int dm, int dmp, int H, int E, int HEp) {
   __shared__ float red[4];
-  const int sh_ = blockIdx.x;
-  const int side = sh_ / H, h = sh_ % H;
-  const unsigned short* W = (const unsigned short*)(side ? W1 : W0);
   const int HE = H * E;
+  const int side = blockIdx.x / HE, col = blockIdx.x % HE;   // col = h*E + e
+  const unsigned short* W = (const unsigned short*)(side ? W1 : W0);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  // this head's columns of the padded copy Wp[side][i][HEp] for the logits GEMM (the last head also
-  // zeroes the padding columns)
   unsigned short* wp = Wp + (long)side * dm * HEp;
-  if (h == H - 1)
+  if (col == HE - 1)
     for (int t = threadIdx.x; t < dm * (HEp - HE); t += 256) wp[(long)(t / (HEp - HE)) * HEp + HE + t % (HEp - HE)] = 0;
-  float mx = 0.f;
-  for (int e = 0; e < E; ++e) {
-    float s = 0.f;
-    unsigned short* wt = Wt + ((long)side * HE + h * E + e) * dmp;
-    for (int i = threadIdx.x; i < dmp; i += 256) {
-      unsigned short v = 0;
-      if (i < dm) {
-        v = W[(long)i * HE + h * E + e];
-        wp[(long)i * HEp + h * E + e] = v;
-      }
-      wt[i] = v;
-      const float f = __uint_as_float((unsigned)v << 16);
-      s = fmaf(f, f, s);
+  float s = 0.f;
+  unsigned short* wt = Wt + ((long)side * HE + col) * dmp;
+  for (int i = threadIdx.x; i < dmp; i += 256) {
+    unsigned short v = 0;
+    if (i < dm) {
+      v = W[(long)i * HE + col];
+      wp[(long)i * HEp + col] = v;
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    __syncthreads();
-    if (lane == 0) red[wave] = s;
-    __syncthreads();
-    mx = fmaxf(mx, red[0] + red[1] + red[2] + red[3]);
+    wt[i] = v;
+    const float f = __uint_as_float((unsigned)v << 16);
+    s = fmaf(f, f, s);
   }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (lane == 0) red[wave] = s;
+  __syncthreads();
   if (threadIdx.x == 0) {
-    wmax[sh_] = sqrtf(mx) * 1.0001f;
-    fixcount[sh_] = 0;
+    wnorm2[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+    if (col % E == 0) fixcount[side * H + col / E] = 0;
   }
 }
 
@@ -302,7 +295,7 @@ constexpr int SEL_TOK = 64;   // tokens per work-group of select_kernel
 // against the error bound; entries that fail are queued for the fp64 recheck.
 __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ Zs, const float* __restrict__ b0,
                                                      const float* __restrict__ b1, const float* __restrict__ xnorm,
-                                                     const float* __restrict__ wmax, int* __restrict__ idx,
+                                                     const float* __restrict__ wnorm2, int* __restrict__ idx,
                                                      float* __restrict__ gate, int* __restrict__ fixlist,
                                                      int* __restrict__ fixcount, int N, int kstep, int H, int E, int k,
                                                      int HEp) {
@@ -320,7 +313,9 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
     const int sh_ = side * H + h;
     const double* z = zt + nl * HEp + h * E;
     // fp32 partial sums of `kstep` exact products, then fp64 adds: see the bound above
-    const double bound0 = 4.0 * (double)kstep * 5.9604645e-8 * (double)xnorm[n] * (double)wmax[sh_];
+    float w2 = 0.f;   // largest squared column norm of this head's router
+    for (int e = 0; e < E; ++e) w2 = fmaxf(w2, wnorm2[(long)sh_ * E + e]);
+    const double bound0 = 4.0 * (double)kstep * 5.9604645e-8 * (double)xnorm[n] * (double)(sqrtf(w2) * 1.0001f);
     unsigned long long sel = 0ull;
     const long o = ((long)sh_ * N + n) * k;
     double prev = 0.0, bprev = 0.0;
@@ -500,7 +495,7 @@ size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off) {
   off[0] = take(2 * (size_t)dm * HEp * 2);   // Wp
   off[1] = take(2 * (size_t)N * HEp * 8);    // Zs: stage-1 logits, fp64
   off[2] = take((size_t)N * 4);              // xnorm
-  off[3] = take(2 * (size_t)H * 4);          // wmax
+  off[3] = take(2 * (size_t)H * E * 4);      // squared column norms
   off[4] = take(2 * (size_t)H * N * 4);      // fixlist
   off[5] = take(2 * (size_t)H * 4 + 256);    // fixcount per (side, head)
   off[6] = take(2 * (size_t)H * E * (((size_t)dm + 1023) / 1024 * 1024) * 2);   // Wt: router columns as vectors
@@ -681,7 +676,7 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
 
   // per (side, head): largest column norm, queue counter cleared, columns copied out as vectors and
   // into the padded matrix the GEMM reads
-  router_prep_kernel<<<a.sides * a.H, 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], wmax, fixcount, Wt,
+  router_prep_kernel<<<a.sides * a.H * a.E, 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], wmax, fixcount, Wt,
                                                    (unsigned short*)Wp, a.dm, dmp, a.H, a.E, HEp);
   // stage 1: z32 = x W on the matrix cores, fp32 accumulation, both sides in one launch
   RowGemmArgs g{};
