@@ -370,30 +370,45 @@ __global__ __launch_bounds__(64 * FIX_WAVES) void fix64_kernel(const bf16_t* __r
   for (int item = blockIdx.x * FIX_WAVES + wave; item < count; item += gridDim.x * FIX_WAVES) {
     const int n = fixlist[(long)sh_ * N + item];
     const unsigned short* xrow = (const unsigned short*)x + (long)n * dm;   // dm % 4 == 0: 8-byte aligned rows
-    for (int e = 0; e < E; ++e) {
-      double acc = 0.0;
+    // eight experts at a time: the token's features are loaded once per slab and the eight columns'
+    // loads are in flight together (one expert after the other pays one memory round trip each)
+    for (int e0 = 0; e0 < E; e0 += 8) {
+      double acc[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc[u] = 0.0;
       for (int s0 = 0; s0 < dmp; s0 += 1024) {
         const int i0 = s0 + lane * 16;
         uint2 xv[4];
-        uint4 wv[2];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           xv[q] = make_uint2(0, 0);
           if (i0 + 4 * q < dm) xv[q] = *(const uint2*)(xrow + i0 + 4 * q);
         }
-        wv[0] = *(const uint4*)(wt0 + (long)e * dmp + i0);
-        wv[1] = *(const uint4*)(wt0 + (long)e * dmp + i0 + 8);
-        const unsigned xw[8] = {xv[0].x, xv[0].y, xv[1].x, xv[1].y, xv[2].x, xv[2].y, xv[3].x, xv[3].y};
-        const unsigned ww[8] = {wv[0].x, wv[0].y, wv[0].z, wv[0].w, wv[1].x, wv[1].y, wv[1].z, wv[1].w};
+        uint4 wv[8][2];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          acc = fma((double)__uint_as_float(xw[q] << 16), (double)__uint_as_float(ww[q] << 16), acc);
-          acc = fma((double)__uint_as_float(xw[q] & 0xffff0000u), (double)__uint_as_float(ww[q] & 0xffff0000u), acc);
+        for (int u = 0; u < 8; ++u) {
+          const int e = e0 + u < E ? e0 + u : E - 1;   // past the last expert: a repeat, never stored
+          wv[u][0] = *(const uint4*)(wt0 + (long)e * dmp + i0);
+          wv[u][1] = *(const uint4*)(wt0 + (long)e * dmp + i0 + 8);
+        }
+        const unsigned xw[8] = {xv[0].x, xv[0].y, xv[1].x, xv[1].y, xv[2].x, xv[2].y, xv[3].x, xv[3].y};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const unsigned ww[8] = {wv[u][0].x, wv[u][0].y, wv[u][0].z, wv[u][0].w, wv[u][1].x, wv[u][1].y, wv[u][1].z, wv[u][1].w};
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            acc[u] = fma((double)__uint_as_float(xw[q] << 16), (double)__uint_as_float(ww[q] << 16), acc[u]);
+            acc[u] = fma((double)__uint_as_float(xw[q] & 0xffff0000u), (double)__uint_as_float(ww[q] & 0xffff0000u), acc[u]);
+          }
         }
       }
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-      if (lane == 0) zs[wave][e] = acc + (b ? (double)b[h * E + e] : 0.0);
+      for (int u = 0; u < 8; ++u) {
+        double v = acc[u];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        if (lane == 0 && e0 + u < E) zs[wave][e0 + u] = v + (b ? (double)b[h * E + e0 + u] : 0.0);
+      }
     }
     if (lane == 0) {
       double* z = Z + ((long)side * N + n) * HE + (long)h * E;
