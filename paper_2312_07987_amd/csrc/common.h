@@ -121,10 +121,13 @@ struct WgradArgs {
   int chunk;  // rows reduced by one block
   int tag;
   int max_group_rows;  // upper bound of the rows of one group (tokens per call)
-  // Second operand set: heads h >= hsplit (hsplit > 0) use Bm2 / dW2 with head index h - hsplit.
+  // Further operand sets (hsplit > 0): head h belongs to set h / hsplit with head index h % hsplit;
+  // set 1 uses Bm2 / dW2, set 2 (MFMA kernel with partial sums only) Bm3 / dW3.
   const void* Bm2;
   float* dW2;
   int hsplit;
+  const void* Bm3;
+  float* dW3;
   // Deterministic reduction (MFMA kernel): if partial != NULL every block stores the partial
   // sum of its chunk to partial[((h*E + e)*max_chunks + chunk)*Ka*Kb + i*Kb + j] and
   // launch_wgrad_reduce adds the chunks of each group into dW (plain stores, no zero fill).
@@ -237,6 +240,8 @@ void launch_rope_apply(void* P0, void* P1, const float2* tab, long N, int T, int
                        hipStream_t s);
 // out [B, T, dm] (storage type) += add [B, Tq, dm] (fp32) on the last Tq rows of every sequence
 void launch_add_query_rows(void* out, const float* add, long rows, int T, int Tq, int dm, int bf16, hipStream_t s);
+// dW0[i][c] = T[i*ld + c], dW1[i][c] = T[i*ld + HEp + c] for c < HE (either output may be NULL)
+void launch_router_wgrad_split(const float* T, float* dW0, float* dW1, int dm, int ld, int HE, int HEp, hipStream_t s);
 void launch_sum_heads(const void* part, const float* add32, void* out, size_t n, size_t hstride, int H, hipStream_t s);
 
 // out[n,h,:] = sum_j gate[h][n*k+j] * slots[h][n*k+j][:]   (slots [H, N*k, dh], storage type T)

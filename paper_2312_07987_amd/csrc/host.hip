@@ -70,6 +70,7 @@ struct Layout {
   size_t xq, accq;   // fewer queries than keys only: the query tokens' rows of x; their fp32 share of dx
   size_t Z, blockcnt, acc32;                                       // forward scratch
   size_t setid, gset, gsort, setexp, setperm, setoff, setcnt, yh;
+  size_t wrt;                                                      // x^T dz of both routers [dm, dh] fp32 (fused with the Q/K weight gradient)
   size_t dR, wr3;                                                  // wide router dz rows [N, H*dh], routers packed [dm, dh]                 // expert-set path (bf16 only)
   size_t rh;                                                       // two-stage router scratch (bf16 only)
   size_t wpart;                                                    // per-chunk weight-gradient partial sums (bf16 only)
@@ -161,6 +162,7 @@ Layout make_layout(const sh_shape* s) {
   L.dR = take(N * H * dh * esz);   // directly behind dK, same size: a third operand set for the Q/K dgrad GEMM
   L.dV = take(N * H * dh * esz);
   L.wr3 = take(dm * dh * esz);
+  L.wrt = take(dm * dh * 4);
   L.delta = take(N * H * 4);
   L.dgate = take(2 * H * N * k * 4);
   L.dz = take(N * 2 * ((H * E + 7) / 8 * 8) * esz);   // each side padded to a multiple of 8 columns
@@ -182,7 +184,7 @@ Layout make_layout(const sh_shape* s) {
   L.rh = L.wpart = 0;
   if (s->dtype == SH_BF16) {
     // groups x chunks-per-group x one expert matrix, fp32 (the dense Q/K pair counts as 2H groups)
-    const size_t groups = H * E > 2 * H ? H * E : 2 * H;   // expert Q/K banks: H * E groups each, one at a time
+    const size_t groups = H * E > 2 * H + 1 ? H * E : 2 * H + 1;   // expert Q/K banks: H * E groups each, one at a time
     const size_t ce = wgrad_chunk(H * N * k, dm, dh), cd = wgrad_chunk(2 * H * N, dm, dh);
     const size_t cmin = ce < cd ? ce : cd;
     L.wpart = take(groups * ((N + cmin - 1) / cmin) * dm * dh * 4);
@@ -886,11 +888,14 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   float* dxacc = c.bf16 ? c.p<float>(c.L.acc32) : (float*)dx;
   bool qk_partial = false;    // the Q/K share of dx sits in a bf16 partial, not in dxacc
   bool acc_written = false;   // dxacc holds (part of) dx
-  if (!c.qk_experts) {
-    prof_mark(c.st, "bwd.qk_wgrad");
+  // dW_Q, dW_K = x^T dQ, x^T dK as one launch over the 2H (projection, head) pairs; with_router: the
+  // routers' x^T dz rides along as one more head (dz sits in rows shaped like a dQ / dK row)
+  auto qk_wgrad_args = [&](bool with_router) {
     WgradArgs w{};
     w.tag = TAG_QK_WGRAD;
-    w.heads = 2 * H;
+    w.heads = 2 * H + (with_router ? 1 : 0);
+    w.Bm3 = c.p<void>(c.L.dR);
+    w.dW3 = c.p<float>(c.L.wrt);
     w.hsplit = H;
     w.E = 1;
     w.M = N;
@@ -910,6 +915,11 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.w_hstride = (long)dm * dh;
     w.swa = dh;
     w.chunk = chunk_dense;
+    return w;
+  };
+  auto run_qk_wgrad = [&](bool with_router) {
+    prof_mark(c.st, "bwd.qk_wgrad");
+    WgradArgs w = qk_wgrad_args(with_router);
     if (!c.rect) {
       wgrad(c, w);
     } else {   // queries and keys come from different token sets: one launch each
@@ -925,7 +935,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       w.dW = dW_K;
       wgrad(c, w);
     }
-  }
+  };
   // the query tokens' own share of dx (fewer queries than keys): fp32, added to their rows at the end
   float* accq = c.rect ? c.p<float>(c.L.accq) : nullptr;
   bool accq_set = false;
@@ -983,6 +993,16 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   const bool wide_dz = !c.dense && sides_r * HEp_r <= dh && (c.L.dR - c.L.dK) == (c.L.dK - c.L.dQ);
   const bool fuse_router = wide_dz && sets && c.bf16 && use_mfma(c) && !c.qk_experts && !c.rect;
   bool router_fused = false;
+  // the routers' weight gradients ride along with the Q/K weight gradient under the same conditions,
+  // if the three-set launch is one the matrix-core kernel takes (it has no other implementation)
+  bool fuse_router_w = false;
+  if (fuse_router && dW_S && (c.shared || dW_D)) {
+    WgradArgs probe = qk_wgrad_args(true);
+    probe.partial = c.p<float>(c.L.wpart);
+    probe.max_chunks = (probe.M + probe.chunk - 1) / probe.chunk;
+    fuse_router_w = mfma_wgrad_supported(probe);
+  }
+  if (!c.qk_experts && !fuse_router_w) run_qk_wgrad(false);
   auto run_qk_dgrad = [&](bool with_router) {
     RowGemmArgs a = identity_rows(c, 1);
     a.tag = TAG_QK_DGRAD;
@@ -1250,7 +1270,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     float* dWs[2] = {dW_S, c.shared ? nullptr : dW_D};
     float* dbs[2] = {db_S, c.shared ? nullptr : db_D};
     // the small outputs that are accumulated with atomics are cleared by one launch
-    const bool both_w = sides == 2 && dWs[0] && dWs[1];
+    const bool both_w = sides == 2 && dWs[0] && dWs[1] && !fuse_router_w;
     launch_zero4_f32(dbs[0], dbs[0] ? (size_t)HE : 0, dbs[1], dbs[1] ? (size_t)HE : 0, both_w ? dWs[0] : nullptr,
                      both_w ? (size_t)dm * HE : 0, both_w ? dWs[1] : nullptr, both_w ? (size_t)dm * HE : 0, c.st);
     RouterBwdArgs rb{};
@@ -1277,6 +1297,11 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       launch_pack_router_wide(W_S, c.shared ? nullptr : W_D, c.p<void>(c.L.wr3), dm, HE, HEp, sides, dh, c.st);
       run_qk_dgrad(true);
     }
+    if (fuse_router_w) {
+      run_qk_wgrad(true);
+      prof_mark(c.st, "bwd.router_wgrad");
+      launch_router_wgrad_split(c.p<float>(c.L.wrt), dWs[0], dWs[1], dm, dh, HE, HEp, c.st);
+    } else
     // dW_S / dW_D = x^T dz: one launch for both sides when both are wanted
     {
       WgradArgs w{};

@@ -706,10 +706,11 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   __syncthreads();
 
   const int i0 = (tile / tj) * BM, j0 = (tile % tj) * BN;
-  const bool second = a.hsplit > 0 && h >= a.hsplit;
-  const int hh = second ? h - a.hsplit : h;
+  const int which = a.hsplit > 0 ? h / a.hsplit : 0;   // operand set of this head
+  const bool second = which == 1;
+  const int hh = a.hsplit > 0 ? h % a.hsplit : h;
   const unsigned short* A = (const unsigned short*)a.A;
-  const unsigned short* Bm = (const unsigned short*)(second ? a.Bm2 : a.Bm);
+  const unsigned short* Bm = (const unsigned short*)(which == 0 ? a.Bm : which == 1 ? a.Bm2 : a.Bm3);
   const bool scaled = a.gate != nullptr;
 
   constexpr int A_CPR = BM / VEC, B_CPR = BN / VEC;     // chunks per tile row
@@ -876,9 +877,9 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs a) {
     s.z += v.z;
     s.w += v.w;
   }
-  const bool second = a.hsplit > 0 && h >= a.hsplit;
-  const int hh = second ? h - a.hsplit : h;
-  float* dW = (second ? a.dW2 : a.dW) + (long)hh * a.w_hstride + (long)e * a.w_estride;
+  const int which = a.hsplit > 0 ? h / a.hsplit : 0;
+  const int hh = a.hsplit > 0 ? h % a.hsplit : h;
+  float* dW = (which == 0 ? a.dW : which == 1 ? a.dW2 : a.dW3) + (long)hh * a.w_hstride + (long)e * a.w_estride;
   const long ii = i4 / a.Kb, jj = i4 % a.Kb;   // Kb % 4 == 0: the 4 elements share a row
   *(float4*)(dW + ii * a.swa + jj) = s;
 }
@@ -895,7 +896,8 @@ static int wgrad_vec(const WgradArgs& a) {
     const size_t bytes = vec * 2;
     if (aligned_to(a.A, bytes) && aligned_to(a.Bm, bytes) && a.lda % vec == 0 && a.a_hoff % vec == 0 &&
         a.ldb % vec == 0 && a.b_hoff % vec == 0 && a.Ka % vec == 0 && a.Kb % vec == 0 &&
-        (a.hsplit == 0 || aligned_to(a.Bm2, bytes)) && (!a.partial || (a.swa % 4 == 0 && aligned_to(a.dW, 16))))
+        (a.hsplit == 0 || aligned_to(a.Bm2, bytes)) && (a.hsplit == 0 || a.heads <= 2 * a.hsplit || (a.partial && aligned_to(a.Bm3, bytes))) &&
+        (!a.partial || (a.swa % 4 == 0 && aligned_to(a.dW, 16))))
       return vec;
   }
   return 0;

@@ -162,6 +162,23 @@ __global__ __launch_bounds__(256) void rope_apply_vec_kernel(unsigned short* __r
   *ptr = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// T [dm][ld] (fp32) holds x^T dz for both routers side by side (side s in columns s*HEp .. s*HEp+HE-1):
+// the two router weight gradients are its column blocks.
+__global__ __launch_bounds__(256) void router_wgrad_split_kernel(const float* __restrict__ T, float* __restrict__ dW0,
+                                                                 float* __restrict__ dW1, int dm, int ld, int HE, int HEp) {
+  const long id = (long)blockIdx.x * 256 + threadIdx.x;
+  if (id >= (long)dm * HE) return;
+  const long i = id / HE;
+  const int c = (int)(id % HE);
+  if (dW0) dW0[id] = T[i * ld + c];
+  if (dW1) dW1[id] = T[i * ld + HEp + c];
+}
+
+void launch_router_wgrad_split(const float* T, float* dW0, float* dW1, int dm, int ld, int HE, int HEp, hipStream_t s) {
+  const long n = (long)dm * HE;
+  if (n) router_wgrad_split_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(T, dW0, dW1, dm, ld, HE, HEp);
+}
+
 void launch_rope_table(float2* tab, int T, int dh, hipStream_t s) {
   const int half = dh / 2;
   const long n = (long)T * half;
