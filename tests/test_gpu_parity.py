@@ -209,6 +209,23 @@ def test_full_config_cached_context():
     run_case(small("c2", T=1024, T_q=512), seed=63)
 
 
+@pytest.mark.parametrize("family", [0, 1])
+def test_all_variants_together(family):
+    """Expert queries and keys, rotary positions, a cached context and one shared selection in one call."""
+    run_case(dict(name="allf32", dtype="f32", B=2, T=41, d_model=40, nheads=3, d_head=18, E=6, k=2, causal=1, bias0=0.0,
+                  qk_experts=1, rope=1, T_q=17), family=family, shared=True, seed=70)
+    run_case(small("c2", B=2, T=300, d_model=256, nheads=2, qk_experts=1, rope=1, T_q=140), family=family, shared=True, seed=71)
+    run_case(small("c2", B=2, T=300, d_model=256, nheads=2, qk_experts=1, rope=1, T_q=140), family=family, seed=72)
+
+
+def test_bf16_router_weight_gradient_forms():
+    """The routers' weight gradients either ride along the Q/K weight-gradient launch (2 * H * E, padded,
+    fits a head's width) or take a launch of their own: the last size that fits, the first that does not."""
+    run_case(small("c2", B=2, T=256, d_model=256, nheads=4, d_head=128, E=16, k=2), seed=73)
+    run_case(small("c2", B=2, T=256, d_model=256, nheads=4, d_head=128, E=17, k=2), seed=74)
+    run_case(small("c2", B=2, T=256, d_model=256, nheads=4, d_head=128, E=16, k=2), shared=True, seed=75)
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
 def test_full_config(name):
     """The paper-shaped workloads at full size, in the launch configuration bench.py times."""
@@ -239,7 +256,7 @@ def test_rerun_is_stable():
 def test_matrix_core_path_is_deterministic():
     """bf16 storage, expert-set path: no atomic add decides y, dx or the weight gradients of the
     projections (per-chunk partial sums are added in a fixed order), so two runs agree bit for bit.
-    The small router gradients use atomics and are only required to agree closely."""
+    The router bias gradients use atomics and are only required to agree closely."""
     from paper_2312_07987_amd.runner import DeviceLayer
     cfg = small("c2", B=4, T=256)
     t = make_inputs(cfg, seed=5)
