@@ -109,10 +109,12 @@ def time_loop(fn, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def dense_baseline(cfg, steps, warmup):
+def dense_baseline(cfg, steps, warmup, few_heads=False):
     """The same kernels in dense multi-head mode (no routers, E = 1), parameter-matched the way the
     paper matches its dense baselines (Sec. 3.1): H*E heads whose d_head gives the same number of
-    parameters, rounded up to a multiple of 8."""
+    parameters, rounded up to a multiple of 8.  few_heads: the paper's other dense baseline, which
+    keeps SwitchHead's H heads and widens them instead (E times the matched width, capped at the
+    256 the kernels take: 4 heads of 256 at c2, as in the paper's table of model sizes, App. A.3)."""
     from paper_2312_07987_amd.inputs import make_inputs
     from paper_2312_07987_amd.runner import DeviceLayer
     H, E, dh = cfg["nheads"], cfg["E"], cfg["d_head"]
@@ -120,6 +122,8 @@ def dense_baseline(cfg, steps, warmup):
     qk_mats = 2 * H * E if cfg.get("qk_experts") else 2 * H   # query + key matrices of d_model x d_head
     dh_match = ((qk_mats + 2 * H * E) * dh + 2 * H * E) / (4.0 * H * E)
     dh2 = int(-(-dh_match // 8) * 8)
+    if few_heads:
+        heads, dh2 = H, min(256, int(-(-dh_match * E // 8) * 8))
     dc = dict(cfg, nheads=heads, d_head=dh2, E=1, k=1, bias0=0.0, name="dense", qk_experts=0)
     layer = DeviceLayer(dc, make_inputs(dc, seed=1), dense=True)
 
@@ -273,6 +277,8 @@ def main():
             "step_ms": {n: round(v, 4) for n, v in sorted(per_step.items())},
             # with the split backward attention kernels the "bwd.attention" mark covers only the
             # row-sum (delta) pre-pass, which does none of the matmul work
+            # (the routers' weight gradient, where it rides along the Q/K weight-gradient launch, is not
+            # credited to that launch: "bwd.router_wsplit" only splits its result)
             "step_tflops": {n: round(flops[n] / (per_step[n] * 1e-3) / 1e12, 1) for n in sorted(per_step)
                             if n in flops and not (n == "bwd.attention" and "bwd.attention_dkv" in per_step)},
             "expert_counts_side0_head0": [int(v) for v in (counts[0, 0, 1:] - counts[0, 0, :-1])],
@@ -280,6 +286,7 @@ def main():
     }
     if not args.no_dense:
         out["extra"]["dense_mha"] = dense_baseline(cfg, args.steps, args.warmup)
+        out["extra"]["dense_mha_few_heads"] = dense_baseline(cfg, args.steps, args.warmup, few_heads=True)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_tokens)
     print(json.dumps(out))

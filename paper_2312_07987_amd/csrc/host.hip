@@ -1299,7 +1299,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     }
     if (fuse_router_w) {
       run_qk_wgrad(true);
-      prof_mark(c.st, "bwd.router_wgrad");
+      prof_mark(c.st, "bwd.router_wsplit");
       launch_router_wgrad_split(c.p<float>(c.L.wrt), dWs[0], dWs[1], dm, dh, HE, HEp, c.st);
     } else
     // dW_S / dW_D = x^T dz: one launch for both sides when both are wanted
