@@ -51,7 +51,7 @@ def step_work(cfg):
         "bwd.attention_dkv": 2 * attn, "bwd.attention_dq": attn // 2,
         "bwd.o_dgrad": expert_q, "bwd.o_wgrad": expert_q, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
         "bwd.q_wgrad": proj_q, "bwd.k_wgrad": proj, "bwd.qk_wgrad": proj + proj_q, "bwd.q_dgrad": proj_q, "bwd.k_dgrad": proj,
-        "bwd.router_wgrad": router // 2, "bwd.router_dgrad": router // 2,
+        "bwd.router_wgrad": router, "bwd.router_dgrad": router,
         # query / key expert banks (all-expert form): each step has the shape of its value-expert twin
         "fwd.q_experts": expert_q, "fwd.k_experts": expert, "bwd.q_wgrad_e": expert_q, "bwd.k_wgrad_e": expert,
         "bwd.q_dgrad_e": expert_q, "bwd.k_dgrad_e": expert,
