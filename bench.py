@@ -184,7 +184,8 @@ def main():
     ap.add_argument("--copy-only", action="store_true", help="run a plain 256 MiB device copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the layer shards over the batch; see DESIGN.md); "
+        print("bench.py: this build runs on one GPU only (the layer would shard over the batch with one all-reduce of the "
+              "weight gradients; that path is not built); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
@@ -275,12 +276,11 @@ def main():
             "fwd_frac_of_bf16_peak": lf["fwd"] / (ms_fwd * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "fwd_bwd_frac_of_bf16_peak": lf["fwd_bwd"] / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "step_ms": {n: round(v, 4) for n, v in sorted(per_step.items())},
-            # with the split backward attention kernels the "bwd.attention" mark covers only the
-            # row-sum (delta) pre-pass, which does none of the matmul work
-            # (the routers' weight gradient, where it rides along the Q/K weight-gradient launch, is not
-            # credited to that launch: "bwd.router_wsplit" only splits its result)
-            "step_tflops": {n: round(flops[n] / (per_step[n] * 1e-3) / 1e12, 1) for n in sorted(per_step)
-                            if n in flops and not (n == "bwd.attention" and "bwd.attention_dkv" in per_step)},
+            # (the matrix-core family marks its two backward attention kernels, the fp32 family one
+            # "bwd.attention" step; the routers' weight gradient, where it rides along the Q/K
+            # weight-gradient launch, is not credited to that launch: "bwd.router_wsplit" only splits
+            # its result)
+            "step_tflops": {n: round(flops[n] / (per_step[n] * 1e-3) / 1e12, 1) for n in sorted(per_step) if n in flops},
             "expert_counts_side0_head0": [int(v) for v in (counts[0, 0, 1:] - counts[0, 0, :-1])],
         },
     }

@@ -846,7 +846,6 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
 
   // attention
   {
-    prof_mark(c.st, "bwd.attention");
     AttnBwdArgs a{};
     a.Q = c.p<void>(c.L.Q);
     a.K = c.p<void>(c.L.K);
@@ -865,9 +864,11 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.scale = 1.0f / sqrtf((float)dh);
     a.Tq = c.Tq;
     if (use_mfma(c) && mfma_attn_supported(shape->T, dh))
-      launch_mfma_attn_bwd(a, c.st);
-    else
+      launch_mfma_attn_bwd(a, c.st);   // marks its two kernels itself
+    else {
+      prof_mark(c.st, "bwd.attention");
       launch_simt_attn_bwd(a, c.bf16, c.st);
+    }
   }
 
   // back through the rotation of queries and keys: gradients take the opposite turn
