@@ -140,6 +140,40 @@ def dense_baseline(cfg, steps, warmup, few_heads=False):
             "fwd_tokens_per_s": N / (ms_fwd * 1e-3), "fwd_bwd_tokens_per_s": N / (ms_step * 1e-3)}
 
 
+def workload_string(cfg):
+    return "%s: B=%d T=%d d_model=%d nheads=%d d_head=%d E=%d k=%d causal=%d bias0=%g%s" % (
+        cfg["name"], cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
+        cfg["causal"], cfg["bias0"], (" qk_experts=1" if cfg.get("qk_experts") else "") + (" rope=1" if cfg.get("rope") else "") +
+        (" T_q=%d" % cfg["T_q"] if cfg.get("T_q") else ""))
+
+
+def other_workload(name, steps, warmup):
+    """Forward+backward and forward time of another paper-shaped workload (same protocol, fewer words)."""
+    from paper_2312_07987_amd.flops import layer_flops
+    from paper_2312_07987_amd.inputs import config, make_inputs
+    from paper_2312_07987_amd.runner import DeviceLayer
+    cfg = config(name)
+    layer = DeviceLayer(cfg, make_inputs(cfg))
+
+    def step():
+        layer.forward()
+        layer.backward()
+
+    for _ in range(warmup):
+        step()
+    ms_step = time_loop(step, steps)
+    ms_fwd = time_loop(layer.forward, steps)
+    N = cfg["B"] * cfg["T"]
+    lf = layer_flops(cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"], bool(cfg["causal"]))
+    out = {"workload": workload_string(cfg), "fwd_bwd_ms": ms_step, "fwd_ms": ms_fwd,
+           "fwd_bwd_tokens_per_s": N / (ms_step * 1e-3), "fwd_tokens_per_s": N / (ms_fwd * 1e-3),
+           "fwd_bwd_tflops": lf["fwd_bwd"] / (ms_step * 1e-3) / 1e12}
+    if name == "c4":   # skewed routing: the per-expert token counts of one (side, head)
+        counts = layer.routing()["offsets"]
+        out["expert_counts_side0_head0"] = [int(v) for v in (counts[0, 0, 1:] - counts[0, 0, :-1])]
+    return out
+
+
 def cpu_baseline(cfg, budget_tokens):
     """The float64 oracle, forward + backward, on the first sequences of the same workload."""
     import numpy as np
@@ -180,7 +214,8 @@ def main():
                          "front), queries for the last chunk only; tokens/s counts the current chunk's tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=1 << 20, help="token budget of the oracle sample (whole sequences)")
-    ap.add_argument("--no-dense", action="store_true", help="skip the parameter-matched dense multi-head baseline")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="skip the dense multi-head baselines and the short runs of the other workloads")
     ap.add_argument("--copy-only", action="store_true", help="run a plain 256 MiB device copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -264,10 +299,7 @@ def main():
         "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": "%s: B=%d T=%d d_model=%d nheads=%d d_head=%d E=%d k=%d causal=%d bias0=%g%s" % (
-            cfg["name"], cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
-            cfg["causal"], cfg["bias0"], (" qk_experts=1" if cfg.get("qk_experts") else "") + (" rope=1" if cfg.get("rope") else "") +
-            (" T_q=%d" % cfg["T_q"] if cfg.get("T_q") else "")), "tokens_per_step": N},
+        "config": {"workload": workload_string(cfg), "tokens_per_step": N},
         "roofline": roof,
         "extra": {
             "fwd_ms": ms_fwd, "fwd_tokens_per_s": N / (ms_fwd * 1e-3),
@@ -287,6 +319,9 @@ def main():
     if not args.no_dense:
         out["extra"]["dense_mha"] = dense_baseline(cfg, args.steps, args.warmup)
         out["extra"]["dense_mha_few_heads"] = dense_baseline(cfg, args.steps, args.warmup, few_heads=True)
+        if not (args.qk_experts or args.rope or args.context > 1):
+            out["extra"]["other_workloads"] = {n: other_workload(n, args.steps, args.warmup)
+                                               for n in ("c1", "c2", "c3", "c4") if n != cfg["name"]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_tokens)
     print(json.dumps(out))
