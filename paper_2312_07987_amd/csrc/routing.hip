@@ -243,20 +243,19 @@ __global__ void dense_routing_kernel(int* idx, float* gate, int* perm, int* offs
 // a Cauchy-Schwarz bound on sum_i |x_i w_i| times the fp32 error of a KS-term sum, with a
 // factor 4 of slack for the adder tree of the matrix core.  If every gap between consecutive sorted
 // logits down to the (k+1)-th exceeds 2*bound, the ordered top-k list is provably the one
-// the fp64 logits give, and it is written directly.  Otherwise the (token, side, head) is
-// queued and stage 2 re-evaluates its E logits in fp64 and selects from those.  Stage 2 adds
+// the fp64 logits give, and it is written directly.  Otherwise stage 2 (same kernel, one wave per
+// such (token, side, head)) re-evaluates its E logits in fp64 and selects from those.  Stage 2 adds
 // the products in a fixed blocked order (16 per lane, then a butterfly over the lanes), which
 // differs from the sequential fp64 sum by a few ulp of fp64 -- twelve orders of magnitude below
 // the fp32-level gaps that send an entry here -- and gives bit-identical sums for identical
 // columns, so ties still resolve to the lower index.
 // ----------------------------------------------------------------------------------------
 // Per (side, head, expert) work-group: the squared norm of that router column (the error bound takes
-// the largest of a head's), the head's queue counter cleared, the column copied out as a contiguous
+// the largest of a head's), the column copied out as a contiguous
 // vector Wt[side][h*E + e][dmp] (zero padded to dmp, a multiple of 1024) for the fp64 recheck and into
 // the padded matrix Wp[side][i][HEp] the logits GEMM reads (the last column also zeroes the padding).
 __global__ __launch_bounds__(256) void router_prep_kernel(const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
-                                                          float* __restrict__ wnorm2, int* __restrict__ fixcount,
-                                                          unsigned short* __restrict__ Wt, unsigned short* __restrict__ Wp,
+                                                          float* __restrict__ wnorm2, unsigned short* __restrict__ Wt, unsigned short* __restrict__ Wp,
                                                           int dm, int dmp, int H, int E, int HEp) {
   __shared__ float red[4];
   const int HE = H * E;
@@ -282,155 +281,156 @@ __global__ __launch_bounds__(256) void router_prep_kernel(const bf16_t* __restri
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
   if (lane == 0) red[wave] = s;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    wnorm2[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
-    if (col % E == 0) fixcount[side * H + col / E] = 0;
-  }
+  if (threadIdx.x == 0) wnorm2[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
 
 constexpr int SEL_TOK = 64;   // tokens per work-group of select_kernel
 
-// First-stage selection.  A work-group stages the stage-1 logits of SEL_TOK tokens of one side in LDS
-// (whole rows, coalesced), then one thread per (token, head) selects and checks the margins
-// against the error bound; entries that fail are queued for the fp64 recheck.
-__global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ Zs, const float* __restrict__ b0,
-                                                     const float* __restrict__ b1, const float* __restrict__ xnorm,
-                                                     const float* __restrict__ wnorm2, int* __restrict__ idx,
-                                                     float* __restrict__ gate, int* __restrict__ fixlist,
-                                                     int* __restrict__ fixcount, int N, int kstep, int H, int E, int k,
-                                                     int HEp) {
-  extern __shared__ double zt[];   // [SEL_TOK][HEp]
-  const int side = blockIdx.y;
-  const int n0 = blockIdx.x * SEL_TOK;
-  const float* b = side ? b1 : b0;
-  const int ntok = N - n0 < SEL_TOK ? N - n0 : SEL_TOK;
-  const double* src = Zs + ((long)side * N + n0) * (long)HEp;
-  for (int i = threadIdx.x; i < ntok * HEp; i += 256) zt[i] = src[i];
-  __syncthreads();
-  for (int item = threadIdx.x; item < ntok * H; item += 256) {
-    const int nl = item / H, h = item % H;
-    const int n = n0 + nl;
-    const int sh_ = side * H + h;
-    const double* z = zt + nl * HEp + h * E;
-    // fp32 partial sums of `kstep` exact products, then fp64 adds: see the bound above
-    float w2 = 0.f;   // largest squared column norm of this head's router
-    for (int e = 0; e < E; ++e) w2 = fmaxf(w2, wnorm2[(long)sh_ * E + e]);
-    const double bound0 = 4.0 * (double)kstep * 5.9604645e-8 * (double)xnorm[n] * (double)(sqrtf(w2) * 1.0001f);
+// Second stage of the exact router for one (side, head, token) entry, run by one wave: recomputes the
+// head's E logits in fp64 and redoes the selection.  Lane l sums the products of input features
+// 16 l .. 16 l + 15 (per 1024-feature slab) against the head's column vectors, the lanes' sums are added
+// by a butterfly, lane 0 adds the bias and selects.  zs: 64 doubles of LDS owned by the wave.
+__device__ __forceinline__ void recheck_entry(const unsigned short* __restrict__ xrow, const unsigned short* __restrict__ wt0,
+                                              const float* __restrict__ bh, double* __restrict__ zs, double* __restrict__ zout,
+                                              int* __restrict__ idx_out, float* __restrict__ gate_out, int dm, int dmp, int E,
+                                              int k, int lane) {
+  // eight experts at a time: the token's features are loaded once per slab and the eight columns'
+  // loads are in flight together (one expert after the other pays one memory round trip each)
+  for (int e0 = 0; e0 < E; e0 += 8) {
+    double acc[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] = 0.0;
+    for (int s0 = 0; s0 < dmp; s0 += 1024) {
+      const int i0 = s0 + lane * 16;
+      uint2 xv[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        xv[q] = make_uint2(0, 0);
+        if (i0 + 4 * q < dm) xv[q] = *(const uint2*)(xrow + i0 + 4 * q);   // dm % 4 == 0: 8-byte aligned rows
+      }
+      uint4 wv[8][2];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int e = e0 + u < E ? e0 + u : E - 1;   // past the last expert: a repeat, never stored
+        wv[u][0] = *(const uint4*)(wt0 + (long)e * dmp + i0);
+        wv[u][1] = *(const uint4*)(wt0 + (long)e * dmp + i0 + 8);
+      }
+      const unsigned xw[8] = {xv[0].x, xv[0].y, xv[1].x, xv[1].y, xv[2].x, xv[2].y, xv[3].x, xv[3].y};
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const unsigned ww[8] = {wv[u][0].x, wv[u][0].y, wv[u][0].z, wv[u][0].w, wv[u][1].x, wv[u][1].y, wv[u][1].z, wv[u][1].w};
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          acc[u] = fma((double)__uint_as_float(xw[q] << 16), (double)__uint_as_float(ww[q] << 16), acc[u]);
+          acc[u] = fma((double)__uint_as_float(xw[q] & 0xffff0000u), (double)__uint_as_float(ww[q] & 0xffff0000u), acc[u]);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      double v = acc[u];
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+      if (lane == 0 && e0 + u < E) zs[e0 + u] = v + (bh ? (double)bh[e0 + u] : 0.0);
+    }
+  }
+  if (lane == 0) {
+    for (int e = 0; e < E; ++e) zout[e] = zs[e];
     unsigned long long sel = 0ull;
-    const long o = ((long)sh_ * N + n) * k;
-    double prev = 0.0, bprev = 0.0;
-    bool flag = false;
-    const int passes = k < E ? k + 1 : k;
-    for (int j = 0; j < passes; ++j) {
+    for (int j = 0; j < k; ++j) {
       int best = -1;
       double bv = 0.0;
       for (int e = 0; e < E; ++e) {
         if ((sel >> e) & 1ull) continue;
-        double v = z[e] + (b ? (double)b[h * E + e] : 0.0);
+        const double v = zs[e];
         if (best < 0 || v > bv) {
           best = e;
           bv = v;
         }
       }
-      const double bb = bound0 + 1e-13 * (fabs(bv) + 1.0);
-      if (j > 0 && !(prev - bv > bprev + bb)) flag = true;
-      prev = bv;
-      bprev = bb;
       sel |= 1ull << best;
-      if (j < k) {
-        idx[o + j] = best;
-        gate[o + j] = (float)(1.0 / (1.0 + exp(-bv)));
-      }
+      idx_out[j] = best;
+      gate_out[j] = (float)(1.0 / (1.0 + exp(-bv)));
     }
-    if (flag) fixlist[(long)sh_ * N + atomicAdd(&fixcount[sh_], 1)] = n;   // rare: a fraction of a percent
   }
 }
 
-constexpr int FIX_WAVES = 4;   // queued tokens in flight per work-group: one wave per token
-
-// Second stage of the exact router: recomputes the logits of the queued (side, head, token)
-// entries in fp64 and redoes their selection.  One wave per entry: lane l sums the products of
-// input features 16 l .. 16 l + 15 (per 1024-feature slab) against the head's column vectors, the
-// lanes' sums are added by a butterfly, lane 0 adds the bias and selects.
-__global__ __launch_bounds__(64 * FIX_WAVES) void fix64_kernel(const bf16_t* __restrict__ x, const unsigned short* __restrict__ Wt,
-                                                              const float* __restrict__ b0, const float* __restrict__ b1,
-                                                              const int* __restrict__ fixlist, const int* __restrict__ fixcount,
-                                                              double* __restrict__ Z, int* __restrict__ idx,
-                                                              float* __restrict__ gate, int N, int dm, int dmp, int H, int E,
-                                                              int k) {
-  __shared__ double zs[FIX_WAVES][64];
-  const int sh_ = blockIdx.y;
-  const int count = fixcount[sh_];
-  const int side = sh_ / H, h = sh_ % H;
+// Selection.  A work-group stages the stage-1 logits of SEL_TOK tokens of one side in LDS (whole rows,
+// coalesced), then one thread per (token, head) selects and checks the margins against the error
+// bound; the entries that fail (a fraction of a percent, and every exact tie) are listed in LDS and
+// rechecked in fp64 right away, one wave per entry.
+__global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ Zs, const float* __restrict__ b0,
+                                                     const float* __restrict__ b1, const float* __restrict__ xnorm,
+                                                     const float* __restrict__ wnorm2, int* __restrict__ idx,
+                                                     float* __restrict__ gate, const bf16_t* __restrict__ x,
+                                                     const unsigned short* __restrict__ Wt, double* __restrict__ Z, int N,
+                                                     int kstep, int H, int E, int k, int HEp, int dm, int dmp) {
+  extern __shared__ double zt[];   // [SEL_TOK][HEp]
+  __shared__ double zs[4][64];
+  __shared__ int flist[256];       // (token, head) items of this work-group that need the recheck
+  __shared__ int nflag;
+  const int side = blockIdx.y;
+  const int n0 = blockIdx.x * SEL_TOK;
   const float* b = side ? b1 : b0;
-  const int HE = H * E;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const unsigned short* wt0 = Wt + ((long)side * HE + h * E) * dmp;
-  // a small fixed grid walks the queue: empty work-groups are not free to launch
-  for (int item = blockIdx.x * FIX_WAVES + wave; item < count; item += gridDim.x * FIX_WAVES) {
-    const int n = fixlist[(long)sh_ * N + item];
-    const unsigned short* xrow = (const unsigned short*)x + (long)n * dm;   // dm % 4 == 0: 8-byte aligned rows
-    // eight experts at a time: the token's features are loaded once per slab and the eight columns'
-    // loads are in flight together (one expert after the other pays one memory round trip each)
-    for (int e0 = 0; e0 < E; e0 += 8) {
-      double acc[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) acc[u] = 0.0;
-      for (int s0 = 0; s0 < dmp; s0 += 1024) {
-        const int i0 = s0 + lane * 16;
-        uint2 xv[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          xv[q] = make_uint2(0, 0);
-          if (i0 + 4 * q < dm) xv[q] = *(const uint2*)(xrow + i0 + 4 * q);
-        }
-        uint4 wv[8][2];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int e = e0 + u < E ? e0 + u : E - 1;   // past the last expert: a repeat, never stored
-          wv[u][0] = *(const uint4*)(wt0 + (long)e * dmp + i0);
-          wv[u][1] = *(const uint4*)(wt0 + (long)e * dmp + i0 + 8);
-        }
-        const unsigned xw[8] = {xv[0].x, xv[0].y, xv[1].x, xv[1].y, xv[2].x, xv[2].y, xv[3].x, xv[3].y};
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const unsigned ww[8] = {wv[u][0].x, wv[u][0].y, wv[u][0].z, wv[u][0].w, wv[u][1].x, wv[u][1].y, wv[u][1].z, wv[u][1].w};
-#pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            acc[u] = fma((double)__uint_as_float(xw[q] << 16), (double)__uint_as_float(ww[q] << 16), acc[u]);
-            acc[u] = fma((double)__uint_as_float(xw[q] & 0xffff0000u), (double)__uint_as_float(ww[q] & 0xffff0000u), acc[u]);
-          }
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        double v = acc[u];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-        if (lane == 0 && e0 + u < E) zs[wave][e0 + u] = v + (b ? (double)b[h * E + e0 + u] : 0.0);
-      }
-    }
-    if (lane == 0) {
-      double* z = Z + ((long)side * N + n) * HE + (long)h * E;
-      for (int e = 0; e < E; ++e) z[e] = zs[wave][e];
+  const int ntok = N - n0 < SEL_TOK ? N - n0 : SEL_TOK;
+  const double* src = Zs + ((long)side * N + n0) * (long)HEp;
+  if (threadIdx.x == 0) nflag = 0;
+  for (int i = threadIdx.x; i < ntok * HEp; i += 256) zt[i] = src[i];
+  __syncthreads();
+  for (int item0 = 0; item0 < ntok * H; item0 += 256) {
+    const int item = item0 + threadIdx.x;
+    if (item < ntok * H) {
+      const int nl = item / H, h = item % H;
+      const int n = n0 + nl;
+      const int sh_ = side * H + h;
+      const double* z = zt + nl * HEp + h * E;
+      // fp32 partial sums of `kstep` exact products, then fp64 adds: see the bound above
+      float w2 = 0.f;   // largest squared column norm of this head's router
+      for (int e = 0; e < E; ++e) w2 = fmaxf(w2, wnorm2[(long)sh_ * E + e]);
+      const double bound0 = 4.0 * (double)kstep * 5.9604645e-8 * (double)xnorm[n] * (double)(sqrtf(w2) * 1.0001f);
       unsigned long long sel = 0ull;
       const long o = ((long)sh_ * N + n) * k;
-      for (int j = 0; j < k; ++j) {
+      double prev = 0.0, bprev = 0.0;
+      bool flag = false;
+      const int passes = k < E ? k + 1 : k;
+      for (int j = 0; j < passes; ++j) {
         int best = -1;
         double bv = 0.0;
         for (int e = 0; e < E; ++e) {
           if ((sel >> e) & 1ull) continue;
-          const double v = zs[wave][e];
+          double v = z[e] + (b ? (double)b[h * E + e] : 0.0);
           if (best < 0 || v > bv) {
             best = e;
             bv = v;
           }
         }
+        const double bb = bound0 + 1e-13 * (fabs(bv) + 1.0);
+        if (j > 0 && !(prev - bv > bprev + bb)) flag = true;
+        prev = bv;
+        bprev = bb;
         sel |= 1ull << best;
-        idx[o + j] = best;
-        gate[o + j] = (float)(1.0 / (1.0 + exp(-bv)));
+        if (j < k) {
+          idx[o + j] = best;
+          gate[o + j] = (float)(1.0 / (1.0 + exp(-bv)));
+        }
       }
+      if (flag) flist[atomicAdd(&nflag, 1)] = item;
     }
+    __syncthreads();
+    // the recheck overwrites what the first stage wrote for its entries (same thread block, after the barrier)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int HE = H * E;
+    for (int f = wave; f < nflag; f += 4) {
+      const int it = flist[f];
+      const int nl = it / H, h = it % H, n = n0 + nl;
+      const int sh_ = side * H + h;
+      const long o = ((long)sh_ * N + n) * k;
+      recheck_entry((const unsigned short*)x + (long)n * dm, Wt + ((long)side * HE + h * E) * dmp, b ? b + h * E : nullptr,
+                    zs[wave], Z + ((long)side * N + n) * HE + (long)h * E, idx + o, gate + o, dm, dmp, E, k, lane);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) nflag = 0;
+    __syncthreads();
   }
 }
 
@@ -511,8 +511,7 @@ size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off) {
   off[1] = take(2 * (size_t)N * HEp * 8);    // Zs: stage-1 logits, fp64
   off[2] = take((size_t)N * 4);              // xnorm
   off[3] = take(2 * (size_t)H * E * 4);      // squared column norms
-  off[4] = take(2 * (size_t)H * N * 4);      // fixlist
-  off[5] = take(2 * (size_t)H * 4 + 256);    // fixcount per (side, head)
+  off[4] = off[5] = 0;                       // (unused)
   off[6] = take(2 * (size_t)H * E * (((size_t)dm + 1023) / 1024 * 1024) * 2);   // Wt: router columns as vectors
   return o;
 }
@@ -684,14 +683,12 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
   double* Zs = (double*)(scratch + off[1]);
   float* xnorm = (float*)(scratch + off[2]);
   float* wmax = (float*)(scratch + off[3]);
-  int* fixlist = (int*)(scratch + off[4]);
-  int* fixcount = (int*)(scratch + off[5]);
   unsigned short* Wt = (unsigned short*)(scratch + off[6]);
   const int dmp = (a.dm + 1023) / 1024 * 1024;
 
-  // per (side, head): largest column norm, queue counter cleared, columns copied out as vectors and
+  // per (side, head): largest column norm, columns copied out as vectors and
   // into the padded matrix the GEMM reads
-  router_prep_kernel<<<a.sides * a.H * a.E, 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], wmax, fixcount, Wt,
+  router_prep_kernel<<<a.sides * a.H * a.E, 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], wmax, Wt,
                                                    (unsigned short*)Wp, a.dm, dmp, a.H, a.E, HEp);
   // stage 1: z32 = x W on the matrix cores, fp32 accumulation, both sides in one launch
   RowGemmArgs g{};
@@ -717,13 +714,8 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
   launch_mfma_row_gemm(g, s);
 
   dim3 g1((a.N + SEL_TOK - 1) / SEL_TOK, a.sides);
-  select_kernel<<<g1, 256, (size_t)SEL_TOK * HEp * 8, s>>>(Zs, a.b[0], a.b[1], xnorm, wmax, a.idx, a.gate, fixlist, fixcount,
-                                                            a.N, rg_kstep(), a.H, a.E, a.k, HEp);
-  int fix_blocks = (a.N + FIX_WAVES - 1) / FIX_WAVES;
-  if (fix_blocks > 64) fix_blocks = 64;
-  dim3 g3(fix_blocks, a.sides * a.H);
-  fix64_kernel<<<g3, 64 * FIX_WAVES, 0, s>>>((const bf16_t*)a.x, Wt, a.b[0], a.b[1], fixlist, fixcount, a.Z, a.idx, a.gate,
-                                               a.N, a.dm, dmp, a.H, a.E, a.k);
+  select_kernel<<<g1, 256, (size_t)SEL_TOK * HEp * 8, s>>>(Zs, a.b[0], a.b[1], xnorm, wmax, a.idx, a.gate, (const bf16_t*)a.x, Wt,
+                                                            a.Z, a.N, rg_kstep(), a.H, a.E, a.k, HEp, a.dm, dmp);
   const int nblk = router_blocks(a.N);
   dim3 g2(nblk, a.sides * a.H);
   if (a.sets && a.sets->sides == a.sides) {
