@@ -56,6 +56,19 @@ enum {
   TAG_ROUTER                                   // router logits: fp32 partial sums of 64 terms, added up in fp64
 };
 
+// Epilogue of the router logits GEMM (TAG_ROUTER): the selection of Sec. 2.2's router equations on the
+// tile's logits, see router_select.h.  Launch head h is router side h.
+struct RouterSelect {
+  const float* b[2];            // logit bias per side or NULL
+  const float* wnorm2;          // [side][H*E] squared column norms
+  int* idx;                     // [side][H][N][k]
+  float* gate;
+  const void* x;                // bf16 [N][dm]
+  const unsigned short* Wt;     // [side][H*E][dmp] router columns as vectors
+  double* Z;                    // [side][N][H*E] fp64 logits of the rechecked entries
+  int N, kstep, H, E, k, dm, dmp;
+};
+
 struct RowGemmArgs {
   const int* perm;
   const int* offsets;
@@ -89,8 +102,8 @@ struct RowGemmArgs {
   //     against (B, B2 or B3 for p/seg_split = 0, 1, 2) + (p%seg_split)*b_sstride.
   int seg_mode, nseg, experts;
   const int* set_experts;
-  // TAG_ROUTER only: if not NULL, rownorm[row id] = an upper bound of the Euclidean norm of the A row
-  float* rownorm;
+  // TAG_ROUTER only: the selection that consumes the logits in the kernel's epilogue (C is not written)
+  RouterSelect rsel;
   const float* segate;
   int seg_split;
   long a_sstride, a_wstride, b_sstride;

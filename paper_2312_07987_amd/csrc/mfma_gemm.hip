@@ -8,6 +8,7 @@
 //   A operand: A[row r][k = 8g .. 8g+7]      B operand: B[k = 8g .. 8g+7][col r]
 //   D: register q (0..15) holds D[8*(q/4) + 4g + q%4][col r]
 #include "common.h"
+#include "router_select.h"
 #include <cstdlib>
 
 namespace sh {
@@ -427,30 +428,33 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
   // ---- epilogue -------------------------------------------------------------------------
   char* Cb = (char*)(second ? a.C2 : a.C);
   if constexpr (ACC64) {
-    // the router's error bound needs |x_n|: every chunk of the A rows went through this block's
-    // registers, so the first group's blocks add up the squares (8 threads share a row)
-    if (a.rownorm && h == 0 && ct == 0) {
-      float* rs = (float*)smem;   // the operand tiles are dead
-      __syncthreads();
-      for (int t = tid; t < BM; t += 256) rs[t] = 0.f;
-      __syncthreads();
+    // Router: the tile's logits never leave the CU.  They go to LDS (the operand tiles are dead) next to
+    // the rows' sums of squares (the error bound needs |x_n|, and every chunk of the A rows went through
+    // this block's registers: 8 threads share a row), and the selection runs on them right here.
+    static_assert(BM * 32 * 8 + BM * 4 + 4 * 64 * 8 + 256 * 4 + 16 <= Cfg::STAGES * Cfg::STAGE_ELEMS * 2, "router epilogue needs the LDS");
+    double* zt = (double*)smem;                  // [BM][Nc], Nc <= 32
+    double(*zs)[64] = (double(*)[64])(zt + BM * 32);
+    float* rs = (float*)(zs + 4);
+    int* flist = (int*)(rs + BM);
+    int* nflag = flist + 256;
+    __syncthreads();
+    for (int t = tid; t < BM; t += 256) rs[t] = 0.f;
+    if (tid == 0) *nflag = 0;
+    __syncthreads();
 #pragma unroll
-      for (int i = 0; i < A_N; ++i) atomicAdd(&rs[a_lds[i] / LDA], sumsq[i]);
-      __syncthreads();
-      for (int t = tid; t < BM; t += 256)
-        if (ids[t] >= 0) a.rownorm[ids[t]] = sqrtf(rs[t]) * 1.0001f;
-    }
+    for (int i = 0; i < A_N; ++i) atomicAdd(&rs[a_lds[i] / LDA], sumsq[i]);
     if (active) {
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
           const int row = wm + i * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
-          const int id = ids[row];
           const int n = n0 + wn + r;
-          if (id >= 0 && n < Nc) ((double*)Cb)[(long)div_by(id, inv_cdiv) * a.ldc + (long)hh * a.c_hoff + n] = acc64[i][q];
+          if (n < Nc) zt[row * Nc + n] = acc64[i][q];
         }
     }
+    __syncthreads();
+    router_select_tile(a.rsel, h, zt, Nc, rs, ids, BM, zs, flist, nflag);
     return;
   }
   if (VEC == 8 && a.mode == STORE_T) {
@@ -535,7 +539,9 @@ static int row_gemm_vec(const RowGemmArgs& a) {
 
 bool mfma_row_gemm_supported(const RowGemmArgs& a) {
   if (a.seg_mode == 1 && (a.nseg < 1 || a.nseg > 8 || a.E > 128)) return false;   // the tile lookup covers 128 groups
-  if (a.tag == TAG_ROUTER && (a.Nc > 32 || a.mode != STORE_F64 || a.seg_mode != 0)) return false;
+  if (a.tag == TAG_ROUTER && (a.Nc > 32 || a.mode != STORE_F64 || a.seg_mode != 0 || a.perm || a.E != 1 || a.hsplit != 0 ||
+                              a.a_div != 1 || a.Nc < a.rsel.H * a.rsel.E))
+    return false;
   // row ids stay below M; the multiply-high division needs id * divisor < 2^32
   if ((long)a.M * (a.a_div > a.c_div ? a.a_div : a.c_div) >= (1L << 32)) return false;
   return row_gemm_vec(a) != 0;

@@ -284,156 +284,6 @@ __global__ __launch_bounds__(256) void router_prep_kernel(const bf16_t* __restri
   if (threadIdx.x == 0) wnorm2[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
 
-constexpr int SEL_TOK = 64;   // tokens per work-group of select_kernel
-
-// Second stage of the exact router for one (side, head, token) entry, run by one wave: recomputes the
-// head's E logits in fp64 and redoes the selection.  Lane l sums the products of input features
-// 16 l .. 16 l + 15 (per 1024-feature slab) against the head's column vectors, the lanes' sums are added
-// by a butterfly, lane 0 adds the bias and selects.  zs: 64 doubles of LDS owned by the wave.
-__device__ __forceinline__ void recheck_entry(const unsigned short* __restrict__ xrow, const unsigned short* __restrict__ wt0,
-                                              const float* __restrict__ bh, double* __restrict__ zs, double* __restrict__ zout,
-                                              int* __restrict__ idx_out, float* __restrict__ gate_out, int dm, int dmp, int E,
-                                              int k, int lane) {
-  // eight experts at a time: the token's features are loaded once per slab and the eight columns'
-  // loads are in flight together (one expert after the other pays one memory round trip each)
-  for (int e0 = 0; e0 < E; e0 += 8) {
-    double acc[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) acc[u] = 0.0;
-    for (int s0 = 0; s0 < dmp; s0 += 1024) {
-      const int i0 = s0 + lane * 16;
-      uint2 xv[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        xv[q] = make_uint2(0, 0);
-        if (i0 + 4 * q < dm) xv[q] = *(const uint2*)(xrow + i0 + 4 * q);   // dm % 4 == 0: 8-byte aligned rows
-      }
-      uint4 wv[8][2];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int e = e0 + u < E ? e0 + u : E - 1;   // past the last expert: a repeat, never stored
-        wv[u][0] = *(const uint4*)(wt0 + (long)e * dmp + i0);
-        wv[u][1] = *(const uint4*)(wt0 + (long)e * dmp + i0 + 8);
-      }
-      const unsigned xw[8] = {xv[0].x, xv[0].y, xv[1].x, xv[1].y, xv[2].x, xv[2].y, xv[3].x, xv[3].y};
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const unsigned ww[8] = {wv[u][0].x, wv[u][0].y, wv[u][0].z, wv[u][0].w, wv[u][1].x, wv[u][1].y, wv[u][1].z, wv[u][1].w};
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          acc[u] = fma((double)__uint_as_float(xw[q] << 16), (double)__uint_as_float(ww[q] << 16), acc[u]);
-          acc[u] = fma((double)__uint_as_float(xw[q] & 0xffff0000u), (double)__uint_as_float(ww[q] & 0xffff0000u), acc[u]);
-        }
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      double v = acc[u];
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-      if (lane == 0 && e0 + u < E) zs[e0 + u] = v + (bh ? (double)bh[e0 + u] : 0.0);
-    }
-  }
-  if (lane == 0) {
-    for (int e = 0; e < E; ++e) zout[e] = zs[e];
-    unsigned long long sel = 0ull;
-    for (int j = 0; j < k; ++j) {
-      int best = -1;
-      double bv = 0.0;
-      for (int e = 0; e < E; ++e) {
-        if ((sel >> e) & 1ull) continue;
-        const double v = zs[e];
-        if (best < 0 || v > bv) {
-          best = e;
-          bv = v;
-        }
-      }
-      sel |= 1ull << best;
-      idx_out[j] = best;
-      gate_out[j] = (float)(1.0 / (1.0 + exp(-bv)));
-    }
-  }
-}
-
-// Selection.  A work-group stages the stage-1 logits of SEL_TOK tokens of one side in LDS (whole rows,
-// coalesced), then one thread per (token, head) selects and checks the margins against the error
-// bound; the entries that fail (a fraction of a percent, and every exact tie) are listed in LDS and
-// rechecked in fp64 right away, one wave per entry.
-__global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ Zs, const float* __restrict__ b0,
-                                                     const float* __restrict__ b1, const float* __restrict__ xnorm,
-                                                     const float* __restrict__ wnorm2, int* __restrict__ idx,
-                                                     float* __restrict__ gate, const bf16_t* __restrict__ x,
-                                                     const unsigned short* __restrict__ Wt, double* __restrict__ Z, int N,
-                                                     int kstep, int H, int E, int k, int HEp, int dm, int dmp) {
-  extern __shared__ double zt[];   // [SEL_TOK][HEp]
-  __shared__ double zs[4][64];
-  __shared__ int flist[256];       // (token, head) items of this work-group that need the recheck
-  __shared__ int nflag;
-  const int side = blockIdx.y;
-  const int n0 = blockIdx.x * SEL_TOK;
-  const float* b = side ? b1 : b0;
-  const int ntok = N - n0 < SEL_TOK ? N - n0 : SEL_TOK;
-  const double* src = Zs + ((long)side * N + n0) * (long)HEp;
-  if (threadIdx.x == 0) nflag = 0;
-  for (int i = threadIdx.x; i < ntok * HEp; i += 256) zt[i] = src[i];
-  __syncthreads();
-  for (int item0 = 0; item0 < ntok * H; item0 += 256) {
-    const int item = item0 + threadIdx.x;
-    if (item < ntok * H) {
-      const int nl = item / H, h = item % H;
-      const int n = n0 + nl;
-      const int sh_ = side * H + h;
-      const double* z = zt + nl * HEp + h * E;
-      // fp32 partial sums of `kstep` exact products, then fp64 adds: see the bound above
-      float w2 = 0.f;   // largest squared column norm of this head's router
-      for (int e = 0; e < E; ++e) w2 = fmaxf(w2, wnorm2[(long)sh_ * E + e]);
-      const double bound0 = 4.0 * (double)kstep * 5.9604645e-8 * (double)xnorm[n] * (double)(sqrtf(w2) * 1.0001f);
-      unsigned long long sel = 0ull;
-      const long o = ((long)sh_ * N + n) * k;
-      double prev = 0.0, bprev = 0.0;
-      bool flag = false;
-      const int passes = k < E ? k + 1 : k;
-      for (int j = 0; j < passes; ++j) {
-        int best = -1;
-        double bv = 0.0;
-        for (int e = 0; e < E; ++e) {
-          if ((sel >> e) & 1ull) continue;
-          double v = z[e] + (b ? (double)b[h * E + e] : 0.0);
-          if (best < 0 || v > bv) {
-            best = e;
-            bv = v;
-          }
-        }
-        const double bb = bound0 + 1e-13 * (fabs(bv) + 1.0);
-        if (j > 0 && !(prev - bv > bprev + bb)) flag = true;
-        prev = bv;
-        bprev = bb;
-        sel |= 1ull << best;
-        if (j < k) {
-          idx[o + j] = best;
-          gate[o + j] = (float)(1.0 / (1.0 + exp(-bv)));
-        }
-      }
-      if (flag) flist[atomicAdd(&nflag, 1)] = item;
-    }
-    __syncthreads();
-    // the recheck overwrites what the first stage wrote for its entries (same thread block, after the barrier)
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int HE = H * E;
-    for (int f = wave; f < nflag; f += 4) {
-      const int it = flist[f];
-      const int nl = it / H, h = it % H, n = n0 + nl;
-      const int sh_ = side * H + h;
-      const long o = ((long)sh_ * N + n) * k;
-      recheck_entry((const unsigned short*)x + (long)n * dm, Wt + ((long)side * HE + h * E) * dmp, b ? b + h * E : nullptr,
-                    zs[wave], Z + ((long)side * N + n) * HE + (long)h * E, idx + o, gate + o, dm, dmp, E, k, lane);
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) nflag = 0;
-    __syncthreads();
-  }
-}
-
 __device__ __forceinline__ void hist_body(const int* __restrict__ idx, int* __restrict__ blockcnt, int N, int E, int k,
                                           int nblk) {
   __shared__ int cnt[64];
@@ -508,8 +358,8 @@ size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off) {
     return r;
   };
   off[0] = take(2 * (size_t)dm * HEp * 2);   // Wp
-  off[1] = take(2 * (size_t)N * HEp * 8);    // Zs: stage-1 logits, fp64
-  off[2] = take((size_t)N * 4);              // xnorm
+  off[1] = off[2] = 0;                       // (unused: the stage-1 logits and the row norms stay on the CU)
+  (void)N;
   off[3] = take(2 * (size_t)H * E * 4);      // squared column norms
   off[4] = off[5] = 0;                       // (unused)
   off[6] = take(2 * (size_t)H * E * (((size_t)dm + 1023) / 1024 * 1024) * 2);   // Wt: router columns as vectors
@@ -680,8 +530,6 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
   router_hybrid_bytes(a.N, a.dm, a.H, a.E, off);
   const int HE = a.H * a.E, HEp = (HE + 7) / 8 * 8;
   bf16_t* Wp = (bf16_t*)(scratch + off[0]);
-  double* Zs = (double*)(scratch + off[1]);
-  float* xnorm = (float*)(scratch + off[2]);
   float* wmax = (float*)(scratch + off[3]);
   unsigned short* Wt = (unsigned short*)(scratch + off[6]);
   const int dmp = (a.dm + 1023) / 1024 * 1024;
@@ -690,7 +538,8 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
   // into the padded matrix the GEMM reads
   router_prep_kernel<<<a.sides * a.H * a.E, 256, 0, s>>>((const bf16_t*)a.W[0], (const bf16_t*)a.W[1], wmax, Wt,
                                                    (unsigned short*)Wp, a.dm, dmp, a.H, a.E, HEp);
-  // stage 1: z32 = x W on the matrix cores, fp32 accumulation, both sides in one launch
+  // stage 1: z32 = x W on the matrix cores, fp32 accumulation, both sides in one launch; the selection
+  // (and the fp64 recheck of its doubtful entries) is that kernel's epilogue
   RowGemmArgs g{};
   g.heads = a.sides;
   g.E = 1;
@@ -703,19 +552,28 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
   g.b_hstride = (long)a.dm * HEp;
   g.sbk = HEp;
   g.sbn = 1;
-  g.C = Zs;
-  g.ldc = HEp;
-  g.c_hoff = (long)a.N * HEp;
+  g.C = nullptr;   // nothing is stored: the selection consumes the logits inside the kernel
   g.K = a.dm;
   g.Nc = HEp;
   g.mode = STORE_F64;
   g.tag = TAG_ROUTER;
-  g.rownorm = xnorm;   // |x_n| for the error bound, from the tiles the GEMM loads anyway
+  g.rsel.b[0] = a.b[0];
+  g.rsel.b[1] = a.b[1];
+  g.rsel.wnorm2 = wmax;
+  g.rsel.idx = a.idx;
+  g.rsel.gate = a.gate;
+  g.rsel.x = a.x;
+  g.rsel.Wt = Wt;
+  g.rsel.Z = a.Z;
+  g.rsel.N = a.N;
+  g.rsel.kstep = rg_kstep();
+  g.rsel.H = a.H;
+  g.rsel.E = a.E;
+  g.rsel.k = a.k;
+  g.rsel.dm = a.dm;
+  g.rsel.dmp = dmp;
   launch_mfma_row_gemm(g, s);
 
-  dim3 g1((a.N + SEL_TOK - 1) / SEL_TOK, a.sides);
-  select_kernel<<<g1, 256, (size_t)SEL_TOK * HEp * 8, s>>>(Zs, a.b[0], a.b[1], xnorm, wmax, a.idx, a.gate, (const bf16_t*)a.x, Wt,
-                                                            a.Z, a.N, rg_kstep(), a.H, a.E, a.k, HEp, a.dm, dmp);
   const int nblk = router_blocks(a.N);
   dim3 g2(nblk, a.sides * a.H);
   if (a.sets && a.sets->sides == a.sides) {
