@@ -254,7 +254,10 @@ void launch_rope_apply(void* P0, void* P1, const float2* tab, long N, int T, int
 // out [B, T, dm] (storage type) += add [B, Tq, dm] (fp32) on the last Tq rows of every sequence
 void launch_add_query_rows(void* out, const float* add, long rows, int T, int Tq, int dm, int bf16, hipStream_t s);
 // dW0[i][c] = T[i*ld + c], dW1[i][c] = T[i*ld + HEp + c] for c < HE (either output may be NULL)
-void launch_router_wgrad_split(const float* T, float* dW0, float* dW1, int dm, int ld, int HE, int HEp, hipStream_t s);
+// Also, if dbpart is not NULL: db_side[h*E + e] = the sum over the `nblk` block partials router_bwd left there.
+void launch_router_wgrad_split(const float* T, float* dW0, float* dW1, int dm, int ld, int HE, int HEp, const float* dbpart,
+                               int nblk, int E, float* db0, float* db1, hipStream_t s);
+int router_bwd_blocks(int N);   // token blocks of launch_router_bwd
 void launch_sum_heads(const void* part, const float* add32, void* out, size_t n, size_t hstride, int H, hipStream_t s);
 
 // out[n,h,:] = sum_j gate[h][n*k+j] * slots[h][n*k+j][:]   (slots [H, N*k, dh], storage type T)
@@ -282,6 +285,8 @@ struct RouterBwdArgs {
   const float* dgate;   // [2, H, N, k]
   void* dz;             // [N][ld]: side s owns columns s*side_stride .. +HE, the rest of its stride is zeroed
   float* db[2];         // per side [HE] or NULL, atomic add (zeroed by caller)
+  float* dbpart;        // if not NULL: no atomics; block b of (side, head) sh stores its E sums at
+                        // dbpart[(sh * blocks + b) * E + e] and launch_router_wgrad_split adds them up
   int N, H, E, k, sides, shared;
   int ld, side_stride;
   int pad_to;   // columns sides*side_stride .. pad_to-1 of every row are zeroed too (0: none)

@@ -1272,8 +1272,15 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     float* dbs[2] = {db_S, c.shared ? nullptr : db_D};
     // the small outputs that are accumulated with atomics are cleared by one launch
     const bool both_w = sides == 2 && dWs[0] && dWs[1] && !fuse_router_w;
-    launch_zero4_f32(dbs[0], dbs[0] ? (size_t)HE : 0, dbs[1], dbs[1] ? (size_t)HE : 0, both_w ? dWs[0] : nullptr,
-                     both_w ? (size_t)dm * HE : 0, both_w ? dWs[1] : nullptr, both_w ? (size_t)dm * HE : 0, c.st);
+    // fused weight gradient: the bias gradients go through per-block sums that the split kernel adds up
+    // (no atomics, nothing to clear); the dz region proper is free then (the rows sit in dR)
+    const size_t esz_r = c.bf16 ? 2 : 4;
+    const int rblk = router_bwd_blocks(N);
+    const bool db_partial = fuse_router_w && wide_dz && (dbs[0] || dbs[1]) &&
+                            (size_t)sides * H * rblk * E * 4 <= (size_t)N * 2 * ((H * E + 7) / 8 * 8) * esz_r;
+    if (!db_partial)
+      launch_zero4_f32(dbs[0], dbs[0] ? (size_t)HE : 0, dbs[1], dbs[1] ? (size_t)HE : 0, both_w ? dWs[0] : nullptr,
+                       both_w ? (size_t)dm * HE : 0, both_w ? dWs[1] : nullptr, both_w ? (size_t)dm * HE : 0, c.st);
     RouterBwdArgs rb{};
     rb.idx = c.idx(0);
     rb.gate = c.gate(0);
@@ -1281,6 +1288,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     rb.dz = c.p<void>(wide_dz ? c.L.dR : c.L.dz);
     rb.db[0] = dbs[0];
     rb.db[1] = dbs[1];
+    rb.dbpart = db_partial ? c.p<float>(c.L.dz) : nullptr;
     rb.N = N;
     rb.H = H;
     rb.E = E;
@@ -1301,7 +1309,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     if (fuse_router_w) {
       run_qk_wgrad(true);
       prof_mark(c.st, "bwd.router_wsplit");
-      launch_router_wgrad_split(c.p<float>(c.L.wrt), dWs[0], dWs[1], dm, dh, HE, HEp, c.st);
+      launch_router_wgrad_split(c.p<float>(c.L.wrt), dWs[0], dWs[1], dm, dh, HE, HEp, db_partial ? c.p<float>(c.L.dz) : nullptr,
+                                rblk, E, dbs[0], dbs[1], c.st);
     } else
     // dW_S / dW_D = x^T dz: one launch for both sides when both are wanted
     {

@@ -165,8 +165,25 @@ __global__ __launch_bounds__(256) void rope_apply_vec_kernel(unsigned short* __r
 // T [dm][ld] (fp32) holds x^T dz for both routers side by side (side s in columns s*HEp .. s*HEp+HE-1):
 // the two router weight gradients are its column blocks.
 __global__ __launch_bounds__(256) void router_wgrad_split_kernel(const float* __restrict__ T, float* __restrict__ dW0,
-                                                                 float* __restrict__ dW1, int dm, int ld, int HE, int HEp) {
+                                                                 float* __restrict__ dW1, int dm, int ld, int HE, int HEp,
+                                                                 const float* __restrict__ dbpart, int nblk, int E,
+                                                                 float* __restrict__ db0, float* __restrict__ db1) {
   const long id = (long)blockIdx.x * 256 + threadIdx.x;
+  if (dbpart && id < 2L * HE * 64) {
+    // bias gradients, one wave per column: column c of side s = head c / E, expert c % E; every lane adds
+    // the block sums b = lane, lane + 64, ... in that order, a butterfly adds the lanes (a fixed order)
+    const int col = (int)(id >> 6), lane = (int)(id & 63);
+    const int side = col / HE, c = col % HE;
+    float* db = side ? db1 : db0;
+    if (db) {   // wave-uniform
+      const float* p = dbpart + ((long)(side * (HE / E) + c / E) * nblk) * E + c % E;
+      float s = 0.f;
+      for (int b = lane; b < nblk; b += 64) s += p[(long)b * E];
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      if (lane == 0) db[c] = s;
+    }
+  }
   if (id >= (long)dm * HE) return;
   const long i = id / HE;
   const int c = (int)(id % HE);
@@ -174,9 +191,11 @@ __global__ __launch_bounds__(256) void router_wgrad_split_kernel(const float* __
   if (dW1) dW1[id] = T[i * ld + HEp + c];
 }
 
-void launch_router_wgrad_split(const float* T, float* dW0, float* dW1, int dm, int ld, int HE, int HEp, hipStream_t s) {
-  const long n = (long)dm * HE;
-  if (n) router_wgrad_split_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(T, dW0, dW1, dm, ld, HE, HEp);
+void launch_router_wgrad_split(const float* T, float* dW0, float* dW1, int dm, int ld, int HE, int HEp, const float* dbpart,
+                               int nblk, int E, float* db0, float* db1, hipStream_t s) {
+  long n = (long)dm * HE;
+  if (dbpart && n < 128L * HE) n = 128L * HE;   // one wave per bias-gradient column
+  if (n) router_wgrad_split_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(T, dW0, dW1, dm, ld, HE, HEp, dbpart, nblk, E, db0, db1);
 }
 
 void launch_rope_table(float2* tab, int T, int dh, hipStream_t s) {
@@ -375,13 +394,18 @@ void launch_slot_combine(const SlotArgs& a, int bf16, hipStream_t s) {
 // One thread per (token, side, head): writes the E logit-gradient entries it owns.
 template <typename T>
 __global__ __launch_bounds__(256) void router_bwd_kernel(RouterBwdArgs a) {
-  __shared__ float bsum[64];
+  __shared__ float wsum[4][64];   // per wave and expert: the sum of the wave's logit gradients
   const int sh_ = blockIdx.y;  // side*H + h over the sides that own a router
   const int side = sh_ / a.H, h = sh_ % a.H;
   const int n = blockIdx.x * 256 + threadIdx.x;
   const int E = a.E, k = a.k, HE = a.H * a.E;
-  if (threadIdx.x < 64) bsum[threadIdx.x] = 0.f;
-  __syncthreads();
+  int es[8];     // this token's experts and their logit gradients
+  float vs[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    es[j] = -1;
+    vs[j] = 0.f;
+  }
   if (n < a.N) {
     T* dz = (T*)a.dz;
     const long base = (long)n * a.ld + (long)side * a.side_stride + (long)h * E;
@@ -396,19 +420,41 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(RouterBwdArgs a) {
       }
     }
     const long o = ((long)sh_ * a.N + n) * k;  // side-major layout [side][H][N][k]
-    for (int j = 0; j < k; ++j) {
-      int e = a.idx[o + j];
-      float g = a.gate[o + j];
-      float dg = a.dgate[o + j];
-      if (a.shared) dg += a.dgate[(long)a.H * a.N * k + o + j];
-      float v = dg * g * (1.f - g);
-      st(dz, base + e, v);
-      atomicAdd(&bsum[e], v);
-    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < k) {
+        int e = a.idx[o + j];
+        float g = a.gate[o + j];
+        float dg = a.dgate[o + j];
+        if (a.shared) dg += a.dgate[(long)a.H * a.N * k + o + j];
+        float v = dg * g * (1.f - g);
+        st(dz, base + e, v);
+        es[j] = e;
+        vs[j] = v;
+      }
+  }
+  // bias gradient of this block: per expert a butterfly over the lanes, then the waves in order (no
+  // atomics inside the block: the sum has one fixed order)
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int e = 0; e < E; ++e) {
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v += es[j] == e ? vs[j] : 0.f;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    if (lane == 0) wsum[wave][e] = v;
   }
   __syncthreads();
-  if (threadIdx.x < E && a.db[side]) atomicAdd(&a.db[side][h * E + threadIdx.x], bsum[threadIdx.x]);
+  if (threadIdx.x < E) {
+    const float bs = ((wsum[0][threadIdx.x] + wsum[1][threadIdx.x]) + wsum[2][threadIdx.x]) + wsum[3][threadIdx.x];
+    if (a.dbpart)
+      a.dbpart[((long)sh_ * gridDim.x + blockIdx.x) * E + threadIdx.x] = bs;
+    else if (a.db[side])
+      atomicAdd(&a.db[side][h * E + threadIdx.x], bs);
+  }
 }
+
+int router_bwd_blocks(int N) { return (N + 255) / 256; }
 
 void launch_router_bwd(const RouterBwdArgs& a, int bf16, hipStream_t s) {
   dim3 g((a.N + 255) / 256, a.sides * a.H);

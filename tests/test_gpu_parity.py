@@ -255,8 +255,8 @@ def test_rerun_is_stable():
 
 def test_matrix_core_path_is_deterministic():
     """bf16 storage, expert-set path: no atomic add decides y, dx or the weight gradients of the
-    projections (per-chunk partial sums are added in a fixed order), so two runs agree bit for bit.
-    The router bias gradients use atomics and are only required to agree closely."""
+    projections or of the routers (per-chunk and per-block partial sums are added in a fixed order), so
+    two runs agree bit for bit."""
     from paper_2312_07987_amd.runner import DeviceLayer
     cfg = small("c2", B=4, T=256)
     t = make_inputs(cfg, seed=5)
@@ -268,7 +268,5 @@ def test_matrix_core_path_is_deterministic():
         g = layer.grads()
         g["y"] = layer.outputs().copy()
         runs.append({n: np.array(v, copy=True) for n, v in g.items() if v is not None})
-    for n in ("y", "dx", "dW_Q", "dW_K", "dW_V", "dW_O"):
+    for n in ("y", "dx", "dW_Q", "dW_K", "dW_V", "dW_O", "dW_S", "dW_D", "db_S", "db_D"):
         assert np.array_equal(runs[0][n], runs[1][n]), n
-    for n in ("dW_S", "dW_D", "db_S", "db_D"):
-        assert nerr(runs[1][n], runs[0][n]) <= 1e-5, n
