@@ -173,8 +173,54 @@ __global__ __launch_bounds__(256) void scan2_kernel(int* __restrict__ blockcnt, 
     scan_body(setcnt, setoff, nsets, nblk);
 }
 
+// What scan_body would leave for this token block, computed by the block itself from the raw counts
+// cnt[sh][blk][bin] (for tables small enough that every block can read them whole): sbase[bin] = first
+// position of bin `bin` for token block blockIdx.x; token block 0 also writes offsets[sh][0..nbins].
+// One wave per bin, lanes over token blocks.  Called by all RB threads; ends with a barrier.
+__device__ __forceinline__ void block_bases(const int* __restrict__ cnt, int* __restrict__ offsets, int nbins, int nblk,
+                                            int* __restrict__ sbase /* LDS [2 * 128 + 1] */) {
+  const int sh_ = blockIdx.y, blk = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int* c = cnt + (long)sh_ * nblk * nbins;
+  int* tot = sbase + 128;
+  for (int e = wave; e < nbins; e += RB / 64) {
+    int all = 0, pre = 0;
+    for (int b = lane; b < nblk; b += 64) {
+      const int v = c[(long)b * nbins + e];
+      all += v;
+      pre += b < blk ? v : 0;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      all += __shfl_xor(all, o, 64);
+      pre += __shfl_xor(pre, o, 64);
+    }
+    if (lane == 0) {
+      tot[e] = all;
+      sbase[e] = pre;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int i = 0; i < nbins; ++i) {
+      const int t = tot[i];
+      tot[i] = run;
+      sbase[i] += run;
+      run += t;
+    }
+    tot[nbins] = run;
+  }
+  __syncthreads();
+  if (blk == 0)
+    for (int i = threadIdx.x; i <= nbins; i += RB) offsets[(long)sh_ * (nbins + 1) + i] = tot[i];
+}
+
+// LOCAL: the block's bases are in LDS (sbase, from block_bases) instead of the scanned table `base`
+template <bool LOCAL = false>
 __device__ __forceinline__ void scatter_body(const int* __restrict__ idx, const int* __restrict__ base,
-                                             int* __restrict__ perm, int N, int E, int k, int nblk) {
+                                             int* __restrict__ perm, int N, int E, int k, int nblk,
+                                             const int* sbase = nullptr) {
   __shared__ int wcnt[RB / 64][64];
   const int sh_ = blockIdx.y;
   const int n = blockIdx.x * RB + threadIdx.x;
@@ -203,12 +249,15 @@ __device__ __forceinline__ void scatter_body(const int* __restrict__ idx, const 
   }
   __syncthreads();
   if (valid) {
-    const int* bs = base + ((long)sh_ * nblk + blockIdx.x) * E;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       if (j < k) {
         int e = ej[j];
-        int pos = bs[e] + rk[j];
+        int pos = rk[j];
+        if constexpr (LOCAL)
+          pos += sbase[e];
+        else
+          pos += base[((long)sh_ * nblk + blockIdx.x) * E + e];
         for (int w = 0; w < wave; ++w) pos += wcnt[w][e];
         perm[(long)sh_ * N * k + pos] = n * k + j;
       }
@@ -474,9 +523,11 @@ __global__ __launch_bounds__(RB) void hist2_kernel(const int* __restrict__ idx, 
   set_hist_body(idx, gate, setid, gset, setexp, setcnt, N, k, E, nsets, nblk);
 }
 
+template <bool LOCAL = false>
 __device__ __forceinline__ void set_scatter_body(const int* __restrict__ setid, const int* __restrict__ base,
                                                  int* __restrict__ setperm, const float* __restrict__ gset,
-                                                 float* __restrict__ gsort, int N, int k, int nsets, int nblk) {
+                                                 float* __restrict__ gsort, int N, int k, int nsets, int nblk,
+                                                 const int* sbase = nullptr) {
   __shared__ int wcnt[RB / 64][128];
   const int sh_ = blockIdx.y;
   const int n = blockIdx.x * RB + threadIdx.x;
@@ -491,7 +542,11 @@ __device__ __forceinline__ void set_scatter_body(const int* __restrict__ setid, 
   }
   __syncthreads();
   if (sid < 0) return;
-  int pos = base[((long)sh_ * nblk + blockIdx.x) * nsets + sid] + rk;
+  int pos = rk;
+  if constexpr (LOCAL)
+    pos += sbase[sid];
+  else
+    pos += base[((long)sh_ * nblk + blockIdx.x) * nsets + sid];
   for (int w = 0; w < wave; ++w) pos += wcnt[w][sid];
   setperm[(long)sh_ * N + pos] = n;
   for (int j = 0; j < k; ++j) gsort[((long)sh_ * N + pos) * k + j] = gset[((long)sh_ * N + n) * k + j];
@@ -510,6 +565,21 @@ __global__ __launch_bounds__(RB) void scatter2_kernel(const int* __restrict__ id
   scatter_body(idx, base, perm, N, E, k, nblk);
   __syncthreads();
   set_scatter_body(setid, setbase, setperm, gset, gsort, N, k, nsets, nblk);
+}
+// the same with the scans done by every block for itself (small tables): `cnt` and `setcnt` hold the raw
+// per-block counts, the offsets tables are written here
+__global__ __launch_bounds__(RB) void scan_scatter2_kernel(const int* __restrict__ idx, const int* __restrict__ cnt,
+                                                           int* __restrict__ offsets, int* __restrict__ perm,
+                                                           const int* __restrict__ setid, const int* __restrict__ setcnt,
+                                                           int* __restrict__ setoff, int* __restrict__ setperm,
+                                                           const float* __restrict__ gset, float* __restrict__ gsort, int N,
+                                                           int E, int k, int nsets, int nblk) {
+  __shared__ int sb[2][2 * 128 + 1];
+  block_bases(cnt, offsets, E, nblk, sb[0]);
+  block_bases(setcnt, setoff, nsets, nblk, sb[1]);
+  scatter_body<true>(idx, nullptr, perm, N, E, k, nblk, sb[0]);
+  __syncthreads();
+  set_scatter_body<true>(setid, nullptr, setperm, gset, gsort, N, k, nsets, nblk, sb[1]);
 }
 
 void launch_set_sort(const SetSortArgs& a, hipStream_t s) {
@@ -581,6 +651,12 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
     const SetSortArgs& t = *a.sets;
     hist2_kernel<<<g2, RB, 0, s>>>(a.idx, a.gate, a.blockcnt, t.setid, t.gset, t.setexp, t.blockcnt, a.N, a.k, a.E, t.nsets,
                                    nblk);
+    if ((long)nblk * (a.E > t.nsets ? a.E : t.nsets) <= 8192) {
+      // small tables: every scatter block scans the counts it needs itself, one launch less
+      scan_scatter2_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.offsets, a.perm, t.setid, t.blockcnt, t.setoff, t.setperm,
+                                             t.gset, t.gsort, a.N, a.E, a.k, t.nsets, nblk);
+      return;
+    }
     scan2_kernel<<<dim3(a.sides * a.H, 2), 256, 0, s>>>(a.blockcnt, a.offsets, a.E, t.blockcnt, t.setoff, t.nsets, nblk);
     scatter2_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.perm, t.setid, t.blockcnt, t.setperm, t.gset, t.gsort, a.N, a.E,
                                       a.k, t.nsets, nblk);

@@ -226,6 +226,13 @@ def test_bf16_router_weight_gradient_forms():
     run_case(small("c2", B=2, T=256, d_model=256, nheads=4, d_head=128, E=16, k=2), shared=True, seed=75)
 
 
+def test_bf16_sort_tables_too_large_for_the_in_block_scan():
+    """126 expert sets and 66 token blocks: the counting sorts take their separate scan launch (smaller
+    tables are scanned by every scatter block for itself)."""
+    run_case(dict(name="bigsort", dtype="bf16", B=66, T=256, d_model=64, nheads=1, d_head=32, E=9, k=4, causal=1, bias0=0.0),
+             seed=76)
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
 def test_full_config(name):
     """The paper-shaped workloads at full size, in the launch configuration bench.py times."""
