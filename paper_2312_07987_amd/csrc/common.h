@@ -290,6 +290,12 @@ struct RouterBwdArgs {
   int N, H, E, k, sides, shared;
   int ld, side_stride;
   int pad_to;   // columns sides*side_stride .. pad_to-1 of every row are zeroed too (0: none)
+  // Rides along (bf16 only, if wide_out is not NULL): both routers' weights side by side as
+  // wide_out[d_model][wide_width], column side*side_stride + c = W_side[i][c], zeros elsewhere
+  // (what launch_pack_router_wide writes), spread over the launch's threads.
+  const void* W[2];
+  void* wide_out;
+  int dm, wide_width;
 };
 void launch_router_bwd(const RouterBwdArgs& a, int bf16, hipStream_t s);
 
@@ -298,9 +304,6 @@ void launch_router_bwd(const RouterBwdArgs& a, int bf16, hipStream_t s);
 void prof_mark(hipStream_t st, const char* label);
 // both routers' weights as bf16 [side][d_model][HEp], columns HE..HEp-1 zero (W1 unused when sides == 1)
 void launch_pack_router(const void* W0, const void* W1, void* Wp, int dm, int HE, int HEp, int sides, hipStream_t s);
-// the same weights side by side, bf16 [d_model][width]: columns side*HEp + c, zeros elsewhere
-void launch_pack_router_wide(const void* W0, const void* W1, void* out, int dm, int HE, int HEp, int sides, int width,
-                             hipStream_t s);
 
 void launch_simt_row_gemm(const RowGemmArgs& a, int bf16, hipStream_t s);
 void launch_simt_wgrad(const WgradArgs& a, int bf16, hipStream_t s);

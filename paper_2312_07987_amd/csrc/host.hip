@@ -1299,13 +1299,17 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     rb.ld = wide_dz ? (int)hd : sides * HEp;   // wide rows: the shape of a dQ / dK row
     rb.side_stride = HEp;
     rb.pad_to = wide_dz ? dh : 0;
+    if (fuse_router) {   // the packed routers for the Q/K dgrad launch below ride along
+      rb.W[0] = W_S;
+      rb.W[1] = c.shared ? nullptr : W_D;
+      rb.wide_out = c.p<void>(c.L.wr3);
+      rb.dm = dm;
+      rb.wide_width = dh;
+    }
     launch_router_bwd(rb, c.bf16, c.st);
     const size_t esz = c.bf16 ? 2 : 4;
     const char* dz0 = c.p<char>(wide_dz ? c.L.dR : c.L.dz);
-    if (fuse_router) {
-      launch_pack_router_wide(W_S, c.shared ? nullptr : W_D, c.p<void>(c.L.wr3), dm, HE, HEp, sides, dh, c.st);
-      run_qk_dgrad(true);
-    }
+    if (fuse_router) run_qk_dgrad(true);
     if (fuse_router_w) {
       run_qk_wgrad(true);
       prof_mark(c.st, "bwd.router_wsplit");

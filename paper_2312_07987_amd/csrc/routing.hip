@@ -373,26 +373,6 @@ __global__ void pack_router_kernel(const bf16_t* __restrict__ W0, const bf16_t* 
   Wp[i] = v;
 }
 
-__global__ void pack_router_wide_kernel(const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1, bf16_t* __restrict__ out,
-                                        int dm, int HE, int HEp, int sides, int width) {
-  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (long)dm * width) return;
-  const int c = (int)(i % width);
-  const long row = i / width;
-  const int side = c / HEp, cc = c % HEp;
-  bf16_t v;
-  v.v = 0;
-  if (side < sides && cc < HE) v = (side ? W1 : W0)[row * HE + cc];
-  out[i] = v;
-}
-
-void launch_pack_router_wide(const void* W0, const void* W1, void* out, int dm, int HE, int HEp, int sides, int width,
-                             hipStream_t s) {
-  const long tot = (long)dm * width;
-  pack_router_wide_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const bf16_t*)W0, (const bf16_t*)W1, (bf16_t*)out, dm,
-                                                                        HE, HEp, sides, width);
-}
-
 void launch_pack_router(const void* W0, const void* W1, void* Wp, int dm, int HE, int HEp, int sides, hipStream_t s) {
   const long tot = (long)sides * dm * HEp;
   pack_router_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const bf16_t*)W0, (const bf16_t*)W1, (bf16_t*)Wp, dm, HE, HEp, sides);

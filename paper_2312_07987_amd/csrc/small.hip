@@ -399,6 +399,17 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(RouterBwdArgs a) {
   const int side = sh_ / a.H, h = sh_ % a.H;
   const int n = blockIdx.x * 256 + threadIdx.x;
   const int E = a.E, k = a.k, HE = a.H * a.E;
+  if (sizeof(T) == 2 && a.wide_out) {
+    const long tot = (long)a.dm * a.wide_width, nthr = (long)gridDim.x * gridDim.y * 256;
+    for (long i = ((long)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; i < tot; i += nthr) {
+      const int c = (int)(i % a.wide_width);
+      const long row = i / a.wide_width;
+      const int ws = c / a.side_stride, cc = c % a.side_stride;
+      unsigned short v = 0;
+      if (ws < a.sides && cc < HE) v = ((const unsigned short*)a.W[ws])[row * HE + cc];
+      ((unsigned short*)a.wide_out)[i] = v;
+    }
+  }
   int es[8];     // this token's experts and their logit gradients
   float vs[8];
 #pragma unroll
