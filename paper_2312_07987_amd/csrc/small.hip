@@ -298,9 +298,15 @@ __global__ __launch_bounds__(256) void slot_combine_kernel(SlotArgs a) {
     }
   }
   if (a.delta) {
+    // the row sum uses the values as stored (rounded to the storage type): the attention backward
+    // multiplies those, and its dS = P (dP - delta) cancels exactly only if both see the same numbers
     float dd = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dd += acc[i] * oth[i];
+    for (int i = 0; i < 4; ++i) {
+      float v = acc[i];
+      if (out && sizeof(T) == 2) v = bf16_to_f32(f32_to_bf16(v));
+      dd += v * oth[i];
+    }
     dd = wave_sum(dd);
     if (lane == 0) a.delta[pair] = dd;
   }
@@ -360,9 +366,11 @@ __global__ __launch_bounds__(256) void slot_combine_vec_kernel(SlotArgs a) {
     *(uint4*)((unsigned short*)a.out + row) = o;
   }
   if (a.delta) {
+    // from the values as stored (rounded to bf16): the attention backward multiplies those, and its
+    // dS = P (dP - delta) cancels exactly only if both see the same numbers
     float dd = 0.f;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) dd += acc[t] * oth[t];
+    for (int t = 0; t < 8; ++t) dd += (a.out ? bf16_to_f32(f32_to_bf16(acc[t])) : acc[t]) * oth[t];
 #pragma unroll
     for (int o = TPR / 2; o > 0; o >>= 1) dd += __shfl_xor(dd, o, 64);
     if (valid && lane_in == 0) a.delta[pair] = dd;

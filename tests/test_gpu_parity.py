@@ -226,6 +226,17 @@ def test_bf16_router_weight_gradient_forms():
     run_case(small("c2", B=2, T=256, d_model=256, nheads=4, d_head=128, E=16, k=2), shared=True, seed=75)
 
 
+@pytest.mark.parametrize("family", [0, 1])
+def test_bf16_single_token_sequences(family):
+    """T = 1: the attention matrix is the number 1, so the gradients of queries and keys are exactly zero;
+    the row sums of the backward pass must come from the same rounded values its products use, or
+    rounding noise of the size of a normal gradient is left where the reference has nothing."""
+    run_case(dict(name="t1a", dtype="bf16", B=2, T=1, d_model=96, nheads=1, d_head=64, E=12, k=3, causal=1, bias0=1.5),
+             family=family, seed=1027)
+    run_case(dict(name="t1b", dtype="bf16", B=5, T=1, d_model=64, nheads=1, d_head=16, E=5, k=3, causal=0, bias0=0.0,
+                  qk_experts=1, rope=1), family=family, shared=True, seed=1053)
+
+
 def test_bf16_sort_tables_too_large_for_the_in_block_scan():
     """126 expert sets and 66 token blocks: the counting sorts take their separate scan launch (smaller
     tables are scanned by every scatter block for itself)."""
