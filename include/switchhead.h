@@ -139,10 +139,12 @@ sh_status switchhead_forward(const sh_shape* shape,
  *            with shared selection (dW_S then holds the sum of both sides) and all four
  *            are ignored in dense mode.
  * Determinism: with bf16 storage and the matrix-core kernels, dW_Q, dW_K, dW_V, dW_O are
- * sums of per-chunk partial results added in a fixed order (bit-identical from run to run);
- * the small router gradients dW_S, dW_D, db_S, db_D, and every weight gradient of the plain
- * fp32 kernels, are accumulated with fp32 atomic adds over token chunks, so their last bits
- * may differ from run to run.
+ * sums of per-chunk partial results added in a fixed order (bit-identical from run to run),
+ * and so are the router gradients dW_S, dW_D, db_S, db_D where they ride along the query/key
+ * weight-gradient launch (square attention, dense queries and keys, 2 * nheads * E, each side
+ * rounded up to a multiple of 8, not above d_head).  Otherwise the router gradients, and every
+ * weight gradient of the plain fp32 kernels, are accumulated with fp32 atomic adds over token
+ * chunks, so their last bits may differ from run to run.
  */
 sh_status switchhead_backward(const sh_shape* shape,
                               const void* x, const void* W_Q, const void* W_K,
