@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP32_VEC_TFLOPS = 157.3  # MI355X fp32 vector ALU: what the plain fp32 kernels (fp32 storage) run on
 PEAK_FP64_VEC_TFLOPS = 78.6   # MI355X fp64 vector ALU (256 CUs x 4 SIMD x 16 lanes x 2 x 2.4 GHz)
 PEAK_HBM_GBS = 8000.0
 
@@ -274,8 +275,10 @@ def main():
     dom = max(per_step, key=per_step.get)
     if dom in flops:
         ach = flops[dom] / (per_step[dom] * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+        mfma = cfg["dtype"] == "bf16"   # fp32 storage runs the plain fp32 kernels: vector ALU, not MFMA
+        peak = PEAK_BF16_TFLOPS if mfma else PEAK_FP32_VEC_TFLOPS
+        roof = {"bound": "mfma" if mfma else "alu", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                "frac": ach / peak, "traffic": None}
     elif dom in alu:
         ach = alu[dom] / (per_step[dom] * 1e-3) / 1e12
         roof = {"bound": "alu", "achieved": ach, "peak": PEAK_FP64_VEC_TFLOPS, "unit": "TFLOP/s",
