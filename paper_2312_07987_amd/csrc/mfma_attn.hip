@@ -341,7 +341,7 @@ __device__ __forceinline__ void store_rows_T(unsigned short* dst, const f32x16* 
 //   dV^T[d][key] += dO^T[d][q] P[q][key],   dK^T[d][key] += Q^T[d][q] dS[q][key]
 // ----------------------------------------------------------------------------------------
 template <int DH, int VEC, int NW>
-__global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
+__global__ __launch_bounds__(64 * NW, DH <= 64 ? 2 : 1) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
   constexpr int QT = 32, KB = 32 * NW;   // keys per work-group
   constexpr bool SEP = DH <= 128;                       // separate tiles for the two read patterns
   constexpr int LDR = SEP ? DH + 8 : ld_tr(DH), LDT = ld_tr(DH);
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(64 * NW, DH <= 96 ? 2 : 1) void mfma_attn_dkv_kerne
   unsigned short* Gt = SEP ? Gt_ : Gr;
 
   int b, h, ktile;
-  attn_block_map(blockIdx.x, (a.T + KB - 1) / KB, a.B * a.H, a.H, a.causal, false, DH <= 96 ? 2 : 1, b, h, ktile);
+  attn_block_map(blockIdx.x, (a.T + KB - 1) / KB, a.B * a.H, a.H, a.causal, false, DH <= 64 ? 2 : 1, b, h, ktile);
   const int k0 = ktile * KB;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
