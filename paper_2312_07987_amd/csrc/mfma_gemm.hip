@@ -163,6 +163,8 @@ struct TileCfg {
   }
 };
 typedef TileCfg<2, 2, 2, 2, 64, 1> CfgSmall;    // 128 x 128
+typedef TileCfg<2, 2, 2, 2, 80, 1> CfgSmall80;  // the same with an 80-wide K step: a reduction of 65..80 (a head width of 76
+                                                // or 80) then takes one step per segment instead of one and a mostly empty second
 typedef TileCfg<2, 2, 1, 1, 64, 1> CfgRouter;   // 64 x 64: the router logits have <= 32 columns and want many work-groups
 typedef TileCfg<2, 2, 2, 4, 64, 1, 2> CfgWide;     // 128 x 256, wave tile 64 x 128, two work-groups per CU
 typedef TileCfg<2, 2, 4, 2, 64, 1, 2> CfgMed;   // 256 x 128, wave tile 128 x 64, two work-groups per CU
@@ -593,18 +595,30 @@ static void launch_tagged(const RowGemmArgs& a, hipStream_t s) {
   switch (pick_shape(a)) {
     case SHAPE_WIDE: launch_cfg<CfgWide, 8, BNT, TAG, SEG>(a, s); break;
     case SHAPE_MED: launch_cfg<CfgMed, 8, BNT, TAG, SEG>(a, s); break;
-    default: launch_cfg<CfgSmall, 8, BNT, TAG, SEG>(a, s); break;
+    default:
+      if (a.K > 64 && a.K <= 80)
+        launch_cfg<CfgSmall80, 8, BNT, TAG, SEG>(a, s);
+      else
+        launch_cfg<CfgSmall, 8, BNT, TAG, SEG>(a, s);
+      break;
   }
 }
 
+template <class Cfg, int VEC, bool BNT>
+static void launch_generic_cfg(const RowGemmArgs& a, hipStream_t s) {
+  if (a.seg_mode == 1)
+    launch_cfg<Cfg, VEC, BNT, TAG_GENERIC, 1>(a, s);
+  else if (a.seg_mode == 2)
+    launch_cfg<Cfg, VEC, BNT, TAG_GENERIC, 2>(a, s);
+  else
+    launch_cfg<Cfg, VEC, BNT, TAG_GENERIC, 0>(a, s);
+}
 template <int VEC, bool BNT>
 static void launch_generic(const RowGemmArgs& a, hipStream_t s) {
-  if (a.seg_mode == 1)
-    launch_cfg<CfgSmall, VEC, BNT, TAG_GENERIC, 1>(a, s);
-  else if (a.seg_mode == 2)
-    launch_cfg<CfgSmall, VEC, BNT, TAG_GENERIC, 2>(a, s);
+  if (a.K > 64 && a.K <= 80)
+    launch_generic_cfg<CfgSmall80, VEC, BNT>(a, s);
   else
-    launch_cfg<CfgSmall, VEC, BNT, TAG_GENERIC, 0>(a, s);
+    launch_generic_cfg<CfgSmall, VEC, BNT>(a, s);
 }
 
 void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s) {
