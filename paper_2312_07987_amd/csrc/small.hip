@@ -312,43 +312,52 @@ __global__ __launch_bounds__(256) void slot_combine_kernel(SlotArgs a) {
   }
 }
 
-// bf16 rows whose length is a multiple of 8: 16 bytes per thread, dh/8 threads per (token, head)
-// row (a power of two <= 32 so a row never straddles a wave), shuffles inside that lane group.
-template <int TPR>
+// VW (8 or 4) consecutive bf16 -> floats
+template <int VW>
+__device__ __forceinline__ void load_bf16_vec(const unsigned short* p, float* f) {
+  unsigned w[VW / 2];
+  if constexpr (VW == 8) {
+    const uint4 v = *(const uint4*)p;
+    w[0] = v.x, w[1] = v.y, w[2] = v.z, w[3] = v.w;
+  } else {
+    const uint2 v = *(const uint2*)p;
+    w[0] = v.x, w[1] = v.y;
+  }
+#pragma unroll
+  for (int t = 0; t < VW / 2; ++t) {
+    f[2 * t] = __uint_as_float(w[t] << 16);
+    f[2 * t + 1] = __uint_as_float(w[t] & 0xffff0000u);
+  }
+}
+
+// bf16 rows whose length is a multiple of VW (8 or 4): 16 or 8 bytes per thread, dh/VW threads per
+// (token, head) row rounded up to a power of two <= 64 (a row never straddles a wave), shuffles inside
+// that lane group.
+template <int TPR, int VW>
 __global__ __launch_bounds__(256) void slot_combine_vec_kernel(SlotArgs a) {
   const int lane_in = threadIdx.x % TPR;
   const long pair = ((long)blockIdx.x * 256 + threadIdx.x) / TPR;
   const bool valid = pair < (long)a.N * a.H;
   const int n = valid ? (int)(pair / a.H) : 0, h = valid ? (int)(pair % a.H) : 0;
-  const int dh = a.dh, k = a.k, d0 = lane_in * 8;
+  const int dh = a.dh, k = a.k, d0 = lane_in * VW;
   const bool act = valid && d0 < dh;
   const unsigned short* other = (const unsigned short*)a.other;
   const long row = ((long)n * a.H + h) * dh + d0;
-  float oth[8], acc[8];
+  float oth[VW], acc[VW];
 #pragma unroll
-  for (int t = 0; t < 8; ++t) oth[t] = acc[t] = 0.f;
-  if (other && act) {
-    const uint4 v = *(const uint4*)(other + row);
-    const unsigned w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      oth[2 * t] = __uint_as_float(w[t] << 16);
-      oth[2 * t + 1] = __uint_as_float(w[t] & 0xffff0000u);
-    }
-  }
+  for (int t = 0; t < VW; ++t) oth[t] = acc[t] = 0.f;
+  if (other && act) load_bf16_vec<VW>(other + row, oth);
   for (int j = 0; j < k; ++j) {
     const long aid = (long)h * a.N * k + (long)n * k + j;
     float dot = 0.f;
     if (act) {
       const float g = a.gate[aid];
-      const uint4 v = *(const uint4*)((const unsigned short*)a.slots + aid * dh + d0);
-      const unsigned w[4] = {v.x, v.y, v.z, v.w};
+      float v[VW];
+      load_bf16_vec<VW>((const unsigned short*)a.slots + aid * dh + d0, v);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const float lo = __uint_as_float(w[t] << 16), hi = __uint_as_float(w[t] & 0xffff0000u);
-        acc[2 * t] += g * lo;
-        acc[2 * t + 1] += g * hi;
-        dot += oth[2 * t] * lo + oth[2 * t + 1] * hi;
+      for (int t = 0; t < VW; ++t) {
+        acc[t] += g * v[t];
+        dot += oth[t] * v[t];
       }
     }
     if (a.dots) {
@@ -358,40 +367,47 @@ __global__ __launch_bounds__(256) void slot_combine_vec_kernel(SlotArgs a) {
     }
   }
   if (a.out && act) {
-    uint4 o;
-    o.x = pack_bf16x2(acc[0], acc[1]);
-    o.y = pack_bf16x2(acc[2], acc[3]);
-    o.z = pack_bf16x2(acc[4], acc[5]);
-    o.w = pack_bf16x2(acc[6], acc[7]);
-    *(uint4*)((unsigned short*)a.out + row) = o;
+    unsigned o[VW / 2];
+#pragma unroll
+    for (int t = 0; t < VW / 2; ++t) o[t] = pack_bf16x2(acc[2 * t], acc[2 * t + 1]);
+    if constexpr (VW == 8)
+      *(uint4*)((unsigned short*)a.out + row) = make_uint4(o[0], o[1], o[2], o[3]);
+    else
+      *(uint2*)((unsigned short*)a.out + row) = make_uint2(o[0], o[1]);
   }
   if (a.delta) {
     // from the values as stored (rounded to bf16): the attention backward multiplies those, and its
     // dS = P (dP - delta) cancels exactly only if both see the same numbers
     float dd = 0.f;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) dd += (a.out ? bf16_to_f32(f32_to_bf16(acc[t])) : acc[t]) * oth[t];
+    for (int t = 0; t < VW; ++t) dd += (a.out ? bf16_to_f32(f32_to_bf16(acc[t])) : acc[t]) * oth[t];
 #pragma unroll
     for (int o = TPR / 2; o > 0; o >>= 1) dd += __shfl_xor(dd, o, 64);
     if (valid && lane_in == 0) a.delta[pair] = dd;
   }
 }
 
+template <int VW>
+static void launch_slot_combine_vec(const SlotArgs& a, hipStream_t s) {
+  const long pairs = (long)a.N * a.H;
+  int tpr = 1;
+  while (tpr * VW < a.dh) tpr *= 2;   // threads per row, power of two
+  const unsigned g = (unsigned)((pairs * tpr + 255) / 256);
+  switch (tpr) {
+    case 1: slot_combine_vec_kernel<1, VW><<<g, 256, 0, s>>>(a); return;
+    case 2: slot_combine_vec_kernel<2, VW><<<g, 256, 0, s>>>(a); return;
+    case 4: slot_combine_vec_kernel<4, VW><<<g, 256, 0, s>>>(a); return;
+    case 8: slot_combine_vec_kernel<8, VW><<<g, 256, 0, s>>>(a); return;
+    case 16: slot_combine_vec_kernel<16, VW><<<g, 256, 0, s>>>(a); return;
+    case 32: slot_combine_vec_kernel<32, VW><<<g, 256, 0, s>>>(a); return;
+    default: slot_combine_vec_kernel<64, VW><<<g, 256, 0, s>>>(a); return;
+  }
+}
+
 void launch_slot_combine(const SlotArgs& a, int bf16, hipStream_t s) {
   long pairs = (long)a.N * a.H;
-  if (bf16 && a.dh % 8 == 0) {
-    int tpr = 1;
-    while (tpr * 8 < a.dh) tpr *= 2;   // threads per row, power of two
-    const unsigned g = (unsigned)((pairs * tpr + 255) / 256);
-    switch (tpr) {
-      case 1: slot_combine_vec_kernel<1><<<g, 256, 0, s>>>(a); return;
-      case 2: slot_combine_vec_kernel<2><<<g, 256, 0, s>>>(a); return;
-      case 4: slot_combine_vec_kernel<4><<<g, 256, 0, s>>>(a); return;
-      case 8: slot_combine_vec_kernel<8><<<g, 256, 0, s>>>(a); return;
-      case 16: slot_combine_vec_kernel<16><<<g, 256, 0, s>>>(a); return;
-      default: slot_combine_vec_kernel<32><<<g, 256, 0, s>>>(a); return;
-    }
-  }
+  if (bf16 && a.dh % 8 == 0) return launch_slot_combine_vec<8>(a, s);
+  if (bf16 && a.dh % 4 == 0) return launch_slot_combine_vec<4>(a, s);   // rows are 8-byte aligned
   unsigned g = (unsigned)((pairs + 3) / 4);
   if (bf16)
     slot_combine_kernel<bf16_t><<<g, 256, 0, s>>>(a);
