@@ -675,8 +675,8 @@ typedef WgCfg<2, 2, 2, 2, 1> WgSmall;   // 128 x 128
 typedef WgCfg<1, 4, 4, 2, 2> WgWide;    // 128 x 256, wave tile 128 x 64, two work-groups per CU
 typedef WgCfg<4, 1, 2, 4, 2> WgTall;    // 256 x 128, wave tile 64 x 128, two work-groups per CU
 
-// FULL: both feature counts are multiples of the tile, so every load is issued without a condition
-// (rows past the chunk repeat its last row and are zeroed on their way into LDS).  With the loads of a
+// FULL: every load is issued without a condition (rows past the chunk repeat its last row, feature
+// pieces past Ka / Kb repeat the last piece; both are zeroed on their way into LDS).  With the loads of a
 // step a fixed number, the wait before a step is staged names exactly the loads of that step and
 // leaves the younger ones of the next step in flight; a branch around a load makes it wait for all.
 // MODE 0 is the general form; 1..3 are FULL with the gate fixed at compile time (1 none, 2 on the rows
@@ -749,7 +749,8 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       const int c = tid + i * 256;
       const int rr = c / A_CPR, fc = (c % A_CPR) * VEC;
       if constexpr (FULL) {
-        ra[i] = *(const chunk_t*)(A + (long)row_of(ids[min(r0 + rr, rows - 1)], inv_a) * a.lda + (long)hh * a.a_hoff + i0 + fc);
+        ra[i] = *(const chunk_t*)(A + (long)row_of(ids[min(r0 + rr, rows - 1)], inv_a) * a.lda + (long)hh * a.a_hoff +
+                                  min(i0 + fc, a.Ka - VEC));
         continue;
       }
       ra[i] = zero_chunk<VEC>();
@@ -762,7 +763,8 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       const int c = tid + i * 256;
       const int rr = c / B_CPR, fc = (c % B_CPR) * VEC;
       if constexpr (FULL) {
-        rb[i] = *(const chunk_t*)(Bm + (long)row_of(ids[min(r0 + rr, rows - 1)], inv_b) * a.ldb + (long)hh * a.b_hoff + j0 + fc);
+        rb[i] = *(const chunk_t*)(Bm + (long)row_of(ids[min(r0 + rr, rows - 1)], inv_b) * a.ldb + (long)hh * a.b_hoff +
+                                  min(j0 + fc, a.Kb - VEC));
         continue;
       }
       rb[i] = zero_chunk<VEC>();
@@ -781,6 +783,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       const int c = tid + i * 256;
       chunk_t v = ra[i];   // a copy: the register sets themselves are only ever written by the loads
       if (MODE == 2 || (MODE == 0 && scaled && !a.scale_b)) v = scale_chunk(v, gsc[min(staged_r0 + c / A_CPR, Cfg::MAX_CHUNK - 1)]);
+      if constexpr (FULL) v = i0 + (c % A_CPR) * VEC < a.Ka ? v : zero_chunk<VEC>();   // pieces past the last feature
       *(chunk_t*)(&As[(c / A_CPR) * LDA + (c % A_CPR) * VEC]) = v;
     }
 #pragma unroll
@@ -788,7 +791,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
       const int c = tid + i * 256;
       chunk_t v = rb[i];
       if (MODE == 3 || (MODE == 0 && scaled && a.scale_b)) v = scale_chunk(v, gsc[min(staged_r0 + c / B_CPR, Cfg::MAX_CHUNK - 1)]);
-      if constexpr (FULL) v = staged_r0 + c / B_CPR < rows ? v : zero_chunk<VEC>();   // repeated rows count for nothing
+      if constexpr (FULL) v = staged_r0 + c / B_CPR < rows && j0 + (c % B_CPR) * VEC < a.Kb ? v : zero_chunk<VEC>();   // repeats count for nothing
       *(chunk_t*)(&Bs[(c / B_CPR) * LDB + (c % B_CPR) * VEC]) = v;
     }
   };
@@ -932,7 +935,7 @@ static void launch_wg(const WgradArgs& a, hipStream_t s) {
   const int group_rows = a.perm ? a.max_group_rows : a.M;
   dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads * a.E, ti * tj));
   const size_t lds = Cfg::lds_bytes();
-  const bool full = a.Ka % Cfg::BM == 0 && a.Kb % Cfg::BN == 0 && a.a_div == a.b_div;
+  const bool full = a.a_div == a.b_div && a.Ka >= VEC && a.Kb >= VEC;
   const int mode = !full ? 0 : (a.gate == nullptr ? 1 : (a.scale_b ? 3 : 2));
   auto kern = mode == 0 ? mfma_wgrad_kernel<Cfg, VEC, TAG, 0>
             : mode == 1 ? mfma_wgrad_kernel<Cfg, VEC, TAG, 1>
