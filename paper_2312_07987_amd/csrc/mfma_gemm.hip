@@ -956,17 +956,17 @@ static void launch_wg(const WgradArgs& a, hipStream_t s) {
 static int g_force_wshape = -1;   // experiments only
 void wg_force_shape(int shape) { g_force_wshape = shape; }
 
-template <int TAG>
+template <int TAG, int VEC = 8>
 static void launch_wg_tagged(const WgradArgs& a, hipStream_t s) {
   // wide outputs get the 128 x 256 tile, tall ones the 256 x 128 tile
   int shape = a.Kb >= 256 && a.Ka <= 128 ? 1 : (a.Ka >= 256 && a.Kb >= 64 ? 2 : 0);
   if (g_force_wshape >= 0) shape = g_force_wshape;
   if (shape == 1)
-    launch_wg<WgWide, 8, TAG>(a, s);
+    launch_wg<WgWide, VEC, TAG>(a, s);
   else if (shape == 2)
-    launch_wg<WgTall, 8, TAG>(a, s);
+    launch_wg<WgTall, VEC, TAG>(a, s);
   else
-    launch_wg<WgSmall, 8, TAG>(a, s);
+    launch_wg<WgSmall, VEC, TAG>(a, s);
 }
 
 void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s) {
@@ -980,7 +980,7 @@ void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s) {
       default: return launch_wg<WgSmall, 8, TAG_GENERIC>(a, s);
     }
   }
-  launch_wg<WgSmall, 4, TAG_GENERIC>(a, s);
+  launch_wg_tagged<TAG_GENERIC, 4>(a, s);
 }
 
 }  // namespace sh
