@@ -152,7 +152,8 @@ struct TileCfg {
   static constexpr int BM = WM * MI * 32, BN = WN * NJ * 32;
   static constexpr int LDA = BK + 8;        // A tile [BM][LDA], k contiguous
   static constexpr int LDB_NT = BK + 8;     // B tile [BN][LDB_NT] when k is contiguous in memory
-  static constexpr int LDB_NN = BN + 32;    // B tile [BK][LDB_NN] when n is contiguous in memory
+  // B tile [BK][LDB_NN] when n is contiguous in memory: rows 16 banks (mod 64) apart for the transposing reads
+  static constexpr int LDB_NN = BN == 96 ? 160 : BN + 32;
   static constexpr int A_ELEMS = BM * LDA;
   static constexpr int B_ELEMS = (BN * LDB_NT > BK * LDB_NN) ? BN * LDB_NT : BK * LDB_NN;
   static constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
@@ -165,6 +166,8 @@ struct TileCfg {
 typedef TileCfg<2, 2, 2, 2, 64, 1> CfgSmall;    // 128 x 128
 typedef TileCfg<2, 2, 2, 2, 80, 1> CfgSmall80;  // the same with an 80-wide K step: a reduction of 65..80 (a head width of 76
                                                 // or 80) then takes one step per segment instead of one and a mostly empty second
+typedef TileCfg<4, 1, 1, 3, 64, 1> CfgN96;      // 128 x 96, wave tile 32 x 96: outputs 65..96 wide (head widths 76, 80, 96)
+                                                // waste a fifth of a 96-wide tile instead of two fifths of a 128-wide one
 typedef TileCfg<2, 2, 1, 1, 64, 1> CfgRouter;   // 64 x 64: the router logits have <= 32 columns and want many work-groups
 typedef TileCfg<2, 2, 2, 4, 64, 1, 2> CfgWide;     // 128 x 256, wave tile 64 x 128, two work-groups per CU
 typedef TileCfg<2, 2, 4, 2, 64, 1, 2> CfgMed;   // 256 x 128, wave tile 128 x 64, two work-groups per CU
@@ -598,6 +601,8 @@ static void launch_tagged(const RowGemmArgs& a, hipStream_t s) {
     default:
       if (a.K > 64 && a.K <= 80)
         launch_cfg<CfgSmall80, 8, BNT, TAG, SEG>(a, s);
+      else if (a.Nc > 64 && a.Nc <= 96)
+        launch_cfg<CfgN96, 8, BNT, TAG, SEG>(a, s);
       else
         launch_cfg<CfgSmall, 8, BNT, TAG, SEG>(a, s);
       break;
@@ -617,6 +622,8 @@ template <int VEC, bool BNT>
 static void launch_generic(const RowGemmArgs& a, hipStream_t s) {
   if (a.K > 64 && a.K <= 80)
     launch_generic_cfg<CfgSmall80, VEC, BNT>(a, s);
+  else if (a.Nc > 64 && a.Nc <= 96)
+    launch_generic_cfg<CfgN96, VEC, BNT>(a, s);
   else
     launch_generic_cfg<CfgSmall, VEC, BNT>(a, s);
 }
