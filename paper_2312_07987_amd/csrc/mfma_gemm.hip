@@ -462,9 +462,9 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
     router_select_tile(a.rsel, h, zt, Nc, rs, ids, BM, zs, flist, nflag);
     return;
   }
-  if (VEC == 8 && a.mode == STORE_T) {
+  if (a.mode == STORE_T && Nc % VEC == 0) {
     // bf16 output: each wave stages 32 rows of its tile in LDS (the operand tiles are dead: the
-    // main loop ends with a barrier), then stores them as 16-byte pieces along the rows.  The
+    // main loop ends with a barrier), then stores them as 16-byte (8-byte) pieces along the rows.  The
     // staging area is the wave's own and a wave's LDS operations complete in order, so no
     // work-group barrier is needed here, only a fixed instruction order.
     constexpr int LDC = Cfg::LDC;
@@ -480,14 +480,15 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
         for (int j = 0; j < NJ; ++j) Cs[lr * LDC + j * 32 + r] = f32_to_bf16(acc[i][j][q] * sc);
       }
       __builtin_amdgcn_wave_barrier();
+      constexpr int PPR = NJ * 32 / VEC;   // pieces per staged row
 #pragma unroll
-      for (int u = 0; u < 32 * NJ * 4 / 64; ++u) {
+      for (int u = 0; u < 32 * PPR / 64; ++u) {
         const int c = lane + u * 64;
-        const int lr = c / (NJ * 4), cc = (c % (NJ * 4)) * 8;
+        const int lr = c / PPR, cc = (c % PPR) * VEC;
         const int id = ids[wm + i * 32 + lr];
         if (id < 0 || n0 + wn + cc >= Nc) continue;
         const long crow = (long)div_by(id, inv_cdiv) * a.ldc + (long)hh * a.c_hoff;
-        *(uint4*)((unsigned short*)Cb + crow + n0 + wn + cc) = *(const uint4*)(&Cs[lr * LDC + cc]);
+        *(chunk_t*)((unsigned short*)Cb + crow + n0 + wn + cc) = *(const chunk_t*)(&Cs[lr * LDC + cc]);
       }
     }
     return;
