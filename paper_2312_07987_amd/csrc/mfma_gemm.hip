@@ -462,7 +462,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
     router_select_tile(a.rsel, h, zt, Nc, rs, ids, BM, zs, flist, nflag);
     return;
   }
-  if (a.mode == STORE_T && Nc % VEC == 0) {
+  if (a.mode == STORE_T) {   // the host checks Nc % VEC == 0 for this mode
     // bf16 output: each wave stages 32 rows of its tile in LDS (the operand tiles are dead: the
     // main loop ends with a barrier), then stores them as 16-byte (8-byte) pieces along the rows.  The
     // staging area is the wave's own and a wave's LDS operations complete in order, so no
@@ -533,7 +533,7 @@ static int row_gemm_vec(const RowGemmArgs& a) {
     if (a.hsplit > 0 || a.seg_mode == 2) ok = ok && aligned_to(a.B2, bytes);
     if (a.seg_mode == 2 && a.nseg > 2 * a.seg_split) ok = ok && a.B3 && aligned_to(a.B3, bytes) && a.nseg <= 3 * a.seg_split;
     if (a.seg_mode == 2) ok = ok && a.a_sstride % vec == 0 && a.a_wstride % vec == 0 && a.b_sstride % vec == 0;
-    if (a.mode == STORE_T) ok = ok && aligned_to(a.C, bytes) && a.ldc % vec == 0 && a.c_hoff % vec == 0;
+    if (a.mode == STORE_T) ok = ok && aligned_to(a.C, bytes) && a.ldc % vec == 0 && a.c_hoff % vec == 0 && a.Nc % vec == 0;
     if (nt)
       ok = ok && a.sbn % vec == 0;
     else
