@@ -115,7 +115,7 @@ def dense_baseline(cfg, steps, warmup, few_heads=False):
     paper matches its dense baselines (Sec. 3.1): H*E heads whose d_head gives the same number of
     parameters, rounded up to a multiple of 8.  few_heads: the paper's other dense baseline, which
     keeps SwitchHead's H heads and widens them instead (E times the matched width, capped at the
-    256 the kernels take: 4 heads of 256 at c2, as in the paper's table of model sizes, App. A.3)."""
+    256 the kernels take: 4 heads of 256 at c2, as in the paper's table of model sizes, App. A.5 "Hyperparameters")."""
     from paper_2312_07987_amd.inputs import make_inputs
     from paper_2312_07987_amd.runner import DeviceLayer
     H, E, dh = cfg["nheads"], cfg["E"], cfg["d_head"]

@@ -19,8 +19,12 @@
  *     returns an error code, launches nothing and leaves every buffer untouched;
  *     switchhead_last_error() then gives a description (thread-local, static storage);
  *   - storage type of x, weights, y, dy, dx is shape->dtype (fp32 or bf16); arithmetic
- *     accumulates in fp32; router logits are evaluated in fp64 (see below); weight and
- *     bias gradients are always fp32;
+ *     accumulates in fp32; the routers' selection is that of the fp64 logits (see
+ *     switchhead_forward); weight and bias gradients are always fp32;
+ *   - alignment: x, y, dy, dx, the weight tensors and the workspace are read and written
+ *     with 16-byte vector accesses by the matrix-core kernels; with bf16 storage a tensor
+ *     pointer that is not 16-byte aligned makes the call take the plain kernels for the
+ *     whole layer (same results, slower);
  *   - two calls that share a workspace must not overlap in time.
  */
 #ifndef SWITCHHEAD_H
@@ -64,7 +68,7 @@ typedef struct {
                        K^h = sum_{e in E_S^h} s_S^h[e] x W_K^{h,e} (source-side selection),
                        Q^h = sum_{e in E_D^h} s_D^h[e] x W_Q^{h,e} (destination side)      */
   int32_t rope;     /* 1: rotary position embedding of queries and keys, as in the models of the
-                       paper's App. A.5 (method of Su et al.; square attention, no cache): the
+                       paper's App. A.4 "RoPE Positional Encodings" (method of Su et al.; square attention, no cache): the
                        element pair (2i, 2i+1) of every head's query and key at position t (index
                        in its sequence, from 0) turns by t * 10000^(-2i/d), d = the even part of
                        d_head; an odd last element stays.  0: no position term (Sec. 2.2 as
@@ -104,16 +108,24 @@ size_t switchhead_workspace_bytes(const sh_shape* shape);
  *                                            E == 1, k == 1; every gate is 1; Sec. 2.1)
  *   W_D  [d_model, nheads*E]                 destination-side router; NULL = shared
  *                                            selection, the destination side reuses the
- *                                            source side's choice and gates (Sec. 3.5)
+ *                                            source side's choice and gates (Sec. 3.6 "Shared Selection")
  *   b_S, b_D  fp32 [nheads*E] or NULL        logit bias added after the sum (not in the
  *                                            paper; used to skew the routing on purpose)
  *   y    [B, T, d_model]                     output, overwritten
  *
- * Selection: logits z = x W (+ b) are evaluated in fp64 with the sum taken over
- * i = 0..d_model-1 in that order; the k largest logits win, equal logits -> lower expert
- * index; slots are ordered by descending logit; gate = sigmoid(z) stored as fp32; gates
- * are not renormalised.  Per (side, head) the N*k assignments a = n*k + j (n = b*T + t)
- * are stably sorted by expert into `perm`, with `offsets[e]` = first position of expert e.
+ * Selection: the canonical logit is z = x W (+ b) in fp64, products summed over
+ * i = 0..d_model-1 in that order with one accumulator, bias last; the k largest logits
+ * win, equal logits -> lower expert index; slots are ordered by descending logit; gates
+ * are not renormalised.  fp32 storage evaluates exactly that sum.  bf16 storage on the
+ * matrix-core kernels is two-stage: fp32 matrix-core partial sums (64 terms each, added up
+ * in fp64) decide every choice whose margin exceeds a proven bound of their error; every
+ * other choice (and every exact tie) is re-evaluated in fp64, and where two of those
+ * fp64 logits are closer than the reordering error of a blocked fp64 sum, by the canonical
+ * sum itself - so the indices are always those of the canonical logits.  gate = sigmoid(z)
+ * stored as fp32 (on that two-stage path z is the first-stage logit where it decided:
+ * gates agree with the canonical ones to about 1e-6 relative).  Per (side, head) the
+ * N*k assignments a = n*k + j (n = b*T + t) are stably sorted by expert into `perm`, with
+ * `offsets[e]` = first position of expert e.
  */
 sh_status switchhead_forward(const sh_shape* shape,
                              const void* x, const void* W_Q, const void* W_K,
@@ -165,7 +177,7 @@ sh_status switchhead_backward(const sh_shape* shape,
  *   perm            int32 [2, nheads, N*k]       assignment ids sorted by expert (stable)
  *   expert_offsets  int32 [2, nheads, E+1]       exclusive scan of per-expert counts
  * With shared selection (or dense mode) side 1 repeats side 0.  (Sec. 2.2 defines the
- * sets E_S, E_D and scores; Sec. 3.5 names the sorting step that `perm` is the result of.)
+ * sets E_S, E_D and scores; Sec. 3.6 "Shared Selection" names the sorting step that `perm` is the result of.)
  */
 sh_status switchhead_get_routing(const sh_shape* shape,
                                  const void* workspace, size_t workspace_bytes,
@@ -178,7 +190,9 @@ sh_status switchhead_get_routing(const sh_shape* shape,
  * (device-to-device, asynchronous); any destination may be NULL.  For tests and debugging.
  *   Q, K, V, ctx  fp32 [N, nheads, d_head]   queries, keys, mixed values V^h (Sec. 2.2),
  *                                            attention read-out A^h V^h
- *   lse           fp32 [B, nheads, T]        natural-log sum of exp of the scaled logits
+ *   lse           fp32 [B, nheads, T_q]      natural-log sum of exp of the scaled logits
+ *                                            (T_q = T for square attention)
+ * With 0 < T_q < T, Q and ctx hold B*T_q rows packed at the front of their [N, ...] blocks.
  */
 sh_status switchhead_get_intermediates(const sh_shape* shape,
                                        const void* workspace, size_t workspace_bytes,

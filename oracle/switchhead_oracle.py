@@ -35,7 +35,7 @@ Readings where the paper is silent (all listed in the design notes of the reposi
   * causal mask: key u is visible to query t iff u <= t; masked logits are -inf;
   * no dropout, bias or normalisation inside the layer; no positional encoding unless
     `rope` is asked for: then queries and keys are rotated as in the rotary position
-    embedding the paper's App. A.5 models use (Su et al., RoFormer): element pair
+    embedding the paper's App. A.4 "RoPE Positional Encodings" models use (Su et al., RoFormer): element pair
     (2i, 2i+1) of every head's query and key at position t (index in its sequence, from 0)
     turns by the angle t * 10000^(-2i/d), d = the even part of d_head; an odd last element
     is left as it is.  The paper cites the method without restating it; the adjacent-pair
@@ -103,7 +103,7 @@ def routing_tables(idx, E):
       perm    int32 [N*k]  assignment ids sorted by expert, stable (ascending a inside an expert)
       offsets int32 [E+1]  exclusive scan of the per-expert counts
       inv     int32 [N*k]  inverse permutation: inv[perm[p]] = p
-    (the "sorting and top-k steps" mentioned in Sec. 3.5).
+    (the "sorting and top-k steps" mentioned in Sec. 3.6 "Shared Selection").
     """
     flat = np.asarray(idx).reshape(-1)
     perm = np.argsort(flat, kind="stable").astype(np.int32)
@@ -116,7 +116,7 @@ def routing_tables(idx, E):
 
 
 def rotary(P, pos, inverse=False):
-    """Rotary position embedding of query or key rows (App. A.5 of the paper, method of
+    """Rotary position embedding of query or key rows (App. A.4 "RoPE Positional Encodings" of the paper, method of
     Su et al.): P [..., n, d_head] with `pos` [n] the position of each row; the pair
     (P[2i], P[2i+1]) is turned by the angle pos * 10000^(-2i/d), d = 2*floor(d_head/2).
     `inverse` turns by the opposite angle (the transpose of the rotation: what the chain
@@ -160,7 +160,7 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
     destination-side selection.
     W_S, W_D [dm, H*E] (column h*E+e); b_S, b_D [H*E] or None.
     W_D None  -> shared selection: the destination side reuses the source side's choice
-                 (Sec. 3.5).
+                 (Sec. 3.6 "Shared Selection").
     W_S None  -> dense multi-head attention (requires E == 1; every gate is exactly 1;
                  Sec. 2.1, per-head-sum form of the output).
     T_q (None = T): only the last T_q positions of every sequence are queries; y is
@@ -214,7 +214,7 @@ def forward(x, W_Q, W_K, W_V, W_O, W_S, W_D=None, b_S=None, b_D=None, *, k, caus
                     if rows.size:
                         K[rows, h, :] += g_S[h, rows, j][:, None] * (x2[rows] @ W_K[h, e])
 
-    # rotary position embedding of queries and keys (App. A.5), position = index in the sequence
+    # rotary position embedding of queries and keys (App. A.4 "RoPE Positional Encodings"), position = index in the sequence
     if rope:
         pos, posq = np.tile(np.arange(T), B), np.tile(np.arange(T - Tq, T), B)
         for h in range(H):

@@ -245,7 +245,7 @@ void launch_zero4_f32(float* p0, size_t n0, float* p1, size_t n1, float* p2, siz
 void launch_cast_from_f32(const float* src, void* dst, size_t n, int bf16, hipStream_t s);
 void launch_cast_to_f32(const void* src, float* dst, size_t n, int bf16, hipStream_t s);
 // out[i] = sum_h part[h*hstride + i] (+ add32[i]) for bf16 part/out; n must be a multiple of 8
-// Rotary position embedding (App. A.5; Su et al.): tab [T][dh/2] of (cos, sin); apply turns the pairs
+// Rotary position embedding (App. A.4 "RoPE Positional Encodings"; Su et al.): tab [T][dh/2] of (cos, sin); apply turns the pairs
 // (2i, 2i+1) of every row of up to two [N, H, dh] tensors in place, position = n % T.
 void launch_rope_table(float2* tab, int T, int dh, hipStream_t s);
 // (T rows per sequence, the first of them at position pos0)

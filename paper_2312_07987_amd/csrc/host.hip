@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <initializer_list>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -204,6 +205,7 @@ struct Ctx {
   int Tq, Nq;   // queries per sequence and in all; Tq < T: only the last Tq positions are destinations
   bool rect;    // Tq < T
   bool dense, shared, qk_experts;
+  bool aligned = true;   // every tensor pointer of the call is 16-byte aligned (the matrix-core kernels need it)
   int n(int side) const { return side ? Nq : N; }   // tokens of the source (0) / destination (1) side
   template <typename T>
   T* p(size_t off) const {
@@ -252,7 +254,14 @@ sh_status check_launch(const char* what) {
   return SH_OK;
 }
 
-bool use_mfma(const Ctx& c) { return c.bf16 && g_family.load() == 0; }
+bool use_mfma(const Ctx& c) { return c.bf16 && c.aligned && g_family.load() == 0; }
+
+// the matrix-core kernels move 16-byte pieces: NULL counts as aligned
+bool all_aligned16(std::initializer_list<const void*> ps) {
+  for (const void* q : ps)
+    if (((uintptr_t)q & 15) != 0) return false;
+  return true;
+}
 
 void row_gemm(const Ctx& c, const RowGemmArgs& a) {
   if (use_mfma(c) && mfma_row_gemm_supported(a))
@@ -338,10 +347,14 @@ RowGemmArgs set_rows(const Ctx& c, int side) {
   return a;
 }
 
-bool sets_usable(const Ctx& c) {
-  return use_mfma(c) && count_sets(c.E, c.k) <= MAX_SETS && c.dm % 4 == 0 && c.dh % 4 == 0 &&
+// Whether the shape has expert-set tables at all.  Forward builds them whenever this holds, whichever
+// kernel family runs, so that a backward call under another family (or with differently aligned
+// pointers) never finds tables its forward call did not write.
+bool set_tables(const Ctx& c) {
+  return c.bf16 && count_sets(c.E, c.k) <= MAX_SETS && c.dm % 4 == 0 && c.dh % 4 == 0 &&
          ((size_t)c.N * c.dm) % 8 == 0 && ((size_t)c.Nq * c.dm) % 8 == 0;
 }
+bool sets_usable(const Ctx& c) { return use_mfma(c) && set_tables(c); }
 
 RowGemmArgs identity_rows(const Ctx& c, int heads, int side = 0) {
   RowGemmArgs a{};
@@ -425,15 +438,17 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
   if (r != SH_OK) return r;
   if (!x || !W_Q || !W_K || !W_V || !W_O || !y) return fail(SH_ERR_INVALID_ARG, "x, W_Q, W_K, W_V, W_O, y must not be NULL");
   if (c.dense && W_D) return fail(SH_ERR_INVALID_ARG, "W_D given without W_S");
+  c.aligned = all_aligned16({x, W_Q, W_K, W_V, W_O, W_S, W_D, y});
   const int N = c.N, H = c.H, E = c.E, k = c.k, dh = c.dh, dm = c.dm;
   const long hd = (long)H * dh;
 
-  // step 1: routers, top-k, expert-sorted permutation (and, where the expert-set path applies, the
-  // set-sorted one)
+  // step 1: routers, top-k, expert-sorted permutation (and, where the shape has them, the set-sorted
+  // one: `tables`; `sets` says whether this call's kernels use them)
+  const bool tables = set_tables(c);
   const bool sets = sets_usable(c);
   bool sets_sorted = false;
   SetSortArgs sa{};
-  if (sets) {
+  if (tables) {
     sa.idx = c.idx(0);
     sa.gate = c.gate(0);
     sa.setid = c.p<int>(c.L.setid);
@@ -488,7 +503,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
       ra.sides = 1;
       ra.bf16 = c.bf16;
       SetSortArgs s1 = sa;
-      if (sets) {
+      if (tables) {
         s1.idx = c.idx(side);
         s1.gate = c.gate(side);
         s1.setid = sa.setid + (size_t)side * H * N;
@@ -500,12 +515,12 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
         s1.N = n;
         s1.sides = 1;
       }
-      if (g_family.load() == 0 && router_hybrid_supported(ra)) {
-        if (sets) ra.sets = &s1;
+      if (use_mfma(c) && router_hybrid_supported(ra)) {
+        if (tables) ra.sets = &s1;
         launch_router_hybrid(ra, c.p<char>(c.L.rh), c.st);
       } else {
         launch_router(ra, c.st);
-        if (sets) launch_set_sort(s1, c.st);
+        if (tables) launch_set_sort(s1, c.st);
       }
     }
     sets_sorted = true;
@@ -531,8 +546,8 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     ra.k = k;
     ra.sides = c.shared ? 1 : 2;
     ra.bf16 = c.bf16;
-    if (g_family.load() == 0 && router_hybrid_supported(ra)) {
-      if (sets && !c.shared) {   // both sorts in the same three launches
+    if (use_mfma(c) && router_hybrid_supported(ra)) {
+      if (tables && !c.shared) {   // both sorts in the same three launches
         ra.sets = &sa;
         sets_sorted = true;
       }
@@ -550,7 +565,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     (void)hipMemcpyAsync(c.offsets(1), c.offsets(0), (size_t)H * (E + 1) * 4, hipMemcpyDeviceToDevice, c.st);
   }
 
-  if (sets && !sets_sorted) {
+  if (tables && !sets_sorted) {
     prof_mark(c.st, "fwd.set_sort");
     sa.idx = c.idx(0);
     sa.gate = c.gate(0);
@@ -642,7 +657,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     }
   }
 
-  // rotary position embedding of queries and keys (App. A.5)
+  // rotary position embedding of queries and keys (App. A.4 "RoPE Positional Encodings")
   if (shape->rope) {
     prof_mark(c.st, "fwd.rope");
     launch_rope_table(c.p<float2>(c.L.rope), shape->T, dh, c.st);
@@ -775,6 +790,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   if (r != SH_OK) return r;
   if (!x || !W_Q || !W_K || !W_V || !W_O || !dy || !dx || !dW_Q || !dW_K || !dW_V || !dW_O)
     return fail(SH_ERR_INVALID_ARG, "x, W_Q, W_K, W_V, W_O, dy, dx, dW_Q, dW_K, dW_V, dW_O must not be NULL");
+  c.aligned = all_aligned16({x, W_Q, W_K, W_V, W_O, W_S, W_D, dy, dx, dW_Q, dW_K, dW_V, dW_O, dW_S, dW_D});
   const int N = c.N, H = c.H, E = c.E, k = c.k, dh = c.dh, dm = c.dm;
   const long hd = (long)H * dh;
   const int chunk = wgrad_chunk((size_t)H * N * k, dm, dh);         // expert-sorted operands

@@ -9,10 +9,18 @@ namespace sh {
 // head's E logits in fp64 and redoes the selection.  Lane l sums the products of input features
 // 16 l .. 16 l + 15 (per 1024-feature slab) against the head's column vectors, the lanes' sums are added
 // by a butterfly, lane 0 adds the bias and selects.  zs: 64 doubles of LDS owned by the wave.
+//
+// The blocked sum is not the canonical one (one accumulator, i = 0 .. d_model-1 ascending, bias last), but
+// both are fp64 sums of the same exact products, so each lies within d_model * 2^-53 * sum|x_i w_i| of the
+// true value and the two differ by at most twice that.  `reorder` is an upper bound of that difference
+// (Cauchy-Schwarz on sum|x_i w_i|, with slack); any two logits of the head that the blocked sum puts
+// further apart than `reorder` are ordered the same way by the canonical sum.  If some pair is closer
+// (every exact tie is), lane 0 evaluates the canonical sum itself and selects from that, so the indices
+// are those of the canonical logits in every case.
 __device__ __forceinline__ void recheck_entry(const unsigned short* __restrict__ xrow, const unsigned short* __restrict__ wt0,
                                               const float* __restrict__ bh, double* __restrict__ zs, double* __restrict__ zout,
                                               int* __restrict__ idx_out, float* __restrict__ gate_out, int dm, int dmp, int E,
-                                              int k, int lane) {
+                                              int k, int lane, double reorder) {
   // eight experts at a time: the token's features are loaded once per slab and the eight columns'
   // loads are in flight together (one expert after the other pays one memory round trip each)
   for (int e0 = 0; e0 < E; e0 += 8) {
@@ -54,6 +62,18 @@ __device__ __forceinline__ void recheck_entry(const unsigned short* __restrict__
     }
   }
   if (lane == 0) {
+    bool close = false;
+    for (int e = 1; e < E; ++e)
+      for (int f = 0; f < e; ++f) close = close || !(fabs(zs[e] - zs[f]) > reorder);
+    if (close) {
+      for (int e = 0; e < E; ++e) {
+        const unsigned short* w = wt0 + (long)e * dmp;
+        double acc = 0.0;
+        for (int i = 0; i < dm; ++i)
+          acc = fma((double)__uint_as_float((unsigned)xrow[i] << 16), (double)__uint_as_float((unsigned)w[i] << 16), acc);
+        zs[e] = acc + (bh ? (double)bh[e] : 0.0);
+      }
+    }
     for (int e = 0; e < E; ++e) zout[e] = zs[e];
     unsigned long long sel = 0ull;
     for (int j = 0; j < k; ++j) {
@@ -133,8 +153,12 @@ __device__ __forceinline__ void router_select_tile(const RouterSelect& r, int si
       const int fl = it / H, h = it % H, n = ids[fl];
       const int sh_ = side * H + h;
       const long o = ((long)sh_ * N + n) * k;
+      float w2 = 0.f;
+      for (int e = 0; e < E; ++e) w2 = fmaxf(w2, r.wnorm2[(long)sh_ * E + e]);
+      // twice d_model * 2^-53 * |x| * max|w|, doubled again for the rounding of the norms themselves
+      const double reorder = 4.0 * (double)r.dm * 1.1102230246251565e-16 * (double)sqrtf(rs[fl]) * (double)sqrtf(w2);
       recheck_entry((const unsigned short*)r.x + (long)n * r.dm, r.Wt + ((long)side * HE + h * E) * r.dmp, b ? b + h * E : nullptr,
-                    zs[wave], r.Z + ((long)side * N + n) * HE + (long)h * E, r.idx + o, r.gate + o, r.dm, r.dmp, E, k, lane);
+                    zs[wave], r.Z + ((long)side * N + n) * HE + (long)h * E, r.idx + o, r.gate + o, r.dm, r.dmp, E, k, lane, reorder);
     }
     __syncthreads();
     if (threadIdx.x == 0) *nflag = 0;

@@ -1,6 +1,6 @@
 // Router of the SwitchHead layer (arXiv 2312.07987, Sec. 2.2: s = sigmoid(x W), argtopk)
 // and the expert-sorted permutation of the token->expert assignments (the "sorting and
-// top-k steps" of Sec. 3.5).
+// top-k steps" of Sec. 3.6 "Shared Selection").
 //
 //   router_logits  z = x W (+ b) in fp64, summed over i = 0..d_model-1 in that order with
 //                  one accumulator per logit, so the selection is a fixed function of the

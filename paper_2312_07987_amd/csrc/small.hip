@@ -104,7 +104,7 @@ void launch_sum_heads(const void* part, const float* add32, void* out, size_t n,
   if (n8) sum_heads_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, s>>>((const unsigned short*)part, add32, (unsigned short*)out, n8, hstride, H);
 }
 
-// ---- rotary position embedding of queries and keys (App. A.5 of the paper; method of Su et al.) ----
+// ---- rotary position embedding of queries and keys (App. A.4 "RoPE Positional Encodings" of the paper; method of Su et al.) ----
 // tab[t][i] = (cos, sin) of t * 10000^(-2i/d), d = 2*half: evaluated in fp64, stored in fp32
 __global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ tab, int T, int half) {
   const long id = (long)blockIdx.x * 256 + threadIdx.x;

@@ -1,7 +1,7 @@
 """Seeded synthetic inputs for the SwitchHead layer.
 
 This module holds no arithmetic of the method itself: it only draws Gaussian tensors of
-the shapes the paper trains with (hyper-parameter table of App. A.4) and rounds them to
+the shapes the paper trains with (hyper-parameter table of App. A.5 "Hyperparameters") and rounds them to
 the storage type.  Both the float64 oracle (through the tests) and the HIP path consume
 exactly the arrays produced here.
 

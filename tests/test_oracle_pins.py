@@ -537,7 +537,7 @@ def test_expert_qk_backward_matches_autograd_and_differences(shared):
 
 
 # --------------------------------------------------------------------------------------
-# rotary position embedding of queries and keys (App. A.5; method of Su et al.)
+# rotary position embedding of queries and keys (App. A.4 "RoPE Positional Encodings"; method of Su et al.)
 # --------------------------------------------------------------------------------------
 def test_rotary_closed_forms():
     # d_head = 2: theta_0 = 1, so (1, 0) at position t becomes (cos t, sin t)
