@@ -137,6 +137,30 @@ sh_status switchhead_forward(const sh_shape* shape,
                              void* hip_stream);
 
 /*
+ * Forward pass for callers that cannot allocate device memory (code under HIP graph capture,
+ * serving loops, harnesses that forbid hipMalloc): the same computation and the same kernels
+ * as switchhead_forward, with the workspace taken from a device array built into the library
+ * instead of a caller's buffer.  The call allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine) as long as the step profiler is off.
+ *   - limit: shapes with switchhead_workspace_bytes(shape) <= SWITCHHEAD_STATIC_WORKSPACE_BYTES;
+ *     a larger shape returns SH_ERR_WORKSPACE_TOO_SMALL before anything is launched;
+ *   - the array exists once per GPU from the first use of the library on it until the
+ *     process ends; the call uses the copy of the GPU that is current when it is made;
+ *   - every call on a GPU shares that GPU's array, which keeps the previous call's contents
+ *     (the forward pass clears what it needs cleared): calls that overlap in time on one GPU,
+ *     on whatever streams, race; the intermediates are not kept for a backward call.
+ * Arguments as for switchhead_forward, without the workspace.
+ */
+#define SWITCHHEAD_STATIC_WORKSPACE_BYTES (16u << 20)
+sh_status switchhead_forward_static(const sh_shape* shape,
+                                    const void* x, const void* W_Q, const void* W_K,
+                                    const void* W_V, const void* W_O,
+                                    const void* W_S, const void* W_D,
+                                    const float* b_S, const float* b_D,
+                                    void* y,
+                                    void* hip_stream);
+
+/*
  * Backward pass: the chain rule through the six steps of the forward pass (the paper
  * trains with automatic differentiation and prints no backward equations; App. A.2 only
  * notes that all intermediate results are stored).  The top-k choice is piecewise

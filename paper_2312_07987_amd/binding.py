@@ -15,7 +15,9 @@ LIB_PATH = os.path.join(HERE, "libswitchhead.so")
 SH_OK, SH_ERR_INVALID_ARG, SH_ERR_UNSUPPORTED, SH_ERR_WORKSPACE_TOO_SMALL, SH_ERR_HIP = range(5)
 SH_F32, SH_BF16 = 0, 1
 
-EXPORTS = ("switchhead_workspace_bytes", "switchhead_forward", "switchhead_backward",
+STATIC_WORKSPACE_BYTES = 16 << 20
+
+EXPORTS = ("switchhead_workspace_bytes", "switchhead_forward", "switchhead_forward_static", "switchhead_backward",
            "switchhead_get_routing", "switchhead_get_intermediates", "switchhead_last_error",
            "switchhead_set_kernel_family", "switchhead_version",
            "switchhead_profile_enable", "switchhead_profile_read")
@@ -52,6 +54,8 @@ def lib():
     L.switchhead_workspace_bytes.argtypes = [shp]
     L.switchhead_forward.restype = i32
     L.switchhead_forward.argtypes = [shp] + [vp] * 10 + [vp, sz, vp]
+    L.switchhead_forward_static.restype = i32
+    L.switchhead_forward_static.argtypes = [shp] + [vp] * 10 + [vp]
     L.switchhead_backward.restype = i32
     L.switchhead_backward.argtypes = [shp] + [vp] * 8 + [vp, sz] + [vp] * 9 + [vp]
     L.switchhead_get_routing.restype = i32
@@ -115,6 +119,11 @@ def switchhead_forward(shape, x, W_Q, W_K, W_V, W_O, W_S, W_D, b_S, b_D, y, work
                                     _ptr(W_S), _ptr(W_D), _ptr(b_S), _ptr(b_D), _ptr(y),
                                     _ptr(workspace), workspace.numel() * workspace.element_size(),
                                     _stream(stream)))
+
+
+def switchhead_forward_static(shape, x, W_Q, W_K, W_V, W_O, W_S, W_D, b_S, b_D, y, stream=None):
+    _check(lib().switchhead_forward_static(ctypes.byref(shape), _ptr(x), _ptr(W_Q), _ptr(W_K), _ptr(W_V), _ptr(W_O),
+                                           _ptr(W_S), _ptr(W_D), _ptr(b_S), _ptr(b_D), _ptr(y), _stream(stream)))
 
 
 def switchhead_backward(shape, x, W_Q, W_K, W_V, W_O, W_S, W_D, dy, workspace,

@@ -15,6 +15,11 @@
 
 using namespace sh;
 
+// Workspace of switchhead_forward_static: device memory that exists from the moment the code object is
+// loaded on a GPU until the process ends, one copy per GPU.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the address that call returns (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[SWITCHHEAD_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -779,6 +784,37 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
   }
   prof_mark(c.st, nullptr);
   return check_launch("switchhead_forward");
+}
+
+sh_status switchhead_forward_static(const sh_shape* shape, const void* x, const void* W_Q, const void* W_K,
+                                    const void* W_V, const void* W_O, const void* W_S, const void* W_D, const float* b_S,
+                                    const float* b_D, void* y, void* hip_stream) {
+  // the size test needs no GPU and comes first: a shape that does not fit touches nothing
+  sh_status r = check_shape(shape);
+  if (r != SH_OK) return r;
+  const size_t need = make_layout(shape).total;
+  if (need > (size_t)SWITCHHEAD_STATIC_WORKSPACE_BYTES)
+    return fail(SH_ERR_WORKSPACE_TOO_SMALL, "switchhead_forward_static: this shape needs %zu bytes of workspace, the built-in one has %zu",
+                need, (size_t)SWITCHHEAD_STATIC_WORKSPACE_BYTES);
+  // the array's device address on the current GPU, looked up once per GPU
+  static std::mutex mu;
+  static void* addr[64] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    return fail(SH_ERR_HIP, "switchhead_forward_static: no current device (or its index is above 63)");
+  void* ws = nullptr;
+  {
+    std::lock_guard<std::mutex> lk(mu);
+    if (!addr[dev]) {
+      void* q = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !q) return fail(SH_ERR_HIP, "switchhead_forward_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+      addr[dev] = q;
+    }
+    ws = addr[dev];
+  }
+  return switchhead_forward(shape, x, W_Q, W_K, W_V, W_O, W_S, W_D, b_S, b_D, y, ws, (size_t)SWITCHHEAD_STATIC_WORKSPACE_BYTES,
+                            hip_stream);
 }
 
 sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* W_Q, const void* W_K, const void* W_V,

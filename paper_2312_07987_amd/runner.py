@@ -48,6 +48,12 @@ class DeviceLayer:
         binding.switchhead_forward(self.shape, self.x, W["W_Q"], W["W_K"], W["W_V"], W["W_O"], W["W_S"], W["W_D"],
                                    self.b_S, self.b_D, self.y, self.ws, stream)
 
+    def forward_static(self, stream=None):
+        """The same forward pass on the library's built-in workspace (nothing of this object's `ws` is used)."""
+        W = self.W
+        binding.switchhead_forward_static(self.shape, self.x, W["W_Q"], W["W_K"], W["W_V"], W["W_O"], W["W_S"], W["W_D"],
+                                          self.b_S, self.b_D, self.y, stream)
+
     def backward(self, stream=None):
         W, dW = self.W, self.dW
         binding.switchhead_backward(self.shape, self.x, W["W_Q"], W["W_K"], W["W_V"], W["W_O"], W["W_S"], W["W_D"],

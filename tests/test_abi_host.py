@@ -72,6 +72,14 @@ def test_forward_rejects_bad_arguments_without_launching(lib):
     rc = lib.switchhead_forward(ctypes.byref(s), fake, fake, fake, fake, fake, None, None, None, None, fake,
                                 fake, sz(1 << 40), None)
     assert rc == binding.SH_ERR_INVALID_ARG and "dense" in binding.switchhead_last_error()
+    # the allocation-free forward: a shape whose workspace exceeds the built-in one is refused before any GPU call
+    big = binding.make_shape(32, 512, 1024, 4, 128, 5, 3, 1, "bf16")
+    assert binding.switchhead_workspace_bytes(big) > binding.STATIC_WORKSPACE_BYTES
+    rc = lib.switchhead_forward_static(ctypes.byref(big), fake, fake, fake, fake, fake, fake, fake, None, None, fake, None)
+    assert rc == binding.SH_ERR_WORKSPACE_TOO_SMALL and "built-in" in binding.switchhead_last_error()
+    bad = binding.make_shape(2, 64, 64, 2, 32, 4, 5, 1, "f32")
+    rc = lib.switchhead_forward_static(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, fake, None, None, fake, None)
+    assert rc == binding.SH_ERR_INVALID_ARG
     # backward: NULL dy
     rc = lib.switchhead_backward(ctypes.byref(s), fake, fake, fake, fake, fake, fake, fake, None,
                                  fake, sz(1 << 40), fake, fake, fake, fake, fake, None, None, None, None, None)
