@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswitchhead.so")
 OBJ = os.path.join(os.path.dirname(HERE), "_build")
-SOURCES = ["host.hip", "routing.hip", "small.hip", "simt.hip", "mfma_gemm.hip", "mfma_attn.hip"]
+SOURCES = ["host.hip", "routing.hip", "small.hip", "simt.hip", "mfma_gemm.hip", "mfma_pp.hip", "mfma_attn.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

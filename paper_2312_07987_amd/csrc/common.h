@@ -69,6 +69,17 @@ struct RouterSelect {
   int N, kstep, H, E, k, dm, dmp;
 };
 
+// One segment of a concatenated reduction with per-row gates (segment mode 3): the segment's A columns start at
+// A (rows lda apart, shared by all segments), its B matrix at B (strides sbk / sbn shared), and row n of A
+// is scaled by gtab[n * gld + gcol] before it is multiplied (gcol < 0: not scaled).
+struct SegDesc {
+  const void* A;
+  const void* B;
+  int gcol;
+  int pad_;
+};
+enum { MAX_SEGD = 40 };
+
 struct RowGemmArgs {
   const int* perm;
   const int* offsets;
@@ -107,6 +118,13 @@ struct RowGemmArgs {
   const float* segate;
   int seg_split;
   long a_sstride, a_wstride, b_sstride;
+  //  3  gated concatenation (token-ordered rows, M a multiple of 256): nseg segments of length K described by
+  //     segd[]; the expert projections whose experts sit on the reduction side (Sec. 2.2, the y equation, and
+  //     the value experts' input gradient) run over ALL experts of every head this way, an unselected expert
+  //     having gate 0, so that heads and experts are summed in one accumulator and the output is written once.
+  const float* gtab;
+  int gld;
+  SegDesc segd[MAX_SEGD];
 };
 
 // ----------------------------------------------------------------------------------------
@@ -224,6 +242,9 @@ bool router_hybrid_supported(const RouterArgs& a);
 void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s);
 void launch_dense_routing(int* idx, float* gate, int* perm, int* offsets, int N, int H, hipStream_t s);
 int router_blocks(int N);  // token blocks used by the histogram/scatter kernels
+// gtab[side][n][h*E+e] = gate of the selected experts, 0 elsewhere (idx, gate: [side][H][N][k], sides side_stride_in apart)
+void launch_gate_table(const int* idx, const float* gate, float* gtab, int N, int H, int E, int k, int sides, long side_stride_in,
+                       hipStream_t s);
 
 // Sorting of tokens by expert set (see routing.hip).  nsets = C(E,k) <= 128.
 struct SetSortArgs {
@@ -314,6 +335,9 @@ void launch_simt_attn_bwd(const AttnBwdArgs& a, int bf16, hipStream_t s);
 bool mfma_row_gemm_supported(const RowGemmArgs& a);
 int rg_kstep();  // terms summed in fp32 by one K step of the row GEMM
 void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s);
+// 256 x 256 tiles, eight waves in two alternating groups (mfma_pp.hip); launch_mfma_row_gemm routes to it
+bool pp_row_gemm_supported(const RowGemmArgs& a);
+void launch_pp_row_gemm(const RowGemmArgs& a, hipStream_t s);
 bool mfma_wgrad_supported(const WgradArgs& a);
 void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s);
 bool mfma_attn_supported(int T, int dh);

@@ -76,6 +76,7 @@ struct Layout {
   size_t xq, accq;   // fewer queries than keys only: the query tokens' rows of x; their fp32 share of dx
   size_t Z, blockcnt, acc32;                                       // forward scratch
   size_t setid, gset, gsort, setexp, setperm, setoff, setcnt, yh;
+  size_t gtab;                                                     // dense gate table [2][N][H*E] fp32 (gated-concatenation GEMMs)
   size_t wrt;                                                      // x^T dz of both routers [dm, dh] fp32 (fused with the Q/K weight gradient)
   size_t dR, wr3;                                                  // wide router dz rows [N, H*dh], routers packed [dm, dh]                 // expert-set path (bf16 only)
   size_t rh;                                                       // two-stage router scratch (bf16 only)
@@ -187,8 +188,9 @@ Layout make_layout(const sh_shape* s) {
   } else {
     L.setid = L.gset = L.gsort = L.setexp = L.setperm = L.setoff = L.setcnt = L.yh = 0;
   }
-  L.rh = L.wpart = 0;
+  L.rh = L.wpart = L.gtab = 0;
   if (s->dtype == SH_BF16) {
+    L.gtab = take(2 * N * H * E * 4);
     // groups x chunks-per-group x one expert matrix, fp32 (the dense Q/K pair counts as 2H groups)
     const size_t groups = H * E > 2 * H + 1 ? H * E : 2 * H + 1;   // expert Q/K banks: H * E groups each, one at a time
     const size_t ce = wgrad_chunk(H * N * k, dm, dh), cd = wgrad_chunk(2 * H * N, dm, dh);
@@ -360,6 +362,16 @@ bool set_tables(const Ctx& c) {
          ((size_t)c.N * c.dm) % 8 == 0 && ((size_t)c.Nq * c.dm) % 8 == 0;
 }
 bool sets_usable(const Ctx& c) { return use_mfma(c) && set_tables(c); }
+
+// Whether the projections whose experts sit on the reduction side (output experts; the value experts' input
+// gradient) run as ONE token-ordered GEMM over all E experts of every head, an unselected expert having gate 0:
+// heads and experts are then summed inside the accumulator and y / dx are written once, instead of one bf16
+// partial per head that another kernel adds up.  It multiplies E/k times the selected experts' work, so it is
+// taken where that factor is at most 2 (and the shape fills the 256 x 256 tiles); else the expert-set path.
+bool gated_concat(const Ctx& c) {
+  return use_mfma(c) && !c.rect && !c.qk_experts && c.dh % 64 == 0 && c.dm % 256 == 0 && c.N % 256 == 0 && c.N >= 2048 &&
+         c.H * c.E + 2 * c.H + 1 <= MAX_SEGD && c.E <= 2 * c.k;
+}
 
 RowGemmArgs identity_rows(const Ctx& c, int heads, int side = 0) {
   RowGemmArgs a{};
@@ -590,6 +602,12 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     launch_set_sort(sa, c.st);
   }
 
+  const bool gated = gated_concat(c);
+  if (gated && !c.dense) {
+    prof_mark(c.st, "fwd.gate_table");
+    launch_gate_table(c.idx(0), c.gate(0), c.p<float>(c.L.gtab), N, H, E, k, 2, (long)H * N * k, c.st);
+  }
+
   // step 2, all-expert form: queries mix the destination side's experts, keys the source side's,
   // each like the value projection of step 3 (per-slot rows, then the gate-weighted sum)
   if (c.qk_experts) {
@@ -727,9 +745,39 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
       launch_simt_attn_fwd(a, c.bf16, c.st);
   }
 
-  // step 5: output experts.  Expert-set path: per head one GEMM whose reduction runs over the
+  // step 5: output experts.  Gated concatenation: one GEMM over the H*E (head, expert) segments, rows scaled by
+  // the dense gate table, y written once.
+  bool y_done = false;
+  if (gated) {
+    RowGemmArgs a = identity_rows(c, 1, 1);
+    a.tag = TAG_O_EXPERTS;
+    a.seg_mode = 3;
+    a.nseg = H * E;
+    a.lda = hd;
+    a.sbk = dm;
+    a.sbn = 1;
+    a.C = y;
+    a.ldc = dm;
+    a.K = dh;
+    a.Nc = dm;
+    a.mode = STORE_T;
+    a.gtab = c.dense ? nullptr : c.p<float>(c.L.gtab) + (size_t)N * H * E;   // the destination side's gates
+    a.gld = H * E;
+    for (int s_ = 0; s_ < H * E; ++s_) {
+      a.segd[s_].A = c.p<bf16_t>(c.L.ctx) + (size_t)(s_ / E) * dh;
+      a.segd[s_].B = (const bf16_t*)W_O + (size_t)s_ * dh * dm;
+      a.segd[s_].gcol = c.dense ? -1 : s_;
+    }
+    if (pp_row_gemm_supported(a)) {
+      prof_mark(c.st, "fwd.o_experts");
+      launch_pp_row_gemm(a, c.st);
+      y_done = true;
+    }
+  }
+  // Expert-set path: per head one GEMM whose reduction runs over the
   // k gate-scaled copies of the token's read-out row, then the sum over heads.
-  if (sets) {
+  if (y_done) {
+  } else if (sets) {
     prof_mark(c.st, "fwd.o_experts");
     RowGemmArgs a = set_rows(c, 1);
     a.tag = TAG_O_EXPERTS;
@@ -1044,7 +1092,46 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   // launch moves behind the router backward kernel.
   const int HE_r = H * E, HEp_r = (HE_r + 7) / 8 * 8, sides_r = c.shared ? 1 : 2;
   const bool wide_dz = !c.dense && sides_r * HEp_r <= dh && (c.L.dR - c.L.dK) == (c.L.dK - c.L.dQ);
-  const bool fuse_router = wide_dz && sets && c.bf16 && use_mfma(c) && !c.qk_experts && !c.rect;
+  // All of dx as ONE token-ordered GEMM (gated concatenation, see gated_concat): the value experts' input gradient
+  // over all E experts of every head with the source side's dense gates, the 2H query / key segments and, where
+  // the routers' dz rows have the shape of a dQ row, the routers' segment; dx is written once, in bf16.
+  auto merged_dx_args = [&](bool with_router) {
+    RowGemmArgs a = identity_rows(c, 1);
+    a.tag = TAG_QK_DGRAD;
+    a.seg_mode = 3;
+    a.lda = hd;
+    a.sbk = 1;
+    a.sbn = dh;
+    a.C = dx;
+    a.ldc = dm;
+    a.K = dh;
+    a.Nc = dm;
+    a.mode = STORE_T;
+    a.gtab = c.dense ? nullptr : c.p<float>(c.L.gtab);   // the source side's gates
+    a.gld = H * E;
+    int n = 0;
+    for (int s_ = 0; s_ < H * E && n < MAX_SEGD; ++s_, ++n) {
+      a.segd[n].A = c.p<bf16_t>(c.L.dV) + (size_t)(s_ / E) * dh;
+      a.segd[n].B = (const bf16_t*)W_V + (size_t)s_ * dm * dh;
+      a.segd[n].gcol = c.dense ? -1 : s_;
+    }
+    for (int which = 0; which < 2; ++which)
+      for (int h_ = 0; h_ < H && n < MAX_SEGD; ++h_, ++n) {
+        a.segd[n].A = c.p<bf16_t>(which ? c.L.dK : c.L.dQ) + (size_t)h_ * dh;
+        a.segd[n].B = (const bf16_t*)(which ? W_K : W_Q) + (size_t)h_ * dm * dh;
+        a.segd[n].gcol = -1;
+      }
+    if (with_router && n < MAX_SEGD) {
+      a.segd[n].A = c.p<bf16_t>(c.L.dR);
+      a.segd[n].B = c.p<bf16_t>(c.L.wr3);
+      a.segd[n].gcol = -1;
+      ++n;
+    }
+    a.nseg = n;
+    return a;
+  };
+  const bool merged_dx = gated_concat(c) && (c.dense || wide_dz) && pp_row_gemm_supported(merged_dx_args(!c.dense));
+  const bool fuse_router = wide_dz && (sets || merged_dx) && c.bf16 && use_mfma(c) && !c.qk_experts && !c.rect;
   bool router_fused = false;
   // the routers' weight gradients ride along with the Q/K weight gradient under the same conditions,
   // if the three-set launch is one the matrix-core kernel takes (it has no other implementation)
@@ -1127,7 +1214,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       launch_fill_f32(dxacc, (size_t)N * dm, 0.f, c.st);
       acc_written = true;
     }
-  } else if (!fuse_router) {
+  } else if (!fuse_router && !merged_dx) {
     run_qk_dgrad(false);
   }
 
@@ -1178,6 +1265,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.gate_hstride = (long)c.n(side) * k;
     w.chunk = chunk;
     wgrad(c, w);
+    if (merged_dx) return;   // this projection's share of dx is part of the one GEMM that writes dx
     prof_mark(c.st, l_dgrad);
     const bool to_accq = c.rect && side == 1;   // rows of the query tokens: their own fp32 accumulator
     const bool sets = sets_path && !to_accq;
@@ -1361,7 +1449,13 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     launch_router_bwd(rb, c.bf16, c.st);
     const size_t esz = c.bf16 ? 2 : 4;
     const char* dz0 = c.p<char>(wide_dz ? c.L.dR : c.L.dz);
-    if (fuse_router) run_qk_dgrad(true);
+    if (fuse_router && merged_dx) {
+      prof_mark(c.st, "bwd.dx_gemm");
+      launch_pp_row_gemm(merged_dx_args(true), c.st);
+      router_fused = true;
+    } else if (fuse_router) {
+      run_qk_dgrad(true);
+    }
     if (fuse_router_w) {
       run_qk_wgrad(true);
       prof_mark(c.st, "bwd.router_wsplit");
@@ -1465,8 +1559,13 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
       }
     }
   }
-  prof_mark(c.st, "bwd.dx_cast");
-  if (sets)
+  if (merged_dx && c.dense) {
+    prof_mark(c.st, "bwd.dx_gemm");
+    launch_pp_row_gemm(merged_dx_args(false), c.st);
+  }
+  if (!merged_dx) prof_mark(c.st, "bwd.dx_cast");
+  if (merged_dx) {
+  } else if (sets)
     launch_sum_heads(c.p<void>(c.L.yh), acc_written ? dxacc : nullptr, dx, (size_t)N * dm, (size_t)N * dm,
                      yh_taken() + (router_partial ? 1 : 0), c.st);
   else if (c.bf16)

@@ -395,6 +395,26 @@ size_t router_hybrid_bytes(int N, int dm, int H, int E, size_t* off) {
   return o;
 }
 
+// Dense gate table for the gated-concatenation GEMMs: gtab[side][n][h*E + e] = the gate of expert e of head h
+// for token n if the token selected it (Sec. 2.2: e in E^h), else 0.  One thread per (side, head, token).
+__global__ __launch_bounds__(256) void gate_table_kernel(const int* __restrict__ idx, const float* __restrict__ gate,
+                                                         float* __restrict__ gtab, int N, int H, int E, int k, long side_stride_in,
+                                                         long side_stride_out) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  const int h = blockIdx.y, side = blockIdx.z;
+  if (n >= N) return;
+  float* out = gtab + side * side_stride_out + ((long)n * H + h) * E;
+  for (int e = 0; e < E; ++e) out[e] = 0.f;
+  const long o = side * side_stride_in + ((long)h * N + n) * k;
+  for (int j = 0; j < k; ++j) out[idx[o + j]] = gate[o + j];
+}
+
+void launch_gate_table(const int* idx, const float* gate, float* gtab, int N, int H, int E, int k, int sides, long side_stride_in,
+                       hipStream_t s) {
+  dim3 g((N + 255) / 256, H, sides);
+  gate_table_kernel<<<g, 256, 0, s>>>(idx, gate, gtab, N, H, E, k, side_stride_in, (long)N * H * E);
+}
+
 bool router_hybrid_supported(const RouterArgs& a) {
   return a.bf16 && a.dm % 4 == 0 && ((uintptr_t)a.x % 16) == 0 && a.H * a.E <= 32;
 }
