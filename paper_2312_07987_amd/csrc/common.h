@@ -233,6 +233,9 @@ struct RouterArgs {
   // if not NULL (and for as many sides), launch_router_hybrid also sorts the tokens by expert set,
   // sharing the passes of the expert sort; the caller then skips launch_set_sort
   const SetSortArgs* sets;
+  // if not NULL (launch_router_hybrid without `sets`, both sides routed on the same N tokens): the dense gate table
+  // [sides][N][H*E] is written along the histogram pass
+  float* gtab;
 };
 void launch_router(const RouterArgs& a, hipStream_t s);
 // bf16 storage: fp32 matrix-core logits with an fp64 re-evaluation of every decision that

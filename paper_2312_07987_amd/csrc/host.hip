@@ -127,6 +127,15 @@ sh_status check_shape(const sh_shape* s) {
   return SH_OK;
 }
 
+// Shapes whose output experts and input gradient run as gated concatenation (see gated_concat below): a property
+// of the shape alone, so that the workspace layout and both passes agree on it.  Such shapes have no expert-set tables.
+bool gated_shape(const sh_shape* s) {
+  const long long N = (long long)s->B * s->T;
+  const bool rect = s->T_q > 0 && s->T_q < s->T;
+  return s->dtype == SH_BF16 && !rect && !s->qk_experts && s->d_head % 64 == 0 && s->d_model % 256 == 0 && N % 256 == 0 &&
+         N >= 2048 && s->nheads * s->E + 2 * s->nheads + 1 <= MAX_SEGD && s->E <= 2 * s->k;
+}
+
 Layout make_layout(const sh_shape* s) {
   Layout L;
   const size_t N = (size_t)s->B * s->T, H = s->nheads, E = s->E, k = s->k, dh = s->d_head, dm = s->d_model;
@@ -173,7 +182,7 @@ Layout make_layout(const sh_shape* s) {
   L.delta = take(N * H * 4);
   L.dgate = take(2 * H * N * k * 4);
   L.dz = take(N * 2 * ((H * E + 7) / 8 * 8) * esz);   // each side padded to a multiple of 8 columns
-  if (s->dtype == SH_BF16 && count_sets(s->E, s->k) <= MAX_SETS) {
+  if (s->dtype == SH_BF16 && count_sets(s->E, s->k) <= MAX_SETS && !gated_shape(s)) {
     const size_t ns = count_sets(s->E, s->k);
     L.setid = take(2 * H * N * 4);
     L.gset = take(2 * H * N * k * 4);
@@ -357,8 +366,10 @@ RowGemmArgs set_rows(const Ctx& c, int side) {
 // Whether the shape has expert-set tables at all.  Forward builds them whenever this holds, whichever
 // kernel family runs, so that a backward call under another family (or with differently aligned
 // pointers) never finds tables its forward call did not write.
+// (shapes that run the gated concatenation sum heads and experts inside one accumulator: they have neither
+// expert-set tables nor per-head partial sums, in the workspace layout as here)
 bool set_tables(const Ctx& c) {
-  return c.bf16 && count_sets(c.E, c.k) <= MAX_SETS && c.dm % 4 == 0 && c.dh % 4 == 0 &&
+  return c.bf16 && !gated_shape(c.s) && count_sets(c.E, c.k) <= MAX_SETS && c.dm % 4 == 0 && c.dh % 4 == 0 &&
          ((size_t)c.N * c.dm) % 8 == 0 && ((size_t)c.Nq * c.dm) % 8 == 0;
 }
 bool sets_usable(const Ctx& c) { return use_mfma(c) && set_tables(c); }
@@ -368,10 +379,7 @@ bool sets_usable(const Ctx& c) { return use_mfma(c) && set_tables(c); }
 // heads and experts are then summed inside the accumulator and y / dx are written once, instead of one bf16
 // partial per head that another kernel adds up.  It multiplies E/k times the selected experts' work, so it is
 // taken where that factor is at most 2 (and the shape fills the 256 x 256 tiles); else the expert-set path.
-bool gated_concat(const Ctx& c) {
-  return use_mfma(c) && !c.rect && !c.qk_experts && c.dh % 64 == 0 && c.dm % 256 == 0 && c.N % 256 == 0 && c.N >= 2048 &&
-         c.H * c.E + 2 * c.H + 1 <= MAX_SEGD && c.E <= 2 * c.k;
-}
+bool gated_concat(const Ctx& c) { return use_mfma(c) && gated_shape(c.s); }
 
 RowGemmArgs identity_rows(const Ctx& c, int heads, int side = 0) {
   RowGemmArgs a{};
@@ -463,6 +471,11 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
   // one: `tables`; `sets` says whether this call's kernels use them)
   const bool tables = set_tables(c);
   const bool sets = sets_usable(c);
+  const bool gated = gated_concat(c);
+  bool gtab_done = false;
+  // the tables a path uses must have a place in the workspace layout (offset 0 is the top-k indices)
+  if ((tables && (c.L.setperm == 0 || c.L.setid == 0 || c.L.gsort == 0)) || (gated && c.L.gtab == 0) || (sets && c.L.yh == 0))
+    return fail(SH_ERR_UNSUPPORTED, "switchhead_forward: internal error, the workspace layout lacks a table this shape's path uses");
   bool sets_sorted = false;
   SetSortArgs sa{};
   if (tables) {
@@ -564,9 +577,12 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     ra.sides = c.shared ? 1 : 2;
     ra.bf16 = c.bf16;
     if (use_mfma(c) && router_hybrid_supported(ra)) {
-      if (tables && !c.shared) {   // both sorts in the same three launches
+      if (tables && !c.shared) {   // both sorts in the same launches
         ra.sets = &sa;
         sets_sorted = true;
+      } else if (gated && !c.shared && !c.dense) {   // the dense gate table rides along the histogram pass
+        ra.gtab = c.p<float>(c.L.gtab);
+        gtab_done = true;
       }
       launch_router_hybrid(ra, c.p<char>(c.L.rh), c.st);
     } else {
@@ -602,8 +618,7 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     launch_set_sort(sa, c.st);
   }
 
-  const bool gated = gated_concat(c);
-  if (gated && !c.dense) {
+  if (gated && !c.dense && !gtab_done) {
     prof_mark(c.st, "fwd.gate_table");
     launch_gate_table(c.idx(0), c.gate(0), c.p<float>(c.L.gtab), N, H, E, k, 2, (long)H * N * k, c.st);
   }
@@ -880,6 +895,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   const int chunk = wgrad_chunk((size_t)H * N * k, dm, dh);         // expert-sorted operands
   const int chunk_dense = wgrad_chunk((size_t)2 * H * N, dm, dh);   // fused dense Q/K
   const bool sets = sets_usable(c);
+  if ((sets && (c.L.yh == 0 || c.L.setperm == 0)) || (gated_concat(c) && c.L.gtab == 0))
+    return fail(SH_ERR_UNSUPPORTED, "switchhead_backward: internal error, the workspace layout lacks a table this shape's path uses");
   const int Nq = c.Nq;
   const void* xq = c.rect ? c.p<void>(c.L.xq) : x;   // the query tokens' rows of x (copied by forward)
 
@@ -915,6 +932,8 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     sa.k = k;
     sa.dh = dh;
     launch_slot_combine(sa, c.bf16, c.st);
+  }
+  {
     prof_mark(c.st, "bwd.o_wgrad");
     WgradArgs w{};
     w.tag = TAG_O_WGRAD;

@@ -47,7 +47,8 @@ typedef TileCfg<2, 2, 2, 2, 80, 1> CfgSmall80;  // the same with an 80-wide K st
                                                 // or 80) then takes one step per segment instead of one and a mostly empty second
 typedef TileCfg<4, 1, 1, 3, 64, 1> CfgN96;      // 128 x 96, wave tile 32 x 96: outputs 65..96 wide (head widths 76, 80, 96)
                                                 // waste a fifth of a 96-wide tile instead of two fifths of a 128-wide one
-typedef TileCfg<2, 2, 1, 1, 64, 1> CfgRouter;   // 64 x 64: the router logits have <= 32 columns and want many work-groups
+typedef TileCfg<2, 2, 1, 1, 64, 1> CfgRouter;   // 64 x 64: the router logits have <= 32 columns and want many work-groups (a K step of
+                                                // 256, four times the bytes per load round trip but one work-group per CU: 35 -> 50 us at c2)
 typedef TileCfg<2, 2, 2, 4, 64, 1, 2> CfgWide;     // 128 x 256, wave tile 64 x 128, two work-groups per CU
 typedef TileCfg<2, 2, 4, 2, 64, 1, 2> CfgMed;   // 256 x 128, wave tile 128 x 64, two work-groups per CU
 
@@ -263,16 +264,18 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
           if (!ACC64 || j == 0) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if constexpr (ACC64) {
-      // router logits: the fp32 accumulator only ever holds the sum of one K step
+      if constexpr (ACC64) {
+        // router logits: the fp32 accumulator only ever holds the sum of 64 terms
+        if ((kk & 63) == 48) {
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
+          for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          acc64[i][q] += (double)acc[i][0][q];
-          acc[i][0][q] = 0.f;
+            for (int q = 0; q < 16; ++q) {
+              acc64[i][q] += (double)acc[i][0][q];
+              acc[i][0][q] = 0.f;
+            }
         }
+      }
     }
   };
 
@@ -397,7 +400,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_row_gemm_kernel(RowGemmAr
   }
 }
 
-int rg_kstep() { return CfgSmall::BK; }
+int rg_kstep() { return 64; }   // terms the router logits GEMM sums in fp32 before it flushes to fp64
 
 static bool aligned_to(const void* p, size_t b) { return ((uintptr_t)p % b) == 0; }
 

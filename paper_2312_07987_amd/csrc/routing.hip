@@ -356,6 +356,36 @@ __global__ __launch_bounds__(RB) void hist_kernel(const int* __restrict__ idx, i
   hist_body(idx, blockcnt, N, E, k, nblk);
 }
 
+// The expert histogram, and along the same pass over the top-k tables the dense gate rows of the
+// gated-concatenation GEMMs: gtab[sh / H][n][(sh % H) * E + e] = the token's gate of expert e, 0 if not selected.
+__device__ __forceinline__ void gate_row_body(const int* __restrict__ idx, const float* __restrict__ gate,
+                                              float* __restrict__ gtab, int N, int H, int E, int k) {
+  const int sh_ = blockIdx.y, n = blockIdx.x * RB + threadIdx.x;
+  if (n >= N) return;
+  float* out = gtab + ((long)(sh_ / H) * N + n) * (H * E) + (long)(sh_ % H) * E;
+  const long o = ((long)sh_ * N + n) * k;
+  for (int e = 0; e < E; ++e) {
+    float g = 0.f;
+    for (int j = 0; j < k; ++j) g = idx[o + j] == e ? gate[o + j] : g;
+    out[e] = g;
+  }
+}
+__global__ __launch_bounds__(RB) void hist_gate_table_kernel(const int* __restrict__ idx, const float* __restrict__ gate,
+                                                             int* __restrict__ blockcnt, float* __restrict__ gtab, int N, int H,
+                                                             int E, int k, int nblk) {
+  hist_body(idx, blockcnt, N, E, k, nblk);
+  gate_row_body(idx, gate, gtab, N, H, E, k);
+}
+
+// expert scatter whose blocks scan the (small) count table for themselves: one launch instead of scan + scatter
+__global__ __launch_bounds__(RB) void scan_scatter1_kernel(const int* __restrict__ idx, const int* __restrict__ cnt,
+                                                           int* __restrict__ offsets, int* __restrict__ perm, int N, int E, int k,
+                                                           int nblk) {
+  __shared__ int sb[2 * 128 + 1];
+  block_bases(cnt, offsets, E, nblk, sb);
+  scatter_body<true>(idx, nullptr, perm, N, E, k, nblk, sb);
+}
+
 // Wp[side][i][c] = W_side[i][c] for c < HE, 0 for HE <= c < HEp (rows padded to 16 bytes)
 __global__ void pack_router_kernel(const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1, bf16_t* __restrict__ Wp,
                                    int dm, int HE, int HEp, int sides) {
@@ -662,7 +692,14 @@ void launch_router_hybrid(const RouterArgs& a, char* scratch, hipStream_t s) {
                                       a.k, t.nsets, nblk);
     return;
   }
-  hist_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.N, a.E, a.k, nblk);
+  if (a.gtab)
+    hist_gate_table_kernel<<<g2, RB, 0, s>>>(a.idx, a.gate, a.blockcnt, a.gtab, a.N, a.H, a.E, a.k, nblk);
+  else
+    hist_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.N, a.E, a.k, nblk);
+  if ((long)nblk * a.E <= 8192) {
+    scan_scatter1_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.offsets, a.perm, a.N, a.E, a.k, nblk);
+    return;
+  }
   scan_kernel<<<a.sides * a.H, 256, 0, s>>>(a.blockcnt, a.offsets, a.E, nblk);
   scatter_kernel<<<g2, RB, 0, s>>>(a.idx, a.blockcnt, a.perm, a.N, a.E, a.k, nblk);
 }
