@@ -53,6 +53,8 @@ def step_work(cfg):
         "bwd.o_dgrad": expert_q, "bwd.o_wgrad": expert_q, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
         "bwd.q_wgrad": proj_q, "bwd.k_wgrad": proj, "bwd.qk_wgrad": proj + proj_q, "bwd.q_dgrad": proj_q, "bwd.k_dgrad": proj,
         "bwd.router_wgrad": router, "bwd.router_dgrad": router,
+        # all of dx as one GEMM: the value experts' input gradient, the queries' and keys', the routers'
+        "bwd.dx_gemm": expert + proj + proj_q + router,
         # query / key expert banks (all-expert form): each step has the shape of its value-expert twin
         "fwd.q_experts": expert_q, "fwd.k_experts": expert, "bwd.q_wgrad_e": expert_q, "bwd.k_wgrad_e": expert,
         "bwd.q_dgrad_e": expert_q, "bwd.k_dgrad_e": expert,
@@ -68,6 +70,7 @@ def step_work(cfg):
         "bwd.zero_dw": 4 * (2 * H * dm * dh + 2 * H * E * dm * dh),
         "bwd.router": 4 * H * N * k * 4 + N * 2 * H * E * es,
         "fwd.rope": 4 * N * H * dh * es, "bwd.rope": 4 * N * H * dh * es,   # Q and K (dQ and dK) read and written
+        "fwd.gate_table": 2 * H * N * (k * 8 + E * 4),
     }
     return flops, alu, nbytes
 
@@ -75,9 +78,13 @@ def step_work(cfg):
 # Which kernel a profiled step launches, as a pattern on the kernel name rocprofv3 reports
 # (row GEMM: "..., <B transposed>, <tag>, <segment mode>>"; weight gradient: "..., <vec>, <tag>>").
 STEP_KERNEL = {
-    "fwd.qk_proj": r"mfma_row_gemm_kernel<.*, 1, 0(, \w+)?>", "fwd.v_experts": r"mfma_row_gemm_kernel<.*, 2, 0(, \w+)?>",
-    "fwd.o_experts": r"mfma_row_gemm_kernel<.*, 3, 1(, \w+)?>", "bwd.o_dgrad": r"mfma_row_gemm_kernel<.*, 4, 0(, \w+)?>",
-    "bwd.v_dgrad": r"mfma_row_gemm_kernel<.*, 5, 1(, \w+)?>", "bwd.qk_dgrad": r"mfma_row_gemm_kernel<.*, 6, 2(, \w+)?>",
+    "fwd.qk_proj": r"(pp_row_gemm_kernel<false, 1, 0>|mfma_row_gemm_kernel<.*, 1, 0(, \w+)?>)",
+    "fwd.v_experts": r"mfma_row_gemm_kernel<.*, 2, 0(, \w+)?>",
+    "fwd.o_experts": r"(pp_row_gemm_kernel<false, 3, [13]>|mfma_row_gemm_kernel<.*, 3, 1(, \w+)?>)",
+    "bwd.o_dgrad": r"mfma_row_gemm_kernel<.*, 4, 0(, \w+)?>",
+    "bwd.v_dgrad": r"(pp_row_gemm_kernel<true, 5, 1>|mfma_row_gemm_kernel<.*, 5, 1(, \w+)?>)",
+    "bwd.qk_dgrad": r"(pp_row_gemm_kernel<true, 6, 2>|mfma_row_gemm_kernel<.*, 6, 2(, \w+)?>)",
+    "bwd.dx_gemm": r"pp_row_gemm_kernel<true, 6, 3>",
     "bwd.o_wgrad": r"mfma_wgrad_kernel<.*, 8, 7(, \w+)?>", "bwd.v_wgrad": r"mfma_wgrad_kernel<.*, 8, 8(, \w+)?>",
     "bwd.qk_wgrad": r"mfma_wgrad_kernel<.*, 8, 9(, \w+)?>", "bwd.wgrad_reduce": r"wgrad_reduce_kernel",
     "fwd.attention": r"mfma_attn_fwd_kernel", "bwd.attention_dkv": r"mfma_attn_dkv_kernel",
@@ -86,21 +93,37 @@ STEP_KERNEL = {
 }
 
 
+def source_hash():
+    """sha256 (first 16 hex digits) of the kernel sources: a counter summary under profiles/ names the hash it was
+    taken with, and is only quoted while the sources are still those."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2312_07987_amd", "csrc")
+    for n in sorted(os.listdir(d)):
+        if n.endswith((".hip", ".h")):
+            h.update(open(os.path.join(d, n), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(cfg_name, step):
-    """HBM bytes per launch of the step's kernel from the committed rocprofv3 counter summary, or None."""
+    """(HBM bytes per launch of the step's kernel, note) from the committed rocprofv3 counter summary
+    profiles/traffic_<cfg>.json; (None, why) if there is none for this kernel or it was taken from other sources."""
     import re
     path = os.path.join(ROOT, "profiles", "traffic_%s.json" % cfg_name)
     pat = STEP_KERNEL.get(step)
     if pat is None or not os.path.exists(path):
-        return None
+        return None, "no counter summary for this step"
     t = json.load(open(path))
+    if t.get("source_sha16") != source_hash():
+        return None, "profiles/traffic_%s.json was taken from other kernel sources (%s)" % (cfg_name, t.get("source_sha16"))
     for name, v in t["kernels"].items():
         if re.search(pat, name):
-            return v["fetch_bytes"] + v["write_bytes"]
-    return None
+            return v["fetch_bytes"] + v["write_bytes"], "from the committed profiles/traffic_%s.json (same sources), not from this run" % cfg_name
+    return None, "kernel not in profiles/traffic_%s.json" % cfg_name
 
 
 def time_loop(fn, steps):
+    """Wall-clock milliseconds per call over exactly `steps` calls, bracketed by device synchronisation."""
     import torch
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -108,6 +131,56 @@ def time_loop(fn, steps):
         fn()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def event_median(fn, steps):
+    """Median over `steps` calls of the time between two HIP events recorded around each call on the launch
+    stream (torch's current stream, the one the binding hands to the library)."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in ev)
+    return ts[len(ts) // 2]
+
+
+def profile_steps(layer, steps):
+    """Per-step milliseconds from the HIP events the library records on the launch stream (separate pass, same work)."""
+    import torch
+    from paper_2312_07987_amd import binding
+    binding.switchhead_profile_enable(True)
+    for _ in range(steps):
+        layer.forward()
+        layer.backward()
+    torch.cuda.synchronize()
+    prof = binding.switchhead_profile_read()
+    binding.switchhead_profile_enable(False)
+    return {n: ms / c for n, (ms, c) in prof.items() if c}
+
+
+def roofline_of(cfg, per_step):
+    """The step with the largest time: its algorithmic work over its event-timed duration against the peak that bounds it."""
+    flops, alu, nbytes = step_work(cfg)
+    dom = max(per_step, key=per_step.get)
+    if dom in flops:
+        ach = flops[dom] / (per_step[dom] * 1e-3) / 1e12
+        mfma = cfg["dtype"] == "bf16"   # fp32 storage runs the plain fp32 kernels: vector ALU, not MFMA
+        peak = PEAK_BF16_TFLOPS if mfma else PEAK_FP32_VEC_TFLOPS
+        roof = {"bound": "mfma" if mfma else "alu", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak}
+    elif dom in alu:
+        ach = alu[dom] / (per_step[dom] * 1e-3) / 1e12
+        roof = {"bound": "alu", "achieved": ach, "peak": PEAK_FP64_VEC_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_FP64_VEC_TFLOPS}
+    else:
+        ach = nbytes.get(dom, 0) / (per_step[dom] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+    roof["traffic"], roof["traffic_note"] = measured_traffic(cfg["name"], dom)
+    roof["step"] = dom
+    roof["avg_ms"] = per_step[dom]
+    return roof
 
 
 def dense_baseline(cfg, steps, warmup, few_heads=False):
@@ -149,7 +222,8 @@ def workload_string(cfg):
 
 
 def other_workload(name, steps, warmup):
-    """Forward+backward and forward time of another paper-shaped workload (same protocol, fewer words)."""
+    """Forward+backward and forward time of another paper-shaped workload (same protocol), its per-step times and
+    the roofline entry of its dominant step."""
     from paper_2312_07987_amd.flops import layer_flops
     from paper_2312_07987_amd.inputs import config, make_inputs
     from paper_2312_07987_amd.runner import DeviceLayer
@@ -164,14 +238,21 @@ def other_workload(name, steps, warmup):
         step()
     ms_step = time_loop(step, steps)
     ms_fwd = time_loop(layer.forward, steps)
+    per_step = profile_steps(layer, steps)
+    flops = step_work(cfg)[0]
     N = cfg["B"] * cfg["T"]
     lf = layer_flops(cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"], bool(cfg["causal"]))
     out = {"workload": workload_string(cfg), "fwd_bwd_ms": ms_step, "fwd_ms": ms_fwd,
+           "fwd_bwd_ms_median_events": event_median(step, steps),
            "fwd_bwd_tokens_per_s": N / (ms_step * 1e-3), "fwd_tokens_per_s": N / (ms_fwd * 1e-3),
-           "fwd_bwd_tflops": lf["fwd_bwd"] / (ms_step * 1e-3) / 1e12}
-    if name == "c4":   # skewed routing: the per-expert token counts of one (side, head)
+           "fwd_bwd_tflops": lf["fwd_bwd"] / (ms_step * 1e-3) / 1e12,
+           "fwd_bwd_frac_of_bf16_peak": lf["fwd_bwd"] / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "roofline": roofline_of(cfg, per_step),
+           "step_ms": {n: round(v, 4) for n, v in sorted(per_step.items())},
+           "step_tflops": {n: round(flops[n] / (per_step[n] * 1e-3) / 1e12, 1) for n in sorted(per_step) if n in flops}}
+    if name == "c4":   # skewed routing: the per-expert token counts of every (side, head)
         counts = layer.routing()["offsets"]
-        out["expert_counts_side0_head0"] = [int(v) for v in (counts[0, 0, 1:] - counts[0, 0, :-1])]
+        out["expert_counts_side_head_expert"] = (counts[..., 1:] - counts[..., :-1]).tolist()
     return out
 
 
@@ -204,8 +285,8 @@ def cpu_baseline(cfg, budget_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c2", help="c1..c4 (c2 = the 262M-model-scale layer)")
     ap.add_argument("--qk-experts", action="store_true",
                     help="all four projections as expert mixtures (query and key banks like the value bank)")
@@ -263,33 +344,12 @@ def main():
     ms_step = time_loop(step, args.steps)
     ms_fwd = time_loop(layer.forward, args.steps)
 
-    # per-step times from HIP events on the launch stream (separate pass, same work)
-    binding.switchhead_profile_enable(True)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    prof = binding.switchhead_profile_read()
-    binding.switchhead_profile_enable(False)
-    per_step = {n: ms / c for n, (ms, c) in prof.items() if c}
-    flops, alu, nbytes = step_work(cfg)
-    dom = max(per_step, key=per_step.get)
-    if dom in flops:
-        ach = flops[dom] / (per_step[dom] * 1e-3) / 1e12
-        mfma = cfg["dtype"] == "bf16"   # fp32 storage runs the plain fp32 kernels: vector ALU, not MFMA
-        peak = PEAK_BF16_TFLOPS if mfma else PEAK_FP32_VEC_TFLOPS
-        roof = {"bound": "mfma" if mfma else "alu", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": ach / peak, "traffic": None}
-    elif dom in alu:
-        ach = alu[dom] / (per_step[dom] * 1e-3) / 1e12
-        roof = {"bound": "alu", "achieved": ach, "peak": PEAK_FP64_VEC_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_FP64_VEC_TFLOPS, "traffic": None}
-    else:
-        ach = nbytes.get(dom, 0) / (per_step[dom] * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None}
-    roof["step"] = dom
-    roof["avg_ms"] = per_step[dom]
-    roof["traffic"] = measured_traffic(cfg["name"], dom)
+    ms_step_median = event_median(step, args.steps)
+    ms_fwd_median = event_median(layer.forward, args.steps)
+    per_step = profile_steps(layer, args.steps)
+    flops = step_work(cfg)[0]
+    roof = roofline_of(cfg, per_step)
+    kept, scratch = binding.switchhead_workspace_parts(layer.shape)
 
     lf = layer_flops(cfg["B"], cfg["T"], cfg["d_model"], cfg["nheads"], cfg["d_head"], cfg["E"], cfg["k"],
                      bool(cfg["causal"]), qk_experts=bool(cfg.get("qk_experts")), T_q=cfg.get("T_q"))
@@ -306,6 +366,10 @@ def main():
         "roofline": roof,
         "extra": {
             "fwd_ms": ms_fwd, "fwd_tokens_per_s": N / (ms_fwd * 1e-3),
+            # medians of per-call HIP-event times on the launch stream (ms_per_step and fwd_ms are wall-clock means
+            # over exactly --steps calls between two device synchronisations)
+            "fwd_bwd_ms_median_events": ms_step_median, "fwd_ms_median_events": ms_fwd_median,
+            "workspace_bytes": {"kept_for_backward": kept, "scratch": scratch, "total": kept + scratch},
             "fwd_tflops": lf["fwd"] / (ms_fwd * 1e-3) / 1e12,
             "fwd_bwd_tflops": lf["fwd_bwd"] / (ms_step * 1e-3) / 1e12,
             "fwd_frac_of_bf16_peak": lf["fwd"] / (ms_fwd * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -316,7 +380,7 @@ def main():
             # weight-gradient launch, is not credited to that launch: "bwd.router_wsplit" only splits
             # its result)
             "step_tflops": {n: round(flops[n] / (per_step[n] * 1e-3) / 1e12, 1) for n in sorted(per_step) if n in flops},
-            "expert_counts_side0_head0": [int(v) for v in (counts[0, 0, 1:] - counts[0, 0, :-1])],
+            "expert_counts_side_head_expert": (counts[..., 1:] - counts[..., :-1]).tolist(),
         },
     }
     if not args.no_dense:

@@ -94,6 +94,20 @@ typedef struct {
  * invalid or unsupported (switchhead_last_error() says why).  Host-only, no GPU needed.  */
 size_t switchhead_workspace_bytes(const sh_shape* shape);
 
+/* The two parts of that workspace (their sum is switchhead_workspace_bytes; either pointer may be NULL):
+ *   kept     what forward leaves for backward, get_routing and get_intermediates: the routing tables
+ *            (top-k indices, gates, permutation, offsets; with bf16 storage the dense gate table or the
+ *            expert-set tables), Q, K, V, the attention read-out and its log-sum-exp, and the unscaled
+ *            value rows of every slot [nheads, N*k, d_head] that the gates' gradient reads - the one kept
+ *            buffer that grows with k (App. A.2 "Resource Usage of Different Methods" counts the k-weighted
+ *            average as free; storing the slot rows is this build's choice against a second pass over x);
+ *   scratch  buffers one pass writes and reads itself (fp32 accumulators, per-slot gradient rows,
+ *            dQ/dK/dV, weight-gradient partial sums, router scratch); their contents mean nothing
+ *            between calls.  The two parts are interleaved in the buffer: this call reports sizes, not
+ *            address ranges, and the whole workspace must stay untouched between forward and backward.
+ * Host-only.  Returns SH_OK or the shape's error. */
+sh_status switchhead_workspace_parts(const sh_shape* shape, size_t* kept_bytes, size_t* scratch_bytes);
+
 /*
  * Forward pass: Sec. 2.2, the equations for s_S, E_S, s_D, E_D, V^h and y.
  *

@@ -17,7 +17,7 @@ SH_F32, SH_BF16 = 0, 1
 
 STATIC_WORKSPACE_BYTES = 16 << 20
 
-EXPORTS = ("switchhead_workspace_bytes", "switchhead_forward", "switchhead_forward_static", "switchhead_backward",
+EXPORTS = ("switchhead_workspace_bytes", "switchhead_workspace_parts", "switchhead_forward", "switchhead_forward_static", "switchhead_backward",
            "switchhead_get_routing", "switchhead_get_intermediates", "switchhead_last_error",
            "switchhead_set_kernel_family", "switchhead_version",
            "switchhead_profile_enable", "switchhead_profile_read")
@@ -52,6 +52,8 @@ def lib():
     shp = ctypes.POINTER(sh_shape)
     L.switchhead_workspace_bytes.restype = sz
     L.switchhead_workspace_bytes.argtypes = [shp]
+    L.switchhead_workspace_parts.restype = i32
+    L.switchhead_workspace_parts.argtypes = [shp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     L.switchhead_forward.restype = i32
     L.switchhead_forward.argtypes = [shp] + [vp] * 10 + [vp, sz, vp]
     L.switchhead_forward_static.restype = i32
@@ -100,6 +102,13 @@ def _check(code):
 
 def switchhead_workspace_bytes(shape):
     return int(lib().switchhead_workspace_bytes(ctypes.byref(shape)))
+
+
+def switchhead_workspace_parts(shape):
+    """(kept bytes, scratch bytes) of the workspace of this shape."""
+    kept, scratch = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().switchhead_workspace_parts(ctypes.byref(shape), ctypes.byref(kept), ctypes.byref(scratch)))
+    return int(kept.value), int(scratch.value)
 
 
 def switchhead_last_error():

@@ -69,7 +69,7 @@ namespace {
 inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-  size_t total = 0;
+  size_t total = 0, kept = 0;   // kept: bytes forward leaves for backward; the rest is scratch of one pass
   size_t idx, gate, perm, offsets, Q, K, V, ctx, lse, pV;          // saved by forward
   size_t pQ, pK;                                                   // per-slot query / key rows (expert Q/K only)
   size_t rope;                                                     // (cos, sin) table [T][dh/2] (rotary embedding only)
@@ -140,33 +140,35 @@ Layout make_layout(const sh_shape* s) {
   Layout L;
   const size_t N = (size_t)s->B * s->T, H = s->nheads, E = s->E, k = s->k, dh = s->d_head, dm = s->d_model;
   const size_t esz = s->dtype == SH_BF16 ? 2 : 4;
-  size_t off = 0;
-  auto take = [&](size_t bytes) {
+  size_t off = 0, kept = 0;
+  // keep = true: forward leaves it for backward (and for get_routing / get_intermediates); false: scratch of one pass
+  auto take = [&](size_t bytes, bool keep = false) {
     size_t o = off;
     off += align_up(bytes);
+    if (keep) kept += align_up(bytes);
     return o;
   };
-  L.idx = take(2 * H * N * k * 4);
-  L.gate = take(2 * H * N * k * 4);
-  L.perm = take(2 * H * N * k * 4);
-  L.offsets = take(2 * H * (E + 1) * 4);
-  L.Q = take(N * H * dh * esz);
-  L.K = take(N * H * dh * esz);
-  L.V = take(N * H * dh * esz);
-  L.ctx = take(N * H * dh * esz);
-  L.lse = take(N * H * 4);
-  L.pV = take(H * N * k * dh * esz);
+  L.idx = take(2 * H * N * k * 4, true);
+  L.gate = take(2 * H * N * k * 4, true);
+  L.perm = take(2 * H * N * k * 4, true);
+  L.offsets = take(2 * H * (E + 1) * 4, true);
+  L.Q = take(N * H * dh * esz, true);
+  L.K = take(N * H * dh * esz, true);
+  L.V = take(N * H * dh * esz, true);
+  L.ctx = take(N * H * dh * esz, true);
+  L.lse = take(N * H * 4, true);
+  L.pV = take(H * N * k * dh * esz, true);   // the per-slot value rows: what the gates' gradient costs (the only kept part that grows with k)
   L.pQ = L.pK = 0;
-  L.rope = s->rope ? take((size_t)s->T * (dh / 2 > 0 ? dh / 2 : 1) * 8) : 0;
+  L.rope = s->rope ? take((size_t)s->T * (dh / 2 > 0 ? dh / 2 : 1) * 8, true) : 0;
   L.xq = L.accq = 0;
   if (s->T_q > 0 && s->T_q < s->T) {
     const size_t Nq = (size_t)s->B * s->T_q;
-    L.xq = take(Nq * dm * esz);
+    L.xq = take(Nq * dm * esz, true);
     L.accq = take(Nq * dm * 4);
   }
   if (s->qk_experts) {
-    L.pQ = take(H * N * k * dh * esz);
-    L.pK = take(H * N * k * dh * esz);
+    L.pQ = take(H * N * k * dh * esz, true);
+    L.pK = take(H * N * k * dh * esz, true);
   }
   L.Z = take(2 * N * H * E * 8);
   L.blockcnt = take(2 * H * (size_t)router_blocks((int)N) * E * 4);
@@ -186,10 +188,10 @@ Layout make_layout(const sh_shape* s) {
     const size_t ns = count_sets(s->E, s->k);
     L.setid = take(2 * H * N * 4);
     L.gset = take(2 * H * N * k * 4);
-    L.gsort = take(2 * H * N * k * 4);
-    L.setexp = take((size_t)MAX_SETS * 8 * 4);
-    L.setperm = take(2 * H * N * 4);
-    L.setoff = take(2 * H * (ns + 1) * 4);
+    L.gsort = take(2 * H * N * k * 4, true);
+    L.setexp = take((size_t)MAX_SETS * 8 * 4, true);
+    L.setperm = take(2 * H * N * 4, true);
+    L.setoff = take(2 * H * (ns + 1) * 4, true);
     L.setcnt = take(2 * H * (size_t)router_blocks((int)N) * ns * 4);
     // partial sums of dx (y in the forward pass): one per head from the value experts, then either one
     // for the dense Q/K pair or one per head for each of the query and key experts, one for the routers
@@ -199,7 +201,7 @@ Layout make_layout(const sh_shape* s) {
   }
   L.rh = L.wpart = L.gtab = 0;
   if (s->dtype == SH_BF16) {
-    L.gtab = take(2 * N * H * E * 4);
+    L.gtab = take(2 * N * H * E * 4, true);
     // groups x chunks-per-group x one expert matrix, fp32 (the dense Q/K pair counts as 2H groups)
     const size_t groups = H * E > 2 * H + 1 ? H * E : 2 * H + 1;   // expert Q/K banks: H * E groups each, one at a time
     const size_t ce = wgrad_chunk(H * N * k, dm, dh), cd = wgrad_chunk(2 * H * N, dm, dh);
@@ -209,6 +211,7 @@ Layout make_layout(const sh_shape* s) {
     L.rh = take(router_hybrid_bytes((int)N, (int)dm, (int)H, (int)E, o7));
   }
   L.total = off;
+  L.kept = kept;
   return L;
 }
 
@@ -453,6 +456,15 @@ int32_t switchhead_profile_read(char* labels, size_t labels_bytes, float* total_
 size_t switchhead_workspace_bytes(const sh_shape* shape) {
   if (check_shape(shape) != SH_OK) return 0;
   return make_layout(shape).total;
+}
+
+sh_status switchhead_workspace_parts(const sh_shape* shape, size_t* kept_bytes, size_t* scratch_bytes) {
+  sh_status r = check_shape(shape);
+  if (r != SH_OK) return r;
+  const Layout L = make_layout(shape);
+  if (kept_bytes) *kept_bytes = L.kept;
+  if (scratch_bytes) *scratch_bytes = L.total - L.kept;
+  return SH_OK;
 }
 
 sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W_Q, const void* W_K, const void* W_V,

@@ -50,6 +50,19 @@ def _avg(path, name):
     return {k: tot[k] / cnt[k] for k in tot}
 
 
+def _source_hash():
+    """sha256 (first 16 hex digits) of the kernel sources the figures were taken with; bench.py quotes a figure
+    only while the sources still hash to this."""
+    import hashlib
+    import os
+    d = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
+    h = hashlib.sha256()
+    for n in sorted(os.listdir(d)):
+        if n.endswith((".hip", ".h")):
+            h.update(open(os.path.join(d, n), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def traffic(fetch, write, copy_fetch, copy_write, copy_bytes=256 << 20):
     import json
     cf = _avg(copy_fetch, "FETCH_SIZE")
@@ -60,7 +73,7 @@ def traffic(fetch, write, copy_fetch, copy_write, copy_bytes=256 << 20):
     sw = copy_bytes / (cw[kw[0]] * 1024.0)
     f = _avg(fetch, "FETCH_SIZE")
     w = _avg(write, "WRITE_SIZE")
-    out = {"fetch_scale": sf, "write_scale": sw, "copy_kernel": kf[0], "kernels": {}}
+    out = {"source_sha16": _source_hash(), "fetch_scale": sf, "write_scale": sw, "copy_kernel": kf[0], "kernels": {}}
     for k in sorted(set(f) | set(w)):
         out["kernels"][k] = {"fetch_bytes": f.get(k, 0.0) * 1024.0 * sf, "write_bytes": w.get(k, 0.0) * 1024.0 * sw}
     print(json.dumps(out, indent=1))

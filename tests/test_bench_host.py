@@ -45,3 +45,15 @@ def test_step_table_adds_up_to_the_layer_totals(name, variant):
     assert abs(bwd - lf["bwd"]) <= 2   # integer halves of the attention count
     if not cfg.get("T_q"):
         assert flops["fwd.qk_proj"] == qk_fwd or cfg.get("qk_experts")
+    if not cfg.get("qk_experts"):
+        # the one GEMM that writes all of dx is priced as the three input gradients it replaces
+        assert flops["bwd.dx_gemm"] == flops["bwd.v_dgrad"] + flops["bwd.q_dgrad"] + flops["bwd.k_dgrad"] + flops["bwd.router_dgrad"]
+
+
+def test_counter_summaries_name_the_sources_they_were_taken_from():
+    """bench.py quotes roofline.traffic from profiles/traffic_<cfg>.json only while the kernel sources hash to the value
+    the summary names; both sides compute the hash the same way."""
+    from paper_2312_07987_amd import prof_summary
+    assert bench.source_hash() == prof_summary._source_hash()
+    value, note = bench.measured_traffic("c2", "no.such.step")
+    assert value is None and note
