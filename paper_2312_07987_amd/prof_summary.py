@@ -11,6 +11,7 @@
            utilisation per kernel from one `rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE` run
            = busy cycles (summed over the chip's 1024 SIMDs) / (active cycles, which rocprofv3 reports
            summed over the 8 XCDs, x 128 SIMDs per XCD).
+`traffic_table`: python -m paper_2312_07987_amd.prof_summary traffic_table <traffic.json>: that JSON as a table.
 `traffic`: HBM bytes per dispatch of every kernel as JSON, from a `--pmc FETCH_SIZE` and a
            `--pmc WRITE_SIZE` run of the benchmark (counters in KiB), each scaled by what the same
            counter reads for `bench.py --copy-only` (a 256 MiB device copy, 5 launches).
@@ -79,6 +80,16 @@ def traffic(fetch, write, copy_fetch, copy_write, copy_bytes=256 << 20):
     print(json.dumps(out, indent=1))
 
 
+def traffic_table(path):
+    """The figures of a traffic JSON (see `traffic`) as a table, MiB per launch, largest first."""
+    import json
+    t = json.load(open(path))
+    print("%-110s %10s %12s" % ("kernel", "read MiB", "written MiB"))
+    ks = t["kernels"]
+    for k in sorted(ks, key=lambda k: -(ks[k]["fetch_bytes"] + ks[k]["write_bytes"])):
+        print("%-110s %10.1f %12.1f" % (k[:110], ks[k]["fetch_bytes"] / 2 ** 20, ks[k]["write_bytes"] / 2 ** 20))
+
+
 def mfma(path, simds=128):
     busy = _avg(path, "SQ_VALU_MFMA_BUSY_CYCLES")
     act = _avg(path, "GRBM_GUI_ACTIVE")
@@ -96,5 +107,7 @@ if __name__ == "__main__":
         stats(sys.argv[2])
     elif sys.argv[1] == "traffic":
         traffic(*sys.argv[2:6])
+    elif sys.argv[1] == "traffic_table":
+        traffic_table(sys.argv[2])
     else:
         pmc(sys.argv[2], sys.argv[3])
