@@ -212,6 +212,11 @@ struct AttnBwdArgs {
   int B, T, H, dh, causal;
   float scale;
   int Tq;   // as in AttnArgs: Q, dO, dQ, lse, delta have Tq rows per sequence, K, V, dK, dV have T
+  // Optional scratch for the score gradient dS^T[b][h][key][query] (bf16, rows of ds_ld queries, ds_rows keys per
+  // (b, h); see attn_ds_dims).  If not NULL the dK / dV kernel leaves dS there and dQ = dS K is a plain product
+  // that reads it back instead of recomputing the scores and probabilities.
+  void* dSt;
+  int ds_ld, ds_rows;
 };
 
 // ----------------------------------------------------------------------------------------
@@ -344,6 +349,9 @@ void launch_pp_row_gemm(const RowGemmArgs& a, hipStream_t s);
 bool mfma_wgrad_supported(const WgradArgs& a);
 void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s);
 bool mfma_attn_supported(int T, int dh);
+// row length (queries) and rows (keys) per (sequence, head) of the score-gradient scratch of launch_mfma_attn_bwd;
+// false if this head width does not use it
+bool attn_ds_dims(int T, int Tq, int dh, int* ld, int* rows);
 void launch_mfma_attn_fwd(const AttnArgs& a, hipStream_t s);
 void launch_mfma_attn_bwd(const AttnBwdArgs& a, hipStream_t s);
 

@@ -82,6 +82,7 @@ struct Layout {
   size_t rh;                                                       // two-stage router scratch (bf16 only)
   size_t wpart;                                                    // per-chunk weight-gradient partial sums (bf16 only)
   size_t u, dctx, dQ, dK, dV, delta, dgate, dz;                    // backward scratch
+  size_t dst;                                                      // score gradient dS^T of the attention backward (0: recomputed)
 };
 
 // number of k-subsets of E experts, saturating at MAX_SETS + 1
@@ -209,6 +210,16 @@ Layout make_layout(const sh_shape* s) {
     L.wpart = take(groups * ((N + cmin - 1) / cmin) * dm * dh * 4);
     size_t o7[7];
     L.rh = take(router_hybrid_bytes((int)N, (int)dm, (int)H, (int)E, o7));
+  }
+  // The score gradient of the attention backward, [B][H][keys][queries] bf16: the dK / dV kernel leaves it for the
+  // dQ product instead of that kernel recomputing scores and probabilities.  Quadratic in T, so only up to 1 GiB.
+  L.dst = 0;
+  {
+    int ld = 0, rows = 0;
+    if (s->dtype == SH_BF16 && attn_ds_dims(s->T, s->T_q, (int)dh, &ld, &rows)) {
+      const size_t bytes = (size_t)s->B * H * rows * ld * 2;
+      if (bytes <= ((size_t)1 << 30)) L.dst = take(bytes);
+    }
   }
   L.total = off;
   L.kept = kept;
@@ -994,6 +1005,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.causal = shape->causal;
     a.scale = 1.0f / sqrtf((float)dh);
     a.Tq = c.Tq;
+    if (c.L.dst != 0 && attn_ds_dims(shape->T, c.Tq, dh, &a.ds_ld, &a.ds_rows)) a.dSt = c.p<void>(c.L.dst);
     if (use_mfma(c) && mfma_attn_supported(shape->T, dh))
       launch_mfma_attn_bwd(a, c.st);   // marks its two kernels itself
     else {

@@ -92,43 +92,52 @@ __device__ __forceinline__ bf16x8 global_frag(const unsigned short* row, int d, 
   return u.v;
 }
 
-// NROWS rows of `dh` bf16 (zero padded to DH columns and beyond `valid_rows`) on their way
-// from global memory to LDS: load() issues the global loads into registers, store() writes
-// them to one or two LDS tiles (the second with another row stride, for the transposing
-// reads).  Keeping the two apart lets the next tile travel while the current one is used.
+// NROWS rows of `dh` bf16 on their way from global memory to LDS: load() issues the global loads into registers,
+// store() writes them to one or two LDS tiles (the second with another row stride, for the transposing reads).
+// Keeping the two apart lets the next tile travel while the current one is used.
+// The loads carry no tests (a test per load costs a branch and a dozen instructions, a fifth of the forward kernel's
+// time at T = 4096): a row past `valid_rows` reads the last valid row instead, and a column past `dh` reads column 0
+// and is replaced by zero in store().  The kernels mask every product that involves a row past the end (the
+// probability of such a key or query is exactly zero), so what the repeated row holds does not matter as long as it
+// is finite; the padding columns enter the sums over d and must be zero.
 template <int DH, int VEC, int NROWS, int NT = 256>
 struct RowTile {
   static constexpr int CPR = DH / VEC, TOTAL = NROWS * CPR, NCH = (TOTAL + NT - 1) / NT;
   uint4 r[NCH];   // VEC == 4 uses .x/.y only
   __device__ __forceinline__ void load(const unsigned short* src, long row_stride, int valid_rows, int dh, int tid) {
+    if (valid_rows <= 0) {   // uniform: the tile lies past the end, nothing may be read
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) r[i] = make_uint4(0, 0, 0, 0);
+      return;
+    }
+    const int last = (valid_rows < NROWS ? valid_rows : NROWS) - 1;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + i * NT;
       const int row = c / CPR, d = (c % CPR) * VEC;
-      r[i] = make_uint4(0, 0, 0, 0);
-      if (c < TOTAL && row < valid_rows && d < dh) {
-        if constexpr (VEC == 8) {
-          r[i] = *(const uint4*)(src + (long)row * row_stride + d);
-        } else {
-          const uint2 v = *(const uint2*)(src + (long)row * row_stride + d);
-          r[i].x = v.x;
-          r[i].y = v.y;
-        }
+      const int rc = row < last ? row : last;
+      const char* p = (const char*)src + ((unsigned)rc * (unsigned)row_stride + (unsigned)(d < dh ? d : 0)) * 2u;
+      if constexpr (VEC == 8) {
+        r[i] = *(const uint4*)p;
+      } else {
+        const uint2 v = *(const uint2*)p;
+        r[i] = make_uint4(v.x, v.y, 0, 0);
       }
     }
   }
-  __device__ __forceinline__ void store(unsigned short* t0, int ld0, unsigned short* t1, int ld1, int tid) const {
+  __device__ __forceinline__ void store(unsigned short* t0, int ld0, unsigned short* t1, int ld1, int tid, int dh) const {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + i * NT;
       if (c >= TOTAL) continue;
       const int row = c / CPR, d = (c % CPR) * VEC;
+      const uint4 v = d < dh ? r[i] : make_uint4(0, 0, 0, 0);
       if constexpr (VEC == 8) {
-        *(uint4*)(t0 + row * ld0 + d) = r[i];
-        if (t1 != t0) *(uint4*)(t1 + row * ld1 + d) = r[i];
+        *(uint4*)(t0 + row * ld0 + d) = v;
+        if (t1 != t0) *(uint4*)(t1 + row * ld1 + d) = v;
       } else {
-        *(uint2*)(t0 + row * ld0 + d) = make_uint2(r[i].x, r[i].y);
-        if (t1 != t0) *(uint2*)(t1 + row * ld1 + d) = make_uint2(r[i].x, r[i].y);
+        *(uint2*)(t0 + row * ld0 + d) = make_uint2(v.x, v.y);
+        if (t1 != t0) *(uint2*)(t1 + row * ld1 + d) = make_uint2(v.x, v.y);
       }
     }
   }
@@ -158,23 +167,27 @@ __device__ __forceinline__ void attn_block_map(int L, int ntile, int P, int H, b
 }
 
 // ----------------------------------------------------------------------------------------
-// forward: block = 4 waves x 32 queries, key tiles of KT keys
+// forward: block = NG groups of 4 waves x 32 queries, key tiles of KT keys.  With NG = 2 the two wave groups work on the same
+// 128 queries and take alternate key tiles (the serial chain of a long row of tiles halves and every SIMD holds two waves of
+// the work-group throughout); their partial (o, m, l) are merged through LDS at the end.
 // ----------------------------------------------------------------------------------------
-template <int DH, int VEC>
-__global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_fwd_kernel(AttnArgs a) {
+template <int DH, int VEC, int NG = 1>
+__global__ __launch_bounds__(256 * NG, (DH <= 128 && NG == 1) ? 2 : 1) void mfma_attn_fwd_kernel(AttnArgs a) {
   constexpr int KT = DH > 128 ? 32 : 64;
   constexpr int LDK = DH + 8, LDV = ld_tr(DH);
   constexpr int NKD = DH / 16;   // k steps of Q K^T
   constexpr int NDB = DH / 32;   // 32-wide d blocks of the output
-  __shared__ __attribute__((aligned(16))) unsigned short Ks[KT * LDK];
-  __shared__ __attribute__((aligned(16))) unsigned short Vs[KT * LDV];
+  constexpr int TILE = KT * (LDK + LDV);   // one K tile and one V tile
+  __shared__ __attribute__((aligned(16))) unsigned short kv_[NG * 2 * TILE];   // per group: two buffers in turn
 
   int b, h, qt;
   const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
   const int off = T - Tq;   // position of query 0 among the keys
-  attn_block_map(blockIdx.x, (Tq + 127) / 128, a.B * a.H, a.H, a.causal, true, DH <= 128 ? 2 : 1, b, h, qt);
+  attn_block_map(blockIdx.x, (Tq + 127) / 128, a.B * a.H, a.H, a.causal, true, (DH <= 128 && NG == 1) ? 2 : 1, b, h, qt);
   const int q0 = qt * 128;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = NG > 1 ? threadIdx.x >> 8 : 0;     // wave group: key tiles grp, grp + NG, ...
+  const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
+  unsigned short* const kv = kv_ + grp * 2 * TILE;
   const int r = lane & 31, g = lane >> 5;
   const long rs = (long)a.H * dh;
   const long base = ((long)b * T) * rs + (long)h * dh;
@@ -200,81 +213,126 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_fwd_kernel(A
 
   const int kend = a.causal ? min(T, q0 + 128 + off) : T;
   RowTile<DH, VEC, KT> tk, tv;
-  tk.load(K, rs, T, dh, tid);
-  tv.load(V, rs, T, dh, tid);
-  for (int k0 = 0; k0 < kend; k0 += KT) {
-    __syncthreads();
-    tk.store(Ks, LDK, Ks, LDK, tid);
-    tv.store(Vs, LDV, Vs, LDV, tid);
-    __syncthreads();
-    if (k0 + KT < kend) {   // the next tile travels while this one is used
-      tk.load(K + (long)(k0 + KT) * rs, rs, T - k0 - KT, dh, tid);
-      tv.load(V + (long)(k0 + KT) * rs, rs, T - k0 - KT, dh, tid);
+  // (rows past the end of the sequence load as zeros: a group whose first tile lies past `kend` stages zeros once)
+  tk.load(K + (long)(grp * KT) * rs, rs, T - grp * KT, dh, tid);
+  tv.load(V + (long)(grp * KT) * rs, rs, T - grp * KT, dh, tid);
+  tk.store(kv, LDK, kv, LDK, tid, dh);
+  tv.store(kv + KT * LDK, LDV, kv + KT * LDK, LDV, tid, dh);
+  if ((grp + NG) * KT < kend) {
+    tk.load(K + (long)((grp + NG) * KT) * rs, rs, T - (grp + NG) * KT, dh, tid);
+    tv.load(V + (long)((grp + NG) * KT) * rs, rs, T - (grp + NG) * KT, dh, tid);
+  }
+  __syncthreads();
+  // One barrier per trip: while a tile is multiplied out of one buffer the next one (loaded a trip ago) is written into the
+  // other and the one after that starts to travel.  Every group makes the same number of trips (the barriers are the
+  // work-group's); a trip past `kend` only waits.
+  int cur = 0;
+  for (int kb0 = 0; kb0 < kend; kb0 += NG * KT, cur ^= 1) {
+    const int k0 = kb0 + grp * KT;
+    const unsigned short* Ks = kv + cur * TILE;
+    const unsigned short* Vs = Ks + KT * LDK;
+    if (k0 + NG * KT < kend) {
+      unsigned short* nk = kv + (cur ^ 1) * TILE;   // last read a trip ago, before the barrier that ended it
+      tk.store(nk, LDK, nk, LDK, tid, dh);
+      tv.store(nk + KT * LDK, LDV, nk + KT * LDK, LDV, tid, dh);
+      if (k0 + 2 * NG * KT < kend) {
+        tk.load(K + (long)(k0 + 2 * NG * KT) * rs, rs, T - k0 - 2 * NG * KT, dh, tid);
+        tv.load(V + (long)(k0 + 2 * NG * KT) * rs, rs, T - k0 - 2 * NG * KT, dh, tid);
+      }
     }
-    if (a.causal && k0 > wq_last) continue;      // wave-uniform: nothing visible to this wave
-
-    float s[KT / 32][16];
+    // wave-uniform: a trip past the end, or a tile with nothing visible to this wave
+    if (k0 < kend && !(a.causal && k0 > wq_last)) {
+      float s[KT / 32][16];
 #pragma unroll
-    for (int kb = 0; kb < KT / 32; ++kb) {
-      f32x16 acc;
+      for (int kb = 0; kb < KT / 32; ++kb) {
+        f32x16 acc;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < NKD; ++kk)
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Ks[(kb * 32 + r) * LDK + kk * 16 + 8 * g]), qf[kk], acc, 0,
-                                                      0, 0);
+        for (int kk = 0; kk < NKD; ++kk)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Ks[(kb * 32 + r) * LDK + kk * 16 + 8 * g]), qf[kk], acc, 0,
+                                                        0, 0);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[kb][i] = acc[i];
-    }
-    const bool need_mask = (a.causal && k0 + KT - 1 > q0 + wave * 32 + off) || (k0 + KT > T);
-    if (need_mask) {
+        for (int i = 0; i < 16; ++i) s[kb][i] = acc[i];
+      }
+      const bool need_mask = (a.causal && k0 + KT - 1 > q0 + wave * 32 + off) || (k0 + KT > T);
+      if (need_mask) {
+#pragma unroll
+        for (int kb = 0; kb < KT / 32; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key = k0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+            if (key >= T || (a.causal && key > qpos)) s[kb][i] = -INFINITY;
+          }
+      }
+      float mt = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < KT / 32; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mt = fmaxf(mt, s[kb][i]);
+      mt = fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc;  // sc > 0: the maximum of the scaled logits
+      const float mn = fmaxf(m, mt);
+      const bool moved = mn > m;                    // wave-uniform test below: most tiles move no maximum
+      const float alpha = moved ? __builtin_amdgcn_exp2f(m - mn) : 1.f;   // m = -inf on the first tile -> 0
+      m = mn;
+      float ps = 0.f;
 #pragma unroll
       for (int kb = 0; kb < KT / 32; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int key = k0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-          if (key >= T || (a.causal && key > qpos)) s[kb][i] = -INFINITY;
+          s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], sc, -mn));   // masked: -inf -> 0
+          ps += s[kb][i];
         }
-    }
-    float mt = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < KT / 32; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, s[kb][i]);
-    mt = fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc;  // sc > 0: the maximum of the scaled logits
-    const float mn = fmaxf(m, mt);
-    const bool moved = mn > m;                    // wave-uniform test below: most tiles move no maximum
-    const float alpha = moved ? __builtin_amdgcn_exp2f(m - mn) : 1.f;   // m = -inf on the first tile -> 0
-    m = mn;
-    float ps = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < KT / 32; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], sc, -mn));   // masked: -inf -> 0
-        ps += s[kb][i];
-      }
-    l = l * alpha + ps;
-    if (__ballot(moved)) {
-#pragma unroll
-      for (int d = 0; d < NDB; ++d)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
-    }
-
-#pragma unroll
-    for (int kb = 0; kb < KT / 32; ++kb)
-#pragma unroll
-      for (int st = 0; st < 2; ++st) {
-        const bf16x8 pb = pack8(&s[kb][8 * st]);
-        const int kb0 = kb * 32 + 16 * st + 4 * g;
+      l = l * alpha + ps;
+      if (__ballot(moved)) {
 #pragma unroll
         for (int d = 0; d < NDB; ++d)
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Vs, LDV, kb0, kb0 + 8, d * 32, lane), pb, o[d], 0, 0, 0);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
       }
+
+#pragma unroll
+      for (int kb = 0; kb < KT / 32; ++kb)
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+          const bf16x8 pb = pack8(&s[kb][8 * st]);
+          const int kr = kb * 32 + 16 * st + 4 * g;
+#pragma unroll
+          for (int d = 0; d < NDB; ++d)
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Vs, LDV, kr, kr + 8, d * 32, lane), pb, o[d], 0, 0, 0);
+        }
+    }
+    __syncthreads();
   }
 
   l += __shfl_xor(l, 32, 64);
+  if constexpr (NG > 1) {
+    // merge the groups' partial results: group 1 parks (o, m, l) in LDS (the key / value tiles are dead), group 0 of the
+    // same wave index and lane holds the same query and the same output elements
+    static_assert(NG == 2, "two groups");
+    static_assert(4 * (NDB * 16 + 2) * 64 * 4 <= NG * 2 * TILE * 2, "the parked accumulators fit in the tiles");
+    float* park = (float*)kv_ + (long)wave * (NDB * 16 + 2) * 64;
+    if (grp == 1) {
+#pragma unroll
+      for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) park[(d * 16 + i) * 64 + lane] = o[d][i];
+      park[(NDB * 16) * 64 + lane] = m;
+      park[(NDB * 16 + 1) * 64 + lane] = l;
+    }
+    __syncthreads();
+    if (grp == 1) return;
+    const float m1 = park[(NDB * 16) * 64 + lane], l1 = park[(NDB * 16 + 1) * 64 + lane];
+    const float mn = fmaxf(m, m1);
+    // a group that saw no key has m = -inf, l = 0, o = 0: its factor is exp2(-inf) = 0 (both empty cannot happen: key 0 is visible)
+    const float f0 = __builtin_amdgcn_exp2f(m - mn), f1 = __builtin_amdgcn_exp2f(m1 - mn);
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[d][i] = o[d][i] * f0 + park[(d * 16 + i) * 64 + lane] * f1;
+    l = l * f0 + l1 * f1;
+    m = mn;
+  }
   if (q < Tq) {
     const float inv = 1.f / l;
     unsigned short* O = (unsigned short*)a.O + qbase + (long)q * rs;
@@ -340,9 +398,14 @@ __device__ __forceinline__ void store_rows_T(unsigned short* dst, const f32x16* 
 //   S[q][key] = Q K^T,  P = exp(S - lse),  dP[q][key] = dO V^T,  dS = P (dP - delta)
 //   dV^T[d][key] += dO^T[d][q] P[q][key],   dK^T[d][key] += Q^T[d][q] dS[q][key]
 // ----------------------------------------------------------------------------------------
-template <int DH, int VEC, int NW>
+// queries per staged tile of the dK / dV kernel; 64 (half the barriers, two independent blocks per trip) measured 6 %
+// slower at T = 4096.  The dQ-from-dS kernel derives from it which part of a dS^T row was written.
+constexpr int DKV_QT = 32;
+
+template <int DH, int VEC, int NW, int QT>
 __global__ __launch_bounds__(64 * NW, DH <= 64 ? 2 : 1) void mfma_attn_dkv_kernel(AttnBwdArgs a) {
-  constexpr int QT = 32, KB = 32 * NW;   // keys per work-group
+  constexpr int KB = 32 * NW;    // keys per work-group
+  constexpr int NQ = QT / 32;   // 32-query blocks per staged tile: independent chains the scheduler can interleave
   constexpr bool SEP = DH <= 128;                       // separate tiles for the two read patterns
   constexpr int LDR = SEP ? DH + 8 : ld_tr(DH), LDT = ld_tr(DH);
   constexpr int NKD = DH / 16, NDB = DH / 32;
@@ -373,6 +436,8 @@ __global__ __launch_bounds__(64 * NW, DH <= 64 ? 2 : 1) void mfma_attn_dkv_kerne
   const float* delta = a.delta + (long)b * Tq * a.H + h;
 
   const int key = k0 + wave * 32 + r;
+  // this lane's row of dS^T (keys past T lie inside the padded row count and receive zeros)
+  unsigned short* dsrow = a.dSt ? (unsigned short*)a.dSt + (((long)b * a.H + h) * a.ds_rows + key) * a.ds_ld + 4 * g : nullptr;
   const int wk_first = k0 + wave * 32;
   bf16x8 kf[NKD], vf[NKD];
 #pragma unroll
@@ -408,8 +473,8 @@ __global__ __launch_bounds__(64 * NW, DH <= 64 ? 2 : 1) void mfma_attn_dkv_kerne
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
   for (int q0 = qbeg; q0 < Tq; q0 += QT) {
     __syncthreads();
-    tq.store(Qr, LDR, Qt, LDT, tid);
-    tg.store(Gr, LDR, Gt, LDT, tid);
+    tq.store(Qr, LDR, Qt, LDT, tid, dh);
+    tg.store(Gr, LDR, Gt, LDT, tid, dh);
     if (tid < QT) {
       lse_s[tid] = nlse * 1.44269504088896340736f;
       del_s[tid] = ndel;
@@ -419,57 +484,74 @@ __global__ __launch_bounds__(64 * NW, DH <= 64 ? 2 : 1) void mfma_attn_dkv_kerne
     // (a wave whose keys all follow the tile's queries multiplies zeros here: a branch around the
     //  body costs more registers than the diagonal tiles cost time)
 
-    f32x16 S, dP;
+    f32x16 S[NQ], dP[NQ];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) S[i] = dP[i] = 0.f;
+    for (int qb = 0; qb < NQ; ++qb)
 #pragma unroll
-    for (int kk = 0; kk < NKD; ++kk) {
-      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Qr[r * LDR + kk * 16 + 8 * g]), kf[kk], S, 0, 0, 0);
-      dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Gr[r * LDR + kk * 16 + 8 * g]), vf[kk], dP, 0, 0, 0);
-    }
-    float p[16], ds[16];
-    // wave-uniform: most tiles lie wholly inside the visible region and need no per-element test
-    const bool need_mask = q0 + QT > Tq || wk_first + 32 > T || (a.causal && wk_first + 31 > q0 + off);
-    if (need_mask) {
+      for (int i = 0; i < 16; ++i) S[qb][i] = dP[qb][i] = 0.f;
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const float4 L = *(const float4*)&lse_s[8 * i4 + 4 * g];
-        const float4 D = *(const float4*)&del_s[8 * i4 + 4 * g];
-        const float Lv[4] = {L.x, L.y, L.z, L.w}, Dv[4] = {D.x, D.y, D.z, D.w};
+    for (int kk = 0; kk < NKD; ++kk)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int i = 4 * i4 + t;
-          const int qq = q0 + 8 * i4 + 4 * g + t;
-          const bool vis = qq < Tq && key < T && (!a.causal || key <= qq + off);
-          // the mask caps the argument (exp2(-inf) = 0): nothing is left that a branch could skip
-          const float pv = __builtin_amdgcn_exp2f(fminf(fmaf(S[i], sc, -Lv[t]), vis ? INFINITY : -INFINITY));
-          p[i] = pv;
-          ds[i] = pv * (dP[i] - Dv[t]);
+      for (int qb = 0; qb < NQ; ++qb) {
+        S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Qr[(qb * 32 + r) * LDR + kk * 16 + 8 * g]), kf[kk], S[qb], 0, 0, 0);
+        dP[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Gr[(qb * 32 + r) * LDR + kk * 16 + 8 * g]), vf[kk], dP[qb], 0, 0, 0);
+      }
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+      const int qs = q0 + qb * 32;   // first query of this block
+      float p[16], ds[16];
+      // wave-uniform: most blocks lie wholly inside the visible region and need no per-element test
+      const bool need_mask = qs + 32 > Tq || wk_first + 32 > T || (a.causal && wk_first + 31 > qs + off);
+      if (need_mask) {
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const float4 L = *(const float4*)&lse_s[qb * 32 + 8 * i4 + 4 * g];
+          const float4 D = *(const float4*)&del_s[qb * 32 + 8 * i4 + 4 * g];
+          const float Lv[4] = {L.x, L.y, L.z, L.w}, Dv[4] = {D.x, D.y, D.z, D.w};
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const int i = 4 * i4 + t;
+            const int qq = qs + 8 * i4 + 4 * g + t;
+            const bool vis = qq < Tq && key < T && (!a.causal || key <= qq + off);
+            // the mask caps the argument (exp2(-inf) = 0): nothing is left that a branch could skip
+            const float pv = __builtin_amdgcn_exp2f(fminf(fmaf(S[qb][i], sc, -Lv[t]), vis ? INFINITY : -INFINITY));
+            p[i] = pv;
+            ds[i] = pv * (dP[qb][i] - Dv[t]);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const float4 L = *(const float4*)&lse_s[qb * 32 + 8 * i4 + 4 * g];
+          const float4 D = *(const float4*)&del_s[qb * 32 + 8 * i4 + 4 * g];
+          const float Lv[4] = {L.x, L.y, L.z, L.w}, Dv[4] = {D.x, D.y, D.z, D.w};
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const int i = 4 * i4 + t;
+            const float pv = __builtin_amdgcn_exp2f(fmaf(S[qb][i], sc, -Lv[t]));
+            p[i] = pv;
+            ds[i] = pv * (dP[qb][i] - Dv[t]);
+          }
         }
       }
-    } else {
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const float4 L = *(const float4*)&lse_s[8 * i4 + 4 * g];
-        const float4 D = *(const float4*)&del_s[8 * i4 + 4 * g];
-        const float Lv[4] = {L.x, L.y, L.z, L.w}, Dv[4] = {D.x, D.y, D.z, D.w};
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int i = 4 * i4 + t;
-          const float pv = __builtin_amdgcn_exp2f(fmaf(S[i], sc, -Lv[t]));
-          p[i] = pv;
-          ds[i] = pv * (dP[i] - Dv[t]);
+      for (int st = 0; st < 2; ++st) {
+        const bf16x8 pb = pack8(&p[8 * st]), db = pack8(&ds[8 * st]);
+        const int kb0 = qb * 32 + 16 * st + 4 * g;
+        if (dsrow) {   // uniform.  Elements 0..3 / 4..7 of db: queries qs + 16 st + 4 g + {0..3} / + 8 + {0..3} of this lane's key
+          union {
+            bf16x8 v;
+            uint2 h[2];
+          } u;
+          u.v = db;
+          *(uint2*)(dsrow + qs + 16 * st) = u.h[0];
+          *(uint2*)(dsrow + qs + 16 * st + 8) = u.h[1];
         }
-      }
-    }
 #pragma unroll
-    for (int st = 0; st < 2; ++st) {
-      const bf16x8 pb = pack8(&p[8 * st]), db = pack8(&ds[8 * st]);
-      const int kb0 = 16 * st + 4 * g;
-#pragma unroll
-      for (int d = 0; d < NDB; ++d) {
-        accV[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Gt, LDT, kb0, kb0 + 8, d * 32, lane), pb, accV[d], 0, 0, 0);
-        accK[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Qt, LDT, kb0, kb0 + 8, d * 32, lane), db, accK[d], 0, 0, 0);
+        for (int d = 0; d < NDB; ++d) {
+          accV[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Gt, LDT, kb0, kb0 + 8, d * 32, lane), pb, accV[d], 0, 0, 0);
+          accK[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Qt, LDT, kb0, kb0 + 8, d * 32, lane), db, accK[d], 0, 0, 0);
+        }
       }
     }
   }
@@ -535,8 +617,8 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
   tv.load(V, rs, T, dh, tid);
   for (int k0 = 0; k0 < kend; k0 += KT) {
     __syncthreads();
-    tk.store(Kr, LDR, Kt, LDT, tid);
-    tv.store(Vr, LDR, Vr, LDR, tid);
+    tk.store(Kr, LDR, Kt, LDT, tid, dh);
+    tv.store(Vr, LDR, Vr, LDR, tid, dh);
     __syncthreads();
     if (k0 + KT < kend) {
       tk.load(K + (long)(k0 + KT) * rs, rs, T - k0 - KT, dh, tid);
@@ -576,6 +658,111 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
   if (q < Tq) store_rows_T<NDB>((unsigned short*)a.dQ + qbase + (long)q * rs, acc, a.scale, g, dh);
 }
 
+// ----------------------------------------------------------------------------------------
+// backward, dQ from the stored score gradient: dQ[q][:] = scale * sum_key dS[q][key] K[key][:], a plain product.
+// block = 4 waves x 64 queries; key tiles of 64 rows of K and of dS^T (as the dK / dV kernel left it, [key][query])
+// are staged in LDS and both read with transposing loads:
+//   dQ^T[d][q] += K^T[d][key] dS^T[key][q]
+// The dK / dV work-group of 128 keys starting at kt0 wrote the queries from (max(kt0 - off, 0) / DKV_QT) * DKV_QT on (every
+// earlier query sees none of its keys); what lies before that in a row was never written and is replaced by zeros here.
+// ----------------------------------------------------------------------------------------
+template <int DH, int VEC, int QB>
+__global__ __launch_bounds__(256, QB == 128 ? 3 : 2) void mfma_attn_dq_ds_kernel(AttnBwdArgs a) {
+  constexpr int KT = 64;
+  constexpr int LDT = ld_tr(DH), LDD = ld_tr(QB);
+  constexpr int NDB = DH / 32;
+  // QB = 256: a wave owns 64 queries and all of d.  QB = 128 (twice the work-groups: short sequence counts fill the chip
+  // and heavy and light causal tiles pair up): 64 queries and half of d.
+  constexpr int DSPLIT = QB == 128 ? 2 : 1;
+  static_assert(NDB % DSPLIT == 0, "d blocks split evenly");
+  constexpr int ND = NDB / DSPLIT;
+  constexpr int CPRD = QB / 8, NP = KT * CPRD / 256, RSTEP = 256 / CPRD;   // dS^T tile: 16-byte pieces per row, per thread
+  __shared__ __attribute__((aligned(16))) unsigned short Kt[KT * LDT];
+  __shared__ __attribute__((aligned(16))) unsigned short Dt[KT * LDD];
+
+  int b, h, qt;
+  const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
+  const int off = T - Tq;
+  attn_block_map(blockIdx.x, (Tq + QB - 1) / QB, a.B * a.H, a.H, a.causal, true, QB == 128 ? 3 : 2, b, h, qt);
+  const int q0 = qt * QB;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int wq = (DSPLIT == 2 ? (wave & 1) : wave) * 64;   // the wave's first query in the tile
+  const int d0 = DSPLIT == 2 ? (wave >> 1) * ND : 0;       // its first d block
+  const long rs = (long)a.H * dh;
+  const unsigned short* K = (const unsigned short*)a.K + ((long)b * T) * rs + (long)h * dh;
+  const unsigned short* D = (const unsigned short*)a.dSt + (((long)b * a.H + h) * a.ds_rows) * a.ds_ld + q0;
+  const int wq_last = q0 + wq + 63 + off;
+
+  f32x16 acc[2][ND];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int d = 0; d < ND; ++d)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[j][d][i] = 0.f;
+
+  const int kend = a.causal ? min(T, q0 + QB + off) : T;
+  RowTile<DH, VEC, KT> tk;
+  // the dS^T tile: KT rows of QB queries: rows tid / CPRD + RSTEP i, queries 8 (tid % CPRD) ..
+  uint4 td[NP];
+  const int dq8 = (tid % CPRD) * 8;
+  const unsigned d_voff = (unsigned)(((tid / CPRD) * a.ds_ld + dq8) * 2);
+  auto load_d = [&](int k0) {
+    const char* p = (const char*)(D + (long)k0 * a.ds_ld);
+#pragma unroll
+    for (int i = 0; i < NP; ++i) td[i] = *(const uint4*)(p + (unsigned)(RSTEP * i * a.ds_ld * 2) + d_voff);
+  };
+  tk.load(K, rs, T, dh, tid);
+  load_d(0);
+  for (int k0 = 0; k0 < kend; k0 += KT) {
+    // first query the writer of this tile's keys covered
+    const int written = a.causal ? (max((k0 / 128) * 128 - off, 0) / DKV_QT) * DKV_QT : 0;
+    const bool keep = q0 + dq8 >= written;
+    __syncthreads();
+    tk.store(Kt, LDT, Kt, LDT, tid, dh);
+#pragma unroll
+    for (int i = 0; i < NP; ++i) *(uint4*)(&Dt[(tid / CPRD + RSTEP * i) * LDD + dq8]) = keep ? td[i] : make_uint4(0, 0, 0, 0);
+    __syncthreads();
+    if (k0 + KT < kend) {
+      tk.load(K + (long)(k0 + KT) * rs, rs, T - k0 - KT, dh, tid);
+      load_d(k0 + KT);
+    }
+    if (a.causal && k0 > wq_last) continue;   // wave-uniform: nothing visible to this wave's queries
+#pragma unroll
+    for (int kb = 0; kb < KT / 32; ++kb)
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        const int kr = kb * 32 + 16 * st + 4 * g;
+        bf16x8 bq[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bq[j] = trfrag(Dt, LDD, kr, kr + 8, wq + j * 32, lane);
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+          const bf16x8 ka = trfrag(Kt, LDT, kr, kr + 8, (d0 + d) * 32, lane);
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[j][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, bq[j], acc[j][d], 0, 0, 0);
+        }
+      }
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int q = q0 + wq + j * 32 + r;
+    if (q < Tq)
+      store_rows_T<ND>((unsigned short*)a.dQ + ((long)b * Tq) * rs + (long)h * dh + (long)q * rs + d0 * 32, acc[j], a.scale, g, dh - d0 * 32);
+  }
+}
+
+// The score-gradient scratch is used for head widths of 64 .. 128 (one work-group per CU otherwise, and the recomputing
+// kernel is already the smaller part there); rows of ds_ld = Tq rounded up to 256 queries, T rounded up to 128 keys per (b, h).
+bool attn_ds_dims(int T, int Tq, int dh, int* ld, int* rows) {
+  if (Tq <= 0) Tq = T;
+  if (dh < 64 || dh > 128 || dh % 8 != 0) return false;
+  *ld = (Tq + 255) / 256 * 256;
+  *rows = (T + 127) / 128 * 128;
+  return true;
+}
+
 static int attn_vec(int dh) { return dh % 8 == 0 ? 8 : (dh % 4 == 0 ? 4 : 0); }
 
 bool mfma_attn_supported(int T, int dh) { return T >= 1 && dh >= 4 && dh <= 256 && attn_vec(dh) != 0; }
@@ -584,6 +771,17 @@ template <int DH>
 static void launch_dh(const AttnArgs* f, const AttnBwdArgs* bw, hipStream_t s) {
   if (f) {
     dim3 g((((f->Tq > 0 ? f->Tq : f->T) + 127) / 128) * f->H * f->B);
+    // long sequences: two wave groups per work-group split the key tiles of a query tile between them
+    const bool split = DH <= 128 && DH >= 64 && f->T >= 1024;
+    if constexpr (DH <= 128 && DH >= 64) {
+      if (split) {
+        if (attn_vec(f->dh) == 8)
+          mfma_attn_fwd_kernel<DH, 8, 2><<<g, 512, 0, s>>>(*f);
+        else
+          mfma_attn_fwd_kernel<DH, 4, 2><<<g, 512, 0, s>>>(*f);
+        return;
+      }
+    }
     if (attn_vec(f->dh) == 8)
       mfma_attn_fwd_kernel<DH, 8><<<g, 256, 0, s>>>(*f);
     else
@@ -594,12 +792,28 @@ static void launch_dh(const AttnArgs* f, const AttnBwdArgs* bw, hipStream_t s) {
     // four waves (128 keys) per work-group; two-wave work-groups (two per CU where the registers
     // leave one wave per SIMD) were measured 7 % slower: the Q / dO staging doubles
     constexpr int NW = 4;
+    constexpr int QT = DKV_QT;
+    static_assert(32 * NW == 128, "the dQ-from-dS kernel and attn_ds_dims assume work-groups of 128 keys");
     dim3 gk(((bw->T + 32 * NW - 1) / (32 * NW)) * bw->H * bw->B);
     if (attn_vec(bw->dh) == 8)
-      mfma_attn_dkv_kernel<DH, 8, NW><<<gk, 64 * NW, 0, s>>>(*bw);
+      mfma_attn_dkv_kernel<DH, 8, NW, QT><<<gk, 64 * NW, 0, s>>>(*bw);
     else
-      mfma_attn_dkv_kernel<DH, 4, NW><<<gk, 64 * NW, 0, s>>>(*bw);
+      mfma_attn_dkv_kernel<DH, 4, NW, QT><<<gk, 64 * NW, 0, s>>>(*bw);
     prof_mark(s, "bwd.attention_dq");
+    if constexpr (DH >= 64 && DH <= 128) {
+      if (bw->dSt) {
+        const int tq = bw->Tq > 0 ? bw->Tq : bw->T;
+        // 128-query tiles (half of d per wave) unless 256-query tiles already give every CU three work-groups
+        constexpr bool can_split = (DH / 32) % 2 == 0;
+        const long big = (long)((tq + 255) / 256) * bw->H * bw->B;
+        if (can_split && big < 3 * 256) {
+          if constexpr (can_split) mfma_attn_dq_ds_kernel<DH, 8, 128><<<dim3(((tq + 127) / 128) * bw->H * bw->B), 256, 0, s>>>(*bw);
+        } else {
+          mfma_attn_dq_ds_kernel<DH, 8, 256><<<dim3((unsigned)big), 256, 0, s>>>(*bw);
+        }
+        return;
+      }
+    }
     if (attn_vec(bw->dh) == 8)
       mfma_attn_dq_kernel<DH, 8><<<g, 256, 0, s>>>(*bw);
     else

@@ -226,6 +226,17 @@ def test_bf16_fewer_queries_than_keys(family):
     run_case(small("c2", B=2, T=260, d_model=256, nheads=2, T_q=77, causal=0), family=family, shared=True, seed=62)
 
 
+@pytest.mark.parametrize("family", [0, 1])
+def test_bf16_long_ragged_sequences(family):
+    """Sequences past 1024 positions (two wave groups share a query tile's key tiles in the forward kernel) whose lengths
+    are no multiple of any tile, with and without the causal mask, and with a cached context whose offset is odd: the
+    last key tile repeats its last row instead of zeros, and the score gradient kept for the dQ product has ragged
+    rows and a region the dK / dV kernel never writes."""
+    run_case(small("c2", B=1, T=1100, d_model=256, nheads=2, d_head=128), family=family, seed=64)
+    run_case(small("c2", B=1, T=1337, d_model=256, nheads=2, d_head=64, T_q=901), family=family, seed=65)
+    run_case(small("c2", B=2, T=1030, d_model=256, nheads=1, d_head=96, causal=0), family=family, seed=66)
+
+
 def test_full_config_cached_context():
     """The paper's main setting at c2's sizes: a context twice the current chunk (T = 2 * 512 keys, 512
     queries per sequence), in the launch configuration bench.py times."""

@@ -1,6 +1,6 @@
 """Register budgets of the hot kernels, read from the compiler's own summary (hipcc -S, no GPU needed).
 The expert-gathered row GEMMs run three work-groups per CU (at most 168 registers), the dense-row and
-weight-gradient tiles and the forward / dQ attention kernels two (at most 256), and none of them may
+weight-gradient tiles, the ping-pong GEMM's waves and the forward / dQ attention kernels two per SIMD (at most 256), and none of them may
 spill to scratch memory: a few registers more in a shared template silently cost a work-group per CU."""
 import os
 import re
@@ -47,10 +47,30 @@ def test_row_gemm_and_weight_gradient_budgets(tmp_path):
 
 def test_attention_budgets(tmp_path):
     t = kernel_table("mfma_attn.hip", tmp_path)
+    seen = 0
     for k, (vgpr, scratch) in t.items():
-        if "mfma_attn_fwd_kernel<128, 8>" in k or "mfma_attn_fwd_kernel<64, 8>" in k:
+        if "mfma_attn_fwd_kernel<128, 8, " in k or "mfma_attn_fwd_kernel<64, 8, " in k:   # one or two wave groups
             assert vgpr <= 256 and scratch == 0, (k, vgpr, scratch)
+            seen += 1
         if "mfma_attn_dq_kernel<128, 8>" in k:
             assert vgpr <= 256 and scratch <= 32, (k, vgpr, scratch)   # five spilled dwords, outside the products
+            seen += 1
+        if "mfma_attn_dq_ds_kernel<128, 8, 128>" in k or "mfma_attn_dq_ds_kernel<64, 8, 128>" in k:
+            assert vgpr <= 168 and scratch == 0, (k, vgpr, scratch)    # three work-groups per CU
+            seen += 1
+        if "mfma_attn_dq_ds_kernel<" in k and ", 256>" in k:
+            assert vgpr <= 256 and scratch == 0, (k, vgpr, scratch)
+            seen += 1
         if "mfma_attn_dkv_kernel<128, 8" in k or "mfma_attn_dkv_kernel<96," in k:
             assert scratch == 0, (k, vgpr, scratch)
+            seen += 1
+    assert seen >= 12, seen
+
+
+def test_ping_pong_gemm_budgets(tmp_path):
+    # eight waves, one work-group per CU: two waves per SIMD leave 256 registers each
+    t = kernel_table("mfma_pp.hip", tmp_path)
+    kernels = [k for k in t if "pp_row_gemm_kernel<" in k]
+    assert len(kernels) >= 6
+    for k in kernels:
+        assert t[k][0] <= 256 and t[k][1] == 0, (k, t[k])
