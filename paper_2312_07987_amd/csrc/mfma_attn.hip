@@ -562,6 +562,191 @@ __global__ __launch_bounds__(64 * NW, DH <= 64 ? 2 : 1) void mfma_attn_dkv_kerne
 }
 
 // ----------------------------------------------------------------------------------------
+// backward, dK and dV with two kinds of waves (head widths 64 .. 128).  The kernel above runs one wave per SIMD (its
+// accumulators and key / value fragments need more than 256 registers), and whatever such a wave does besides multiplying
+// (the softmax arithmetic, LDS traffic, the staging of the next tile) is time the matrix cores stand idle.  Here a
+// work-group has eight waves, two per SIMD, that split the work of a 32-key block between them:
+//   a score wave   holds the block's K and V fragments, computes S = Q K^T and dP = dO V^T of one query tile, turns them
+//                  into P and dS = P (dP - delta), and leaves both as bf16 operand fragments in LDS (and dS^T in memory
+//                  for the dQ product);
+//   a gradient wave holds the block's dK and dV accumulators and adds dO^T P and Q^T dS of the PREVIOUS query tile, taken
+//                  from those fragments.
+// Each needs well under 256 registers, both issue 16 MFMAs per tile, and on every SIMD one of each kind is resident: the
+// gradient wave's products fill the time the score wave spends on exponentials and conversions.  Query tiles go through
+// three LDS stages (written one trip ahead, read by the score waves in the next trip and by the gradient waves in the
+// one after), the fragments through two buffers; one work-group barrier per trip.
+// ----------------------------------------------------------------------------------------
+template <int DH, int VEC>
+__global__ __launch_bounds__(512, 1) void mfma_attn_dkv_ws_kernel(AttnBwdArgs a) {
+  constexpr int QT = DKV_QT, KB = 128, NST = 3;
+  static_assert(QT == 32, "one 32-query block per tile");
+  // One tile per matrix serves both read patterns: rows 2 DH + 32 bytes apart put the 8 rows a 16-byte fragment read
+  // touches per clock 8 banks apart, and the 4 rows x 32 bytes of a transposing read's 16 lanes in 4 different bank groups.
+  constexpr int LD = DH + 16;
+  constexpr int NKD = DH / 16, NDB = DH / 32;
+  constexpr int STAGE = 2 * QT * LD;   // Q tile, dO tile
+  __shared__ __attribute__((aligned(16))) unsigned short tiles[NST * STAGE];
+  __shared__ __attribute__((aligned(16))) uint4 hand[2][4][4][64];   // [buffer][key block][P st 0, P st 1, dS st 0, dS st 1][lane]
+  __shared__ __attribute__((aligned(16))) float lse_s[NST][QT];
+  __shared__ __attribute__((aligned(16))) float del_s[NST][QT];
+
+  int b, h, ktile;
+  attn_block_map(blockIdx.x, (a.T + KB - 1) / KB, a.B * a.H, a.H, a.causal, false, 1, b, h, ktile);
+  const int k0 = ktile * KB;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int blk = wave & 3;          // 32-key block of the wave
+  const bool score = wave < 4;       // waves 0..3 score, 4..7 gradient: one of each per SIMD
+  const int r = lane & 31, g = lane >> 5;
+  const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
+  const int off = T - Tq;   // position of query 0 among the keys
+  const long rs = (long)a.H * dh;
+  const long base = ((long)b * T) * rs + (long)h * dh;
+  const long qbase = ((long)b * Tq) * rs + (long)h * dh;
+  const unsigned short* Q = (const unsigned short*)a.Q + qbase;
+  const unsigned short* dO = (const unsigned short*)a.dO + qbase;
+  const float* lse = a.lse + ((long)b * a.H + h) * Tq;
+  const float* delta = a.delta + (long)b * Tq * a.H + h;
+  const int key = k0 + blk * 32 + r;
+  const int wk_first = k0 + blk * 32;
+
+  const int qbeg = a.causal ? (max(k0 - off, 0) / QT) * QT : 0;   // first query tile that sees a key of this tile
+  const int n = qbeg < Tq ? (Tq - qbeg + QT - 1) / QT : 0;        // query tiles
+  // The gradient waves (threads 256..511) also move the query tiles: they have the time, the score waves' chain of
+  // products, exponentials and conversions is what a trip waits for.  (A second register set, so that a tile has two
+  // trips to arrive, cost more registers than the kernel has: 334 against 238 us at T = 4096.)
+  const int gt = tid - 256;
+  RowTile<DH, VEC, QT, 256> tq, tg;
+  float nlse = 0.f, ndel = 0.f;
+  auto prefetch = [&](int q0) {
+    tq.load(Q + (long)q0 * rs, rs, Tq - q0, dh, gt);
+    tg.load(dO + (long)q0 * rs, rs, Tq - q0, dh, gt);
+    const int qi = min(q0 + (gt & (QT - 1)), Tq - 1);   // rows past the end repeat the last query: masked below
+    nlse = lse[qi];
+    ndel = delta[(long)qi * a.H];
+  };
+  auto stage = [&](int st) {
+    unsigned short* t = tiles + st * STAGE;
+    tq.store(t, LD, t, LD, gt, dh);
+    tg.store(t + QT * LD, LD, t + QT * LD, LD, gt, dh);
+    if (gt < QT) {
+      lse_s[st][gt] = nlse * 1.44269504088896340736f;
+      del_s[st][gt] = ndel;
+    }
+  };
+
+  if (score) {
+    const unsigned short* K = (const unsigned short*)a.K + base;
+    const unsigned short* V = (const unsigned short*)a.V + base;
+    bf16x8 kf[NKD], vf[NKD];
+#pragma unroll
+    for (int kk = 0; kk < NKD; ++kk) {
+      kf[kk] = global_frag<VEC>(K + (long)key * rs, kk * 16 + 8 * g, dh, key < T);
+      vf[kk] = global_frag<VEC>(V + (long)key * rs, kk * 16 + 8 * g, dh, key < T);
+    }
+    unsigned short* dsrow = a.dSt ? (unsigned short*)a.dSt + (((long)b * a.H + h) * a.ds_rows + key) * a.ds_ld + 4 * g : nullptr;
+    const float sc = a.scale * 1.44269504088896340736f;
+    for (int it = 0; it <= n; ++it) {
+      __syncthreads();
+      if (it == n) break;
+      const int q0 = qbeg + it * QT;
+      const unsigned short* Qr = tiles + (it % NST) * STAGE;
+      const unsigned short* Gr = Qr + QT * LD;
+      f32x16 S, dP;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[i] = dP[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NKD; ++kk) {
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Qr[r * LD + kk * 16 + 8 * g]), kf[kk], S, 0, 0, 0);
+        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowfrag(&Gr[r * LD + kk * 16 + 8 * g]), vf[kk], dP, 0, 0, 0);
+      }
+      float p[16], ds[16];
+      const float* Ls = lse_s[it % NST];
+      const float* Ds = del_s[it % NST];
+      // wave-uniform: most tiles lie wholly inside the visible region and need no per-element test
+      const bool need_mask = q0 + QT > Tq || wk_first + 32 > T || (a.causal && wk_first + 31 > q0 + off);
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const float4 L = *(const float4*)&Ls[8 * i4 + 4 * g];
+        const float4 D = *(const float4*)&Ds[8 * i4 + 4 * g];
+        const float Lv[4] = {L.x, L.y, L.z, L.w}, Dv[4] = {D.x, D.y, D.z, D.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int i = 4 * i4 + t;
+          float arg = fmaf(S[i], sc, -Lv[t]);
+          if (need_mask) {
+            const int qq = q0 + 8 * i4 + 4 * g + t;
+            const bool vis = qq < Tq && key < T && (!a.causal || key <= qq + off);
+            arg = fminf(arg, vis ? INFINITY : -INFINITY);   // exp2(-inf) = 0
+          }
+          const float pv = __builtin_amdgcn_exp2f(arg);
+          p[i] = pv;
+          ds[i] = pv * (dP[i] - Dv[t]);
+        }
+      }
+      uint4* hd = hand[it & 1][blk][0] + lane;
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        union {
+          bf16x8 v;
+          uint4 q;
+          uint2 hh[2];
+        } up, ud;
+        up.v = pack8(&p[8 * st]);
+        ud.v = pack8(&ds[8 * st]);
+        hd[st * 64] = up.q;
+        hd[(2 + st) * 64] = ud.q;
+        if (dsrow) {   // uniform.  Elements 0..3 / 4..7: queries q0 + 16 st + 4 g + {0..3} / + 8 + {0..3} of this lane's key
+          *(uint2*)(dsrow + q0 + 16 * st) = ud.hh[0];
+          *(uint2*)(dsrow + q0 + 16 * st + 8) = ud.hh[1];
+        }
+      }
+    }
+  } else {
+    f32x16 accK[NDB], accV[NDB];
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) accK[d][i] = accV[d][i] = 0.f;
+    if (n > 0) {
+      prefetch(qbeg);
+      stage(0);
+      if (n > 1) prefetch(qbeg + QT);
+    }
+    for (int it = 0; it <= n; ++it) {
+      __syncthreads();
+      // the tile it + 1 (requested a trip ago) goes into its stage and the tile it + 2 starts to travel
+      if (it + 1 < n) {
+        stage((it + 1) % NST);
+        if (it + 2 < n) prefetch(qbeg + (it + 2) * QT);
+      }
+      if (it == 0) continue;
+      const unsigned short* Qt = tiles + ((it - 1) % NST) * STAGE;
+      const unsigned short* Gt = Qt + QT * LD;
+      const uint4* hd = hand[(it - 1) & 1][blk][0] + lane;
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        union {
+          uint4 q;
+          bf16x8 v;
+        } up, ud;
+        up.q = hd[st * 64];
+        ud.q = hd[(2 + st) * 64];
+        const int kb0 = 16 * st + 4 * g;
+#pragma unroll
+        for (int d = 0; d < NDB; ++d) {
+          accV[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Gt, LD, kb0, kb0 + 8, d * 32, lane), up.v, accV[d], 0, 0, 0);
+          accK[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Qt, LD, kb0, kb0 + 8, d * 32, lane), ud.v, accK[d], 0, 0, 0);
+        }
+      }
+    }
+    if (key < T) {
+      store_rows_T<NDB>((unsigned short*)a.dK + base + (long)key * rs, accK, a.scale, g, dh);
+      store_rows_T<NDB>((unsigned short*)a.dV + base + (long)key * rs, accV, 1.f, g, dh);
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------------------
 // backward, dQ: block = 4 waves x 32 queries (Q and dO rows of a wave live in registers);
 // key tiles of K (both read patterns) and V are staged in LDS.
 //   S^T[key][q] = K Q^T, dP^T[key][q] = V dO^T, dS^T = P^T (dP^T - delta),
@@ -795,7 +980,12 @@ static void launch_dh(const AttnArgs* f, const AttnBwdArgs* bw, hipStream_t s) {
     constexpr int QT = DKV_QT;
     static_assert(32 * NW == 128, "the dQ-from-dS kernel and attn_ds_dims assume work-groups of 128 keys");
     dim3 gk(((bw->T + 32 * NW - 1) / (32 * NW)) * bw->H * bw->B);
-    if (attn_vec(bw->dh) == 8)
+    if constexpr (DH >= 64 && DH <= 128) {
+      if (attn_vec(bw->dh) == 8)
+        mfma_attn_dkv_ws_kernel<DH, 8><<<gk, 512, 0, s>>>(*bw);
+      else
+        mfma_attn_dkv_ws_kernel<DH, 4><<<gk, 512, 0, s>>>(*bw);
+    } else if (attn_vec(bw->dh) == 8)
       mfma_attn_dkv_kernel<DH, 8, NW, QT><<<gk, 64 * NW, 0, s>>>(*bw);
     else
       mfma_attn_dkv_kernel<DH, 4, NW, QT><<<gk, 64 * NW, 0, s>>>(*bw);
