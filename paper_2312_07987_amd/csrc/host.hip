@@ -218,7 +218,13 @@ Layout make_layout(const sh_shape* s) {
     int ld = 0, rows = 0;
     if (s->dtype == SH_BF16 && attn_ds_dims(s->T, s->T_q, (int)dh, &ld, &rows)) {
       const size_t bytes = (size_t)s->B * H * rows * ld * 2;
-      if (bytes <= ((size_t)1 << 30)) L.dst = take(bytes);
+      // It lives from the dK / dV kernel to the dQ product.  The fp32 accumulator of dx (first written after the
+      // attention backward) and the per-slot rows of the output experts' dgrad (consumed before it), which lie next to
+      // each other, are dead in between: the score gradient takes their place if it fits.
+      if (L.u == L.acc32 + align_up(N * dm * 4) && bytes <= align_up(N * dm * 4) + align_up(H * N * k * dh * esz))
+        L.dst = L.acc32;
+      else if (bytes <= ((size_t)1 << 30))
+        L.dst = take(bytes);
     }
   }
   L.total = off;
