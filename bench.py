@@ -47,8 +47,8 @@ def step_work(cfg):
         "fwd.v_experts": expert, "fwd.o_experts": expert_q,
         "fwd.attention": attn, "bwd.attention": 5 * attn // 2,
         # backward attention = 5 matmuls of attn/2 flops each: S and dP (shared), dV, dK, dQ; the dK/dV
-        # kernel is credited with four of them, the dQ kernel with dQ alone (its recomputation of S and
-        # dP is not algorithmic work)
+        # kernel is credited with four of them, the dQ kernel with dQ alone (it reads the score gradient the
+        # dK/dV kernel left, or recomputes S and dP where that scratch is not used: not algorithmic work)
         "bwd.attention_dkv": 2 * attn, "bwd.attention_dq": attn // 2,
         "bwd.o_dgrad": expert_q, "bwd.o_wgrad": expert_q, "bwd.v_wgrad": expert, "bwd.v_dgrad": expert,
         "bwd.q_wgrad": proj_q, "bwd.k_wgrad": proj, "bwd.qk_wgrad": proj + proj_q, "bwd.q_dgrad": proj_q, "bwd.k_dgrad": proj,
@@ -87,8 +87,8 @@ STEP_KERNEL = {
     "bwd.dx_gemm": r"pp_row_gemm_kernel<true, 6, 3>",
     "bwd.o_wgrad": r"mfma_wgrad_kernel<.*, 8, 7(, \w+)?>", "bwd.v_wgrad": r"mfma_wgrad_kernel<.*, 8, 8(, \w+)?>",
     "bwd.qk_wgrad": r"mfma_wgrad_kernel<.*, 8, 9(, \w+)?>", "bwd.wgrad_reduce": r"wgrad_reduce_kernel",
-    "fwd.attention": r"mfma_attn_fwd_kernel", "bwd.attention_dkv": r"mfma_attn_dkv_kernel",
-    "bwd.attention_dq": r"mfma_attn_dq_kernel", "fwd.y_sum": r"sum_heads_kernel", "bwd.dx_cast": r"sum_heads_kernel",
+    "fwd.attention": r"mfma_attn_fwd_kernel", "bwd.attention_dkv": r"mfma_attn_dkv(_ws)?_kernel",
+    "bwd.attention_dq": r"mfma_attn_dq(_ds)?_kernel", "fwd.y_sum": r"sum_heads_kernel", "bwd.dx_cast": r"sum_heads_kernel",
     "fwd.v_combine": r"slot_combine", "bwd.dctx_combine": r"slot_combine", "bwd.dgate_s": r"slot_combine",
 }
 
