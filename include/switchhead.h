@@ -103,8 +103,9 @@ size_t switchhead_workspace_bytes(const sh_shape* shape);
  *            average as free; storing the slot rows is this build's choice against a second pass over x);
  *   scratch  buffers one pass writes and reads itself (fp32 accumulators, per-slot gradient rows,
  *            dQ/dK/dV, weight-gradient partial sums, router scratch, and with bf16 storage and head
- *            widths 64..128 the attention's score gradient [B, nheads, T, T_q] in bf16, rounded up to
- *            tiles, which the backward keeps between its dK/dV and dQ kernels: quadratic in T, used up to
+ *            widths 64..128 the attention's score gradient [B, nheads, T, T_q] in bf16 (under the causal
+ *            mask only the visible half), which the backward keeps between its dK/dV and dQ kernels:
+ *            quadratic in T, used up to
  *            1 GiB, recomputed beyond; it shares the place of other scratch where it fits); their
  *            contents mean nothing between calls.  The two parts are interleaved in the buffer: this call reports sizes, not
  *            address ranges, and the whole workspace must stay untouched between forward and backward.

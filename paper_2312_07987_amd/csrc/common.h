@@ -212,11 +212,12 @@ struct AttnBwdArgs {
   int B, T, H, dh, causal;
   float scale;
   int Tq;   // as in AttnArgs: Q, dO, dQ, lse, delta have Tq rows per sequence, K, V, dK, dV have T
-  // Optional scratch for the score gradient dS^T[b][h][key][query] (bf16, rows of ds_ld queries, ds_rows keys per
-  // (b, h); see attn_ds_dims).  If not NULL the dK / dV kernel leaves dS there and dQ = dS K is a plain product
-  // that reads it back instead of recomputing the scores and probabilities.
+  // Optional scratch for the score gradient dS^T[b][h][key][query] in bf16 (layout: attn_ds_dims).  If not NULL the
+  // dK / dV kernel leaves dS there and dQ = dS K is a plain product that reads it back instead of recomputing the
+  // scores and probabilities.  ds_ld: queries rounded up to 256; ds_per: elements per (b, h).
   void* dSt;
-  int ds_ld, ds_rows;
+  int ds_ld;
+  long ds_per;
 };
 
 // ----------------------------------------------------------------------------------------
@@ -349,9 +350,11 @@ void launch_pp_row_gemm(const RowGemmArgs& a, hipStream_t s);
 bool mfma_wgrad_supported(const WgradArgs& a);
 void launch_mfma_wgrad(const WgradArgs& a, hipStream_t s);
 bool mfma_attn_supported(int T, int dh);
-// row length (queries) and rows (keys) per (sequence, head) of the score-gradient scratch of launch_mfma_attn_bwd;
-// false if this head width does not use it
-bool attn_ds_dims(int T, int Tq, int dh, int* ld, int* rows);
+// The score-gradient scratch of launch_mfma_attn_bwd: per (sequence, head) the blocks of 128 keys follow each other; block t
+// holds, for each of its keys, the queries from ds_block_start(t) on (under a causal mask earlier queries see none of the
+// block's keys), i.e. rows of ld - ds_block_start(t) elements.  Returns ld (queries rounded up to 256) and the elements
+// per (sequence, head); false if this head width does not use the scratch.
+bool attn_ds_dims(int T, int Tq, int dh, int causal, int* ld, long* per);
 void launch_mfma_attn_fwd(const AttnArgs& a, hipStream_t s);
 void launch_mfma_attn_bwd(const AttnBwdArgs& a, hipStream_t s);
 

@@ -215,9 +215,10 @@ Layout make_layout(const sh_shape* s) {
   // dQ product instead of that kernel recomputing scores and probabilities.  Quadratic in T, so only up to 1 GiB.
   L.dst = 0;
   {
-    int ld = 0, rows = 0;
-    if (s->dtype == SH_BF16 && attn_ds_dims(s->T, s->T_q, (int)dh, &ld, &rows)) {
-      const size_t bytes = (size_t)s->B * H * rows * ld * 2;
+    int ld = 0;
+    long per = 0;
+    if (s->dtype == SH_BF16 && attn_ds_dims(s->T, s->T_q, (int)dh, s->causal, &ld, &per)) {
+      const size_t bytes = (size_t)s->B * H * (size_t)per * 2;
       // It lives from the dK / dV kernel to the dQ product.  The fp32 accumulator of dx (first written after the
       // attention backward) and the per-slot rows of the output experts' dgrad (consumed before it), which lie next to
       // each other, are dead in between: the score gradient takes their place if it fits.
@@ -1011,7 +1012,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     a.causal = shape->causal;
     a.scale = 1.0f / sqrtf((float)dh);
     a.Tq = c.Tq;
-    if (c.L.dst != 0 && attn_ds_dims(shape->T, c.Tq, dh, &a.ds_ld, &a.ds_rows)) a.dSt = c.p<void>(c.L.dst);
+    if (c.L.dst != 0 && attn_ds_dims(shape->T, c.Tq, dh, shape->causal, &a.ds_ld, &a.ds_per)) a.dSt = c.p<void>(c.L.dst);
     if (use_mfma(c) && mfma_attn_supported(shape->T, dh))
       launch_mfma_attn_bwd(a, c.st);   // marks its two kernels itself
     else {

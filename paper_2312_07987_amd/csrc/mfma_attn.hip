@@ -398,6 +398,19 @@ __device__ __forceinline__ void store_rows_T(unsigned short* dst, const f32x16* 
 //   S[q][key] = Q K^T,  P = exp(S - lse),  dP[q][key] = dO V^T,  dS = P (dP - delta)
 //   dV^T[d][key] += dO^T[d][q] P[q][key],   dK^T[d][key] += Q^T[d][q] dS[q][key]
 // ----------------------------------------------------------------------------------------
+// Score-gradient scratch: first query column kept for the block of 128 keys number t (a multiple of 256 at or below the
+// first query that sees one of the block's keys; `off` = position of query 0 among the keys), and where that block starts
+// within its (sequence, head) part (elements).
+__host__ __device__ inline int ds_block_start(int t, int off, int causal) {
+  const int u = 128 * t - off;
+  return causal && u > 0 ? (u >> 8) << 8 : 0;
+}
+__host__ __device__ inline long ds_block_offset(int t, int ld, int off, int causal) {
+  long o = 0;
+  for (int j = 0; j < t; ++j) o += 128L * (ld - ds_block_start(j, off, causal));
+  return o;
+}
+
 // queries per staged tile of the dK / dV kernel; 64 (half the barriers, two independent blocks per trip) measured 6 %
 // slower at T = 4096.  The dQ-from-dS kernel derives from it which part of a dS^T row was written.
 constexpr int DKV_QT = 32;
@@ -437,7 +450,13 @@ __global__ __launch_bounds__(64 * NW, DH <= 64 ? 2 : 1) void mfma_attn_dkv_kerne
 
   const int key = k0 + wave * 32 + r;
   // this lane's row of dS^T (keys past T lie inside the padded row count and receive zeros)
-  unsigned short* dsrow = a.dSt ? (unsigned short*)a.dSt + (((long)b * a.H + h) * a.ds_rows + key) * a.ds_ld + 4 * g : nullptr;
+  unsigned short* dsrow = nullptr;
+  if (a.dSt) {
+    static_assert(KB == 128, "the score-gradient scratch is laid out in blocks of 128 keys");
+    const int s0 = ds_block_start(ktile, off, a.causal);
+    dsrow = (unsigned short*)a.dSt + ((long)b * a.H + h) * a.ds_per + ds_block_offset(ktile, a.ds_ld, off, a.causal) +
+            (long)(wave * 32 + r) * (a.ds_ld - s0) - s0 + 4 * g;
+  }
   const int wk_first = k0 + wave * 32;
   bf16x8 kf[NKD], vf[NKD];
 #pragma unroll
@@ -643,7 +662,12 @@ __global__ __launch_bounds__(512, 1) void mfma_attn_dkv_ws_kernel(AttnBwdArgs a)
       kf[kk] = global_frag<VEC>(K + (long)key * rs, kk * 16 + 8 * g, dh, key < T);
       vf[kk] = global_frag<VEC>(V + (long)key * rs, kk * 16 + 8 * g, dh, key < T);
     }
-    unsigned short* dsrow = a.dSt ? (unsigned short*)a.dSt + (((long)b * a.H + h) * a.ds_rows + key) * a.ds_ld + 4 * g : nullptr;
+    unsigned short* dsrow = nullptr;
+    if (a.dSt) {
+      const int s0 = ds_block_start(ktile, off, a.causal);
+      dsrow = (unsigned short*)a.dSt + ((long)b * a.H + h) * a.ds_per + ds_block_offset(ktile, a.ds_ld, off, a.causal) +
+              (long)(blk * 32 + r) * (a.ds_ld - s0) - s0 + 4 * g;
+    }
     const float sc = a.scale * 1.44269504088896340736f;
     for (int it = 0; it <= n; ++it) {
       __syncthreads();
@@ -876,7 +900,7 @@ __global__ __launch_bounds__(256, QB == 128 ? 3 : 2) void mfma_attn_dq_ds_kernel
   const int d0 = DSPLIT == 2 ? (wave >> 1) * ND : 0;       // its first d block
   const long rs = (long)a.H * dh;
   const unsigned short* K = (const unsigned short*)a.K + ((long)b * T) * rs + (long)h * dh;
-  const unsigned short* D = (const unsigned short*)a.dSt + (((long)b * a.H + h) * a.ds_rows) * a.ds_ld + q0;
+  const unsigned short* D = (const unsigned short*)a.dSt + ((long)b * a.H + h) * a.ds_per;
   const int wq_last = q0 + wq + 63 + off;
 
   f32x16 acc[2][ND];
@@ -892,11 +916,20 @@ __global__ __launch_bounds__(256, QB == 128 ? 3 : 2) void mfma_attn_dq_ds_kernel
   // the dS^T tile: KT rows of QB queries: rows tid / CPRD + RSTEP i, queries 8 (tid % CPRD) ..
   uint4 td[NP];
   const int dq8 = (tid % CPRD) * 8;
-  const unsigned d_voff = (unsigned)(((tid / CPRD) * a.ds_ld + dq8) * 2);
+  // the tile's block of 128 keys: its start within D and its first kept query; load_d is called with rising k0
+  int blk_t = 0, blk_s = 0;
+  long blk_off = 0;
   auto load_d = [&](int k0) {
-    const char* p = (const char*)(D + (long)k0 * a.ds_ld);
+    while (blk_t < (k0 >> 7)) {
+      blk_off += 128L * (a.ds_ld - blk_s);
+      ++blk_t;
+      blk_s = ds_block_start(blk_t, off, a.causal);
+    }
+    const int ldt = a.ds_ld - blk_s;   // q0 >= blk_s: the block's keys are visible to this tile's queries or it is not read
+    const char* p = (const char*)(D + blk_off + (long)(k0 & 127) * ldt + (q0 - blk_s));
+    const unsigned voff = (unsigned)(((tid / CPRD) * ldt + dq8) * 2);
 #pragma unroll
-    for (int i = 0; i < NP; ++i) td[i] = *(const uint4*)(p + (unsigned)(RSTEP * i * a.ds_ld * 2) + d_voff);
+    for (int i = 0; i < NP; ++i) td[i] = *(const uint4*)(p + (unsigned)(RSTEP * i * ldt * 2) + voff);
   };
   tk.load(K, rs, T, dh, tid);
   load_d(0);
@@ -939,12 +972,12 @@ __global__ __launch_bounds__(256, QB == 128 ? 3 : 2) void mfma_attn_dq_ds_kernel
 }
 
 // The score-gradient scratch is used for head widths of 64 .. 128 (one work-group per CU otherwise, and the recomputing
-// kernel is already the smaller part there); rows of ds_ld = Tq rounded up to 256 queries, T rounded up to 128 keys per (b, h).
-bool attn_ds_dims(int T, int Tq, int dh, int* ld, int* rows) {
+// kernel is already the smaller part there).
+bool attn_ds_dims(int T, int Tq, int dh, int causal, int* ld, long* per) {
   if (Tq <= 0) Tq = T;
   if (dh < 64 || dh > 128 || dh % 8 != 0) return false;
   *ld = (Tq + 255) / 256 * 256;
-  *rows = (T + 127) / 128 * 128;
+  *per = ds_block_offset((T + 127) / 128, *ld, T - Tq, causal);
   return true;
 }
 
