@@ -173,12 +173,15 @@ __device__ __forceinline__ void attn_block_map(int L, int ntile, int P, int H, b
 // ----------------------------------------------------------------------------------------
 template <int DH, int VEC, int NG = 1>
 __global__ __launch_bounds__(256 * NG, (DH <= 128 && NG == 1) ? 2 : 1) void mfma_attn_fwd_kernel(AttnArgs a) {
+  // two K/V buffers per group (one barrier per trip) for the long sequences that run two groups; short ones do better
+  // with one buffer and two barriers (c2: 27 against 31 us)
+  constexpr int NBUF = NG == 2 ? 2 : 1;
   constexpr int KT = DH > 128 ? 32 : 64;
   constexpr int LDK = DH + 8, LDV = ld_tr(DH);
   constexpr int NKD = DH / 16;   // k steps of Q K^T
   constexpr int NDB = DH / 32;   // 32-wide d blocks of the output
   constexpr int TILE = KT * (LDK + LDV);   // one K tile and one V tile
-  __shared__ __attribute__((aligned(16))) unsigned short kv_[NG * 2 * TILE];   // per group: two buffers in turn
+  __shared__ __attribute__((aligned(16))) unsigned short kv_[NG * NBUF * TILE];   // per group: NBUF buffers in turn
 
   int b, h, qt;
   const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
@@ -187,7 +190,7 @@ __global__ __launch_bounds__(256 * NG, (DH <= 128 && NG == 1) ? 2 : 1) void mfma
   const int q0 = qt * 128;
   const int grp = NG > 1 ? threadIdx.x >> 8 : 0;     // wave group: key tiles grp, grp + NG, ...
   const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
-  unsigned short* const kv = kv_ + grp * 2 * TILE;
+  unsigned short* const kv = kv_ + grp * NBUF * TILE;
   const int r = lane & 31, g = lane >> 5;
   const long rs = (long)a.H * dh;
   const long base = ((long)b * T) * rs + (long)h * dh;
@@ -216,28 +219,42 @@ __global__ __launch_bounds__(256 * NG, (DH <= 128 && NG == 1) ? 2 : 1) void mfma
   // (rows past the end of the sequence load as zeros: a group whose first tile lies past `kend` stages zeros once)
   tk.load(K + (long)(grp * KT) * rs, rs, T - grp * KT, dh, tid);
   tv.load(V + (long)(grp * KT) * rs, rs, T - grp * KT, dh, tid);
-  tk.store(kv, LDK, kv, LDK, tid, dh);
-  tv.store(kv + KT * LDK, LDV, kv + KT * LDK, LDV, tid, dh);
-  if ((grp + NG) * KT < kend) {
-    tk.load(K + (long)((grp + NG) * KT) * rs, rs, T - (grp + NG) * KT, dh, tid);
-    tv.load(V + (long)((grp + NG) * KT) * rs, rs, T - (grp + NG) * KT, dh, tid);
+  if constexpr (NBUF == 2) {
+    tk.store(kv, LDK, kv, LDK, tid, dh);
+    tv.store(kv + KT * LDK, LDV, kv + KT * LDK, LDV, tid, dh);
+    if ((grp + NG) * KT < kend) {
+      tk.load(K + (long)((grp + NG) * KT) * rs, rs, T - (grp + NG) * KT, dh, tid);
+      tv.load(V + (long)((grp + NG) * KT) * rs, rs, T - (grp + NG) * KT, dh, tid);
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  // One barrier per trip: while a tile is multiplied out of one buffer the next one (loaded a trip ago) is written into the
-  // other and the one after that starts to travel.  Every group makes the same number of trips (the barriers are the
-  // work-group's); a trip past `kend` only waits.
+  // NBUF = 2, one barrier per trip: while a tile is multiplied out of one buffer the next one (loaded a trip ago) is
+  // written into the other and the one after that starts to travel.  NBUF = 1: the tile in the registers is written
+  // between two barriers and the next one starts to travel.  Every group makes the same number of trips (the barriers
+  // are the work-group's); a trip past `kend` only waits.
   int cur = 0;
-  for (int kb0 = 0; kb0 < kend; kb0 += NG * KT, cur ^= 1) {
+  for (int kb0 = 0; kb0 < kend; kb0 += NG * KT, cur ^= NBUF - 1) {
     const int k0 = kb0 + grp * KT;
     const unsigned short* Ks = kv + cur * TILE;
     const unsigned short* Vs = Ks + KT * LDK;
-    if (k0 + NG * KT < kend) {
-      unsigned short* nk = kv + (cur ^ 1) * TILE;   // last read a trip ago, before the barrier that ended it
-      tk.store(nk, LDK, nk, LDK, tid, dh);
-      tv.store(nk + KT * LDK, LDV, nk + KT * LDK, LDV, tid, dh);
-      if (k0 + 2 * NG * KT < kend) {
-        tk.load(K + (long)(k0 + 2 * NG * KT) * rs, rs, T - k0 - 2 * NG * KT, dh, tid);
-        tv.load(V + (long)(k0 + 2 * NG * KT) * rs, rs, T - k0 - 2 * NG * KT, dh, tid);
+    if constexpr (NBUF == 2) {
+      if (k0 + NG * KT < kend) {
+        unsigned short* nk = kv + (cur ^ 1) * TILE;   // last read a trip ago, before the barrier that ended it
+        tk.store(nk, LDK, nk, LDK, tid, dh);
+        tv.store(nk + KT * LDK, LDV, nk + KT * LDK, LDV, tid, dh);
+        if (k0 + 2 * NG * KT < kend) {
+          tk.load(K + (long)(k0 + 2 * NG * KT) * rs, rs, T - k0 - 2 * NG * KT, dh, tid);
+          tv.load(V + (long)(k0 + 2 * NG * KT) * rs, rs, T - k0 - 2 * NG * KT, dh, tid);
+        }
+      }
+    } else {
+      __syncthreads();
+      tk.store(kv, LDK, kv, LDK, tid, dh);
+      tv.store(kv + KT * LDK, LDV, kv + KT * LDK, LDV, tid, dh);
+      __syncthreads();
+      if (k0 + NG * KT < kend) {
+        tk.load(K + (long)(k0 + NG * KT) * rs, rs, T - k0 - NG * KT, dh, tid);
+        tv.load(V + (long)(k0 + NG * KT) * rs, rs, T - k0 - NG * KT, dh, tid);
       }
     }
     // wave-uniform: a trip past the end, or a tile with nothing visible to this wave
@@ -302,7 +319,7 @@ __global__ __launch_bounds__(256 * NG, (DH <= 128 && NG == 1) ? 2 : 1) void mfma
             o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trfrag(Vs, LDV, kr, kr + 8, d * 32, lane), pb, o[d], 0, 0, 0);
         }
     }
-    __syncthreads();
+    if constexpr (NBUF == 2) __syncthreads();
   }
 
   l += __shfl_xor(l, 32, 64);
@@ -310,7 +327,7 @@ __global__ __launch_bounds__(256 * NG, (DH <= 128 && NG == 1) ? 2 : 1) void mfma
     // merge the groups' partial results: group 1 parks (o, m, l) in LDS (the key / value tiles are dead), group 0 of the
     // same wave index and lane holds the same query and the same output elements
     static_assert(NG == 2, "two groups");
-    static_assert(4 * (NDB * 16 + 2) * 64 * 4 <= NG * 2 * TILE * 2, "the parked accumulators fit in the tiles");
+    static_assert(4 * (NDB * 16 + 2) * 64 * 4 <= NG * NBUF * TILE * 2, "the parked accumulators fit in the tiles");
     float* park = (float*)kv_ + (long)wave * (NDB * 16 + 2) * 64;
     if (grp == 1) {
 #pragma unroll
