@@ -1,7 +1,9 @@
 // Fused attention on bf16 matrix cores for the SwitchHead layer (arXiv 2312.07987):
 // A^h = softmax(Q^h K^h^T / sqrt(d_head)) and the read-out A^h V^h of Sec. 2.1, one
 // attention matrix per head, computed tile by tile with a running maximum so that the
-// T x T matrix never exists in memory; plus the matching backward kernels.
+// T x T matrix of probabilities never exists in memory; plus the matching backward kernels
+// (which, at head widths 64..128 and up to 1 GiB, do keep one T x T quantity between them: the
+// score gradient dS in bf16, the visible half under a causal mask; see attn_ds_dims).
 //
 // Everything is computed transposed, S^T[key][query] = K Q^T, so that one query lives in
 // one lane column of the MFMA result: the softmax statistics of a query are lane-local
@@ -51,26 +53,6 @@ __device__ __forceinline__ bf16x8 pack8(const float* v) {
 
 // row stride (elements) of a tile read with transposing loads: 16 banks (mod 64) apart
 __host__ __device__ constexpr int ld_tr(int dh) { return dh <= 32 ? 32 : (dh <= 160 ? 160 : 288); }
-
-// copies `nrows` rows of `dh` bf16 (zero padded to DH columns and beyond `valid_rows`) into
-// an LDS tile with row stride ld.  VEC = 8 or 4 elements per load.
-template <int DH, int VEC>
-__device__ __forceinline__ void stage_rows(unsigned short* tile, int ld, const unsigned short* src, long row_stride,
-                                           int nrows, int valid_rows, int dh, int tid) {
-  constexpr int CPR = DH / VEC;
-  for (int c = tid; c < nrows * CPR; c += 256) {
-    const int r = c / CPR, d = (c % CPR) * VEC;
-    if constexpr (VEC == 8) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (r < valid_rows && d < dh) v = *(const uint4*)(src + (long)r * row_stride + d);
-      *(uint4*)(tile + r * ld + d) = v;
-    } else {
-      uint2 v = make_uint2(0, 0);
-      if (r < valid_rows && d < dh) v = *(const uint2*)(src + (long)r * row_stride + d);
-      *(uint2*)(tile + r * ld + d) = v;
-    }
-  }
-}
 
 // 8 consecutive elements of a global row as an operand fragment, zero beyond dh / invalid row
 template <int VEC>
@@ -366,29 +348,6 @@ __global__ __launch_bounds__(256 * NG, (DH <= 128 && NG == 1) ? 2 : 1) void mfma
         }
       }
     if (g == 0) a.lse[((long)b * a.H + h) * Tq + q] = (m + log2f(l)) * 0.69314718055994530942f;
-  }
-}
-
-// copies rows into two LDS tiles at once (one read with row fragments, one with transposing
-// loads; they need different row strides to stay free of bank conflicts).  t1 may equal t0.
-template <int DH, int VEC>
-__device__ __forceinline__ void stage_rows2(unsigned short* t0, int ld0, unsigned short* t1, int ld1,
-                                            const unsigned short* src, long row_stride, int nrows, int valid_rows,
-                                            int dh, int tid) {
-  constexpr int CPR = DH / VEC;
-  for (int c = tid; c < nrows * CPR; c += 256) {
-    const int r = c / CPR, d = (c % CPR) * VEC;
-    if constexpr (VEC == 8) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (r < valid_rows && d < dh) v = *(const uint4*)(src + (long)r * row_stride + d);
-      *(uint4*)(t0 + r * ld0 + d) = v;
-      if (t1 != t0) *(uint4*)(t1 + r * ld1 + d) = v;
-    } else {
-      uint2 v = make_uint2(0, 0);
-      if (r < valid_rows && d < dh) v = *(const uint2*)(src + (long)r * row_stride + d);
-      *(uint2*)(t0 + r * ld0 + d) = v;
-      if (t1 != t0) *(uint2*)(t1 + r * ld1 + d) = v;
-    }
   }
 }
 

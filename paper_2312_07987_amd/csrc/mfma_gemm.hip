@@ -460,10 +460,7 @@ static void launch_cfg(const RowGemmArgs& a, hipStream_t s) {
 
 // tile shape for a launch: the big tiles pay off when a group has enough rows to fill them
 enum { SHAPE_SMALL, SHAPE_WIDE, SHAPE_MED };
-static int g_force_shape = -1;   // experiments only
-void rg_force_shape(int shape) { g_force_shape = shape; }
 static int pick_shape(const RowGemmArgs& a) {
-  if (g_force_shape >= 0 && a.tag != TAG_ROUTER && a.tag != TAG_GENERIC) return g_force_shape;
   const int group_rows = a.perm ? a.max_group_rows : a.M;
   if (a.tag == TAG_ROUTER || a.tag == TAG_GENERIC) return SHAPE_SMALL;
   // measured on MI355X: the 256 x 128 tile with two work-groups per CU wins where the rows are
@@ -513,7 +510,7 @@ static void launch_generic(const RowGemmArgs& a, hipStream_t s) {
 
 void launch_mfma_row_gemm(const RowGemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.Nc <= 0) return;
-  if (g_force_shape < 0 && pp_row_gemm_supported(a)) return launch_pp_row_gemm(a, s);
+  if (pp_row_gemm_supported(a)) return launch_pp_row_gemm(a, s);
   const int vec = row_gemm_vec(a);
   const bool nt = a.sbk == 1;
   if (vec == 8) {
@@ -844,14 +841,10 @@ static void launch_wg(const WgradArgs& a, hipStream_t s) {
   kern<<<g, 256, lds, s>>>(a);
 }
 
-static int g_force_wshape = -1;   // experiments only
-void wg_force_shape(int shape) { g_force_wshape = shape; }
-
 template <int TAG, int VEC = 8>
 static void launch_wg_tagged(const WgradArgs& a, hipStream_t s) {
   // wide outputs get the 128 x 256 tile, tall ones the 256 x 128 tile
   int shape = a.Kb >= 256 && a.Ka <= 128 ? 1 : (a.Ka >= 256 && a.Kb >= 64 ? 2 : 0);
-  if (g_force_wshape >= 0) shape = g_force_wshape;
   if (shape == 1)
     launch_wg<WgWide, VEC, TAG>(a, s);
   else if (shape == 2)
