@@ -237,6 +237,19 @@ def test_bf16_long_ragged_sequences(family):
     run_case(small("c2", B=2, T=1030, d_model=256, nheads=1, d_head=96, causal=0), family=family, seed=66)
 
 
+def test_bf16_mixed_shapes_long_context():
+    """Shapes off the beaten track for the attention kernels of head widths 64..128: head widths that are padded to the
+    next compiled width (72, 104), cached contexts with odd offsets past 1024 keys, rotary turns, no causal mask, E = 8."""
+    run_case(dict(name="mix1", dtype="bf16", B=2, T=2049, d_model=320, nheads=3, d_head=128, E=5, k=3, causal=1, bias0=0.0,
+                  T_q=722, rope=1), seed=1012)
+    run_case(dict(name="mix2", dtype="bf16", B=2, T=2049, d_model=256, nheads=3, d_head=64, E=8, k=3, causal=0, bias0=0.0,
+                  T_q=1482, rope=1), seed=1019)
+    run_case(dict(name="mix3", dtype="bf16", B=1, T=2049, d_model=320, nheads=3, d_head=104, E=2, k=2, causal=1, bias0=0.0,
+                  T_q=1411), seed=1022)
+    run_case(dict(name="mix4", dtype="bf16", B=2, T=1100, d_model=512, nheads=1, d_head=72, E=8, k=2, causal=1, bias0=0.0,
+                  T_q=150, rope=1), seed=1006)
+
+
 def test_full_config_cached_context():
     """The paper's main setting at c2's sizes: a context twice the current chunk (T = 2 * 512 keys, 512
     queries per sequence), in the launch configuration bench.py times."""
