@@ -48,6 +48,32 @@ def test_workspace_bytes_and_shape_errors(lib):
         assert word in binding.switchhead_last_error()
 
 
+def test_workspace_split_and_score_gradient_scratch(lib):
+    """The two parts add up; the kept part does not depend on what backward needs; the attention backward's score-gradient
+    scratch (quadratic in T, head widths 64..128, bf16 only) hides in dead buffers at c2, is packed to the causal half at
+    c3 and is dropped beyond 1 GiB."""
+    c2 = binding.make_shape(32, 512, 1024, 4, 128, 5, 3, 1, "bf16")
+    kept, scratch = binding.switchhead_workspace_parts(c2)
+    assert kept + scratch == binding.switchhead_workspace_bytes(c2)
+    assert kept < 130e6 and kept + scratch < 500e6
+    c3 = binding.make_shape(4, 4096, 1024, 4, 128, 8, 2, 1, "bf16")
+    c3_nomask = binding.make_shape(4, 4096, 1024, 4, 128, 8, 2, 0, "bf16")
+    k3, s3 = binding.switchhead_workspace_parts(c3)
+    k3n, s3n = binding.switchhead_workspace_parts(c3_nomask)
+    assert k3 == k3n
+    full = 4 * 4 * 4096 * 4096 * 2                      # the unpacked [B, H, T, T] bf16
+    assert 0.45 * full < s3n - s3 < 0.5 * full          # the mask saves almost half of it
+    # a head width outside 64..128 keeps no score gradient, so the mask changes nothing there
+    narrow = [binding.switchhead_workspace_parts(binding.make_shape(4, 4096, 1024, 16, 32, 8, 2, c, "bf16")) for c in (0, 1)]
+    assert narrow[0] == narrow[1]
+    # beyond 1 GiB (here 2 GiB unpacked, a little over 1 GiB packed) it is recomputed instead: again no difference
+    long_ = [binding.switchhead_workspace_parts(binding.make_shape(4, 8192, 1024, 4, 128, 8, 2, c, "bf16")) for c in (0, 1)]
+    assert long_[0] == long_[1] and long_[0][1] < s3n
+    # fp32 storage never keeps it
+    f32 = [binding.switchhead_workspace_parts(binding.make_shape(4, 4096, 1024, 4, 128, 8, 2, c, "f32")) for c in (0, 1)]
+    assert f32[0] == f32[1]
+
+
 def test_forward_rejects_bad_arguments_without_launching(lib):
     s = binding.make_shape(2, 64, 64, 2, 32, 4, 2, 1, "f32")
     fake = ctypes.c_void_p(256)          # never dereferenced: every check below fails first
