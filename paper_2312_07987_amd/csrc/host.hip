@@ -924,6 +924,9 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
   const long hd = (long)H * dh;
   const int chunk = wgrad_chunk((size_t)H * N * k, dm, dh);         // expert-sorted operands
   const int chunk_dense = wgrad_chunk((size_t)2 * H * N, dm, dh);   // fused dense Q/K
+  // ... with the routers' x^T dz as one more head: sized for 2H + 1 groups, or the launch spills into a second round
+  // (c2: 540 work-groups for 512 places with the chunk of 2H groups, 468 with this one)
+  const int chunk_dense_r = wgrad_chunk((size_t)(2 * H + 1) * N, dm, dh);
   const bool sets = sets_usable(c);
   if ((sets && (c.L.yh == 0 || c.L.setperm == 0)) || (gated_concat(c) && c.L.gtab == 0))
     return fail(SH_ERR_UNSUPPORTED, "switchhead_backward: internal error, the workspace layout lacks a table this shape's path uses");
@@ -1065,7 +1068,7 @@ sh_status switchhead_backward(const sh_shape* shape, const void* x, const void* 
     w.dW2 = dW_K;
     w.w_hstride = (long)dm * dh;
     w.swa = dh;
-    w.chunk = chunk_dense;
+    w.chunk = with_router ? chunk_dense_r : chunk_dense;
     return w;
   };
   auto run_qk_wgrad = [&](bool with_router) {

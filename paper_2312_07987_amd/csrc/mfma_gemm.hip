@@ -587,9 +587,47 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   const int ti_ = (a.Ka + BM - 1) / BM, tj = (a.Kb + BN - 1) / BN;
   const int ntile = ti_ * tj;
   const int G = a.heads * a.E;
-  int unit, tile;
-  decode_block(blockIdx.x, ntile, unit, tile);
-  const int w = unit / G, grp = unit % G;
+  int w, grp, tile;
+  if (G <= 64) {
+    // Window-major placement.  The chunk windows of all groups cover about the same tokens (the w-th chunk of every
+    // expert's sorted rows lies near the same token range), so the work-groups of one window should meet in one L2:
+    // the non-empty (window, group) units are counted window by window, and XCD x (work-group ids x, x + 8, ...) takes
+    // the x-th eighth of that list, i.e. one or two windows, instead of every eighth unit of all windows.  Every wave
+    // derives the list from the group sizes by itself (lane g holds the rows of group g).
+    const int lane_ = threadIdx.x & 63;
+    int grows = 0;
+    if (lane_ < G) {
+      const int gh = lane_ / a.E, ge = lane_ % a.E;
+      grows = a.perm ? a.offsets[(long)gh * (a.E + 1) + ge + 1] - a.offsets[(long)gh * (a.E + 1) + ge] : a.M;
+    }
+    long units = 0;
+    for (int ww = 0;; ++ww) {
+      const int cw = __popcll(__ballot(grows > ww * a.chunk));
+      if (cw == 0) break;
+      units += cw;
+    }
+    const long total = units * ntile, share = (total + 7) / 8;
+    const long slot = blockIdx.x >> 3, q = (long)(blockIdx.x & 7) * share + slot;
+    if (slot >= share || q >= total) return;
+    long u = q / ntile;
+    tile = (int)(q % ntile);
+    int ww = 0;
+    unsigned long long m = 0;
+    for (;; ++ww) {
+      m = __ballot(grows > ww * a.chunk);
+      const int cw = __popcll(m);
+      if (u < cw) break;
+      u -= cw;
+    }
+    for (long t = 0; t < u; ++t) m &= m - 1;   // drop the u lowest groups of the window
+    w = ww;
+    grp = __ffsll((long long)m) - 1;
+  } else {
+    int unit;
+    decode_block(blockIdx.x, ntile, unit, tile);
+    w = unit / G;
+    grp = unit % G;
+  }
   if (w * a.chunk >= (a.perm ? a.max_group_rows : a.M)) return;
   const int h = grp / a.E, e = grp % a.E;
   int row0, rows;
