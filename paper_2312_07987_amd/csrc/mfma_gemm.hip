@@ -580,10 +580,8 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   int* ids = (int*)(smem + 2 * Cfg::STAGE_ELEMS);
   float* gsc = (float*)(ids + Cfg::MAX_CHUNK);
 
-  // unit = (chunk window, group); the output tiles of a unit share an XCD (they read the same
-  // rows), consecutive units go to different XCDs.  Coarser units (all experts of a head on one
-  // XCD, to share the gathered rows in its L2) gained nothing and unbalance the XCDs when the
-  // routing is skewed.
+  // unit = (chunk window, group); the output tiles of a unit share an XCD (they read the same rows).  Which XCD
+  // a unit runs on: see the window-major placement below.
   const int ti_ = (a.Ka + BM - 1) / BM, tj = (a.Kb + BN - 1) / BN;
   const int ntile = ti_ * tj;
   const int G = a.heads * a.E;
