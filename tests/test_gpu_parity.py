@@ -303,6 +303,12 @@ def test_full_config(name):
         assert np.all(counts[..., 0] > 0.95 * cfg["B"] * cfg["T"])   # the biased expert takes nearly every token
 
 
+def test_gated_gemms_second_round_of_tiles():
+    """c2's layer with more tokens than one round of the 256-row tiles holds (36 sequences: 72 row tiles x 4 column
+    tiles = 288 work-groups for 256 CUs): the tiles of the second round, and a token count that is no power of two."""
+    run_case(small("c2", B=36), seed=70)
+
+
 def _tie_columns(E):
     """Input edit for the tie cases: in head 0 expert 2 repeats expert 0's router column, in head 1 every
     expert has the same column (all E logits of a token are bitwise equal under any fixed summation order)."""
