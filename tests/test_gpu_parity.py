@@ -309,6 +309,21 @@ def test_gated_gemms_second_round_of_tiles():
     run_case(small("c2", B=36), seed=70)
 
 
+@pytest.mark.parametrize("E,k", [(4, 2), (6, 2)])
+def test_bf16_empty_expert(E, k):
+    """An expert nobody picks (bias -50) on the matrix-core kernels: an empty group in the sorted tables, in the
+    list of non-empty units the weight-gradient work-groups place themselves by, and an all-zero weight gradient.
+    E = 4, k = 2 takes the gated concatenation (a gate column that is zero for every token), E = 6 the expert sets."""
+    cfg = dict(name="empty16", dtype="bf16", B=4, T=300, d_model=256, nheads=2, d_head=64, E=E, k=k, causal=1, bias0=-50.0)
+    f, routing = run_case(cfg, seed=71)
+    assert np.all(np.diff(routing["offsets"], axis=-1)[..., 0] == 0)
+
+
+def test_bf16_max_limits():
+    """The largest E, k and d_head the library accepts, bf16 storage."""
+    run_case(dict(name="max16", dtype="bf16", B=2, T=140, d_model=64, nheads=1, d_head=256, E=64, k=8, causal=1, bias0=0.0), seed=72)
+
+
 def _tie_columns(E):
     """Input edit for the tie cases: in head 0 expert 2 repeats expert 0's router column, in head 1 every
     expert has the same column (all E logits of a token are bitwise equal under any fixed summation order)."""
