@@ -314,14 +314,16 @@ def test_bf16_empty_expert(E, k):
     """An expert nobody picks (bias -50) on the matrix-core kernels: an empty group in the sorted tables, in the
     list of non-empty units the weight-gradient work-groups place themselves by, and an all-zero weight gradient.
     E = 4, k = 2 takes the gated concatenation (a gate column that is zero for every token), E = 6 the expert sets."""
-    cfg = dict(name="empty16", dtype="bf16", B=4, T=300, d_model=256, nheads=2, d_head=64, E=E, k=k, causal=1, bias0=-50.0)
-    f, routing = run_case(cfg, seed=71)
+    cfg = dict(name="empty16", dtype="bf16", B=8, T=320, d_model=256, nheads=2, d_head=64, E=E, k=k, causal=1, bias0=-50.0)
+    f, routing = run_case(cfg, seed=71)   # 2560 tokens, a multiple of 256: what the gated concatenation asks for
     assert np.all(np.diff(routing["offsets"], axis=-1)[..., 0] == 0)
 
 
 def test_bf16_max_limits():
     """The largest E, k and d_head the library accepts, bf16 storage."""
     run_case(dict(name="max16", dtype="bf16", B=2, T=140, d_model=64, nheads=1, d_head=256, E=64, k=8, causal=1, bias0=0.0), seed=72)
+    # more than 64 (head, expert) groups: the weight-gradient work-groups find their unit by the plain decoding
+    run_case(dict(name="groups80", dtype="bf16", B=2, T=256, d_model=128, nheads=5, d_head=64, E=16, k=2, causal=1, bias0=0.0), seed=73)
 
 
 def _tie_columns(E):
