@@ -557,7 +557,8 @@ struct WgCfg {
   static constexpr int LDA = BM + 32, LDB = BN + 32;      // row strides 16 banks (mod 64) apart
   static constexpr int STAGE_ELEMS = BK * (LDA + LDB);
   static constexpr int MAX_CHUNK = 2048;
-  static constexpr size_t lds_bytes() { return (size_t)2 * STAGE_ELEMS * 2 + (size_t)MAX_CHUNK * 8; }
+  static constexpr int ROW_CAP = MAX_CHUNK + 4 * BK;   // the row tables reach past the chunk as far as the prefetch does
+  static constexpr size_t lds_bytes() { return (size_t)2 * STAGE_ELEMS * 2 + (size_t)ROW_CAP * 8; }
 };
 typedef WgCfg<2, 2, 2, 2, 1> WgSmall;   // 128 x 128
 typedef WgCfg<1, 4, 4, 2, 2> WgWide;    // 128 x 256, wave tile 128 x 64, two work-groups per CU
@@ -578,7 +579,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   typedef typename Chunk<VEC>::type chunk_t;
   extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
   int* ids = (int*)(smem + 2 * Cfg::STAGE_ELEMS);
-  float* gsc = (float*)(ids + Cfg::MAX_CHUNK);
+  float* gsc = (float*)(ids + Cfg::ROW_CAP);
 
   // unit = (chunk window, group); the output tiles of a unit share an XCD (they read the same rows).  Which XCD
   // a unit runs on: see the window-major placement below.
@@ -586,6 +587,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   const int ntile = ti_ * tj;
   const int G = a.heads * a.E;
   int w, grp, tile;
+  int g_first = 0, g_rows = 0;   // the group's first row in the sorted order, its row count
   if (G <= 64) {
     // Window-major placement.  The chunk windows of all groups cover about the same tokens (the w-th chunk of every
     // expert's sorted rows lies near the same token range), so the work-groups of one window should meet in one L2:
@@ -593,10 +595,15 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     // the x-th eighth of that list, i.e. one or two windows, instead of every eighth unit of all windows.  Every wave
     // derives the list from the group sizes by itself (lane g holds the rows of group g).
     const int lane_ = threadIdx.x & 63;
-    int grows = 0;
+    int grows = 0, gstart = 0;
     if (lane_ < G) {
       const int gh = lane_ / a.E, ge = lane_ % a.E;
-      grows = a.perm ? a.offsets[(long)gh * (a.E + 1) + ge + 1] - a.offsets[(long)gh * (a.E + 1) + ge] : a.M;
+      if (a.perm) {
+        gstart = a.offsets[(long)gh * (a.E + 1) + ge];
+        grows = a.offsets[(long)gh * (a.E + 1) + ge + 1] - gstart;
+      } else {
+        grows = a.M;
+      }
     }
     long units = 0;
     for (int ww = 0;; ++ww) {
@@ -620,34 +627,62 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     for (long t = 0; t < u; ++t) m &= m - 1;   // drop the u lowest groups of the window
     w = ww;
     grp = __ffsll((long long)m) - 1;
+    // the group's first row and row count sit in lane grp: no second trip to the offsets
+    g_first = __shfl(gstart, grp);
+    g_rows = __shfl(grows, grp);
   } else {
     int unit;
     decode_block(blockIdx.x, ntile, unit, tile);
     w = unit / G;
     grp = unit % G;
+    if (w * a.chunk >= (a.perm ? a.max_group_rows : a.M)) return;
+    if (a.perm) {
+      const int* off = a.offsets + (long)(grp / a.E) * (a.E + 1);
+      g_first = off[grp % a.E];
+      g_rows = off[grp % a.E + 1] - g_first;
+    } else {
+      g_rows = a.M;
+    }
   }
-  if (w * a.chunk >= (a.perm ? a.max_group_rows : a.M)) return;
   const int h = grp / a.E, e = grp % a.E;
-  int row0, rows;
-  if (a.perm) {
-    const int* off = a.offsets + (long)h * (a.E + 1);
-    row0 = off[e] + w * a.chunk;
-    const int end = off[e + 1];
-    if (row0 >= end) return;
-    rows = end - row0 < a.chunk ? end - row0 : a.chunk;
-  } else {
-    row0 = w * a.chunk;
-    if (row0 >= a.M) return;
-    rows = a.M - row0 < a.chunk ? a.M - row0 : a.chunk;
-  }
+  if (w * a.chunk >= g_rows) return;
+  const int row0 = g_first + w * a.chunk;
+  const int rows = g_rows - w * a.chunk < a.chunk ? g_rows - w * a.chunk : a.chunk;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int t = tid; t < rows; t += 256) {
-    int id = a.perm ? a.perm[(long)h * a.M + row0 + t] : row0 + t;
-    ids[t] = FULL ? div_by(id, div_magic(a.a_div)) : id;
-    gsc[t] = a.gate ? a.gate[(long)h * a.gate_hstride + id] : 1.f;
+  // the chunk's row ids, then their gates: every thread requests all of its ids before it waits for one, and
+  // likewise the gates (two round trips; a loop over the rows would make two per 256 rows, and every work-group
+  // of the launch stands in this prologue at the same time)
+  {
+    constexpr int PR = Cfg::MAX_CHUNK / 256;
+    int idv[PR];
+    float gv[PR];
+#pragma unroll
+    for (int i = 0; i < PR; ++i) {
+      const int t = tid + 256 * i;
+      idv[i] = t < rows ? (a.perm ? a.perm[(long)h * a.M + row0 + t] : row0 + t) : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < PR; ++i) gv[i] = a.gate && tid + 256 * i < rows ? a.gate[(long)h * a.gate_hstride + idv[i]] : 1.f;
+#pragma unroll
+    for (int i = 0; i < PR; ++i) {
+      const int t = tid + 256 * i;
+      if (t < rows) {
+        ids[t] = FULL ? div_by(idv[i], div_magic(a.a_div)) : idv[i];
+        gsc[t] = gv[i];
+      }
+    }
   }
-  // rows past the chunk that a computed step can touch are staged as zeros; give them a zero gate too
-  for (int t = rows + tid; t < rows + 2 * BK && t < Cfg::MAX_CHUNK; t += 256) gsc[t] = 0.f;
+  // rows past the chunk that a step can touch (the loop rounds the step count up to an even number and requests
+  // rows two steps ahead): a zero gate, and in the FULL modes the row of the chunk's last entry, so that the
+  // loads need no clamp
+  __syncthreads();
+  {
+    const int last = ids[rows - 1];
+    for (int t = rows + tid; t < rows + 4 * BK && t < Cfg::ROW_CAP; t += 256) {
+      gsc[t] = 0.f;
+      if (FULL) ids[t] = last;
+    }
+  }
   __syncthreads();
 
   const int i0 = (tile / tj) * BM, j0 = (tile % tj) * BN;
@@ -667,16 +702,28 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
   // two register sets: a step's rows are requested two steps before they are multiplied, so a
   // load has two steps of the work-group (and of its neighbour on the CU) to arrive
   chunk_t ra0[A_N], rb0[B_N], ra1[A_N], rb1[B_N];
+  // FULL: a load's address is the operand's base (uniform) plus a 32-bit byte offset, row * stride + this thread's
+  // column, one 24-bit multiply-add (the launcher checks that rows and strides stay below 2^24 and the operand
+  // below 4 GiB); the row comes from the padded table, so nothing is clamped
+  const char* Ab = (const char*)(A + (long)hh * a.a_hoff);
+  const char* Bb = (const char*)(Bm + (long)hh * a.b_hoff);
+  const unsigned lda2 = (unsigned)a.lda * 2, ldb2 = (unsigned)a.ldb * 2;
+  const unsigned col_a2 = (unsigned)min(i0 + (tid % A_CPR) * VEC, a.Ka - VEC) * 2;
+  const unsigned col_b2 = (unsigned)min(j0 + (tid % B_CPR) * VEC, a.Kb - VEC) * 2;
   auto load_global = [&](chunk_t (&ra)[A_N], chunk_t (&rb)[B_N], int r0) {
+    if constexpr (FULL) {
+      const int* ia = ids + r0 + tid / A_CPR;
+      const int* ib = ids + r0 + tid / B_CPR;
+#pragma unroll
+      for (int i = 0; i < A_N; ++i) ra[i] = *(const chunk_t*)(Ab + (__umul24((unsigned)ia[i * (256 / A_CPR)], lda2) + col_a2));
+#pragma unroll
+      for (int i = 0; i < B_N; ++i) rb[i] = *(const chunk_t*)(Bb + (__umul24((unsigned)ib[i * (256 / B_CPR)], ldb2) + col_b2));
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
       const int c = tid + i * 256;
       const int rr = c / A_CPR, fc = (c % A_CPR) * VEC;
-      if constexpr (FULL) {
-        ra[i] = *(const chunk_t*)(A + (long)row_of(ids[min(r0 + rr, rows - 1)], inv_a) * a.lda + (long)hh * a.a_hoff +
-                                  min(i0 + fc, a.Ka - VEC));
-        continue;
-      }
       ra[i] = zero_chunk<VEC>();
       if (r0 + rr < rows && i0 + fc < a.Ka) {
         ra[i] = *(const chunk_t*)(A + (long)row_of(ids[r0 + rr], inv_a) * a.lda + (long)hh * a.a_hoff + i0 + fc);
@@ -686,11 +733,6 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     for (int i = 0; i < B_N; ++i) {
       const int c = tid + i * 256;
       const int rr = c / B_CPR, fc = (c % B_CPR) * VEC;
-      if constexpr (FULL) {
-        rb[i] = *(const chunk_t*)(Bm + (long)row_of(ids[min(r0 + rr, rows - 1)], inv_b) * a.ldb + (long)hh * a.b_hoff +
-                                  min(j0 + fc, a.Kb - VEC));
-        continue;
-      }
       rb[i] = zero_chunk<VEC>();
       if (r0 + rr < rows && j0 + fc < a.Kb) {
         rb[i] = *(const chunk_t*)(Bm + (long)row_of(ids[r0 + rr], inv_b) * a.ldb + (long)hh * a.b_hoff + j0 + fc);
@@ -702,11 +744,32 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     unsigned short* Bs = As + BK * LDA;
     // the gate is applied here, not at the load, so that the load stays in flight while the
     // previous steps are multiplied (rows past the chunk hold zeros and a zero gate)
+    if constexpr (FULL) {
+      // every row of the step lies in the chunk (a uniform test): nothing to zero.  Columns past the last feature of a
+      // ragged tile hold a repeat of the last piece here; they only reach output elements that are never stored.
+      if (staged_r0 + BK <= rows) {
+        const float* ga = gsc + staged_r0 + tid / A_CPR;
+        const float* gb = gsc + staged_r0 + tid / B_CPR;
+#pragma unroll
+        for (int i = 0; i < A_N; ++i) {
+          chunk_t v = ra[i];
+          if (MODE == 2) v = scale_chunk(v, ga[i * (256 / A_CPR)]);
+          *(chunk_t*)(&As[(tid / A_CPR + i * (256 / A_CPR)) * LDA + (tid % A_CPR) * VEC]) = v;
+        }
+#pragma unroll
+        for (int i = 0; i < B_N; ++i) {
+          chunk_t v = rb[i];
+          if (MODE == 3) v = scale_chunk(v, gb[i * (256 / B_CPR)]);
+          *(chunk_t*)(&Bs[(tid / B_CPR + i * (256 / B_CPR)) * LDB + (tid % B_CPR) * VEC]) = v;
+        }
+        return;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < A_N; ++i) {
       const int c = tid + i * 256;
       chunk_t v = ra[i];   // a copy: the register sets themselves are only ever written by the loads
-      if (MODE == 2 || (MODE == 0 && scaled && !a.scale_b)) v = scale_chunk(v, gsc[min(staged_r0 + c / A_CPR, Cfg::MAX_CHUNK - 1)]);
+      if (MODE == 2 || (MODE == 0 && scaled && !a.scale_b)) v = scale_chunk(v, gsc[min(staged_r0 + c / A_CPR, Cfg::ROW_CAP - 1)]);
       if constexpr (FULL) v = i0 + (c % A_CPR) * VEC < a.Ka ? v : zero_chunk<VEC>();   // pieces past the last feature
       *(chunk_t*)(&As[(c / A_CPR) * LDA + (c % A_CPR) * VEC]) = v;
     }
@@ -714,7 +777,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     for (int i = 0; i < B_N; ++i) {
       const int c = tid + i * 256;
       chunk_t v = rb[i];
-      if (MODE == 3 || (MODE == 0 && scaled && a.scale_b)) v = scale_chunk(v, gsc[min(staged_r0 + c / B_CPR, Cfg::MAX_CHUNK - 1)]);
+      if (MODE == 3 || (MODE == 0 && scaled && a.scale_b)) v = scale_chunk(v, gsc[min(staged_r0 + c / B_CPR, Cfg::ROW_CAP - 1)]);
       if constexpr (FULL) v = staged_r0 + c / B_CPR < rows && j0 + (c % B_CPR) * VEC < a.Kb ? v : zero_chunk<VEC>();   // repeats count for nothing
       *(chunk_t*)(&Bs[(c / B_CPR) * LDB + (c % B_CPR) * VEC]) = v;
     }
@@ -859,18 +922,31 @@ static void launch_wg(const WgradArgs& a, hipStream_t s) {
   const int group_rows = a.perm ? a.max_group_rows : a.M;
   dim3 g(grid_windows(((group_rows + a.chunk - 1) / a.chunk) * a.heads * a.E, ti * tj));
   const size_t lds = Cfg::lds_bytes();
-  const bool full = a.a_div == a.b_div && a.Ka >= VEC && a.Kb >= VEC;
-  const int mode = !full ? 0 : (a.gate == nullptr ? 1 : (a.scale_b ? 3 : 2));
-  auto kern = mode == 0 ? mfma_wgrad_kernel<Cfg, VEC, TAG, 0>
-            : mode == 1 ? mfma_wgrad_kernel<Cfg, VEC, TAG, 1>
-            : mode == 2 ? mfma_wgrad_kernel<Cfg, VEC, TAG, 2> : mfma_wgrad_kernel<Cfg, VEC, TAG, 3>;
+  // the unconditional-load modes address both operands by 32-bit byte offsets made by a 24-bit multiply
+  const size_t op_rows = ((size_t)a.M + (a.a_div > 0 ? a.a_div : 1) - 1) / (a.a_div > 0 ? a.a_div : 1);
+  const size_t ldmax = (size_t)(a.lda > a.ldb ? a.lda : a.ldb);
+  const bool small_offsets = op_rows < ((size_t)1 << 24) && ldmax * 2 < ((size_t)1 << 24) && op_rows * ldmax * 2 < ((size_t)1 << 32);
+  const bool full = a.a_div == a.b_div && a.Ka >= VEC && a.Kb >= VEC && small_offsets;
+  // the gate scales the rows of the narrower side of the tile (the same product, half the elements to scale); square
+  // tiles take the side the caller names
+  constexpr bool can_a = Cfg::BM <= Cfg::BN, can_b = Cfg::BM >= Cfg::BN;
+  const bool on_b = !can_a || (can_b && a.scale_b);
+  const int mode = !full ? 0 : (a.gate == nullptr ? 1 : (on_b ? 3 : 2));
+  void (*kern)(WgradArgs) = mfma_wgrad_kernel<Cfg, VEC, TAG, 0>;
+  if (mode == 1) kern = mfma_wgrad_kernel<Cfg, VEC, TAG, 1>;
+  if constexpr (can_a)
+    if (mode == 2) kern = mfma_wgrad_kernel<Cfg, VEC, TAG, 2>;
+  if constexpr (can_b)
+    if (mode == 3) kern = mfma_wgrad_kernel<Cfg, VEC, TAG, 3>;
   if (lds > 64 * 1024) {
     static bool raised = false;
     if (!raised) {
       (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if constexpr (can_a)
+        (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if constexpr (can_b)
+        (void)hipFuncSetAttribute((const void*)mfma_wgrad_kernel<Cfg, VEC, TAG, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       raised = true;
     }
   }
