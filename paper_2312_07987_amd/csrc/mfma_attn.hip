@@ -845,15 +845,18 @@ __global__ __launch_bounds__(256, DH <= 128 ? 2 : 1) void mfma_attn_dq_kernel(At
 
 // ----------------------------------------------------------------------------------------
 // backward, dQ from the stored score gradient: dQ[q][:] = scale * sum_key dS[q][key] K[key][:], a plain product.
-// block = 4 waves x 64 queries; key tiles of 64 rows of K and of dS^T (as the dK / dV kernel left it, [key][query])
+// block = 4 waves x 64 queries; key tiles of KT rows of K and of dS^T (as the dK / dV kernel left it, [key][query])
 // are staged in LDS and both read with transposing loads:
 //   dQ^T[d][q] += K^T[d][key] dS^T[key][q]
 // The dK / dV work-group of 128 keys starting at kt0 wrote the queries from (max(kt0 - off, 0) / DKV_QT) * DKV_QT on (every
 // earlier query sees none of its keys); what lies before that in a row was never written and is replaced by zeros here.
 // ----------------------------------------------------------------------------------------
 template <int DH, int VEC, int QB>
-__global__ __launch_bounds__(256, QB == 128 ? 3 : 2) void mfma_attn_dq_ds_kernel(AttnBwdArgs a) {
-  constexpr int KT = 64;
+__global__ __launch_bounds__(256, 2) void mfma_attn_dq_ds_kernel(AttnBwdArgs a) {
+  // keys per trip.  Under a causal mask the last query tile of a sequence walks all keys while its light partner on the
+  // CU is long done, one wave per SIMD and a barrier pair per trip: fewer, longer trips shorten that chain (T = 4096:
+  // 101 -> 90 us with 128 keys; two work-groups per CU either way).  The 256-query tile has no LDS left for it.
+  constexpr int KT = QB == 128 ? 128 : 64;
   constexpr int LDT = ld_tr(DH), LDD = ld_tr(QB);
   constexpr int NDB = DH / 32;
   // QB = 256: a wave owns 64 queries and all of d.  QB = 128 (twice the work-groups: short sequence counts fill the chip
@@ -868,7 +871,7 @@ __global__ __launch_bounds__(256, QB == 128 ? 3 : 2) void mfma_attn_dq_ds_kernel
   int b, h, qt;
   const int T = a.T, dh = a.dh, Tq = a.Tq > 0 ? a.Tq : a.T;
   const int off = T - Tq;
-  attn_block_map(blockIdx.x, (Tq + QB - 1) / QB, a.B * a.H, a.H, a.causal, true, QB == 128 ? 3 : 2, b, h, qt);
+  attn_block_map(blockIdx.x, (Tq + QB - 1) / QB, a.B * a.H, a.H, a.causal, true, 2, b, h, qt);
   const int q0 = qt * QB;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
@@ -1002,7 +1005,7 @@ static void launch_dh(const AttnArgs* f, const AttnBwdArgs* bw, hipStream_t s) {
     if constexpr (DH >= 64 && DH <= 128) {
       if (bw->dSt) {
         const int tq = bw->Tq > 0 ? bw->Tq : bw->T;
-        // 128-query tiles (half of d per wave) unless 256-query tiles already give every CU three work-groups
+        // 128-query tiles (half of d per wave) unless 256-query tiles already make three work-groups per CU
         constexpr bool can_split = (DH / 32) % 2 == 0;
         const long big = (long)((tq + 255) / 256) * bw->H * bw->B;
         if (can_split && big < 3 * 256) {

@@ -56,7 +56,7 @@ def test_attention_budgets(tmp_path):
             assert vgpr <= 256 and scratch <= 32, (k, vgpr, scratch)   # five spilled dwords, outside the products
             seen += 1
         if "mfma_attn_dq_ds_kernel<128, 8, 128>" in k or "mfma_attn_dq_ds_kernel<64, 8, 128>" in k:
-            assert vgpr <= 168 and scratch == 0, (k, vgpr, scratch)    # three work-groups per CU
+            assert vgpr <= 256 and scratch == 0, (k, vgpr, scratch)    # two work-groups per CU (trips of 128 keys)
             seen += 1
         if "mfma_attn_dq_ds_kernel<" in k and ", 256>" in k:
             assert vgpr <= 256 and scratch == 0, (k, vgpr, scratch)
