@@ -656,13 +656,23 @@ __global__ __launch_bounds__(256, Cfg::MINB) void mfma_wgrad_kernel(WgradArgs a)
     constexpr int PR = Cfg::MAX_CHUNK / 256;
     int idv[PR];
     float gv[PR];
+    // (clamped indices instead of tests: a test around a load costs a branch and a wait for every load before it)
+    if (a.perm) {
+      const int* pp = a.perm + (long)h * a.M + row0;
 #pragma unroll
-    for (int i = 0; i < PR; ++i) {
-      const int t = tid + 256 * i;
-      idv[i] = t < rows ? (a.perm ? a.perm[(long)h * a.M + row0 + t] : row0 + t) : 0;
+      for (int i = 0; i < PR; ++i) idv[i] = pp[min(tid + 256 * i, rows - 1)];
+    } else {
+#pragma unroll
+      for (int i = 0; i < PR; ++i) idv[i] = row0 + min(tid + 256 * i, rows - 1);
     }
+    if (a.gate) {
+      const float* gp = a.gate + (long)h * a.gate_hstride;
 #pragma unroll
-    for (int i = 0; i < PR; ++i) gv[i] = a.gate && tid + 256 * i < rows ? a.gate[(long)h * a.gate_hstride + idv[i]] : 1.f;
+      for (int i = 0; i < PR; ++i) gv[i] = gp[idv[i]];
+    } else {
+#pragma unroll
+      for (int i = 0; i < PR; ++i) gv[i] = 1.f;
+    }
 #pragma unroll
     for (int i = 0; i < PR; ++i) {
       const int t = tid + 256 * i;
