@@ -274,12 +274,16 @@ __global__ __launch_bounds__(256 * NG, (DH <= 128 && NG == 1) ? 2 : 1) void mfma
       const bool moved = mn > m;                    // wave-uniform test below: most tiles move no maximum
       const float alpha = moved ? __builtin_amdgcn_exp2f(m - mn) : 1.f;   // m = -inf on the first tile -> 0
       m = mn;
+      // A query that has seen no key yet and sees none in this tile (the second wave group starts at tile 1, and with
+      // fewer queries than keys a wave's tile can hold a row's first key in a later tile) has mn = -inf: take 0 as the
+      // base there, -inf - (-inf) would be a NaN
+      const float mb = mn == -INFINITY ? 0.f : mn;
       float ps = 0.f;
 #pragma unroll
       for (int kb = 0; kb < KT / 32; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], sc, -mn));   // masked: -inf -> 0
+          s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], sc, -mb));   // masked: -inf -> 0
           ps += s[kb][i];
         }
       l = l * alpha + ps;

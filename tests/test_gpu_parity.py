@@ -237,6 +237,15 @@ def test_bf16_long_ragged_sequences(family):
     run_case(small("c2", B=2, T=1030, d_model=256, nheads=1, d_head=96, causal=0), family=family, seed=66)
 
 
+@pytest.mark.parametrize("d_head", [48, 128])
+def test_bf16_long_causal_context_not_a_multiple_of_the_key_tile(d_head):
+    """T >= 1024 (the forward kernel's two wave groups take alternate key tiles) under a causal mask with 22 cached
+    positions: queries 32..41 see keys up to position 54..63 only, so for them the second group's first tile (keys
+    64..127, visited because the wave's last query sees key 64) is fully masked before any key was seen."""
+    run_case(dict(name="off22", dtype="bf16", B=1, T=1100, d_model=64, nheads=2, d_head=d_head, E=5, k=2, causal=1, bias0=0.0,
+                  T_q=1078), seed=74)
+
+
 def test_bf16_mixed_shapes_long_context():
     """Shapes off the beaten track for the attention kernels of head widths 64..128: head widths that are padded to the
     next compiled width (72, 104), cached contexts with odd offsets past 1024 keys, rotary turns, no causal mask, E = 8."""
