@@ -540,8 +540,24 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
     const int nblk = router_blocks(N), ns = count_sets(E, k);
     for (int side = 0; side < 2; ++side) {
       const int n = c.n(side);
+      // this side's expert-set tables (the set sort of each side runs on its own tokens)
+      SetSortArgs s1 = sa;
+      if (tables) {
+        s1.idx = c.idx(side);
+        s1.gate = c.gate(side);
+        s1.setid = sa.setid + (size_t)side * H * N;
+        s1.gset = sa.gset + (size_t)side * H * N * k;
+        s1.gsort = sa.gsort + (size_t)side * H * N * k;
+        s1.setperm = sa.setperm + (size_t)side * H * N;
+        s1.setoff = sa.setoff + (size_t)side * H * (ns + 1);
+        s1.blockcnt = sa.blockcnt + (size_t)side * H * nblk * ns;
+        s1.N = n;
+        s1.sides = 1;
+      }
       if (c.dense) {
+        // (dense attention has one expert set, but the kernels of the set path still read its tables)
         launch_dense_routing(c.idx(side), c.gate(side), c.perm(side), c.offsets(side), n, H, c.st);
+        if (tables) launch_set_sort(s1, c.st);
         continue;
       }
       const bool own = side == 1 && !c.shared;   // the destination side's own router
@@ -562,19 +578,6 @@ sh_status switchhead_forward(const sh_shape* shape, const void* x, const void* W
       ra.k = k;
       ra.sides = 1;
       ra.bf16 = c.bf16;
-      SetSortArgs s1 = sa;
-      if (tables) {
-        s1.idx = c.idx(side);
-        s1.gate = c.gate(side);
-        s1.setid = sa.setid + (size_t)side * H * N;
-        s1.gset = sa.gset + (size_t)side * H * N * k;
-        s1.gsort = sa.gsort + (size_t)side * H * N * k;
-        s1.setperm = sa.setperm + (size_t)side * H * N;
-        s1.setoff = sa.setoff + (size_t)side * H * (ns + 1);
-        s1.blockcnt = sa.blockcnt + (size_t)side * H * nblk * ns;
-        s1.N = n;
-        s1.sides = 1;
-      }
       if (use_mfma(c) && router_hybrid_supported(ra)) {
         if (tables) ra.sets = &s1;
         launch_router_hybrid(ra, c.p<char>(c.L.rh), c.st);

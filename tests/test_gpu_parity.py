@@ -246,6 +246,14 @@ def test_bf16_long_causal_context_not_a_multiple_of_the_key_tile(d_head):
                   T_q=1078), seed=74)
 
 
+@pytest.mark.parametrize("T,T_q", [(300, 143), (1024, 143)])
+def test_bf16_dense_mode_fewer_queries_than_keys(T, T_q):
+    """Dense multi-head attention (no routers) over a cached context on the matrix-core kernels: each side's
+    expert-set tables (one set, but the set-path kernels read them) are built on that side's own tokens."""
+    run_case(dict(name="dense_ctx", dtype="bf16", B=2, T=T, d_model=64, nheads=2, d_head=64, E=1, k=1, causal=1, bias0=0.0, T_q=T_q),
+             dense=True, seed=75)
+
+
 def test_bf16_mixed_shapes_long_context():
     """Shapes off the beaten track for the attention kernels of head widths 64..128: head widths that are padded to the
     next compiled width (72, 104), cached contexts with odd offsets past 1024 keys, rotary turns, no causal mask, E = 8."""
