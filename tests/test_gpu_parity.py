@@ -343,6 +343,20 @@ def test_bf16_max_limits():
     run_case(dict(name="groups80", dtype="bf16", B=2, T=256, d_model=128, nheads=5, d_head=64, E=16, k=2, causal=1, bias0=0.0), seed=73)
 
 
+def test_bf16_decoding_and_many_short_sequences():
+    """Shapes from random sweeps that the other cases do not reach: one query against a long cached context (with rotary
+    turns and expert queries / keys; with shared selection), hundreds of sequences of a few tokens, 64 experts with six
+    active over a cached context."""
+    run_case(dict(name="dec1", dtype="bf16", B=1, T=3000, d_model=256, nheads=4, d_head=64, E=4, k=3, causal=1, bias0=0.0, T_q=1,
+                  rope=1, qk_experts=1), family=1, seed=8014)
+    run_case(dict(name="dec2", dtype="bf16", B=1, T=1500, d_model=128, nheads=2, d_head=32, E=2, k=1, causal=1, bias0=0.0, T_q=1),
+             shared=True, seed=8017)
+    run_case(dict(name="short1", dtype="bf16", B=300, T=17, d_model=512, nheads=2, d_head=64, E=5, k=2, causal=1, bias0=0.0), seed=8021)
+    run_case(dict(name="short2", dtype="bf16", B=777, T=3, d_model=128, nheads=4, d_head=32, E=2, k=2, causal=0, bias0=0.0), seed=8022)
+    run_case(dict(name="e64", dtype="bf16", B=1, T=1100, d_model=128, nheads=1, d_head=128, E=64, k=6, causal=0, bias0=2.0, T_q=92),
+             seed=7019)
+
+
 def _tie_columns(E):
     """Input edit for the tie cases: in head 0 expert 2 repeats expert 0's router column, in head 1 every
     expert has the same column (all E logits of a token are bitwise equal under any fixed summation order)."""
